@@ -1,0 +1,486 @@
+"""Pins for the CPU oracle: everything here checks oracle/ against something other than itself.
+
+Sources of truth used: central finite differences of a scalar loss (the definition of a
+gradient), hand-computed fixtures under tests/golden/ (each cites the passage it follows),
+exact rational arithmetic for rounding, brute-force Python loops on tiny inputs, closed forms
+and the Gram identity for norms, and numbers printed in the paper.
+"""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import lomo_oracle as O
+from golden_io import read_golden
+
+RNG = np.random.default_rng(1234)
+
+
+def f16(a):
+    return np.asarray(a, dtype=np.float64).astype(np.float16)
+
+
+# ----------------------------------------------------------------------------- P1 finite differences
+
+
+class TinyModel:
+    """embedding -> RMSNorm gain -> linear -> tanh -> linear -> scalar loss, all fp64."""
+
+    def __init__(self, rng, T=5, V=6, H=4, D=3, Oo=2):
+        self.ids = np.array([2, 0, 2, 5, 0][:T])
+        self.V = V
+        self.p = {
+            "E": rng.normal(size=(V, H)),
+            "g": 1.0 + 0.1 * rng.normal(size=(H,)),
+            "W1": rng.normal(size=(D, H)) * 0.7,
+            "W2": rng.normal(size=(Oo, D)) * 0.7,
+        }
+        self.C = rng.normal(size=(T, Oo))
+
+    def forward(self, p):
+        e = p["E"][self.ids]
+        r = np.sqrt((e * e).mean(axis=1, keepdims=True) + 1e-5)
+        xhat = e / r
+        y = xhat * p["g"]
+        h1 = y @ p["W1"].T
+        a = np.tanh(h1)
+        h2 = a @ p["W2"].T
+        loss = 0.5 * (h2 * h2).sum() + (self.C * h2).sum()
+        return loss, dict(e=e, r=r, xhat=xhat, y=y, a=a, h2=h2)
+
+    def grads_via_oracle(self, lin=None, inp=None, vec=None, emb=None):
+        lin = lin or O.linear_grad
+        inp = inp or O.input_grad_f64
+        vec = vec or O.vector_grad
+        emb = emb or O.embedding_grad
+        p = self.p
+        _, c = self.forward(p)
+        dh2 = c["h2"] + self.C
+        gW2 = lin(c["a"], dh2)
+        da = inp(dh2, p["W2"])
+        dh1 = da * (1.0 - c["a"] ** 2)
+        gW1 = lin(c["y"], dh1)
+        dy = inp(dh1, p["W1"])
+        gg = vec(c["xhat"], dy)
+        dxhat = dy * p["g"]
+        de = (dxhat - c["xhat"] * (dxhat * c["xhat"]).mean(axis=1, keepdims=True)) / c["r"]
+        gE = emb(self.ids, de, self.V)
+        return {"E": gE, "g": gg, "W1": gW1, "W2": gW2}
+
+    def grads_fd(self, h=1e-6):
+        out = {}
+        for name, arr in self.p.items():
+            g = np.zeros_like(arr)
+            it = np.nditer(arr, flags=["multi_index"])
+            for _ in it:
+                idx = it.multi_index
+                old = arr[idx]
+                arr[idx] = old + h
+                lp, _ = self.forward(self.p)
+                arr[idx] = old - h
+                lm, _ = self.forward(self.p)
+                arr[idx] = old
+                g[idx] = (lp - lm) / (2 * h)
+            out[name] = g
+        return out
+
+
+def _fd_check(model, **mut):
+    an = model.grads_via_oracle(**mut)
+    fd = model.grads_fd()
+    for k in fd:
+        assert an[k].shape == fd[k].shape, k
+        np.testing.assert_allclose(an[k], fd[k], rtol=2e-6, atol=2e-8, err_msg=k)
+
+
+def test_p1_finite_differences_two_layer_model():
+    _fd_check(TinyModel(np.random.default_rng(7)))
+
+
+@pytest.mark.parametrize("mut", [
+    dict(lin=lambda X, dY: O.as_f64(X).T @ O.as_f64(dY)),                 # transposed layout
+    dict(lin=lambda X, dY: -O.linear_grad(X, dY)),                        # sign
+    dict(inp=lambda dY, W: O.as_f64(dY) @ O.as_f64(W)[:, ::-1]),          # wrong index
+    dict(vec=lambda xh, dY: O.as_f64(dY).sum(axis=0)),                    # dropped factor
+    dict(emb=lambda ids, dY, V: O.embedding_grad(ids[::-1], dY, V)),      # wrong position order
+])
+def test_p1_is_sensitive_to_planted_mistakes(mut):
+    with pytest.raises((AssertionError, ValueError)):
+        _fd_check(TinyModel(np.random.default_rng(7)), **mut)
+
+
+# ----------------------------------------------------------------------------- P2 hand examples
+
+
+def test_p2_hand_linear_2x3(golden_dir):
+    g = read_golden(os.path.join(golden_dir, "hand_linear_2x3.txt"))
+    X, dY, W = f16(g["X"]), f16(g["dY"]), f16(g["W"])
+    G = O.linear_grad(X, dY)
+    np.testing.assert_array_equal(G, g["G"])
+    assert O.sqnorm(G) == g["sqnorm"]
+    Wn = O.sgd_update(W, G, g["lr"], 1.0, g["loss_scale"])
+    np.testing.assert_array_equal(Wn.astype(np.float64), g["W_new"])
+    np.testing.assert_array_equal(O.input_grad(dY, W).astype(np.float64), g["dX"])
+    # the whole-step driver with clipping: coef = 1/(sqrt(335)+eps)
+    res = O.step_materialised([dict(kind="linear", X=X, dY=dY, W=W)], g["lr"], 1.0, 1.0, 1e-6)
+    coef = 1.0 / (math.sqrt(335.0) + 1e-6)
+    assert res["clip_coef"] == pytest.approx(coef, rel=1e-15)
+    expect = f16(g["W"] - g["lr"] * coef * g["G"])
+    np.testing.assert_array_equal(res["W"][0], expect)
+
+
+def test_p2_hand_sgd_4x4_with_loss_scale(golden_dir):
+    g = read_golden(os.path.join(golden_dir, "hand_sgd_4x4.txt"))
+    X, dY, W = f16(g["X"]), f16(g["dY"]), f16(g["W"])
+    G = O.linear_grad(X, dY)
+    np.testing.assert_array_equal(G, g["G"])
+    Wn = O.sgd_update(W, G, g["lr"], 1.0, g["loss_scale"])
+    assert Wn.dtype == np.float16
+    np.testing.assert_array_equal(Wn.astype(np.float64), g["W_new"])
+    # textbook SGD typed out independently: W - lr * (dY^T / S)
+    np.testing.assert_array_equal(Wn.astype(np.float64), g["W"] - g["lr"] * (g["dY"].T / g["loss_scale"]))
+
+
+def test_hand_embedding_and_vector(golden_dir):
+    g = read_golden(os.path.join(golden_dir, "hand_embedding_vector.txt"))
+    ids = g["ids"][0].astype(np.int32)
+    G = O.embedding_grad(ids, f16(g["emb_dY"]), 4)
+    np.testing.assert_array_equal(G, g["emb_G"])
+    u, off, perm = O.embedding_grouping(ids)
+    np.testing.assert_array_equal(perm, g["perm"][0])
+    np.testing.assert_array_equal(u, g["unique_ids"][0])
+    np.testing.assert_array_equal(off, g["seg_offsets"][0])
+    np.testing.assert_array_equal(O.vector_grad(f16(g["xhat"]), f16(g["vec_dY"])), g["vec_g"][0])
+
+
+# ----------------------------------------------------------------------------- P3 LOMO order == SGD
+
+
+def _random_step_tensors(rng, S=64.0, with_inf=False):
+    def h(*s, sd=1.0):
+        return (rng.normal(size=s) * sd).astype(np.float16)
+    T, V, H = 12, 9, 8
+    ts = [
+        dict(kind="linear", X=h(T, 8), dY=h(T, 6, sd=0.05 * S), W=h(6, 8, sd=0.3)),
+        dict(kind="vector", X=h(T, H), dY=h(T, H, sd=0.05 * S), W=np.ones(H, np.float16)),
+        dict(kind="linear", X=h(T, 10), dY=h(T, 8, sd=0.05 * S), W=h(8, 10, sd=0.3)),
+        dict(kind="embedding", ids=rng.integers(0, V, size=T).astype(np.int32), dY=h(T, H, sd=0.05 * S),
+             W=h(V, H, sd=0.3)),
+    ]
+    if with_inf:
+        ts[2]["dY"][3, 1] = np.inf
+    return ts
+
+
+def _assert_same_step(a, b):
+    assert a["overflow"] == b["overflow"] and a["flags"] == b["flags"]
+    for x, y in zip(a["W"], b["W"]):
+        np.testing.assert_array_equal(x.view(np.uint16), y.view(np.uint16))
+    for x, y in zip(a["dX"], b["dX"]):
+        assert (x is None) == (y is None)
+        if x is not None:
+            np.testing.assert_array_equal(x.view(np.uint16), y.view(np.uint16))
+
+
+def test_p3_fused_order_equals_materialised_sgd():
+    ts = _random_step_tensors(np.random.default_rng(3))
+    a = O.step_materialised(ts, 0.25, 64.0)
+    b = O.step_fused_order(ts, 0.25, 64.0)
+    _assert_same_step(a, b)
+    assert a["clip_coef"] == b["clip_coef"] < 1.0
+    # and the update is visible: most weights moved
+    moved = sum(int((x.view(np.uint16) != t["W"].view(np.uint16)).sum()) for x, t in zip(a["W"], ts))
+    assert moved > 100
+
+
+def test_p3_dx_uses_pre_update_weights():
+    ts = _random_step_tensors(np.random.default_rng(4))
+    res = O.step_fused_order(ts, 0.25, 64.0)
+    lin = ts[0]
+    brute = np.zeros((lin["dY"].shape[0], lin["W"].shape[1]))
+    for t in range(brute.shape[0]):
+        for k in range(brute.shape[1]):
+            brute[t, k] = math.fsum(float(lin["dY"][t, n]) * float(lin["W"][n, k]) for n in range(lin["W"].shape[0]))
+    np.testing.assert_array_equal(res["dX"][0], f16(brute))
+    post = O.input_grad(lin["dY"], res["W"][0])
+    assert (post.view(np.uint16) != res["dX"][0].view(np.uint16)).any()
+
+
+# ----------------------------------------------------------------------------- P4 norms
+
+
+def test_p4_bruteforce_gradient_and_norm():
+    rng = np.random.default_rng(5)
+    X = rng.normal(size=(7, 5)).astype(np.float16)
+    dY = rng.normal(size=(7, 3)).astype(np.float16)
+    G = O.linear_grad(X, dY)
+    assert G.shape == (3, 5)
+    tot = []
+    for n in range(3):
+        for k in range(5):
+            v = math.fsum(float(dY[t, n]) * float(X[t, k]) for t in range(7))
+            assert G[n, k] == pytest.approx(v, rel=1e-14, abs=1e-15)
+            tot.append(v * v)
+    assert O.sqnorm(G) == pytest.approx(math.fsum(tot), rel=1e-13)
+
+
+def test_p4_closed_forms():
+    rng = np.random.default_rng(6)
+    x = rng.normal(size=(1, 9)).astype(np.float16)
+    dy = rng.normal(size=(1, 4)).astype(np.float16)
+    nx = math.sqrt(math.fsum(float(v) ** 2 for v in x[0]))
+    ny = math.sqrt(math.fsum(float(v) ** 2 for v in dy[0]))
+    assert math.sqrt(O.sqnorm(O.linear_grad(x, dy))) == pytest.approx(nx * ny, rel=1e-13)   # rank one
+    eye = np.eye(6, dtype=np.float16)
+    dY = rng.normal(size=(6, 4)).astype(np.float16)
+    assert O.sqnorm(O.linear_grad(eye, dY)) == pytest.approx(
+        math.fsum(float(v) ** 2 for v in dY.ravel()), rel=1e-13)
+
+
+def test_p4_gram_identity():
+    rng = np.random.default_rng(8)
+    X = rng.normal(size=(11, 13)).astype(np.float16).astype(np.float64)
+    dY = rng.normal(size=(11, 6)).astype(np.float16).astype(np.float64)
+    gram = 0.0
+    for t in range(11):
+        for u in range(11):
+            gram += float(X[t] @ X[u]) * float(dY[t] @ dY[u])
+    assert O.sqnorm(O.linear_grad(X.astype(np.float16), dY.astype(np.float16))) == pytest.approx(gram, rel=1e-12)
+
+
+def test_global_norm_is_over_all_tensors_and_unscaled():
+    ts = _random_step_tensors(np.random.default_rng(9), S=64.0)
+    res = O.step_materialised(ts, 0.1, 64.0)
+    per = [O.sqnorm(O.tensor_grad(t)) for t in ts]
+    assert res["norm"] == pytest.approx(math.sqrt(math.fsum(per)) / 64.0, rel=1e-14)
+    assert res["norm"] > max(math.sqrt(p) / 64.0 for p in per)     # not a per-tensor norm
+
+
+# ----------------------------------------------------------------------------- P5 printed numbers
+
+
+def test_p5_table1_parameter_and_gradient_memory(golden_dir):
+    from lomo_synth import llama_tensor_list, count_params
+    g = read_golden(os.path.join(golden_dir, "paper_printed_values.txt"))
+    ts = llama_tensor_list(4096, 4096, 11008, 32, 32000, final_norm=True)
+    n = count_params(ts)
+    assert n == 6_738_415_616
+    assert round(n * 2 / 2 ** 30, 2) == g["params_gb"]
+    largest = max(t.n_params for t in ts)
+    assert largest == 32000 * 4096
+    assert round(largest * 2 / 2 ** 30, 2) == g["lomo_grad_gb"]
+    assert g["max_grad_norm"] == 1.0
+
+
+# ----------------------------------------------------------------------------- P6..P8 invariants
+
+
+def test_p6_loss_scale_invariance_is_bit_exact():
+    rng = np.random.default_rng(10)
+    ts = _random_step_tensors(rng, S=64.0)
+    ts2 = [dict(t) for t in ts]
+    for t, t0 in zip(ts2, ts):
+        t["dY"] = (t0["dY"].astype(np.float64) * 2).astype(np.float16)
+        assert np.array_equal(t["dY"].astype(np.float64), t0["dY"].astype(np.float64) * 2)
+    a = O.step_materialised(ts, 0.25, 64.0)
+    b = O.step_materialised(ts2, 0.25, 128.0)
+    assert a["norm"] == b["norm"] and a["flags"] == b["flags"]
+    for x, y in zip(a["W"], b["W"]):
+        np.testing.assert_array_equal(x.view(np.uint16), y.view(np.uint16))
+    for x, y in zip(a["dX"], b["dX"]):       # dX carries the scale: it doubles exactly
+        if x is not None:
+            np.testing.assert_array_equal(x.astype(np.float64) * 2, y.astype(np.float64))
+
+
+def test_p7_clip_invariants():
+    assert O.clip_coef(0.5, 1.0, 1e-6) == 1.0                 # below the threshold: plain SGD
+    assert O.clip_coef(1.0 - 2e-6, 1.0, 1e-6) == 1.0
+    c = O.clip_coef(20.0, 1.0, 1e-6)
+    assert c == pytest.approx(1 / 20.000001, rel=1e-15)
+    assert c * 20.0 == pytest.approx(20.0 / 20.000001, rel=1e-15)   # post-clip norm = c*norm/(norm+eps)
+    assert O.clip_coef(4.0, 2.0, 0.0) == 0.5
+    assert O.grad_norm(3.0 ** 2 * 8.0 ** 2, 8.0) == 3.0
+    # small gradient => unclipped step equals plain SGD
+    X = np.eye(4, dtype=np.float16)
+    dY = (np.full((4, 4), 0.125)).astype(np.float16)
+    W = np.zeros((4, 4), np.float16)
+    res = O.step_materialised([dict(kind="linear", X=X, dY=dY, W=W)], 0.5, 1.0)
+    assert res["clip_coef"] == 1.0
+    np.testing.assert_array_equal(res["W"][0].astype(np.float64), -0.0625 * np.ones((4, 4)))
+
+
+def test_p8_overflow_skips_every_tensor_and_halves_scale():
+    ts = _random_step_tensors(np.random.default_rng(11), with_inf=True)
+    for fn in (O.step_materialised, O.step_fused_order):
+        res = fn(ts, 0.25, 64.0)
+        assert res["overflow"] and res["flags"] == [False, False, True, False]
+        for w, t in zip(res["W"], ts):
+            np.testing.assert_array_equal(w.view(np.uint16), t["W"].view(np.uint16))
+    nan_ts = _random_step_tensors(np.random.default_rng(11))
+    nan_ts[1]["X"][0, 0] = np.nan
+    assert O.step_materialised(nan_ts, 0.25, 64.0)["flags"] == [False, True, False, False]
+    emb_ts = _random_step_tensors(np.random.default_rng(11))
+    emb_ts[3]["dY"][2, 2] = -np.inf
+    assert O.step_materialised(emb_ts, 0.25, 64.0)["flags"] == [False, False, False, True]
+
+
+def test_p8_lr_zero_leaves_weights_and_dx_correct():
+    ts = _random_step_tensors(np.random.default_rng(12))
+    res = O.step_materialised(ts, 0.0, 64.0)
+    for w, t in zip(res["W"], ts):
+        np.testing.assert_array_equal(w.view(np.uint16), t["W"].view(np.uint16))
+    assert res["dX"][0] is not None and np.isfinite(res["dX"][0].astype(np.float64)).all()
+
+
+def test_scaler_state_machine():
+    S, c = 65536.0, 0
+    S, c = O.scaler_step(S, c, 2, True);  assert (S, c) == (32768.0, 0)
+    S, c = O.scaler_step(S, c, 2, False); assert (S, c) == (32768.0, 1)
+    S, c = O.scaler_step(S, c, 2, False); assert (S, c) == (65536.0, 0)
+    S, c = O.scaler_step(S, c, 2, False); assert (S, c) == (65536.0, 1)
+    S, c = O.scaler_step(S, c, 2, True);  assert (S, c) == (32768.0, 0)
+    assert O.scaler_step(1.0, 5, 2, True) == (1.0, 0)
+    assert O.scaler_step(2.0 ** 24, 1, 2, False) == (2.0 ** 24, 0)
+
+
+# ----------------------------------------------------------------------------- P9, P10 reductions
+
+
+def test_p9_embedding_is_onehot_linear():
+    rng = np.random.default_rng(13)
+    T, V, H = 17, 7, 5
+    ids = rng.integers(0, V, size=T).astype(np.int32)
+    dY = rng.normal(size=(T, H)).astype(np.float16)
+    onehot = np.zeros((T, V), np.float16)
+    onehot[np.arange(T), ids] = 1
+    # G_emb [V x H] = onehot^T dY = linear_grad(X=dY, dY=onehot)
+    np.testing.assert_allclose(O.embedding_grad(ids, dY, V), O.linear_grad(dY, onehot), rtol=1e-14, atol=1e-14)
+    same = np.full(T, 3, np.int32)
+    G = O.embedding_grad(same, dY, V)
+    np.testing.assert_allclose(G[3], dY.astype(np.float64).sum(axis=0), rtol=1e-14)
+    assert not G[[0, 1, 2, 4, 5, 6]].any()
+    distinct = rng.permutation(V)[:5].astype(np.int32)
+    G = O.embedding_grad(distinct, dY[:5], V)
+    np.testing.assert_array_equal(G[distinct], dY[:5].astype(np.float64))
+
+
+def test_p9_grouping_bruteforce():
+    rng = np.random.default_rng(14)
+    for T in (0, 1, 2, 33):
+        ids = rng.integers(0, 6, size=T).astype(np.int32)
+        u, off, perm = O.embedding_grouping(ids)
+        pairs = sorted((int(v), t) for t, v in enumerate(ids))
+        assert [t for _, t in pairs] == perm.tolist()
+        uniq = sorted(set(int(v) for v in ids))
+        assert u.tolist() == uniq
+        assert off.tolist() == [sum(1 for v, _ in pairs if v < x) for x in uniq] + [T]
+
+
+def test_untouched_embedding_rows_are_bit_identical():
+    ts = _random_step_tensors(np.random.default_rng(15))
+    res = O.step_materialised(ts, 0.25, 64.0)
+    emb, new = ts[3], res["W"][3]
+    absent = sorted(set(range(9)) - set(int(v) for v in emb["ids"]))
+    assert absent
+    np.testing.assert_array_equal(new[absent].view(np.uint16), emb["W"][absent].view(np.uint16))
+
+
+def test_p10_vector_grad_is_diagonal_of_linear():
+    rng = np.random.default_rng(16)
+    xh = rng.normal(size=(9, 6)).astype(np.float16)
+    dY = rng.normal(size=(9, 6)).astype(np.float16)
+    np.testing.assert_allclose(O.vector_grad(xh, dY), np.diag(O.linear_grad(xh, dY)), rtol=1e-14)
+
+
+def test_p11_clip_by_value_printed_example(golden_dir):
+    g = read_golden(os.path.join(golden_dir, "paper_printed_values.txt"))
+    W = np.zeros(2, np.float16)
+    out = O.sgd_update_clip_value(W, g["clip_value_in"][0], 1.0, 1.0, 1.0)
+    np.testing.assert_array_equal(out, f16(-g["clip_value_out"][0]))
+    out = O.sgd_update_clip_value(W, -4.0 * g["clip_value_in"][0], 1.0, 1.0, 4.0)   # scaled, other sign
+    np.testing.assert_array_equal(out, f16(g["clip_value_out"][0]))
+
+
+# ----------------------------------------------------------------------------- rounding
+
+
+def _all_finite_f16():
+    bits = np.arange(0, 0x7C00, dtype=np.uint16)
+    return bits.view(np.float16).astype(np.float64)        # non-negative finite values, ascending
+
+
+_POS = _all_finite_f16()
+
+
+def _rne_exact(v: float) -> float:
+    """Nearest fp16 to an fp64 value by exact rational comparison; ties to even mantissa."""
+    s = -1.0 if v < 0 or (v == 0 and math.copysign(1, v) < 0) else 1.0
+    a = Fraction(abs(v))
+    if a >= Fraction(65520):
+        return s * math.inf
+    hi = int(np.searchsorted(_POS, float(abs(v)), side="left"))
+    hi = min(hi, len(_POS) - 1)
+    lo = max(hi - 1, 0)
+    dl, dh = a - Fraction(_POS[lo]), Fraction(_POS[hi]) - a
+    if dh < 0:
+        return s * _POS[hi]
+    if dl < dh:
+        return s * _POS[lo]
+    if dh < dl:
+        return s * _POS[hi]
+    return s * (_POS[lo] if lo % 2 == 0 else _POS[hi])
+
+
+def test_round_f16_is_direct_rne():
+    rng = np.random.default_rng(17)
+    vals = np.concatenate([
+        rng.normal(size=400) * 0.02, rng.normal(size=200) * 100, rng.normal(size=200) * 1e-6,
+        [1 + 2.0 ** -11, 1 + 3 * 2.0 ** -11, 1 + 2.0 ** -11 + 2.0 ** -40, 1 + 2.0 ** -11 - 2.0 ** -40,
+         65504.0, 65519.999, 65520.0, -65520.0, 2.0 ** -25, 2.0 ** -25 + 2.0 ** -60, 3 * 2.0 ** -25, 0.0, -0.0],
+    ])
+    got = O.round_f16(vals).astype(np.float64)
+    for v, g in zip(vals, got):
+        assert g == _rne_exact(float(v)), v
+    # the double-rounding hazard: via fp32 this value would become a tie and round down to 1.0
+    hazard = 1 + 2.0 ** -11 + 2.0 ** -40
+    assert float(O.round_f16(np.array([hazard]))[0]) == 1 + 2.0 ** -10
+    assert float(np.float32(hazard).astype(np.float16)) == 1.0
+
+
+def test_update_is_full_precision_rounded_once():
+    """Section 3.3.2: the update runs in full precision; an fp16-arithmetic update differs."""
+    rng = np.random.default_rng(18)
+    W = (rng.normal(size=(32, 32)) * 0.02).astype(np.float16)
+    G = rng.normal(size=(32, 32)) * 40.0
+    lr, coef, S = 1e-2, 0.05, 64.0
+    got = O.sgd_update(W, G, lr, coef, S).astype(np.float64)
+    for idx in [(0, 0), (3, 7), (31, 31), (10, 20)]:
+        exact = Fraction(float(W[idx])) - Fraction(lr) * Fraction(coef) * Fraction(float(G[idx])) / Fraction(S)
+        assert got[idx] == _rne_exact(float(exact))
+    straw = (W - (np.float16(lr) * (G / S * coef).astype(np.float16)).astype(np.float16)).astype(np.float16)
+    assert (straw.view(np.uint16) != O.sgd_update(W, G, lr, coef, S).view(np.uint16)).any()
+
+
+def test_ulp_distance():
+    one = np.array([1.0], np.float16)
+    nxt = (one.view(np.uint16) + 1).view(np.float16)
+    assert O.ulp_distance_f16(one, nxt)[0] == 1
+    assert O.ulp_distance_f16(np.array([0.0], np.float16), np.array([-0.0], np.float16))[0] == 0
+    tiny = np.array([1], np.uint16).view(np.float16)
+    assert O.ulp_distance_f16(tiny, -tiny)[0] == 2
+    assert O.ulp_distance_f16(np.array([2.0], np.float16), np.array([1.0], np.float16))[0] == 1024
+
+
+def test_oracle_does_not_import_the_hip_path():
+    import ast
+    import oracle.lomo_oracle as mod
+    tree = ast.parse(open(mod.__file__).read())
+    names = set()
+    for node in ast.walk(tree):
+        if isinstance(node, ast.Import):
+            names |= {a.name.split(".")[0] for a in node.names}
+        elif isinstance(node, ast.ImportFrom):
+            names.add((node.module or "").split(".")[0])
+    assert names <= {"__future__", "math", "typing", "numpy"}, names
