@@ -1,0 +1,160 @@
+/*
+ * lomo.h -- C ABI of the LOMO fused backward + update hot path for AMD MI355X (gfx950).
+ *
+ * LOMO (LOw-Memory Optimization, arXiv 2306.09782) applies the SGD update of a parameter
+ * inside back-propagation, as soon as that parameter's gradient exists, and never stores
+ * a gradient tensor (paper section 3.2, Algorithm 1).  With global gradient-norm clipping
+ * and a dynamic loss scaler the step takes two passes over the parameters (section 3.3):
+ *
+ *   pass 1  for every parameter, in backward order: form its gradient, add its squared
+ *           norm into one accumulator, raise a flag if it holds inf/NaN, drop it;
+ *   host    norm -> clipping coefficient; overflow -> the step is dropped, scale halved;
+ *   pass 2  for every parameter: dX from the pre-update weights, then gradient and update
+ *           fused: W <- round_fp16( W - lr * clip * G / loss_scale ), computed in fp32.
+ *
+ * Conventions that hold for every call unless stated otherwise
+ *   - lomo_half is IEEE binary16 bits.  All tensors are row-major and live in DEVICE memory.
+ *   - linear tensor: W [N x K] (N out-features, K in-features), X [T x K], dY [T x N],
+ *     dX [T x K]; forward was Y = X W^T; scaled gradient G = dY^T X; dX = dY W.
+ *     dY carries the loss scale; inv_loss_scale = 1 / loss_scale removes it.
+ *   - the caller owns every buffer; the library allocates nothing, keeps no state between
+ *     calls, launches on `stream` (a hipStream_t, NULL = default stream) and never
+ *     synchronises.  `acc` and `overflow_flag` are zeroed by the caller before pass 1.
+ *   - pointers must be 16-byte aligned; K, N and H must be multiples of 8; T >= 0 is free.
+ *     X / dY must not alias W / dX.  Token ids must lie in [0, V).
+ *   - errors are return codes; a call that does not return LOMO_OK has launched nothing.
+ *     Sizes equal to zero are accepted and do nothing.
+ */
+#ifndef LOMO_H
+#define LOMO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LOMO_OK = 0,
+    LOMO_ERR_NULL = 1,       /* a required pointer is NULL                       */
+    LOMO_ERR_SHAPE = 2,      /* negative size, or K/N/H not a multiple of 8      */
+    LOMO_ERR_ALIGN = 3,      /* a pointer is not 16-byte aligned                 */
+    LOMO_ERR_WORKSPACE = 4,  /* workspace NULL or smaller than *_workspace_bytes */
+    LOMO_ERR_LAUNCH = 5      /* the HIP runtime refused a launch                 */
+} lomo_status;
+
+typedef uint16_t lomo_half;
+
+/* Library version (major * 1000 + minor). */
+int lomo_version(void);
+/* Static string for a status code. */
+const char* lomo_status_str(lomo_status s);
+
+/* ---------------------------------------------------------------- pass 1 (section 3.3.1: the
+ * additional backward pass that accumulates every parameter's gradient norm; section 3.3.2: the
+ * same pass identifies overflow). */
+
+/* acc[0] += sum_{n,k} ( sum_t dY[t,n] * X[t,k] )^2  -- squared Frobenius norm of the SCALED
+ * gradient of one linear tensor, without storing it.  fp16 inputs, fp32 MFMA accumulation,
+ * fp32 partial sums per workgroup, one double atomic per workgroup into acc (device double).
+ * overflow_flag (device int32, may be NULL): set to 1 if any gradient element is inf/NaN. */
+lomo_status lomo_wgrad_sqnorm(const lomo_half* X, const lomo_half* dY,
+                              int64_t T, int64_t K, int64_t N,
+                              double* acc, int32_t* overflow_flag, void* stream);
+
+/* Same quantity for an embedding table [V x H] whose rows were gathered by ids [T] (device
+ * int32): the gradient of row v is the sum of the dY rows at the positions holding id v.
+ * ws: device workspace of at least lomo_embedding_workspace_bytes(T, H) bytes. */
+lomo_status lomo_embedding_sqnorm(const int32_t* ids, const lomo_half* dY,
+                                  int64_t T, int64_t H, int64_t V,
+                                  void* ws, size_t ws_bytes,
+                                  double* acc, int32_t* overflow_flag, void* stream);
+
+/* Same quantity for an RMSNorm gain w [H] in y = xhat * w: g[j] = sum_t dY[t,j] * xhat[t,j].
+ * Xhat, dY: [T x H].  ws: at least lomo_vector_workspace_bytes(T, H) bytes. */
+lomo_status lomo_vector_sqnorm(const lomo_half* Xhat, const lomo_half* dY,
+                               int64_t T, int64_t H,
+                               void* ws, size_t ws_bytes,
+                               double* acc, int32_t* overflow_flag, void* stream);
+
+/* ---------------------------------------------------------------- host step between the passes */
+
+/* clip = min(1, max_norm / (sqrt(acc_sqnorm_scaled) / loss_scale + eps)): global-norm clipping
+ * of the unscaled gradient (appendix A: max grad norm 1.0).  Host function, host arguments. */
+double lomo_clip_coef(double acc_sqnorm_scaled, double loss_scale, double max_norm, double eps);
+
+/* Dynamic loss scaler of section 3.3.2 (host function, host pointers): on overflow the scale is
+ * halved and the clean-step counter reset; otherwise the counter is incremented and, when it
+ * reaches growth_interval, the scale is doubled and the counter reset.  Scale stays in [1, 2^24]. */
+void lomo_scaler_step(float* loss_scale, int32_t* clean_steps, int32_t growth_interval, int overflow);
+
+/* out[0] = 1 if any of flags[0..n) is non-zero else 0 (device pointers).  Lets a caller keep one
+ * flag per tensor for diagnosis and still hand a single step flag to pass 2. */
+lomo_status lomo_reduce_flags(const int32_t* flags, int64_t n, int32_t* out, void* stream);
+
+/* ---------------------------------------------------------------- pass 2 (section 3.2, Algorithm 1:
+ * theta_l <- theta_l - lr * g_l as soon as g_l exists; section 3.3.2: in full precision) */
+
+/* One linear tensor: if dX != NULL, dX = round_fp16(dY W) is computed first from the pre-update W;
+ * then W[n,k] <- round_fp16( float(W[n,k]) - s * sum_t dY[t,n] X[t,k] ) with
+ * s = lr * clip_coef * inv_loss_scale formed once in double and rounded to float; the product is
+ * accumulated in fp32 on the matrix cores and the result rounded once (nearest-even) to fp16.
+ * No gradient element is written to memory.  overflow_flag (device, may be NULL): if it holds a
+ * non-zero value when the kernel runs, W is left untouched (dX is still produced). */
+lomo_status lomo_linear_backward_update(const lomo_half* X, const lomo_half* dY, lomo_half* W,
+                                        lomo_half* dX,
+                                        int64_t T, int64_t K, int64_t N,
+                                        float lr, float inv_loss_scale, float clip_coef,
+                                        const int32_t* overflow_flag, void* stream);
+
+/* Embedding table W [V x H]: positions are grouped by id with a stable sort (ties by position),
+ * each touched row's gradient is the fp32 sum of its dY rows in ascending position order
+ * (deterministic), and the row is updated in place as above.  Rows whose id does not occur are
+ * neither read nor written. */
+lomo_status lomo_embedding_update(const int32_t* ids, const lomo_half* dY, lomo_half* W,
+                                  int64_t T, int64_t H, int64_t V,
+                                  float lr, float inv_loss_scale, float clip_coef,
+                                  const int32_t* overflow_flag,
+                                  void* ws, size_t ws_bytes, void* stream);
+
+/* RMSNorm gain w [H]: w[j] <- round_fp16( float(w[j]) - s * sum_t dY[t,j] * xhat[t,j] ). */
+lomo_status lomo_vector_update(const lomo_half* Xhat, const lomo_half* dY, lomo_half* w,
+                               int64_t T, int64_t H,
+                               float lr, float inv_loss_scale, float clip_coef,
+                               const int32_t* overflow_flag,
+                               void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------- helpers */
+
+/* Workspace sizes in bytes (host functions; 0 for T == 0). */
+size_t lomo_embedding_workspace_bytes(int64_t T, int64_t H);
+size_t lomo_vector_workspace_bytes(int64_t T, int64_t H);
+
+/* The grouping that the embedding calls use, exposed so it can be compared bit for bit:
+ * perm [T] = positions sorted by (id, position); unique_ids [<= T] ascending; seg_offsets
+ * [<= T + 1] with segment u = perm[seg_offsets[u] .. seg_offsets[u+1]); n_unique [1].
+ * All outputs are device int32 arrays owned by the caller (capacity T, T, T + 1, 1). */
+lomo_status lomo_embedding_grouping(const int32_t* ids, int64_t T, int64_t V,
+                                    void* ws, size_t ws_bytes,
+                                    int32_t* unique_ids, int32_t* seg_offsets, int32_t* perm,
+                                    int32_t* n_unique, void* stream);
+
+/* ---------------------------------------------------------------- diagnostics */
+
+/* Kernel families for lomo_timing_read. */
+enum { LOMO_KERNEL_WGRAD_UPDATE = 0, LOMO_KERNEL_WGRAD_SQNORM = 1, LOMO_KERNEL_DGRAD = 2,
+       LOMO_KERNEL_EMBEDDING = 3, LOMO_KERNEL_VECTOR = 4, LOMO_KERNEL_FAMILIES = 5 };
+
+/* Per-kernel timing for benchmarks: while enabled, each launch of a kernel family is bracketed
+ * by two HIP events recorded on the launch stream (the only host-side state the library keeps;
+ * events are created on first use and reused).  Enabling or disabling resets the counters.
+ * lomo_timing_read waits for the recorded events of one family and returns the summed kernel
+ * time in milliseconds and the number of timed launches (host pointers). */
+lomo_status lomo_timing_enable(int on);
+lomo_status lomo_timing_read(int family, double* total_ms, int64_t* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOMO_H */

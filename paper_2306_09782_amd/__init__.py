@@ -1,0 +1,15 @@
+"""LOMO fused backward + update hot path for AMD MI355X: thin Python binding over liblomo.so.
+
+The arithmetic lives in hand-written HIP kernels behind the C ABI declared in include/lomo.h;
+this package only marshals arguments (torch tensors -> device pointers, sizes, stream).
+There is no CPU fallback: without the built library every call raises.
+"""
+from .binding import (LomoError, library_path, load_library, lomo_version, lomo_status_str, lomo_wgrad_sqnorm,
+                      lomo_embedding_sqnorm, lomo_vector_sqnorm, lomo_clip_coef, lomo_scaler_step,
+                      lomo_reduce_flags, lomo_linear_backward_update, lomo_embedding_update,
+                      lomo_vector_update, lomo_embedding_workspace_bytes, lomo_vector_workspace_bytes,
+                      lomo_embedding_grouping, lomo_timing_enable, lomo_timing_read, KERNEL_FAMILIES,
+                      EXPORTED_SYMBOLS)
+
+__all__ = [n for n in dir() if n.startswith("lomo_")] + ["LomoError", "library_path", "load_library",
+                                                         "EXPORTED_SYMBOLS"]

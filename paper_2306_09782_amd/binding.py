@@ -1,0 +1,176 @@
+"""ctypes binding: one Python function per C entry point of include/lomo.h, same names.
+
+Tensors are torch CUDA(HIP) tensors used purely as device memory; shapes supply T, K, N, H, V.
+``stream`` is a torch.cuda.Stream (or None for the current stream).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import c_void_p, c_int64, c_int32, c_float, c_double, c_size_t, c_int, c_char_p, POINTER
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+EXPORTED_SYMBOLS = (
+    "lomo_version", "lomo_status_str", "lomo_wgrad_sqnorm", "lomo_embedding_sqnorm", "lomo_vector_sqnorm",
+    "lomo_clip_coef", "lomo_scaler_step", "lomo_reduce_flags", "lomo_linear_backward_update",
+    "lomo_embedding_update", "lomo_vector_update", "lomo_embedding_workspace_bytes",
+    "lomo_vector_workspace_bytes", "lomo_embedding_grouping", "lomo_timing_enable", "lomo_timing_read",
+)
+
+
+class LomoError(RuntimeError):
+    pass
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "lib", "liblomo.so")
+
+
+def load_library():
+    """Load liblomo.so (built in-tree by ``python -m paper_2306_09782_amd.build``). No fallback."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise LomoError(f"{path} is missing: build it with `python paper_2306_09782_amd/build.py` "
+                        "(there is no CPU fallback)")
+    lib = ctypes.CDLL(path)
+    P, I64 = c_void_p, c_int64
+    sig = {
+        "lomo_version": (c_int, []),
+        "lomo_status_str": (c_char_p, [c_int]),
+        "lomo_wgrad_sqnorm": (c_int, [P, P, I64, I64, I64, P, P, P]),
+        "lomo_embedding_sqnorm": (c_int, [P, P, I64, I64, I64, P, c_size_t, P, P, P]),
+        "lomo_vector_sqnorm": (c_int, [P, P, I64, I64, P, c_size_t, P, P, P]),
+        "lomo_clip_coef": (c_double, [c_double, c_double, c_double, c_double]),
+        "lomo_scaler_step": (None, [POINTER(c_float), POINTER(c_int32), c_int32, c_int]),
+        "lomo_reduce_flags": (c_int, [P, I64, P, P]),
+        "lomo_linear_backward_update": (c_int, [P, P, P, P, I64, I64, I64, c_float, c_float, c_float, P, P]),
+        "lomo_embedding_update": (c_int, [P, P, P, I64, I64, I64, c_float, c_float, c_float, P, P, c_size_t, P]),
+        "lomo_vector_update": (c_int, [P, P, P, I64, I64, c_float, c_float, c_float, P, P, c_size_t, P]),
+        "lomo_embedding_workspace_bytes": (c_size_t, [I64, I64]),
+        "lomo_vector_workspace_bytes": (c_size_t, [I64, I64]),
+        "lomo_embedding_grouping": (c_int, [P, I64, I64, P, c_size_t, P, P, P, P, P]),
+        "lomo_timing_enable": (c_int, [c_int]),
+        "lomo_timing_read": (c_int, [c_int, POINTER(c_double), POINTER(c_int64)]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    _LIB = lib
+    return lib
+
+
+def _ptr(t):
+    return None if t is None else c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return c_void_p(stream.cuda_stream)
+
+
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def _check(code):
+    if code != 0:
+        raise LomoError(f"lomo status {code}: {load_library().lomo_status_str(code).decode()}")
+
+
+def lomo_version() -> int:
+    return load_library().lomo_version()
+
+
+def lomo_status_str(code: int) -> str:
+    return load_library().lomo_status_str(code).decode()
+
+
+def lomo_wgrad_sqnorm(X, dY, acc, overflow_flag=None, stream=None):
+    T, K = X.shape
+    N = dY.shape[1]
+    assert dY.shape[0] == T
+    _check(load_library().lomo_wgrad_sqnorm(_ptr(X), _ptr(dY), T, K, N, _ptr(acc), _ptr(overflow_flag), _stream(stream)))
+
+
+def lomo_embedding_sqnorm(ids, dY, V, ws, acc, overflow_flag=None, stream=None):
+    T, H = dY.shape
+    _check(load_library().lomo_embedding_sqnorm(_ptr(ids), _ptr(dY), T, H, V, _ptr(ws), _nbytes(ws), _ptr(acc),
+                                                _ptr(overflow_flag), _stream(stream)))
+
+
+def lomo_vector_sqnorm(Xhat, dY, ws, acc, overflow_flag=None, stream=None):
+    T, H = dY.shape
+    _check(load_library().lomo_vector_sqnorm(_ptr(Xhat), _ptr(dY), T, H, _ptr(ws), _nbytes(ws), _ptr(acc),
+                                             _ptr(overflow_flag), _stream(stream)))
+
+
+def lomo_clip_coef(acc_sqnorm_scaled: float, loss_scale: float, max_norm: float = 1.0, eps: float = 1e-6) -> float:
+    return load_library().lomo_clip_coef(acc_sqnorm_scaled, loss_scale, max_norm, eps)
+
+
+def lomo_scaler_step(loss_scale: float, clean_steps: int, growth_interval: int, overflow: bool):
+    s, c = c_float(loss_scale), c_int32(clean_steps)
+    load_library().lomo_scaler_step(ctypes.byref(s), ctypes.byref(c), growth_interval, int(bool(overflow)))
+    return s.value, c.value
+
+
+def lomo_reduce_flags(flags, out, stream=None):
+    _check(load_library().lomo_reduce_flags(_ptr(flags), flags.numel(), _ptr(out), _stream(stream)))
+
+
+def lomo_linear_backward_update(X, dY, W, dX, lr, inv_loss_scale, clip_coef, overflow_flag=None, stream=None):
+    T, K = X.shape
+    N = dY.shape[1]
+    assert dY.shape[0] == T and tuple(W.shape) == (N, K) and (dX is None or tuple(dX.shape) == (T, K))
+    _check(load_library().lomo_linear_backward_update(_ptr(X), _ptr(dY), _ptr(W), _ptr(dX), T, K, N, lr, inv_loss_scale,
+                                                      clip_coef, _ptr(overflow_flag), _stream(stream)))
+
+
+def lomo_embedding_update(ids, dY, W, lr, inv_loss_scale, clip_coef, ws, overflow_flag=None, stream=None):
+    T, H = dY.shape
+    V = W.shape[0]
+    assert W.shape[1] == H
+    _check(load_library().lomo_embedding_update(_ptr(ids), _ptr(dY), _ptr(W), T, H, V, lr, inv_loss_scale, clip_coef,
+                                                _ptr(overflow_flag), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def lomo_vector_update(Xhat, dY, w, lr, inv_loss_scale, clip_coef, ws, overflow_flag=None, stream=None):
+    T, H = dY.shape
+    assert w.numel() == H
+    _check(load_library().lomo_vector_update(_ptr(Xhat), _ptr(dY), _ptr(w), T, H, lr, inv_loss_scale, clip_coef,
+                                             _ptr(overflow_flag), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def lomo_embedding_workspace_bytes(T: int, H: int) -> int:
+    return load_library().lomo_embedding_workspace_bytes(T, H)
+
+
+def lomo_vector_workspace_bytes(T: int, H: int) -> int:
+    return load_library().lomo_vector_workspace_bytes(T, H)
+
+
+def lomo_embedding_grouping(ids, V, ws, unique_ids, seg_offsets, perm, n_unique, stream=None):
+    T = ids.numel()
+    _check(load_library().lomo_embedding_grouping(_ptr(ids), T, V, _ptr(ws), _nbytes(ws), _ptr(unique_ids),
+                                                  _ptr(seg_offsets), _ptr(perm), _ptr(n_unique), _stream(stream)))
+
+
+KERNEL_FAMILIES = ("wgrad_update", "wgrad_sqnorm", "dgrad", "embedding", "vector")
+
+
+def lomo_timing_enable(on: bool):
+    _check(load_library().lomo_timing_enable(int(bool(on))))
+
+
+def lomo_timing_read(family: int):
+    """(total kernel milliseconds, timed launches) of one kernel family since timing was enabled."""
+    ms, n = c_double(0.0), c_int64(0)
+    _check(load_library().lomo_timing_read(family, ctypes.byref(ms), ctypes.byref(n)))
+    return ms.value, n.value

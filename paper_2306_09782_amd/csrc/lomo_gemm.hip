@@ -1,0 +1,307 @@
+// MFMA contraction kernels of the LOMO hot path for gfx950 (CDNA4, wave64).
+//
+// One kernel template serves the three dense steps of a linear tensor:
+//   * fused wgrad + SGD update (paper section 3.2, Algorithm 1: theta <- theta - lr * g, the
+//     gradient never leaves the accumulators; section 3.3.2: update arithmetic in fp32),
+//   * wgrad squared norm + overflow detection (section 3.3.1 / 3.3.2, first backward pass),
+//   * dgrad dX = dY W for the continuing back-propagation.
+//
+// Layout.  The output tile is Out[n][m] with m contiguous in memory.  Operand "A" supplies the m
+// index and is always stored with the contraction index as its slow dimension (X[t][k] for wgrad,
+// W[n][k] for dgrad), so it has to be transposed on its way to the matrix cores: a lane fetches
+// dwords (two neighbouring m) from eight consecutive contraction rows, repacks them with byte
+// permutes into two 16-byte runs along the contraction, and stores those to LDS in [m][c] order.
+// Operand "B" supplies n and is transposed the same way (dY[t][n] for wgrad) or copied straight
+// (dY[t][n] for dgrad, where n_out is the contraction).  MFMA 32x32x16 f16 then reads 16-byte
+// fragments from LDS rows of 80 bytes (64 + 16 pad), which makes ds_read_b128 conflict free.
+// With A on the MFMA row side, each lane's four consecutive accumulator registers are four
+// consecutive m, i.e. an 8-byte run of W / dX: the read-modify-write epilogue is vectorised.
+#include "lomo_kernels.h"
+
+#include <hip/hip_fp16.h>
+
+namespace lomo {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int NT = 256;        // threads per workgroup: 4 waves in a 2 x 2 arrangement
+constexpr int BK = 32;         // contraction slice per pipeline stage
+constexpr int LROW = BK + 8;   // halves per LDS row
+
+// ---- global -> registers ------------------------------------------------------------------
+
+// Contraction-strided operand: tile of BK rows x BX columns starting at `base` (row stride ld).
+// Item = (column pair p, row octet q): eight dword loads down the rows.
+template <int BX, bool GUARD>
+__device__ __forceinline__ void load_strided(const uint16_t* __restrict__ base, int64_t ld, int c_rem, int x_rem,
+                                             uint32_t (&r)[BX / 128][8], int tid) {
+#pragma unroll
+    for (int it = 0; it < BX / 128; ++it) {
+        const int item = tid + it * NT;
+        const int p = item % (BX / 2);
+        const int q = item / (BX / 2);
+        const uint16_t* src = base + (int64_t)(8 * q) * ld + 2 * p;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (!GUARD || (8 * q + i < c_rem && 2 * p < x_rem))
+                r[it][i] = *reinterpret_cast<const uint32_t*>(src + (int64_t)i * ld);
+            else
+                r[it][i] = 0u;
+        }
+    }
+}
+
+template <int BX>
+__device__ __forceinline__ void store_strided(uint16_t* __restrict__ lds, const uint32_t (&r)[BX / 128][8], int tid) {
+#pragma unroll
+    for (int it = 0; it < BX / 128; ++it) {
+        const int item = tid + it * NT;
+        const int p = item % (BX / 2);
+        const int q = item / (BX / 2);
+        u32x4 lo, hi;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            lo[j] = __builtin_amdgcn_perm(r[it][2 * j + 1], r[it][2 * j], 0x05040100u);
+            hi[j] = __builtin_amdgcn_perm(r[it][2 * j + 1], r[it][2 * j], 0x07060302u);
+        }
+        *reinterpret_cast<u32x4*>(lds + (2 * p) * LROW + 8 * q) = lo;
+        *reinterpret_cast<u32x4*>(lds + (2 * p + 1) * LROW + 8 * q) = hi;
+    }
+}
+
+// Contraction-contiguous operand: tile of BX rows x BK halves, 16-byte chunks.
+template <int BX, bool GUARD>
+__device__ __forceinline__ void load_contig(const uint16_t* __restrict__ base, int64_t ld, int c_rem, int x_rem,
+                                            u32x4 (&r)[BX / 64], int tid) {
+#pragma unroll
+    for (int it = 0; it < BX / 64; ++it) {
+        const int item = tid + it * NT;
+        const int n = item / (BK / 8);
+        const int q = item % (BK / 8);
+        if (!GUARD || (n < x_rem && 8 * q < c_rem))
+            r[it] = *reinterpret_cast<const u32x4*>(base + (int64_t)n * ld + 8 * q);
+        else
+            r[it] = u32x4{0u, 0u, 0u, 0u};
+    }
+}
+
+template <int BX>
+__device__ __forceinline__ void store_contig(uint16_t* __restrict__ lds, const u32x4 (&r)[BX / 64], int tid) {
+#pragma unroll
+    for (int it = 0; it < BX / 64; ++it) {
+        const int item = tid + it * NT;
+        const int n = item / (BK / 8);
+        const int q = item % (BK / 8);
+        *reinterpret_cast<u32x4*>(lds + n * LROW + 8 * q) = r[it];
+    }
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// ---- the kernel ---------------------------------------------------------------------------
+
+template <int BM, int BN, bool B_STRIDED, int EPI>
+__global__ __launch_bounds__(NT) void lomo_contract_kernel(GemmArgs g) {
+    constexpr int TM = BM / 64, TN = BN / 64;          // 32x32 MFMA tiles per wave
+    constexpr int STAGE = (BM + BN) * LROW;            // halves per LDS stage
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+
+    if (EPI == EPI_UPDATE && g.flag_in != nullptr && *g.flag_in != 0) {
+        return;   // overflow seen in pass 1: the step is dropped, W stays as it is
+    }
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave & 1, wn = wave >> 1;
+    const int l32 = lane & 31, lh = lane >> 5;
+
+    const int tiles_m = (int)((g.M + BM - 1) / BM);
+    const int64_t m0 = (int64_t)(blockIdx.x % tiles_m) * BM;
+    const int64_t n0 = (int64_t)(blockIdx.x / tiles_m) * BN;
+    const int m_rem = (int)((g.M - m0 < BM) ? (g.M - m0) : BM);
+    const int n_rem = (int)((g.Nn - n0 < BN) ? (g.Nn - n0) : BN);
+    const bool full_mn = (m_rem == BM) && (n_rem == BN);
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const uint16_t* pa = g.A + m0;                                           // (c = 0, m0)
+    const uint16_t* pb = B_STRIDED ? (g.B + n0) : (g.B + n0 * g.ldb);        // (c = 0, n0)
+    const int64_t a_step = (int64_t)BK * g.lda;
+    const int64_t b_step = B_STRIDED ? (int64_t)BK * g.ldb : (int64_t)BK;
+
+    uint32_t ra[BM / 128][8];
+    uint32_t rbs[B_STRIDED ? BN / 128 : 1][8];
+    u32x4 rbc[B_STRIDED ? 1 : BN / 64];
+
+    const int KT = (int)((g.C + BK - 1) / BK);
+
+    auto fetch = [&](int kt) {
+        const int c_rem = (int)(g.C - (int64_t)kt * BK);
+        const bool guard = !full_mn || c_rem < BK;
+        const uint16_t* a = pa + (int64_t)kt * a_step;
+        const uint16_t* b = pb + (int64_t)kt * b_step;
+        if (!guard) {
+            load_strided<BM, false>(a, g.lda, c_rem, m_rem, ra, tid);
+            if constexpr (B_STRIDED) load_strided<BN, false>(b, g.ldb, c_rem, n_rem, rbs, tid);
+            else load_contig<BN, false>(b, g.ldb, c_rem, n_rem, rbc, tid);
+        } else {
+            load_strided<BM, true>(a, g.lda, c_rem, m_rem, ra, tid);
+            if constexpr (B_STRIDED) load_strided<BN, true>(b, g.ldb, c_rem, n_rem, rbs, tid);
+            else load_contig<BN, true>(b, g.ldb, c_rem, n_rem, rbc, tid);
+        }
+    };
+    auto stash = [&](int buf) {
+        uint16_t* as = smem + buf * STAGE;
+        uint16_t* bs = as + BM * LROW;
+        store_strided<BM>(as, ra, tid);
+        if constexpr (B_STRIDED) store_strided<BN>(bs, rbs, tid);
+        else store_contig<BN>(bs, rbc, tid);
+    };
+
+    if (KT > 0) {
+        fetch(0);
+        stash(0);
+    }
+    __syncthreads();
+
+    for (int kt = 0; kt < KT; ++kt) {
+        const bool more = kt + 1 < KT;
+        if (more) fetch(kt + 1);
+
+        const uint16_t* as = smem + (kt & 1) * STAGE + (wm * (BM / 2) + l32) * LROW + 8 * lh;
+        const uint16_t* bs = smem + (kt & 1) * STAGE + BM * LROW + (wn * (BN / 2) + l32) * LROW + 8 * lh;
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            half8 a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const half8*>(as + i * 32 * LROW + kk * 16);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const half8*>(bs + j * 32 * LROW + kk * 16);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+
+        if (more) stash((kt + 1) & 1);
+        __syncthreads();
+    }
+
+    // ---- epilogues.  Lane (l32, lh) of MFMA tile (i, j) holds, in register 4*q4 + e,
+    //      the element  m = 32 i + 8 q4 + 4 lh + e,  n = 32 j + l32  of the wave's sub-tile.
+    if constexpr (EPI == EPI_SQNORM) {
+        float sum = 0.f;
+        uint32_t worst = 0u;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float v = acc[i][j][r];
+                    sum = fmaf(v, v, sum);
+                    const uint32_t mag = __float_as_uint(v) & 0x7fffffffu;
+                    worst = mag > worst ? mag : worst;
+                }
+        sum = wave_sum(sum);
+        const bool bad = __any(worst >= 0x7f800000u);
+        float* red = reinterpret_cast<float*>(smem);   // main loop is over: LDS is free
+        int* redflag = reinterpret_cast<int*>(smem) + 8;
+        if (lane == 0) {
+            red[wave] = sum;
+            redflag[wave] = bad ? 1 : 0;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            const float total = (red[0] + red[1]) + (red[2] + red[3]);
+            atomicAdd(g.acc, (double)total);
+            if (g.flag_out != nullptr && (redflag[0] | redflag[1] | redflag[2] | redflag[3])) atomicOr(g.flag_out, 1);
+        }
+    } else {
+        const float s = g.s;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int nl = wn * (BN / 2) + 32 * j + l32;
+            if (nl >= n_rem) continue;
+            uint16_t* row = g.Out + (n0 + nl) * g.ldo + m0;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const int ml = wm * (BM / 2) + 32 * i + 8 * q4 + 4 * lh;
+                    if (ml >= m_rem) continue;
+                    half4* p = reinterpret_cast<half4*>(row + ml);
+                    half4 out;
+                    if constexpr (EPI == EPI_UPDATE) {
+                        const half4 w = *p;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            out[e] = (_Float16)fmaf(-s, acc[i][j][4 * q4 + e], (float)w[e]);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) out[e] = (_Float16)acc[i][j][4 * q4 + e];
+                    }
+                    *p = out;
+                }
+            }
+        }
+    }
+}
+
+// ---- host side ----------------------------------------------------------------------------
+
+template <int BM, int BN, bool B_STRIDED, int EPI>
+static hipError_t launch_one(const GemmArgs& a, hipStream_t st) {
+    if (a.M <= 0 || a.Nn <= 0) return hipSuccess;
+    constexpr size_t lds = 2u * (BM + BN) * LROW * sizeof(uint16_t);
+    auto kern = lomo_contract_kernel<BM, BN, B_STRIDED, EPI>;
+    static bool configured = false;   // benign race: the attribute call is idempotent
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int64_t tiles = ((a.M + BM - 1) / BM) * ((a.Nn + BN - 1) / BN);
+    if (tiles > 0x7fffffff) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(NT), lds, st, a);
+    return hipGetLastError();
+}
+
+// Tile choice: 256 x 256 when that still gives every CU at least one tile, else 128 x 128.
+static inline bool use_big_tiles(int64_t M, int64_t Nn) {
+    const int64_t big = ((M + 255) / 256) * ((Nn + 255) / 256);
+    return big >= 192;
+}
+
+hipError_t launch_wgrad_update(const GemmArgs& a, hipStream_t st) {
+    ScopedTiming t(LOMO_KERNEL_WGRAD_UPDATE, st);
+    return use_big_tiles(a.M, a.Nn) ? launch_one<256, 256, true, EPI_UPDATE>(a, st)
+                                    : launch_one<128, 128, true, EPI_UPDATE>(a, st);
+}
+hipError_t launch_wgrad_sqnorm(const GemmArgs& a, hipStream_t st) {
+    ScopedTiming t(LOMO_KERNEL_WGRAD_SQNORM, st);
+    return use_big_tiles(a.M, a.Nn) ? launch_one<256, 256, true, EPI_SQNORM>(a, st)
+                                    : launch_one<128, 128, true, EPI_SQNORM>(a, st);
+}
+hipError_t launch_dgrad(const GemmArgs& a, hipStream_t st) {
+    ScopedTiming t(LOMO_KERNEL_DGRAD, st);
+    return use_big_tiles(a.M, a.Nn) ? launch_one<256, 256, false, EPI_STORE>(a, st)
+                                    : launch_one<128, 128, false, EPI_STORE>(a, st);
+}
+
+}  // namespace lomo

@@ -1,0 +1,74 @@
+// Internal launch interface between the C-ABI shim and the HIP kernels (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lomo.h"
+
+namespace lomo {
+
+// Which epilogue the contraction kernel ends with.
+enum Epilogue : int {
+    EPI_UPDATE = 0,   // W <- rne16(W - s * acc)            (fused wgrad + SGD update)
+    EPI_SQNORM = 1,   // acc_out += sum acc^2, overflow flag (norm pass)
+    EPI_STORE = 2     // Out <- rne16(acc)                  (dgrad)
+};
+
+// One contraction  Out[n][m] (+)= sum_c A(c, m) * B(c, n).
+//   A is always "contraction-strided":   A[c * lda + m]
+//   B is contraction-strided  (B[c * ldb + n])  or contraction-contiguous (B[n * ldb + c]).
+// wgrad: A = X, B = dY (strided), Out = W;   M = K_in, Nn = N_out, C = T.
+// dgrad: A = W, B = dY (contiguous), Out = dX; M = K_in, Nn = T, C = N_out.
+struct GemmArgs {
+    const uint16_t* A;
+    const uint16_t* B;
+    uint16_t* Out;
+    int64_t M, Nn, C;
+    int64_t lda, ldb, ldo;
+    float s;                 // update step (EPI_UPDATE)
+    double* acc;             // squared-norm accumulator (EPI_SQNORM)
+    int32_t* flag_out;       // overflow flag to raise (EPI_SQNORM), may be null
+    const int32_t* flag_in;  // overflow flag to honour (EPI_UPDATE), may be null
+};
+
+hipError_t launch_wgrad_update(const GemmArgs& a, hipStream_t st);
+hipError_t launch_wgrad_sqnorm(const GemmArgs& a, hipStream_t st);
+hipError_t launch_dgrad(const GemmArgs& a, hipStream_t st);
+
+// Row-wise kernels -------------------------------------------------------------------------
+struct EmbeddingWs {          // carved out of the caller's workspace
+    uint64_t* keys;           // [Tpad] (id << 32 | position), padded with all-ones
+    int32_t* perm;            // [T]
+    int32_t* unique_ids;      // [T]
+    int32_t* seg_offsets;     // [T + 1]
+    int32_t* n_unique;        // [1]
+};
+size_t embedding_ws_bytes(int64_t T, int64_t H);
+EmbeddingWs carve_embedding_ws(void* ws, int64_t T);
+hipError_t launch_embedding_grouping(const int32_t* ids, int64_t T, const EmbeddingWs& w, hipStream_t st);
+// mode 0: squared norm into acc (+ flag_out); mode 1: in-place row update honouring flag_in.
+hipError_t launch_embedding_rows(const uint16_t* dY, uint16_t* W, int64_t T, int64_t H, const EmbeddingWs& w,
+                                 int mode, float s, double* acc, int32_t* flag_out, const int32_t* flag_in,
+                                 hipStream_t st);
+
+size_t vector_ws_bytes(int64_t T, int64_t H);
+hipError_t launch_vector(const uint16_t* Xhat, const uint16_t* dY, uint16_t* w, int64_t T, int64_t H,
+                         void* ws, int mode, float s, double* acc, int32_t* flag_out, const int32_t* flag_in,
+                         hipStream_t st);
+
+// Event timing (lomo_timing.hip): begin returns true iff a start event was recorded.
+bool timing_begin(int family, hipStream_t st);
+void timing_end(int family, hipStream_t st);
+struct ScopedTiming {
+    int family;
+    hipStream_t st;
+    bool on;
+    ScopedTiming(int f, hipStream_t s) : family(f), st(s), on(timing_begin(f, s)) {}
+    ~ScopedTiming() {
+        if (on) timing_end(family, st);
+    }
+};
+
+hipError_t launch_reduce_flags(const int32_t* flags, int64_t n, int32_t* out, hipStream_t st);
+
+}  // namespace lomo

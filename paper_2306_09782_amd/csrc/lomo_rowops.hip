@@ -1,0 +1,381 @@
+// Bandwidth-bound kernels of the LOMO hot path for gfx950: embedding rows and RMSNorm gains.
+//
+// Every parameter gets its gradient and its update inside back-propagation (paper section 3.2);
+// for an embedding table only the rows whose token occurs in the batch have a gradient, and for a
+// gain vector the gradient is a column reduction.  Both run in two modes: squared norm + overflow
+// detection (first pass, section 3.3) and in-place fp32 update rounded once to fp16 (second pass).
+// All reductions have a fixed order, so results are bit-reproducible from run to run.
+#include "lomo_kernels.h"
+
+namespace lomo {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+
+static inline int64_t next_pow2(int64_t v) {
+    int64_t p = 1;
+    while (p < v) p <<= 1;
+    return p;
+}
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ------------------------------------------------------------------------------------------
+// Embedding grouping: bitonic sort of unique 64-bit keys (id << 32 | position).  Unique keys make
+// any correct sort stable by construction: ties between equal ids are broken by position.
+// ------------------------------------------------------------------------------------------
+
+constexpr int SORT_NT = 1024;
+constexpr int SORT_CHUNK = 8192;   // keys sorted per workgroup in LDS (64 KB)
+
+__global__ void emb_make_keys(const int32_t* __restrict__ ids, int64_t T, int64_t Tpad, uint64_t* __restrict__ keys) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= Tpad) return;
+    keys[i] = (i < T) ? (((uint64_t)(uint32_t)ids[i] << 32) | (uint64_t)(uint32_t)i) : ~0ull;
+}
+
+__device__ __forceinline__ void cmpx(uint64_t& a, uint64_t& b, bool up) {
+    if ((a > b) == up) {
+        const uint64_t t = a;
+        a = b;
+        b = t;
+    }
+}
+
+// Runs, inside LDS, the stages j = j_start .. 1 of merge step k for k = k_first .. k_last.
+// Each workgroup owns SORT_CHUNK (or fewer) consecutive keys.
+__global__ __launch_bounds__(SORT_NT) void emb_bitonic_local(uint64_t* __restrict__ keys, int64_t Tpad,
+                                                             int64_t k_first, int64_t k_last) {
+    __shared__ uint64_t s[SORT_CHUNK];
+    const int64_t chunk = Tpad < SORT_CHUNK ? Tpad : SORT_CHUNK;
+    const int64_t base = (int64_t)blockIdx.x * chunk;
+    for (int64_t i = threadIdx.x; i < chunk; i += SORT_NT) s[i] = keys[base + i];
+    __syncthreads();
+    for (int64_t k = k_first; k <= k_last; k <<= 1) {
+        int64_t j = (k >> 1) < chunk ? (k >> 1) : (chunk >> 1);
+        for (; j > 0; j >>= 1) {
+            for (int64_t pidx = threadIdx.x; pidx < (chunk >> 1); pidx += SORT_NT) {
+                const int64_t lo = ((pidx & ~(j - 1)) << 1) | (pidx & (j - 1));
+                const bool up = (((base + lo) & k) == 0);
+                uint64_t a = s[lo], b = s[lo + j];
+                cmpx(a, b, up);
+                s[lo] = a;
+                s[lo + j] = b;
+            }
+            __syncthreads();
+        }
+    }
+    for (int64_t i = threadIdx.x; i < chunk; i += SORT_NT) keys[base + i] = s[i];
+}
+
+// One global compare-exchange stage (j >= SORT_CHUNK).
+__global__ void emb_bitonic_global(uint64_t* __restrict__ keys, int64_t Tpad, int64_t k, int64_t j) {
+    const int64_t pidx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (pidx >= (Tpad >> 1)) return;
+    const int64_t lo = ((pidx & ~(j - 1)) << 1) | (pidx & (j - 1));
+    const bool up = ((lo & k) == 0);
+    uint64_t a = keys[lo], b = keys[lo + j];
+    cmpx(a, b, up);
+    keys[lo] = a;
+    keys[lo + j] = b;
+}
+
+// Head flags + exclusive scan over the sorted keys: one workgroup walks the array.
+__global__ __launch_bounds__(SORT_NT) void emb_segments(const uint64_t* __restrict__ keys, int64_t T,
+                                                        int32_t* __restrict__ perm, int32_t* __restrict__ unique_ids,
+                                                        int32_t* __restrict__ seg_offsets, int32_t* __restrict__ n_unique) {
+    __shared__ int32_t wsum[SORT_NT / 64];
+    __shared__ int32_t carry_s;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) carry_s = 0;
+    __syncthreads();
+    for (int64_t start = 0; start < T; start += SORT_NT) {
+        const int64_t i = start + tid;
+        int32_t head = 0;
+        uint32_t id = 0;
+        if (i < T) {
+            const uint64_t key = keys[i];
+            id = (uint32_t)(key >> 32);
+            perm[i] = (int32_t)(uint32_t)key;
+            head = (i == 0) || ((uint32_t)(keys[i - 1] >> 32) != id);
+        }
+        // inclusive scan inside the wave, then across waves
+        int32_t v = head;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int32_t o = __shfl_up(v, off, 64);
+            if (lane >= off) v += o;
+        }
+        if (lane == 63) wsum[wave] = v;
+        __syncthreads();
+        int32_t before = 0;
+        for (int w = 0; w < wave; ++w) before += wsum[w];
+        const int32_t carry = carry_s;
+        const int32_t excl = carry + before + v - head;
+        if (head) {
+            unique_ids[excl] = (int32_t)id;
+            seg_offsets[excl] = (int32_t)i;
+        }
+        __syncthreads();
+        if (tid == SORT_NT - 1) carry_s = carry + before + v;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        n_unique[0] = carry_s;
+        seg_offsets[carry_s] = (int32_t)T;
+    }
+}
+
+size_t embedding_ws_bytes(int64_t T, int64_t /*H*/) {
+    if (T <= 0) return 0;
+    const int64_t Tpad = next_pow2(T);
+    size_t b = align_up((size_t)Tpad * 8, 256);
+    b += align_up((size_t)T * 4, 256) * 2;         // perm, unique_ids
+    b += align_up((size_t)(T + 1) * 4, 256);       // seg_offsets
+    b += 256;                                      // n_unique
+    return b;
+}
+
+EmbeddingWs carve_embedding_ws(void* ws, int64_t T) {
+    EmbeddingWs w;
+    char* p = static_cast<char*>(ws);
+    const int64_t Tpad = next_pow2(T);
+    w.keys = reinterpret_cast<uint64_t*>(p);
+    p += align_up((size_t)Tpad * 8, 256);
+    w.perm = reinterpret_cast<int32_t*>(p);
+    p += align_up((size_t)T * 4, 256);
+    w.unique_ids = reinterpret_cast<int32_t*>(p);
+    p += align_up((size_t)T * 4, 256);
+    w.seg_offsets = reinterpret_cast<int32_t*>(p);
+    p += align_up((size_t)(T + 1) * 4, 256);
+    w.n_unique = reinterpret_cast<int32_t*>(p);
+    return w;
+}
+
+hipError_t launch_embedding_grouping(const int32_t* ids, int64_t T, const EmbeddingWs& w, hipStream_t st) {
+    if (T == 0) {   // empty batch: zero segments
+        hipLaunchKernelGGL(emb_segments, dim3(1), dim3(SORT_NT), 0, st, w.keys, T, w.perm, w.unique_ids, w.seg_offsets,
+                           w.n_unique);
+        return hipGetLastError();
+    }
+    const int64_t Tpad = next_pow2(T);
+    hipLaunchKernelGGL(emb_make_keys, dim3((unsigned)((Tpad + 255) / 256)), dim3(256), 0, st, ids, T, Tpad, w.keys);
+    const int64_t chunk = Tpad < SORT_CHUNK ? Tpad : SORT_CHUNK;
+    const unsigned nblk = (unsigned)(Tpad / chunk);
+    if (Tpad >= 2) {
+        hipLaunchKernelGGL(emb_bitonic_local, dim3(nblk), dim3(SORT_NT), 0, st, w.keys, Tpad, (int64_t)2, chunk);
+        for (int64_t k = chunk << 1; k <= Tpad; k <<= 1) {
+            for (int64_t j = k >> 1; j >= chunk; j >>= 1)
+                hipLaunchKernelGGL(emb_bitonic_global, dim3((unsigned)(((Tpad >> 1) + 255) / 256)), dim3(256), 0, st,
+                                   w.keys, Tpad, k, j);
+            hipLaunchKernelGGL(emb_bitonic_local, dim3(nblk), dim3(SORT_NT), 0, st, w.keys, Tpad, k, k);
+        }
+    }
+    hipLaunchKernelGGL(emb_segments, dim3(1), dim3(SORT_NT), 0, st, w.keys, T, w.perm, w.unique_ids, w.seg_offsets,
+                       w.n_unique);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Embedding rows: one workgroup per (segment, 2048-column slab); fp32 sums in position order.
+// ------------------------------------------------------------------------------------------
+
+constexpr int ROW_NT = 256;
+
+__device__ __forceinline__ float block_sum_256(float v, float* red) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+template <int MODE>
+__global__ __launch_bounds__(ROW_NT) void emb_rows_kernel(const uint16_t* __restrict__ dY, uint16_t* __restrict__ W,
+                                                          int64_t H, const int32_t* __restrict__ perm,
+                                                          const int32_t* __restrict__ unique_ids,
+                                                          const int32_t* __restrict__ seg_offsets,
+                                                          const int32_t* __restrict__ n_unique, float s,
+                                                          double* __restrict__ acc, int32_t* __restrict__ flag_out,
+                                                          const int32_t* __restrict__ flag_in) {
+    __shared__ float red[4];
+    __shared__ int redflag[4];
+    const int seg = blockIdx.x;
+    if (seg >= n_unique[0]) return;
+    if (MODE == 1 && flag_in != nullptr && flag_in[0] != 0) return;
+    const int64_t col = ((int64_t)blockIdx.y * ROW_NT + threadIdx.x) * 8;
+    const bool active = col < H;
+    const int beg = seg_offsets[seg], end = seg_offsets[seg + 1];
+    float g[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) g[e] = 0.f;
+    if (active) {
+        int r = beg;
+        for (; r + 4 <= end; r += 4) {
+            half8 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                v[u] = *reinterpret_cast<const half8*>(dY + (int64_t)perm[r + u] * H + col);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) g[e] += (float)v[u][e];
+        }
+        for (; r < end; ++r) {
+            const half8 v = *reinterpret_cast<const half8*>(dY + (int64_t)perm[r] * H + col);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) g[e] += (float)v[e];
+        }
+    }
+    if (MODE == 0) {
+        float sum = 0.f;
+        uint32_t worst = 0u;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            sum = fmaf(g[e], g[e], sum);
+            const uint32_t mag = __float_as_uint(g[e]) & 0x7fffffffu;
+            worst = mag > worst ? mag : worst;
+        }
+        const bool bad = __any(worst >= 0x7f800000u);
+        if ((threadIdx.x & 63) == 0) redflag[threadIdx.x >> 6] = bad ? 1 : 0;
+        const float total = block_sum_256(sum, red);
+        if (threadIdx.x == 0) {
+            atomicAdd(acc, (double)total);
+            if (flag_out != nullptr && (redflag[0] | redflag[1] | redflag[2] | redflag[3])) atomicOr(flag_out, 1);
+        }
+    } else if (active) {
+        half8* p = reinterpret_cast<half8*>(W + (int64_t)unique_ids[seg] * H + col);
+        const half8 w = *p;
+        half8 o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = (_Float16)fmaf(-s, g[e], (float)w[e]);
+        *p = o;
+    }
+}
+
+hipError_t launch_embedding_rows(const uint16_t* dY, uint16_t* W, int64_t T, int64_t H, const EmbeddingWs& w, int mode,
+                                 float s, double* acc, int32_t* flag_out, const int32_t* flag_in, hipStream_t st) {
+    const dim3 grid((unsigned)T, (unsigned)((H + ROW_NT * 8 - 1) / (ROW_NT * 8)));
+    if (mode == 0)
+        hipLaunchKernelGGL(emb_rows_kernel<0>, grid, dim3(ROW_NT), 0, st, dY, W, H, w.perm, w.unique_ids, w.seg_offsets,
+                           w.n_unique, s, acc, flag_out, flag_in);
+    else
+        hipLaunchKernelGGL(emb_rows_kernel<1>, grid, dim3(ROW_NT), 0, st, dY, W, H, w.perm, w.unique_ids, w.seg_offsets,
+                           w.n_unique, s, acc, flag_out, flag_in);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// RMSNorm gain: g[j] = sum_t dY[t, j] * xhat[t, j].  Stage 1 writes fp32 partial column sums per
+// row split, stage 2 adds the splits in order and finishes (norm or update).
+// ------------------------------------------------------------------------------------------
+
+constexpr int VEC_COLS = 64;        // columns per workgroup: 8 lanes x 8 halves = 128 bytes per row
+constexpr int VEC_ROWS = ROW_NT / 8;
+
+static inline int vector_splits(int64_t T) {
+    int64_t s = (T + 255) / 256;
+    if (s < 1) s = 1;
+    if (s > 64) s = 64;
+    return (int)s;
+}
+
+size_t vector_ws_bytes(int64_t T, int64_t H) {
+    if (T <= 0 || H <= 0) return 0;
+    return align_up((size_t)vector_splits(T) * (size_t)H * sizeof(float), 256);
+}
+
+__global__ __launch_bounds__(ROW_NT) void vec_partial_kernel(const uint16_t* __restrict__ Xh,
+                                                             const uint16_t* __restrict__ dY, int64_t T, int64_t H,
+                                                             int splits, float* __restrict__ partial) {
+    __shared__ float red[VEC_ROWS][VEC_COLS + 1];
+    const int cx = threadIdx.x & 7, ry = threadIdx.x >> 3;
+    const int64_t col = (int64_t)blockIdx.x * VEC_COLS + cx * 8;
+    const int split = blockIdx.y;
+    const int64_t rows_per = (T + splits - 1) / splits;
+    const int64_t t0 = (int64_t)split * rows_per;
+    const int64_t t1 = (t0 + rows_per < T) ? (t0 + rows_per) : T;
+    float g[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) g[e] = 0.f;
+    if (col < H) {
+        for (int64_t t = t0 + ry; t < t1; t += VEC_ROWS) {
+            const half8 a = *reinterpret_cast<const half8*>(Xh + t * H + col);
+            const half8 b = *reinterpret_cast<const half8*>(dY + t * H + col);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) g[e] = fmaf((float)a[e], (float)b[e], g[e]);
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[ry][cx * 8 + e] = g[e];
+    __syncthreads();
+    if (threadIdx.x < VEC_COLS) {
+        const int64_t c = (int64_t)blockIdx.x * VEC_COLS + threadIdx.x;
+        if (c < H) {
+            float sum = 0.f;
+#pragma unroll
+            for (int r = 0; r < VEC_ROWS; ++r) sum += red[r][threadIdx.x];
+            partial[(int64_t)split * H + c] = sum;
+        }
+    }
+}
+
+template <int MODE>
+__global__ __launch_bounds__(ROW_NT) void vec_finish_kernel(const float* __restrict__ partial, int64_t H, int splits,
+                                                            uint16_t* __restrict__ w, float s, double* __restrict__ acc,
+                                                            int32_t* __restrict__ flag_out,
+                                                            const int32_t* __restrict__ flag_in) {
+    __shared__ float red[4];
+    __shared__ int redflag[4];
+    if (MODE == 1 && flag_in != nullptr && flag_in[0] != 0) return;
+    const int64_t j = (int64_t)blockIdx.x * ROW_NT + threadIdx.x;
+    float g = 0.f;
+    if (j < H)
+        for (int sp = 0; sp < splits; ++sp) g += partial[(int64_t)sp * H + j];
+    if (MODE == 0) {
+        const bool bad = __any((__float_as_uint(g) & 0x7fffffffu) >= 0x7f800000u);
+        if ((threadIdx.x & 63) == 0) redflag[threadIdx.x >> 6] = bad ? 1 : 0;
+        const float total = block_sum_256(g * g, red);
+        if (threadIdx.x == 0) {
+            atomicAdd(acc, (double)total);
+            if (flag_out != nullptr && (redflag[0] | redflag[1] | redflag[2] | redflag[3])) atomicOr(flag_out, 1);
+        }
+    } else if (j < H) {
+        const _Float16 old = *reinterpret_cast<const _Float16*>(w + j);
+        *reinterpret_cast<_Float16*>(w + j) = (_Float16)fmaf(-s, g, (float)old);
+    }
+}
+
+hipError_t launch_vector(const uint16_t* Xhat, const uint16_t* dY, uint16_t* w, int64_t T, int64_t H, void* ws, int mode,
+                         float s, double* acc, int32_t* flag_out, const int32_t* flag_in, hipStream_t st) {
+    const int splits = vector_splits(T);
+    float* partial = static_cast<float*>(ws);
+    hipLaunchKernelGGL(vec_partial_kernel, dim3((unsigned)((H + VEC_COLS - 1) / VEC_COLS), (unsigned)splits),
+                       dim3(ROW_NT), 0, st, Xhat, dY, T, H, splits, partial);
+    const dim3 grid((unsigned)((H + ROW_NT - 1) / ROW_NT));
+    if (mode == 0)
+        hipLaunchKernelGGL(vec_finish_kernel<0>, grid, dim3(ROW_NT), 0, st, partial, H, splits, w, s, acc, flag_out,
+                           flag_in);
+    else
+        hipLaunchKernelGGL(vec_finish_kernel<1>, grid, dim3(ROW_NT), 0, st, partial, H, splits, w, s, acc, flag_out,
+                           flag_in);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+
+__global__ void reduce_flags_kernel(const int32_t* __restrict__ flags, int64_t n, int32_t* __restrict__ out) {
+    __shared__ int any_s;
+    if (threadIdx.x == 0) any_s = 0;
+    __syncthreads();
+    int mine = 0;
+    for (int64_t i = threadIdx.x; i < n; i += blockDim.x) mine |= (flags[i] != 0);
+    if (mine) any_s = 1;   // benign: every writer stores the same value
+    __syncthreads();
+    if (threadIdx.x == 0) out[0] = any_s;
+}
+
+hipError_t launch_reduce_flags(const int32_t* flags, int64_t n, int32_t* out, hipStream_t st) {
+    hipLaunchKernelGGL(reduce_flags_kernel, dim3(1), dim3(256), 0, st, flags, n, out);
+    return hipGetLastError();
+}
+
+}  // namespace lomo

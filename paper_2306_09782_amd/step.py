@@ -1,0 +1,65 @@
+"""Two-pass LOMO step over a list of tensors: sequencing of C-ABI calls only (no arithmetic).
+
+Pass 1 adds every tensor's squared gradient norm into one device accumulator and raises
+per-tensor overflow flags; one host read-back yields the clipping coefficient (computed by the
+library's host function); pass 2 applies the fused updates.  Tensors are visited in the order
+given (backward order: last layer first).
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional
+
+import torch
+
+from . import binding as B
+
+
+class LomoStep:
+    def __init__(self, device="cuda:0", max_T: int = 8192, max_H: int = 8192, max_tensors: int = 1024):
+        self.device = torch.device(device)
+        self.acc = torch.zeros(1, dtype=torch.float64, device=self.device)
+        self.flags = torch.zeros(max_tensors + 1, dtype=torch.int32, device=self.device)
+        nbytes = max(B.lomo_embedding_workspace_bytes(max_T, max_H), B.lomo_vector_workspace_bytes(max_T, max_H), 256)
+        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        assert self.ws.data_ptr() % 256 == 0
+
+    def norm_pass(self, tensors: List[Dict], stream=None):
+        n = len(tensors)
+        assert n < self.flags.numel()
+        self.acc.zero_()
+        self.flags.zero_()
+        for i, t in enumerate(tensors):
+            flag = self.flags[i:i + 1]
+            if t["kind"] == "linear":
+                B.lomo_wgrad_sqnorm(t["X"], t["dY"], self.acc, flag, stream)
+            elif t["kind"] == "embedding":
+                B.lomo_embedding_sqnorm(t["ids"], t["dY"], t["W"].shape[0], self.ws, self.acc, flag, stream)
+            else:
+                B.lomo_vector_sqnorm(t["X"], t["dY"], self.ws, self.acc, flag, stream)
+        B.lomo_reduce_flags(self.flags[:n], self.flags[n:n + 1], stream)
+
+    def update_pass(self, tensors: List[Dict], lr: float, inv_loss_scale: float, clip: float, stream=None):
+        n = len(tensors)
+        step_flag = self.flags[n:n + 1]
+        for t in tensors:
+            if t["kind"] == "linear":
+                B.lomo_linear_backward_update(t["X"], t["dY"], t["W"], t.get("dX"), lr, inv_loss_scale, clip,
+                                              step_flag, stream)
+            elif t["kind"] == "embedding":
+                B.lomo_embedding_update(t["ids"], t["dY"], t["W"], lr, inv_loss_scale, clip, self.ws, step_flag, stream)
+            else:
+                B.lomo_vector_update(t["X"], t["dY"], t["W"], lr, inv_loss_scale, clip, self.ws, step_flag, stream)
+
+    def run(self, tensors: List[Dict], lr: float, loss_scale: float, max_norm: float = 1.0, eps: float = 1e-6,
+            stream=None, clip_override: Optional[float] = None) -> Dict:
+        n = len(tensors)
+        self.norm_pass(tensors, stream)
+        host = torch.cat([self.acc.view(torch.int32), self.flags[:n + 1]]).cpu()   # one read-back
+        sq = float(host[:2].view(torch.float64)[0])
+        flags = [bool(v) for v in host[2:2 + n].tolist()]
+        overflow = bool(host[2 + n])
+        clip = B.lomo_clip_coef(sq, loss_scale, max_norm, eps) if clip_override is None else clip_override
+        if not overflow:
+            self.update_pass(tensors, lr, 1.0 / loss_scale, clip, stream)
+        return {"total_sqnorm": sq, "flags": flags, "overflow": overflow, "clip_coef": clip,
+                "norm": (sq ** 0.5) / loss_scale if sq == sq else float("nan")}

@@ -1,0 +1,307 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element.
+
+Tolerances (written here, as the workload statement fixes them):
+  * overflow flags and embedding grouping: bit exact;
+  * squared norm / gradient norm: relative error <= 1e-3 (observed ~1e-6);
+  * updated fp16 weights: within 1 fp16 ulp of the oracle on >= 99.9 % of elements, none beyond 2;
+  * dX: same bar, plus a cancellation guard of 2^-20 * sum_n |dY||W|.
+Because clipped updates are mostly far below one ulp, every shape is also run with a "visible"
+step (clip = 1, lr chosen so the typical update is tens of ulps) and the set of changed
+elements is compared with the oracle's.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import lomo_synth as S
+from oracle import lomo_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2306_09782_amd as L
+    if not os.path.exists(L.library_path()):
+        from paper_2306_09782_amd.build import build
+        build(verbose=False)
+    L.load_library()
+    return L
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def gen(seed, shape, sigma):
+    return S.normal_f16_np(S.tensor_key(seed, 7, 3, len(shape) + int(sigma * 1000) % 97), shape, S.normal_mult(sigma))
+
+
+def assert_weights_close(got16, want16, what=""):
+    d = O.ulp_distance_f16(got16, want16)
+    assert np.isfinite(got16.astype(np.float32)).all(), what
+    frac1 = float((d <= 1).mean())
+    assert d.max() <= 2, f"{what}: max ulp distance {d.max()}"
+    assert frac1 >= 0.999, f"{what}: only {frac1:.5f} within 1 ulp"
+    return float((d == 0).mean())
+
+
+def assert_dx_close(got16, dY, W, what=""):
+    ref64 = O.input_grad_f64(dY, W)
+    want16 = O.round_f16(ref64)
+    d = O.ulp_distance_f16(got16, want16)
+    guard = 2.0 ** -20 * (np.abs(dY.astype(np.float64)) @ np.abs(W.astype(np.float64)))
+    ok = (d <= 2) | (np.abs(got16.astype(np.float64) - ref64) <= guard)
+    assert ok.all(), f"{what}: dX off by {d.max()} ulp"
+    assert float(((d <= 1) | (np.abs(got16.astype(np.float64) - ref64) <= guard)).mean()) >= 0.999, what
+
+
+LINEAR_SHAPES = [
+    (512, 1024, 1024),     # the single-layer workload: 64 tiles of 128 x 128
+    (100, 264, 136),       # ragged in every dimension
+    (33, 8, 8),            # one partial tile
+    (1, 520, 1032),        # a single token: rank-one gradient
+    (300, 776, 392),
+    (70, 3600, 3320),      # 15 x 13 tiles of 256 x 256, ragged tails
+    (64, 4096, 4096),      # 256 full 256 x 256 tiles
+]
+
+
+@pytest.mark.parametrize("T,K,N", LINEAR_SHAPES)
+def test_linear_sqnorm_update_dgrad(L, T, K, N):
+    Sc = 1024.0
+    sig_dy = 0.01
+    X = gen(1, (T, K), 1.0)
+    dY = S.normal_f16_np(S.tensor_key(2, T, K, N), (T, N), S.normal_mult(sig_dy, Sc))
+    W = S.normal_f16_np(S.tensor_key(3, T, K, N), (N, K), S.normal_mult(0.02))
+    G = O.linear_grad(X, dY)
+
+    # pass 1
+    acc = torch.zeros(1, dtype=torch.float64, device=DEV)
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    dXd, dYd = dev(X), dev(dY)
+    L.lomo_wgrad_sqnorm(dXd, dYd, acc, flag)
+    L.lomo_wgrad_sqnorm(dXd, dYd, acc, flag)           # accumulates: twice the norm
+    want = O.sqnorm(G)
+    assert float(acc.item()) == pytest.approx(2 * want, rel=1e-3)
+    assert abs(float(acc.item()) / (2 * want) - 1) < 2e-5
+    assert int(flag.item()) == 0
+
+    # pass 2, visible step: typical |delta| about 30 ulp of a 0.02-sized weight
+    lr = float(np.float32(30 * 2.0 ** -16 / (math.sqrt(T) * sig_dy)))
+    Wd = dev(W)
+    dX = torch.empty(T, K, dtype=torch.float16, device=DEV)
+    L.lomo_linear_backward_update(dXd, dYd, Wd, dX, lr, 1.0 / Sc, 1.0, flag)
+    got = host(Wd)
+    wantW = O.sgd_update(W, G, lr, 1.0, Sc)
+    exact = assert_weights_close(got, wantW, f"W {T}x{K}x{N}")
+    assert exact > 0.98
+    changed_o = wantW.view(np.uint16) != W.view(np.uint16)
+    changed_g = got.view(np.uint16) != W.view(np.uint16)
+    assert changed_o.mean() > 0.9 and (changed_o != changed_g).mean() < 1e-3
+    assert_dx_close(host(dX), dY, W, f"dX {T}x{K}x{N}")
+
+    # clipped step of the workload description (tiny update) from the same start
+    coef = O.clip_coef(O.grad_norm(want, Sc))
+    Wd2 = dev(W)
+    L.lomo_linear_backward_update(dXd, dYd, Wd2, None, 1e-2, 1.0 / Sc, float(np.float32(coef)), None)
+    assert_weights_close(host(Wd2), O.sgd_update(W, G, float(np.float32(1e-2)), float(np.float32(coef)), Sc), "clipped")
+
+
+def test_dgrad_reads_weights_before_the_update(L):
+    T, K, N = 96, 512, 256
+    X, dY, W = gen(4, (T, K), 1.0), gen(5, (T, N), 0.5), gen(6, (N, K), 0.02)
+    Wd, dX = dev(W), torch.empty(T, K, dtype=torch.float16, device=DEV)
+    L.lomo_linear_backward_update(dev(X), dev(dY), Wd, dX, 0.5, 1.0, 1.0, None)    # a huge step
+    assert_dx_close(host(dX), dY, W, "dX before update")
+    after = O.input_grad(dY, host(Wd))
+    assert (O.ulp_distance_f16(host(dX), after) > 4).mean() > 0.5
+
+
+@pytest.mark.parametrize("bad", [np.inf, -np.inf, np.nan])
+@pytest.mark.parametrize("where", ["X", "dY"])
+def test_overflow_flag_and_skip(L, bad, where):
+    T, K, N = 130, 264, 520
+    X, dY, W = gen(7, (T, K), 1.0), gen(8, (T, N), 1.0), gen(9, (N, K), 0.02)
+    (X if where == "X" else dY)[T - 1, 5] = bad
+    assert O.has_overflow(O.linear_grad(X, dY))
+    acc = torch.zeros(1, dtype=torch.float64, device=DEV)
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    L.lomo_wgrad_sqnorm(dev(X), dev(dY), acc, flag)
+    assert int(flag.item()) == 1
+    Wd, dX = dev(W), torch.zeros(T, K, dtype=torch.float16, device=DEV)
+    L.lomo_linear_backward_update(dev(X), dev(dY), Wd, dX, 0.1, 1.0, 1.0, flag)
+    np.testing.assert_array_equal(host(Wd).view(np.uint16), W.view(np.uint16))     # step dropped
+    assert host(dX).any()                                                           # dgrad still ran
+
+
+def test_loss_scale_invariance_on_device(L):
+    T, K, N = 200, 520, 264
+    X, W = gen(10, (T, K), 1.0), gen(11, (N, K), 0.02)
+    dY = S.normal_f16_np(S.tensor_key(12, 0, 0, 0), (T, N), S.normal_mult(0.01, 256.0))
+    dY2 = (dY.astype(np.float32) * 2).astype(np.float16)
+    outs = []
+    for d, Sc in ((dY, 256.0), (dY2, 512.0)):
+        Wd = dev(W)
+        L.lomo_linear_backward_update(dev(X), dev(d), Wd, None, 0.02, 1.0 / Sc, 1.0, None)
+        outs.append(host(Wd).view(np.uint16))
+    np.testing.assert_array_equal(outs[0], outs[1])
+    assert (outs[0] != W.view(np.uint16)).mean() > 0.5
+
+
+def test_lr_zero_keeps_weights(L):
+    T, K, N = 64, 136, 72
+    X, dY, W = gen(13, (T, K), 1.0), gen(14, (T, N), 1.0), gen(15, (N, K), 0.02)
+    Wd = dev(W)
+    L.lomo_linear_backward_update(dev(X), dev(dY), Wd, None, 0.0, 1.0, 1.0, None)
+    np.testing.assert_array_equal(host(Wd).view(np.uint16), W.view(np.uint16))
+
+
+# ------------------------------------------------------------------------------- embedding
+
+
+def _emb_case(T, V, H, mode, seed=0):
+    rng = np.random.default_rng(seed)
+    if mode == "zipf":
+        ids = S.zipf_ids(seed, T, V)
+    elif mode == "same":
+        ids = np.full(T, V // 3, np.int32)
+    elif mode == "distinct":
+        ids = rng.permutation(V)[:T].astype(np.int32)
+    else:
+        ids = rng.integers(0, V, size=T).astype(np.int32)
+    dY = S.normal_f16_np(S.tensor_key(seed, T, V, H), (T, H), S.normal_mult(0.05, 64.0))
+    W = S.normal_f16_np(S.tensor_key(seed + 1, T, V, H), (V, H), S.normal_mult(0.02))
+    return ids, dY, W
+
+
+EMB_CASES = [(4096, 32000, 512, "zipf"), (0, 50, 64, "uniform"), (1, 50, 64, "uniform"), (2, 50, 64, "same"),
+             (777, 100, 72, "uniform"), (300, 1000, 2056, "distinct"), (513, 40, 4096, "same"),
+             (20000, 5000, 64, "zipf"), (8192, 32000, 128, "zipf"), (8193, 300, 8, "uniform")]
+
+
+@pytest.mark.parametrize("T,V,H,mode", EMB_CASES)
+def test_embedding_grouping_norm_update(L, T, V, H, mode):
+    ids, dY, W = _emb_case(T, V, H, mode)
+    wsb = L.lomo_embedding_workspace_bytes(T, H)
+    ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device=DEV)
+    idd = dev(ids) if T else torch.empty(0, dtype=torch.int32, device=DEV)
+    dYd = dev(dY) if T else torch.empty(0, H, dtype=torch.float16, device=DEV)
+
+    u = torch.full((max(T, 1),), -1, dtype=torch.int32, device=DEV)
+    off = torch.full((T + 1,), -1, dtype=torch.int32, device=DEV)
+    perm = torch.full((max(T, 1),), -1, dtype=torch.int32, device=DEV)
+    nu = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    L.lomo_embedding_grouping(idd, V, ws, u, off, perm, nu)
+    ou, ooff, operm = O.embedding_grouping(ids)
+    n = int(nu.item())
+    assert n == ou.size
+    np.testing.assert_array_equal(host(u)[:n], ou)
+    np.testing.assert_array_equal(host(off)[:n + 1], ooff)
+    np.testing.assert_array_equal(host(perm)[:T], operm)
+
+    G = O.embedding_grad(ids, dY, V)
+    acc = torch.zeros(1, dtype=torch.float64, device=DEV)
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    L.lomo_embedding_sqnorm(idd, dYd, V, ws, acc, flag)
+    want = O.sqnorm(G)
+    assert float(acc.item()) == pytest.approx(want, rel=2e-5, abs=1e-30)
+    assert int(flag.item()) == 0
+
+    Wd = dev(W)
+    lr, Sc = 0.01, 64.0
+    L.lomo_embedding_update(idd, dYd, Wd, lr, 1.0 / Sc, 1.0, ws, flag)
+    got = host(Wd)
+    wantW = O.sgd_update(W, G, float(np.float32(lr)), 1.0, Sc)
+    assert_weights_close(got, wantW, "embedding rows")
+    absent = np.setdiff1d(np.arange(V), ids)
+    np.testing.assert_array_equal(got[absent].view(np.uint16), W[absent].view(np.uint16))
+    if T:
+        assert (got[ids[0]].view(np.uint16) != W[ids[0]].view(np.uint16)).any()
+
+    # run-to-run determinism: bit-identical rows
+    Wd2 = dev(W)
+    L.lomo_embedding_update(idd, dYd, Wd2, lr, 1.0 / Sc, 1.0, ws, flag)
+    np.testing.assert_array_equal(host(Wd2).view(np.uint16), got.view(np.uint16))
+
+
+def test_embedding_overflow(L):
+    ids, dY, W = _emb_case(300, 64, 136, "uniform", seed=3)
+    dY[17, 9] = np.inf
+    dY[18, 9] = -np.inf
+    ws = torch.empty(L.lomo_embedding_workspace_bytes(300, 136), dtype=torch.uint8, device=DEV)
+    acc = torch.zeros(1, dtype=torch.float64, device=DEV)
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    L.lomo_embedding_sqnorm(dev(ids), dev(dY), 64, ws, acc, flag)
+    assert int(flag.item()) == 1 and O.has_overflow(O.embedding_grad(ids, dY, 64))
+    Wd = dev(W)
+    L.lomo_embedding_update(dev(ids), dev(dY), Wd, 0.1, 1.0, 1.0, ws, flag)
+    np.testing.assert_array_equal(host(Wd).view(np.uint16), W.view(np.uint16))
+
+
+# ------------------------------------------------------------------------------- gain vectors
+
+
+@pytest.mark.parametrize("T,H", [(4096, 4096), (1, 64), (257, 72), (1000, 5120), (0, 64), (20000, 136)])
+def test_vector_norm_update(L, T, H):
+    Sc = 64.0
+    xh = S.normal_f16_np(S.tensor_key(20, T, H, 0), (T, H), S.normal_mult(1.0))
+    dY = S.normal_f16_np(S.tensor_key(21, T, H, 0), (T, H), S.normal_mult(1e-3, Sc))
+    w = np.ones(H, np.float16)
+    g = O.vector_grad(xh, dY) if T else np.zeros(H)
+    ws = torch.empty(max(L.lomo_vector_workspace_bytes(T, H), 256), dtype=torch.uint8, device=DEV)
+    acc = torch.zeros(1, dtype=torch.float64, device=DEV)
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    xd = dev(xh) if T else torch.empty(0, H, dtype=torch.float16, device=DEV)
+    dd = dev(dY) if T else torch.empty(0, H, dtype=torch.float16, device=DEV)
+    L.lomo_vector_sqnorm(xd, dd, ws, acc, flag)
+    assert float(acc.item()) == pytest.approx(O.sqnorm(g), rel=2e-5, abs=1e-30)
+    assert int(flag.item()) == 0
+    wd = dev(w)
+    lr = 30.0 / max(1.0, math.sqrt(T))       # typical |delta| about 30 ulp of 1.0
+    L.lomo_vector_update(xd, dd, wd, lr, 1.0 / Sc, 1.0, ws, flag)
+    got = host(wd)
+    assert_weights_close(got, O.sgd_update(w, g, float(np.float32(lr)), 1.0, Sc), "gain")
+    if T:
+        assert (got.view(np.uint16) != w.view(np.uint16)).mean() > 0.5
+
+
+def test_vector_overflow(L):
+    T, H = 300, 264
+    xh, dY = gen(22, (T, H), 1.0), gen(23, (T, H), 1.0)
+    xh[299, 263] = np.nan
+    ws = torch.empty(L.lomo_vector_workspace_bytes(T, H), dtype=torch.uint8, device=DEV)
+    acc = torch.zeros(1, dtype=torch.float64, device=DEV)
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    L.lomo_vector_sqnorm(dev(xh), dev(dY), ws, acc, flag)
+    assert int(flag.item()) == 1
+    wd = torch.ones(H, dtype=torch.float16, device=DEV)
+    L.lomo_vector_update(dev(xh), dev(dY), wd, 0.1, 1.0, 1.0, ws, flag)
+    assert (host(wd) == 1.0).all()
+
+
+def test_reduce_flags(L):
+    f = torch.zeros(700, dtype=torch.int32, device=DEV)
+    out = torch.full((1,), 7, dtype=torch.int32, device=DEV)
+    L.lomo_reduce_flags(f, out)
+    assert int(out.item()) == 0
+    f[613] = 1
+    L.lomo_reduce_flags(f, out)
+    assert int(out.item()) == 1
+
+
+def test_generators_agree_on_device():
+    key = S.tensor_key(0, 5, 1, 2)
+    for mult in (S.normal_mult(0.02), S.normal_mult(1e-3, 65536.0)):
+        a = S.normal_f16_np(key, (300, 520), mult)
+        b = S.normal_f16_torch(key, (300, 520), mult, DEV).cpu().numpy()
+        np.testing.assert_array_equal(a.view(np.uint16), b.view(np.uint16))

@@ -1,0 +1,99 @@
+"""Whole two-pass steps of the named workloads on the GPU against the materialising oracle.
+
+linear1024 and llama7b_layer are checked element by element on every tensor, in the launch
+configuration bench.py times (LomoStep.run).  Inputs come from the counter-based generators
+(device twin; the bits the oracle sees are read back from the device).
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import lomo_synth as S
+from oracle import lomo_oracle as O
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2306_09782_amd as L
+    if not os.path.exists(L.library_path()):
+        from paper_2306_09782_amd.build import build
+        build(verbose=False)
+    L.load_library()
+    return L
+
+
+def _device_tensors(wl):
+    out = []
+    for spec in wl.tensors:
+        t = {"kind": spec.kind, "name": spec.name, "dY": wl.dY_torch(spec, DEV), "W": wl.W_torch(spec, DEV)}
+        if spec.kind == "embedding":
+            t["ids"] = torch.from_numpy(wl.ids_np(spec)).to(DEV)
+        else:
+            t["X"] = wl.X_torch(spec, DEV)
+        if spec.kind == "linear":
+            t["dX"] = torch.empty(spec.T, spec.K, dtype=torch.float16, device=DEV)
+        out.append(t)
+    return out
+
+
+def _host(t):
+    return {k: (v.cpu().numpy() if torch.is_tensor(v) else v) for k, v in t.items() if k != "dX"}
+
+
+def _check_ulps(got, want, what):
+    d = O.ulp_distance_f16(got, want)
+    assert d.max() <= 2, f"{what}: {d.max()} ulp"
+    assert (d <= 1).mean() >= 0.999, what
+    return float((d == 0).mean())
+
+
+@pytest.mark.parametrize("name", ["linear1024", "llama7b_layer"])
+def test_two_pass_step_matches_oracle(L, name):
+    from paper_2306_09782_amd.step import LomoStep
+    wl = S.workload(name)
+    gpu = _device_tensors(wl)
+    cpu = [_host(t) for t in gpu]
+    if name == "linear1024":     # the CPU generator yields the same bits
+        np.testing.assert_array_equal(cpu[0]["X"].view(np.uint16), wl.X_np(wl.tensors[0]).view(np.uint16))
+    lr = float(np.float32(wl.lr))
+    stepper = LomoStep(DEV, max_T=wl.T, max_H=max(s.K for s in wl.tensors), max_tensors=len(gpu))
+
+    # oracle, materialised: every gradient of the step is held at once
+    grads = [O.tensor_grad(t) for t in cpu]
+    flags = [O.has_overflow(g) for g in grads]
+    total = math.fsum(O.sqnorm(g) for g in grads)
+    norm = O.grad_norm(total, wl.loss_scale)
+    coef = O.clip_coef(norm, wl.max_norm, wl.eps)
+
+    # 1) the step as the workload states it (clipped: most updates are below one ulp)
+    res = stepper.run(gpu, lr, wl.loss_scale, wl.max_norm, wl.eps)
+    assert res["flags"] == flags and res["overflow"] is False
+    assert abs(res["norm"] / norm - 1) < 1e-3
+    assert abs(res["norm"] / norm - 1) < 1e-5           # what the fp32/fp64 accumulation really gives
+    assert abs(res["clip_coef"] / coef - 1) < 1e-3
+    for g, t, G in zip(gpu, cpu, grads):
+        want = O.sgd_update(t["W"], G, lr, res["clip_coef"], wl.loss_scale)
+        _check_ulps(g["W"].cpu().numpy(), want, f"{name}/{g['name']} clipped")
+        d = O.ulp_distance_f16(g["dX"].cpu().numpy(), O.input_grad(t["dY"], t["W"]))
+        assert d.max() <= 2 and (d <= 1).mean() >= 0.999, g["name"]
+
+    # 2) a visible step from the same start: clip forced to 1, typical update about 30 ulp
+    for g, t in zip(gpu, cpu):
+        g["W"].copy_(torch.from_numpy(t["W"]))
+    sig = wl.tensors[0].sigma_dy
+    lr_vis = float(np.float32(30 * 2.0 ** -16 / (math.sqrt(wl.T) * sig)))
+    stepper.run(gpu, lr_vis, wl.loss_scale, wl.max_norm, wl.eps, clip_override=1.0)
+    for g, t, G in zip(gpu, cpu, grads):
+        want = O.sgd_update(t["W"], G, lr_vis, 1.0, wl.loss_scale)
+        got = g["W"].cpu().numpy()
+        exact = _check_ulps(got, want, f"{name}/{g['name']} visible")
+        assert exact > 0.98
+        changed_o = want.view(np.uint16) != t["W"].view(np.uint16)
+        changed_g = got.view(np.uint16) != t["W"].view(np.uint16)
+        assert changed_o.mean() > 0.9 and (changed_o != changed_g).mean() < 1e-3
