@@ -28,7 +28,7 @@ def cpu_baseline(wl, max_seconds=25.0):
     """The oracle as it stands, on a bounded sample: the first linear tensors of the workload."""
     import numpy as np
     from oracle import lomo_oracle as O
-    budget_flops = 1.2e12          # about 10-20 s of fp64 BLAS on a 16-core host
+    budget_flops = 1.2e13          # about 10-20 s of fp64 BLAS on a 16-core host
     sample, flops = [], 0
     for spec in wl.tensors:
         if spec.kind != "linear":

@@ -53,6 +53,16 @@ def _check_ulps(got, want, what):
     return float((d == 0).mean())
 
 
+def _check_dx(got, dY, W, what):
+    """dX within 1 ulp (2 at most), or within 2^-20 * sum_n |dY||W| where the sum cancels."""
+    ref64 = O.input_grad_f64(dY, W)
+    d = O.ulp_distance_f16(got, O.round_f16(ref64))
+    guard = 2.0 ** -20 * (np.abs(dY.astype(np.float64)) @ np.abs(W.astype(np.float64)))
+    near = np.abs(got.astype(np.float64) - ref64) <= guard
+    assert ((d <= 2) | near).all(), f"{what}: dX off by {d.max()} ulp"
+    assert ((d <= 1) | near).mean() >= 0.999, what
+
+
 @pytest.mark.parametrize("name", ["linear1024", "llama7b_layer"])
 def test_two_pass_step_matches_oracle(L, name):
     from paper_2306_09782_amd.step import LomoStep
@@ -80,8 +90,7 @@ def test_two_pass_step_matches_oracle(L, name):
     for g, t, G in zip(gpu, cpu, grads):
         want = O.sgd_update(t["W"], G, lr, res["clip_coef"], wl.loss_scale)
         _check_ulps(g["W"].cpu().numpy(), want, f"{name}/{g['name']} clipped")
-        d = O.ulp_distance_f16(g["dX"].cpu().numpy(), O.input_grad(t["dY"], t["W"]))
-        assert d.max() <= 2 and (d <= 1).mean() >= 0.999, g["name"]
+        _check_dx(g["dX"].cpu().numpy(), t["dY"], t["W"], g["name"])
 
     # 2) a visible step from the same start: clip forced to 1, typical update about 30 ulp
     for g, t in zip(gpu, cpu):
