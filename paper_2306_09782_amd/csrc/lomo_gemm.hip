@@ -16,18 +16,12 @@
 // fragments from LDS rows of 80 bytes (64 + 16 pad), which makes ds_read_b128 conflict free.
 // With A on the MFMA row side, each lane's four consecutive accumulator registers are four
 // consecutive m, i.e. an 8-byte run of W / dX: the read-modify-write epilogue is vectorised.
-#include "lomo_kernels.h"
+#include "lomo_gemm_common.h"
 
-#include <hip/hip_fp16.h>
+#include <stdlib.h>
 
 namespace lomo {
 
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int NT = 256;        // threads per workgroup: 4 waves in a 2 x 2 arrangement
 constexpr int BK = 32;         // contraction slice per pipeline stage
 constexpr int LROW = BK + 8;   // halves per LDS row
 
@@ -97,12 +91,6 @@ __device__ __forceinline__ void store_contig(uint16_t* __restrict__ lds, const u
         const int q = item % (BK / 8);
         *reinterpret_cast<u32x4*>(lds + n * LROW + 8 * q) = r[it];
     }
-}
-
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
 }
 
 // ---- the kernel ---------------------------------------------------------------------------
@@ -201,65 +189,7 @@ __global__ __launch_bounds__(NT) void lomo_contract_kernel(GemmArgs g) {
         __syncthreads();
     }
 
-    // ---- epilogues.  Lane (l32, lh) of MFMA tile (i, j) holds, in register 4*q4 + e,
-    //      the element  m = 32 i + 8 q4 + 4 lh + e,  n = 32 j + l32  of the wave's sub-tile.
-    if constexpr (EPI == EPI_SQNORM) {
-        float sum = 0.f;
-        uint32_t worst = 0u;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float v = acc[i][j][r];
-                    sum = fmaf(v, v, sum);
-                    const uint32_t mag = __float_as_uint(v) & 0x7fffffffu;
-                    worst = mag > worst ? mag : worst;
-                }
-        sum = wave_sum(sum);
-        const bool bad = __any(worst >= 0x7f800000u);
-        float* red = reinterpret_cast<float*>(smem);   // main loop is over: LDS is free
-        int* redflag = reinterpret_cast<int*>(smem) + 8;
-        if (lane == 0) {
-            red[wave] = sum;
-            redflag[wave] = bad ? 1 : 0;
-        }
-        __syncthreads();
-        if (tid == 0) {
-            const float total = (red[0] + red[1]) + (red[2] + red[3]);
-            atomicAdd(g.acc, (double)total);
-            if (g.flag_out != nullptr && (redflag[0] | redflag[1] | redflag[2] | redflag[3])) atomicOr(g.flag_out, 1);
-        }
-    } else {
-        const float s = g.s;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int nl = wn * (BN / 2) + 32 * j + l32;
-            if (nl >= n_rem) continue;
-            uint16_t* row = g.Out + (n0 + nl) * g.ldo + m0;
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-#pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    const int ml = wm * (BM / 2) + 32 * i + 8 * q4 + 4 * lh;
-                    if (ml >= m_rem) continue;
-                    half4* p = reinterpret_cast<half4*>(row + ml);
-                    half4 out;
-                    if constexpr (EPI == EPI_UPDATE) {
-                        const half4 w = *p;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            out[e] = (_Float16)fmaf(-s, acc[i][j][4 * q4 + e], (float)w[e]);
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) out[e] = (_Float16)acc[i][j][4 * q4 + e];
-                    }
-                    *p = out;
-                }
-            }
-        }
-    }
+    epilogue<BM, BN, EPI>(acc, g, smem, m0, n0, m_rem, n_rem);
 }
 
 // ---- host side ----------------------------------------------------------------------------
@@ -288,18 +218,33 @@ static inline bool use_big_tiles(int64_t M, int64_t Nn) {
     return big >= 192;
 }
 
+// LOMO_DISABLE_FAST=1 forces the generic kernel everywhere (testing aid).
+static bool fast_enabled() {
+    static const bool on = [] {
+        const char* e = getenv("LOMO_DISABLE_FAST");
+        return !(e && e[0] == '1');
+    }();
+    return on;
+}
+
 hipError_t launch_wgrad_update(const GemmArgs& a, hipStream_t st) {
     ScopedTiming t(LOMO_KERNEL_WGRAD_UPDATE, st);
+    hipError_t e;
+    if (fast_enabled() && try_launch_fast<true, EPI_UPDATE>(a, st, &e)) return e;
     return use_big_tiles(a.M, a.Nn) ? launch_one<256, 256, true, EPI_UPDATE>(a, st)
                                     : launch_one<128, 128, true, EPI_UPDATE>(a, st);
 }
 hipError_t launch_wgrad_sqnorm(const GemmArgs& a, hipStream_t st) {
     ScopedTiming t(LOMO_KERNEL_WGRAD_SQNORM, st);
+    hipError_t e;
+    if (fast_enabled() && try_launch_fast<true, EPI_SQNORM>(a, st, &e)) return e;
     return use_big_tiles(a.M, a.Nn) ? launch_one<256, 256, true, EPI_SQNORM>(a, st)
                                     : launch_one<128, 128, true, EPI_SQNORM>(a, st);
 }
 hipError_t launch_dgrad(const GemmArgs& a, hipStream_t st) {
     ScopedTiming t(LOMO_KERNEL_DGRAD, st);
+    hipError_t e;
+    if (fast_enabled() && try_launch_fast<false, EPI_STORE>(a, st, &e)) return e;
     return use_big_tiles(a.M, a.Nn) ? launch_one<256, 256, false, EPI_STORE>(a, st)
                                     : launch_one<128, 128, false, EPI_STORE>(a, st);
 }

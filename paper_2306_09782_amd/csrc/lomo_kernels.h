@@ -31,6 +31,10 @@ struct GemmArgs {
     const int32_t* flag_in;  // overflow flag to honour (EPI_UPDATE), may be null
 };
 
+// Whole-tile fast path (lomo_gemm_fast.hip): returns false when the shape is not eligible.
+template <bool B_STRIDED, int EPI>
+bool try_launch_fast(const GemmArgs& a, hipStream_t st, hipError_t* err);
+
 hipError_t launch_wgrad_update(const GemmArgs& a, hipStream_t st);
 hipError_t launch_wgrad_sqnorm(const GemmArgs& a, hipStream_t st);
 hipError_t launch_dgrad(const GemmArgs& a, hipStream_t st);
