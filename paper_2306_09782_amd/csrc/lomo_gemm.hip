@@ -218,7 +218,8 @@ static inline bool use_big_tiles(int64_t M, int64_t Nn) {
     return big >= 192;
 }
 
-// LOMO_DISABLE_FAST=1 forces the generic kernel everywhere (testing aid).
+// LOMO_DISABLE_FAST=1 forces the generic kernel everywhere, LOMO_DISABLE_DMA=1 skips the
+// direct-to-LDS kernel (testing aids).
 static bool fast_enabled() {
     static const bool on = [] {
         const char* e = getenv("LOMO_DISABLE_FAST");
@@ -227,9 +228,18 @@ static bool fast_enabled() {
     return on;
 }
 
+static bool dma_enabled() {
+    static const bool on = [] {
+        const char* e = getenv("LOMO_DISABLE_DMA");
+        return !(e && e[0] == '1');
+    }();
+    return on;
+}
+
 hipError_t launch_wgrad_update(const GemmArgs& a, hipStream_t st) {
     ScopedTiming t(LOMO_KERNEL_WGRAD_UPDATE, st);
     hipError_t e;
+    if (fast_enabled() && dma_enabled() && try_launch_dma<true, EPI_UPDATE>(a, st, &e)) return e;
     if (fast_enabled() && try_launch_fast<true, EPI_UPDATE>(a, st, &e)) return e;
     return use_big_tiles(a.M, a.Nn) ? launch_one<256, 256, true, EPI_UPDATE>(a, st)
                                     : launch_one<128, 128, true, EPI_UPDATE>(a, st);
@@ -237,6 +247,7 @@ hipError_t launch_wgrad_update(const GemmArgs& a, hipStream_t st) {
 hipError_t launch_wgrad_sqnorm(const GemmArgs& a, hipStream_t st) {
     ScopedTiming t(LOMO_KERNEL_WGRAD_SQNORM, st);
     hipError_t e;
+    if (fast_enabled() && dma_enabled() && try_launch_dma<true, EPI_SQNORM>(a, st, &e)) return e;
     if (fast_enabled() && try_launch_fast<true, EPI_SQNORM>(a, st, &e)) return e;
     return use_big_tiles(a.M, a.Nn) ? launch_one<256, 256, true, EPI_SQNORM>(a, st)
                                     : launch_one<128, 128, true, EPI_SQNORM>(a, st);
@@ -244,6 +255,7 @@ hipError_t launch_wgrad_sqnorm(const GemmArgs& a, hipStream_t st) {
 hipError_t launch_dgrad(const GemmArgs& a, hipStream_t st) {
     ScopedTiming t(LOMO_KERNEL_DGRAD, st);
     hipError_t e;
+    if (fast_enabled() && dma_enabled() && try_launch_dma<false, EPI_STORE>(a, st, &e)) return e;
     if (fast_enabled() && try_launch_fast<false, EPI_STORE>(a, st, &e)) return e;
     return use_big_tiles(a.M, a.Nn) ? launch_one<256, 256, false, EPI_STORE>(a, st)
                                     : launch_one<128, 128, false, EPI_STORE>(a, st);

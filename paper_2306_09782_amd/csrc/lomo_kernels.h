@@ -35,6 +35,10 @@ struct GemmArgs {
 template <bool B_STRIDED, int EPI>
 bool try_launch_fast(const GemmArgs& a, hipStream_t st, hipError_t* err);
 
+// 256 x 256 direct-to-LDS pipeline (lomo_gemm_dma.hip): returns false when not eligible.
+template <bool B_STRIDED, int EPI>
+bool try_launch_dma(const GemmArgs& a, hipStream_t st, hipError_t* err);
+
 hipError_t launch_wgrad_update(const GemmArgs& a, hipStream_t st);
 hipError_t launch_wgrad_sqnorm(const GemmArgs& a, hipStream_t st);
 hipError_t launch_dgrad(const GemmArgs& a, hipStream_t st);
