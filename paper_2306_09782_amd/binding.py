@@ -25,7 +25,8 @@ class LomoError(RuntimeError):
 
 
 def library_path() -> str:
-    return os.path.join(_HERE, "lib", "liblomo.so")
+    """In-tree library; LOMO_LIBRARY names another build of the same sources (development aid)."""
+    return os.environ.get("LOMO_LIBRARY") or os.path.join(_HERE, "lib", "liblomo.so")
 
 
 def load_library():

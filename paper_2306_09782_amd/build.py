@@ -21,10 +21,10 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = True, extra_flags=()) -> str:
-    os.makedirs(LIB_DIR, exist_ok=True)
+def build(verbose: bool = True, extra_flags=(), out_path: str = LIB_PATH) -> str:
+    os.makedirs(os.path.dirname(out_path), exist_ok=True)
     cmd = [HIPCC, *FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB_PATH]
+           *[os.path.join(CSRC, s) for s in SOURCES], "-o", out_path]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -34,7 +34,7 @@ def build(verbose: bool = True, extra_flags=()) -> str:
                                    if "packed-fp32-ops" not in ln and "is not a recognized feature" not in ln) + "\n")
     if res.returncode != 0:
         raise RuntimeError("hipcc failed")
-    return LIB_PATH
+    return out_path
 
 
 if __name__ == "__main__":

@@ -21,8 +21,7 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 // Epilogue of a BM x BN workgroup tile held as 32x32 MFMA accumulators, 4 waves in 2 x 2.
 // Lane (l32, lh) of MFMA tile (i, j) holds, in register 4*q4 + e, the element
-//   m = 32 i + 8 q4 + 4 lh + e,  n = 32 j + l32   of the wave's sub-tile,
-// so four consecutive registers are four consecutive m: an 8-byte run of the output row.
+//   m = 32 i + 8 q4 + 4 lh + e,  n = 32 j + l32   of the wave's sub-tile.
 //   EPI_UPDATE: W <- rne16(float(W) - s * acc)   (section 3.2 update, fp32 as section 3.3.2 asks)
 //   EPI_SQNORM: one fp32 sum of squares per workgroup -> double atomic; inf/NaN -> flag
 //   EPI_STORE : Out <- rne16(acc)
@@ -63,32 +62,61 @@ __device__ __forceinline__ void epilogue(floatx16 (&acc)[BM / 64][BN / 64], cons
             if (g.flag_out != nullptr && (redflag[0] | redflag[1] | redflag[2] | redflag[3])) atomicOr(g.flag_out, 1);
         }
     } else {
+        // Lanes l and l + 32 hold the two 4-row halves of every 8-row block of the same output row n.
+        // v_permlane32_swap exchanges them so that each lane owns 8 consecutive m (16 bytes):
+        // lane half lh covers m = 32 i + 16 a + 8 lh .. + 7.  All W loads of a 32-row stripe are issued
+        // before any of them is used, and the next stripe is loaded while the current one is updated.
+        typedef uint32_t u32x2v __attribute__((ext_vector_type(2)));
         const float s = g.s;
+        auto row_ptr = [&](int j) -> uint16_t* {
+            const int nl = wn * (BN / 2) + 32 * j + l32;
+            return (nl < n_rem) ? g.Out + (n0 + nl) * g.ldo + m0 : nullptr;
+        };
+        auto mloc = [&](int i, int a) { return wm * (BM / 2) + 32 * i + 16 * a + 8 * lh; };
+        half8 wbuf[2][TM][2];
+        auto load_stripe = [&](int j, half8 (&w)[TM][2]) {
+            uint16_t* row = row_ptr(j);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int a = 0; a < 2; ++a) {
+                    const int ml = mloc(i, a);
+                    if (row != nullptr && ml < m_rem) w[i][a] = *reinterpret_cast<const half8*>(row + ml);
+                }
+        };
+        if constexpr (EPI == EPI_UPDATE) load_stripe(0, wbuf[0]);
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            const int nl = wn * (BN / 2) + 32 * j + l32;
-            if (nl >= n_rem) continue;
-            uint16_t* row = g.Out + (n0 + nl) * g.ldo + m0;
+            if constexpr (EPI == EPI_UPDATE) {
+                if (j + 1 < TN) load_stripe(j + 1, wbuf[(j + 1) & 1]);
+            }
+            uint16_t* row = row_ptr(j);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    const int ml = wm * (BM / 2) + 32 * i + 8 * q4 + 4 * lh;
-                    if (ml >= m_rem) continue;
-                    half4* p = reinterpret_cast<half4*>(row + ml);
-                    half4 out;
+                for (int a = 0; a < 2; ++a) {
+                    float v[8];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const u32x2v sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[i][j][8 * a + e]),
+                                                                           __float_as_uint(acc[i][j][8 * a + 4 + e]),
+                                                                           false, false);
+                        v[e] = __uint_as_float(sw[0]);
+                        v[4 + e] = __uint_as_float(sw[1]);
+                    }
+                    const int ml = mloc(i, a);
+                    if (row == nullptr || ml >= m_rem) continue;
+                    half8 out;
                     if constexpr (EPI == EPI_UPDATE) {
-                        const half4 w = *p;
+                        const half8 w = wbuf[j & 1][i][a];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            out[e] = (_Float16)fmaf(-s, acc[i][j][4 * q4 + e], (float)w[e]);
+                        for (int e = 0; e < 8; ++e) out[e] = (_Float16)fmaf(-s, v[e], (float)w[e]);
                     } else {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) out[e] = (_Float16)acc[i][j][4 * q4 + e];
+                        for (int e = 0; e < 8; ++e) out[e] = (_Float16)v[e];
                     }
-                    *p = out;
+                    *reinterpret_cast<half8*>(row + ml) = out;
                 }
-            }
         }
     }
 }

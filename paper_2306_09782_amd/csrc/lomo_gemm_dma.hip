@@ -5,8 +5,9 @@
 //   * global -> LDS without passing through registers: global_load_lds_dwordx4 writes lane L's
 //     16 bytes to M0 + 16 L, and each lane may fetch any global address, so a wave instruction
 //     fills 1 KiB of LDS with the 16-byte chunks of two tile rows in swizzled order;
-//   * four 32 KiB stages: the loads for slice kt+3 are issued while slice kt is multiplied, which
-//     covers HBM latency with two and a half slices of MFMA work and needs no staging registers;
+//   * four 32 KiB stages: the loads for slice kt+3 are issued while slice kt is multiplied (one
+//     load instruction after every fourth MFMA, so the loads never queue up behind each other),
+//     which covers memory latency and needs no staging registers;
 //   * LDS -> MFMA operands with the transposing read ds_read_b64_tr_b16 (contraction-strided
 //     operands) or ds_read_b128 (contraction-contiguous operand of dgrad); the fragments of the
 //     next half-slice are read while the current one is multiplied, across the barrier;
@@ -22,7 +23,6 @@ namespace dma {
 
 constexpr int BM = 256, BN = 256, BK = 32, NS = 4;
 constexpr int A_HALVES = BK * BM, B_HALVES = BK * BN, STAGE_HALVES = A_HALVES + B_HALVES;
-constexpr int LOADS_PER_STAGE = 8;   // per wave: 4 for the A tile, 4 for the B tile
 
 __device__ __forceinline__ int swz_s(int r) { return ((r & 1) * 10) + ((r & 2) * 2); }
 __device__ __forceinline__ int swz_c(int n) { return ((n >> 1) & 3) ^ ((n >> 3) & 1); }
@@ -60,7 +60,11 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(GemmArgs g, int t
         const int bid = blockIdx.x;
         const int x = bid & 7, local = bid >> 3;
         const int q = total >> 3, r = total & 7;
+#ifdef LOMO_EXP_PLAIN_ORDER   // timing experiment: tiles in launch order
+        const int t = bid + 0 * (x + local + q + r);
+#else
         const int t = x * q + (x < r ? x : r) + local;
+#endif
         constexpr int GM = 8;
         const int per_band = GM * tiles_n;
         const int band = t / per_band;
@@ -106,16 +110,22 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(GemmArgs g, int t
     const int64_t b_step = B_STRIDED ? (int64_t)BK * g.ldb : (int64_t)BK;
     const int KT = (int)(g.C / BK);
 
-    auto issue = [&](int stage, int buf) {
+    // One DMA instruction: part 0 = A tile, part 1 = B tile; `it` selects this wave's KiB slot.
+    auto issue1 = [&](int stage, int buf, int part, int it) {
+#ifdef LOMO_EXP_NO_DMA   // timing experiment only: results are meaningless
+        return;
+#endif
         const int s = stage < KT ? stage : KT - 1;   // past the end: harmless re-read, keeps the counter regular
-        const uint16_t* a = pa + (int64_t)s * a_step;
-        const uint16_t* b = pb + (int64_t)s * b_step;
-        const uint32_t la = lds_wave + (uint32_t)buf * (STAGE_HALVES * 2u);
-        const uint32_t lb = la + A_HALVES * 2u;
+        const uint32_t l = lds_wave + (uint32_t)buf * (STAGE_HALVES * 2u) + (uint32_t)part * (A_HALVES * 2u) +
+                           (uint32_t)it * 1024u;
+        if (part == 0) dma16(a_voff[it], pa + (int64_t)s * a_step, l);
+        else dma16(b_voff[it], pb + (int64_t)s * b_step, l);
+    };
+    auto issue = [&](int stage) {
 #pragma unroll
-        for (int it = 0; it < 4; ++it) dma16(a_voff[it], a, la + it * 1024u);
+        for (int it = 0; it < 4; ++it) issue1(stage, stage & 3, 0, it);
 #pragma unroll
-        for (int it = 0; it < 4; ++it) dma16(b_voff[it], b, lb + it * 1024u);
+        for (int it = 0; it < 4; ++it) issue1(stage, stage & 3, 1, it);
     };
 
     // ---- fragment read offsets (halves), as in the register-staged fast path
@@ -130,67 +140,101 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(GemmArgs g, int t
         b_rd = nl * BK + ((lh ^ swz_c(nl)) * 8);
     }
 
-    // Reads are issued in the order the MFMAs consume them: a0, b0..b3, a1..a3.
-    auto load_frags = [&](half8 (&a)[4], half8 (&b)[4], int buf, int kk) {
-        const uint16_t* as = smem + buf * STAGE_HALVES;
-        const uint16_t* bs = as + A_HALVES;
-        auto read_a = [&](int i) {
-            const uint16_t* p = as + ((a_rd ^ (i << 5)) + kk * 16 * BM);
-            a[i] = read_tr8(p, p + 4 * BM);
-        };
-        read_a(0);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if constexpr (B_STRIDED) {
-                const uint16_t* p = bs + ((b_rd ^ (j << 5)) + kk * 16 * BN);
-                b[j] = read_tr8(p, p + 4 * BN);
-            } else {
-                b[j] = *reinterpret_cast<const half8*>(bs + ((b_rd ^ (kk << 4)) + j * 32 * BK));
-            }
-        }
-        read_a(1);
-        read_a(2);
-        read_a(3);
+    // Fragment reads, in the order the MFMAs consume them: a0, b0..b3, a1..a3, cut into four
+    // groups so that group q is read while MFMA group q (a[q] x b[0..3]) of the other set runs.
+    auto read_a = [&](half8 (&a)[4], int buf, int kk, int i) {
+        const uint16_t* p = smem + buf * STAGE_HALVES + ((a_rd ^ (i << 5)) + kk * 16 * BM);
+        a[i] = read_tr8(p, p + 4 * BM);
     };
-    auto mfma_all = [&](const half8 (&a)[4], const half8 (&b)[4]) {
+    auto read_b = [&](half8 (&b)[4], int buf, int kk, int j) {
+        const uint16_t* bs = smem + buf * STAGE_HALVES + A_HALVES;
+        if constexpr (B_STRIDED) {
+            const uint16_t* p = bs + ((b_rd ^ (j << 5)) + kk * 16 * BN);
+            b[j] = read_tr8(p, p + 4 * BN);
+        } else {
+            b[j] = *reinterpret_cast<const half8*>(bs + ((b_rd ^ (kk << 4)) + j * 32 * BK));
+        }
+    };
+    // Fragment groups.  EARLY packs the eight fragments into the first three groups, so that every
+    // read has completed when the half-slice ends at a barrier.
+    auto read_group = [&](half8 (&a)[4], half8 (&b)[4], int buf, int kk, int q, bool early) {
+#ifdef LOMO_EXP_NO_LDSREAD   // timing experiment only
+        if (buf >= 0) return;
+#endif
+        if (early) {
+            if (q == 0) { read_a(a, buf, kk, 0); read_b(b, buf, kk, 0); read_b(b, buf, kk, 1); }
+            if (q == 1) { read_b(b, buf, kk, 2); read_b(b, buf, kk, 3); read_a(a, buf, kk, 1); }
+            if (q == 2) { read_a(a, buf, kk, 2); read_a(a, buf, kk, 3); }
+        } else {
+            if (q == 0) { read_a(a, buf, kk, 0); read_b(b, buf, kk, 0); }
+            if (q == 1) { read_b(b, buf, kk, 1); read_b(b, buf, kk, 2); }
+            if (q == 2) { read_b(b, buf, kk, 3); read_a(a, buf, kk, 1); }
+            if (q == 3) { read_a(a, buf, kk, 2); read_a(a, buf, kk, 3); }
+        }
+    };
+    constexpr int RB = B_STRIDED ? 2 : 1;                       // LDS read instructions per b fragment
+    constexpr int READS_EARLY[4] = {2 + 2 * RB, 2 * RB + 2, 4, 0};
+    constexpr int READS_EVEN[4] = {2 + RB, 2 * RB, RB + 2, 4};
+    // Half a slice: 16 MFMAs on (ua, ub) in four groups; each group is preceded by the reads of one
+    // fragment group of the next half-slice and followed by one direct-to-LDS load, so that LDS reads,
+    // global loads and MFMAs overlap instead of queueing behind each other.
+    auto half_slice = [&](const half8 (&ua)[4], const half8 (&ub)[4], half8 (&la)[4], half8 (&lb)[4], int lbuf, int lkk,
+                          bool early, int dstage, int dbuf, int dpart) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int q = 0; q < 4; ++q) {
+            read_group(la, lb, lbuf, lkk, q, early);
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
-    };
-
-    // ---- prologue: three slices in flight, slice 0 landed and visible, its first fragments read
-    issue(0, 0);
-    issue(1, 1);
-    issue(2, 2);
-    asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
-    half8 fa0[4], fb0[4], fa1[4], fb1[4];
-    load_frags(fa0, fb0, 0, 0);
-
-    // One LDS read is slotted in front of each MFMA, so the fragments of the next half-slice
-    // arrive while the current one is multiplied.
-    auto interleave = [] {
+                acc[q][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ua[q], ub[j], acc[q][j], 0, 0, 0);
+#ifndef LOMO_EXP_NO_LDSREAD
+            {   // spread this group's reads in front of its four MFMAs
+                int left = early ? READS_EARLY[q] : READS_EVEN[q];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one DS read
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                for (int j = 0; j < 4; ++j) {
+                    const int now = (left + (3 - j)) / (4 - j);
+                    if (now == 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS reads
+                    if (now == 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                    if (now == 3) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    left -= now;
+                }
+            }
+#endif
+            __builtin_amdgcn_sched_barrier(0);
+            issue1(dstage, dbuf, dpart, q);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 3;
-        load_frags(fa1, fb1, cur, 1);
-        mfma_all(fa0, fb0);
-        interleave();
-        __builtin_amdgcn_sched_barrier(0);
-        issue(kt + 3, (kt + 3) & 3);
-        // own loads of slice kt+1 landed (two younger slices may still fly); own LDS reads done
-        asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        __builtin_amdgcn_sched_barrier(0);
-        load_frags(fa0, fb0, (kt + 1) & 3, 0);
-        mfma_all(fa1, fb1);
-        interleave();
-        __builtin_amdgcn_sched_barrier(0);
+
+    // ---- prologue: slices 0..2 and the A part of slice 3 in flight; slice 0 landed and visible
+    issue(0);
+    issue(1);
+    issue(2);
+#pragma unroll
+    for (int it = 0; it < 4; ++it) issue1(3, 3, 0, it);
+    asm volatile("s_waitcnt vmcnt(20)\n\ts_barrier" ::: "memory");
+    half8 fa0[4], fb0[4], fa1[4], fb1[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) read_group(fa0, fb0, 0, 0, q, false);
+
+    // KT is a multiple of 4: the body is unrolled over the four LDS stages so that every LDS
+    // address is a register plus an immediate.
+    for (int kt = 0; kt < KT; kt += 4) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            // first half of slice kt+u; reads its second half's fragments; loads the B part of slice kt+u+3
+            half_slice(fa0, fb0, fa1, fb1, u, 1, true, kt + u + 3, (u + 3) & 3, 1);
+            // own loads of slice kt+u+1 landed (two younger slices may still fly); own LDS reads done
+#ifdef LOMO_EXP_NO_BARRIER   // timing experiment only: waves drift apart, results are meaningless
+            asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
+#else
+            asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#endif
+            __builtin_amdgcn_sched_barrier(0);
+            // second half; reads the first fragments of the next slice; loads the A part of slice
+            // kt+u+4 into the buffer of slice kt+u, which nobody reads any more
+            half_slice(fa1, fb1, fa0, fb0, (u + 1) & 3, 0, false, kt + u + 4, u, 0);
+        }
     }
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
@@ -213,11 +257,11 @@ static hipError_t launch_dma_one(const GemmArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
-// Eligible: whole 256 x 256 x 32 tiles, enough of them to fill the chip, 32-bit slice offsets.
+// Eligible: whole 256 x 256 tiles, contraction a multiple of 128, enough of them to fill the chip, 32-bit slice offsets.
 template <bool B_STRIDED, int EPI>
 bool try_launch_dma(const GemmArgs& a, hipStream_t st, hipError_t* err) {
     using namespace dma;
-    const bool ok = a.M > 0 && a.Nn > 0 && a.C >= BK && a.M % BM == 0 && a.Nn % BN == 0 && a.C % BK == 0 &&
+    const bool ok = a.M > 0 && a.Nn > 0 && a.C >= 4 * BK && a.M % BM == 0 && a.Nn % BN == 0 && a.C % (4 * BK) == 0 &&
                     (int64_t)BK * a.lda < (1 << 30) && (int64_t)BN * a.ldb < (1 << 30) &&
                     (a.M / BM) * (a.Nn / BN) >= 192 && (a.M / BM) * (a.Nn / BN) < (1 << 24);
     if (!ok) return false;
