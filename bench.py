@@ -24,6 +24,18 @@ if ROOT not in sys.path:
 PEAK_FP16_TFLOPS = 2500.0     # MI355X dense fp16 MFMA peak, published
 
 
+def profiled_traffic(workload_name):
+    """HBM-side bytes per launch of the fused kernel, from the committed rocprofv3 --pmc summary."""
+    path = os.path.join(ROOT, "profiles", f"lomo_contract_{workload_name}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if "traffic_bytes_per_launch:" in line:
+                return int(line.split("traffic_bytes_per_launch:")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(wl, max_seconds=25.0):
     """The oracle as it stands, on a bounded sample: the first linear tensors of the workload."""
     import numpy as np
@@ -63,6 +75,8 @@ def main():
                     help="llama7b_layer (default), linear1024, llama7b_stack[:layers], llama13b_stack[:n], ...")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dgrad", action="store_true", help="skip dX (diagnostic only; not the metric)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy three times (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one MI355X); --gpus must be 1", file=sys.stderr)
@@ -92,6 +106,14 @@ def main():
             t["dX"] = torch.empty(spec.T, spec.K, dtype=torch.float16, device=dev)
         tensors.append(t)
     torch.cuda.synchronize()
+
+    if args.calibrate_copy:      # known traffic: 1 GiB read + 1 GiB written per copy
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     maxH = max(s.K for s in wl.tensors)
     stepper = LomoStep(dev, max_T=wl.T, max_H=maxH, max_tensors=len(tensors))
@@ -130,9 +152,9 @@ def main():
     k1 = fam_rate("wgrad_update")
     roofline = None
     if k1:
-        roofline = {"kernel": "lomo_contract_kernel<EPI_UPDATE> (fused wgrad + SGD update)", "bound": "mfma",
+        roofline = {"kernel": "fused wgrad + SGD update (lomo_contract_dma_kernel<true, EPI_UPDATE>)", "bound": "mfma",
                     "achieved": k1["tflops"], "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": k1["tflops"] / PEAK_FP16_TFLOPS, "traffic": None,
+                    "frac": k1["tflops"] / PEAK_FP16_TFLOPS, "traffic": profiled_traffic(wl.name),
                     "flops_per_launch": flops_pass / len(lin), "avg_launch_ms": k1["avg_launch_ms"],
                     "launches_timed": k1["launches"]}
 
