@@ -92,8 +92,33 @@ def _i64(v: int) -> int:
     return v - (1 << 64) if v >= (1 << 63) else v
 
 
-def normal_f16_torch(key: int, shape, mult, device, out=None):
-    """Device twin of :func:`normal_f16_np` (full tensor only). Integer ops wrap mod 2^64."""
+_GEN_LIB = None
+
+
+def _gen_lib():
+    """The HIP generator kernel (built in-tree next to this file), or None if it is not built."""
+    global _GEN_LIB
+    if _GEN_LIB is None:
+        import ctypes
+        import os
+        path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libsynthgen.so")
+        if not os.path.exists(path):
+            _GEN_LIB = False
+        else:
+            lib = ctypes.CDLL(path)
+            lib.synth_normal_f16.argtypes = [ctypes.c_uint64, ctypes.c_int64, ctypes.c_int64, ctypes.c_float,
+                                             ctypes.c_void_p, ctypes.c_void_p]
+            lib.synth_normal_f16.restype = ctypes.c_int
+            _GEN_LIB = lib
+    return _GEN_LIB or None
+
+
+def normal_f16_torch(key: int, shape, mult, device, out=None, force_torch_ops: bool = False):
+    """Device twin of :func:`normal_f16_np` (full tensor only). Integer ops wrap mod 2^64.
+
+    On a GPU the fill is one HIP kernel when lomo_synth/lib/libsynthgen.so is built; otherwise (and
+    on the CPU) the same integer recipe runs as torch tensor ops.
+    """
     import torch
 
     n = 1
@@ -103,6 +128,14 @@ def normal_f16_torch(key: int, shape, mult, device, out=None):
         out = torch.empty(n, dtype=torch.float16, device=device)
     flat_out = out.view(-1)
     m = float(np.float32(mult))
+    lib = None if force_torch_ops else _gen_lib()
+    if lib is not None and flat_out.is_cuda:
+        import ctypes
+        rc = lib.synth_normal_f16(key & MASK64, 0, n, m, ctypes.c_void_p(flat_out.data_ptr()),
+                                  ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+        if rc != 0:
+            raise RuntimeError("synth_normal_f16 launch failed")
+        return out.view(*[int(d) for d in shape])
     chunk = 1 << 24
     k, g, m1, m2 = _i64(key), _i64(GOLDEN), _i64(MIX1), _i64(MIX2)
     for i0 in range(0, n, chunk):

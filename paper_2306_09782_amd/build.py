@@ -37,5 +37,21 @@ def build(verbose: bool = True, extra_flags=(), out_path: str = LIB_PATH) -> str
     return out_path
 
 
+def build_synth(verbose: bool = True) -> str:
+    """The input-generator kernel of lomo_synth (not part of the product library)."""
+    src = os.path.join(ROOT, "lomo_synth", "csrc", "synth_gen.hip")
+    out = os.path.join(ROOT, "lomo_synth", "lib", "libsynthgen.so")
+    os.makedirs(os.path.dirname(out), exist_ok=True)
+    cmd = [HIPCC, *FLAGS, src, "-o", out]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        sys.stderr.write(res.stderr)
+        raise RuntimeError("hipcc failed (synth generator)")
+    return out
+
+
 if __name__ == "__main__":
     build()
+    build_synth()

@@ -143,12 +143,20 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(GemmArgs g, int t
     // Fragment reads, in the order the MFMAs consume them: a0, b0..b3, a1..a3, cut into four
     // groups so that group q is read while MFMA group q (a[q] x b[0..3]) of the other set runs.
     auto read_a = [&](half8 (&a)[4], int buf, int kk, int i) {
+#ifdef LOMO_EXP_B128_READS   // timing experiment only: plain 16-byte reads, results are meaningless
+        a[i] = *reinterpret_cast<const half8*>(smem + buf * STAGE_HALVES + (lane & 31) * 32 + (lane >> 5) * 8 + kk * 16 + i * 1024);
+        return;
+#endif
         const uint16_t* p = smem + buf * STAGE_HALVES + ((a_rd ^ (i << 5)) + kk * 16 * BM);
         a[i] = read_tr8(p, p + 4 * BM);
     };
     auto read_b = [&](half8 (&b)[4], int buf, int kk, int j) {
         const uint16_t* bs = smem + buf * STAGE_HALVES + A_HALVES;
         if constexpr (B_STRIDED) {
+#ifdef LOMO_EXP_B128_READS
+            b[j] = *reinterpret_cast<const half8*>(bs + (lane & 31) * 32 + (lane >> 5) * 8 + kk * 16 + j * 1024);
+            return;
+#endif
             const uint16_t* p = bs + ((b_rd ^ (j << 5)) + kk * 16 * BN);
             b[j] = read_tr8(p, p + 4 * BN);
         } else {

@@ -305,3 +305,5 @@ def test_generators_agree_on_device():
         a = S.normal_f16_np(key, (300, 520), mult)
         b = S.normal_f16_torch(key, (300, 520), mult, DEV).cpu().numpy()
         np.testing.assert_array_equal(a.view(np.uint16), b.view(np.uint16))
+        c = S.normal_f16_torch(key, (300, 520), mult, DEV, force_torch_ops=True).cpu().numpy()
+        np.testing.assert_array_equal(a.view(np.uint16), c.view(np.uint16))
