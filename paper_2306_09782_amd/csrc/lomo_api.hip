@@ -45,6 +45,7 @@ lomo_status lomo_wgrad_sqnorm(const lomo_half* X, const lomo_half* dY, int64_t T
     a.M = K; a.Nn = N; a.C = T;
     a.lda = K; a.ldb = N; a.ldo = K;
     a.acc = acc; a.flag_out = overflow_flag;
+    a.family = LOMO_KERNEL_WGRAD_SQNORM;
     return from_hip(launch_wgrad_sqnorm(a, static_cast<hipStream_t>(stream)));
 }
 
@@ -63,6 +64,7 @@ lomo_status lomo_linear_backward_update(const lomo_half* X, const lomo_half* dY,
         d.A = W; d.B = dY; d.Out = dX;
         d.M = K; d.Nn = T; d.C = N;
         d.lda = K; d.ldb = N; d.ldo = K;
+        d.family = LOMO_KERNEL_DGRAD;
         hipError_t e = launch_dgrad(d, st);
         if (e != hipSuccess) return LOMO_ERR_LAUNCH;
     }
@@ -72,6 +74,7 @@ lomo_status lomo_linear_backward_update(const lomo_half* X, const lomo_half* dY,
     a.lda = K; a.ldb = N; a.ldo = K;
     a.s = step_size(lr, inv_loss_scale, clip_coef);
     a.flag_in = overflow_flag;
+    a.family = LOMO_KERNEL_WGRAD_UPDATE;
     return from_hip(launch_wgrad_update(a, st));
 }
 

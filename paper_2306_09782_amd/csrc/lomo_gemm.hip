@@ -208,8 +208,7 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t st) {
     }
     const int64_t tiles = ((a.M + BM - 1) / BM) * ((a.Nn + BN - 1) / BN);
     if (tiles > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(NT), lds, st, a);
-    return hipGetLastError();
+    return launch_timed(a.family, kern, dim3((unsigned)tiles), dim3(NT), lds, st, a);
 }
 
 // Tile choice: 256 x 256 when that still gives every CU at least one tile, else 128 x 128.
@@ -237,7 +236,6 @@ static bool dma_enabled() {
 }
 
 hipError_t launch_wgrad_update(const GemmArgs& a, hipStream_t st) {
-    ScopedTiming t(LOMO_KERNEL_WGRAD_UPDATE, st);
     hipError_t e;
     if (fast_enabled() && dma_enabled() && try_launch_dma<true, EPI_UPDATE>(a, st, &e)) return e;
     if (fast_enabled() && try_launch_fast<true, EPI_UPDATE>(a, st, &e)) return e;
@@ -245,7 +243,6 @@ hipError_t launch_wgrad_update(const GemmArgs& a, hipStream_t st) {
                                     : launch_one<128, 128, true, EPI_UPDATE>(a, st);
 }
 hipError_t launch_wgrad_sqnorm(const GemmArgs& a, hipStream_t st) {
-    ScopedTiming t(LOMO_KERNEL_WGRAD_SQNORM, st);
     hipError_t e;
     if (fast_enabled() && dma_enabled() && try_launch_dma<true, EPI_SQNORM>(a, st, &e)) return e;
     if (fast_enabled() && try_launch_fast<true, EPI_SQNORM>(a, st, &e)) return e;
@@ -253,7 +250,6 @@ hipError_t launch_wgrad_sqnorm(const GemmArgs& a, hipStream_t st) {
                                     : launch_one<128, 128, true, EPI_SQNORM>(a, st);
 }
 hipError_t launch_dgrad(const GemmArgs& a, hipStream_t st) {
-    ScopedTiming t(LOMO_KERNEL_DGRAD, st);
     hipError_t e;
     if (fast_enabled() && dma_enabled() && try_launch_dma<false, EPI_STORE>(a, st, &e)) return e;
     if (fast_enabled() && try_launch_fast<false, EPI_STORE>(a, st, &e)) return e;

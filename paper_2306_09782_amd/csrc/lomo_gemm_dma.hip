@@ -261,8 +261,7 @@ static hipError_t launch_dma_one(const GemmArgs& a, hipStream_t st) {
         configured = true;
     }
     const int tiles_m = (int)(a.M / dma::BM), tiles_n = (int)(a.Nn / dma::BN);
-    hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(NT), lds, st, a, tiles_m, tiles_n);
-    return hipGetLastError();
+    return launch_timed(a.family, kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(NT), lds, st, a, tiles_m, tiles_n);
 }
 
 // Eligible: whole 256 x 256 tiles, contraction a multiple of 128, enough of them to fill the chip, 32-bit slice offsets.

@@ -201,8 +201,7 @@ static hipError_t launch_fast_one(const GemmArgs& a, hipStream_t st) {
         configured = true;
     }
     const int tiles_m = (int)(a.M / BM), tiles_n = (int)(a.Nn / BN);
-    hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(NT), lds, st, a, tiles_m, tiles_n);
-    return hipGetLastError();
+    return launch_timed(a.family, kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(NT), lds, st, a, tiles_m, tiles_n);
 }
 
 // Eligible: whole tiles in every dimension and offsets that fit 32-bit element indices.

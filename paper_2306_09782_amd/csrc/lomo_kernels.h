@@ -1,6 +1,7 @@
 // Internal launch interface between the C-ABI shim and the HIP kernels (not installed).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "lomo.h"
@@ -20,6 +21,7 @@ enum Epilogue : int {
 // wgrad: A = X, B = dY (strided), Out = W;   M = K_in, Nn = N_out, C = T.
 // dgrad: A = W, B = dY (contiguous), Out = dX; M = K_in, Nn = T, C = N_out.
 struct GemmArgs {
+    int family;              // LOMO_KERNEL_* of this launch (host side only: timing)
     const uint16_t* A;
     const uint16_t* B;
     uint16_t* Out;
@@ -64,7 +66,10 @@ hipError_t launch_vector(const uint16_t* Xhat, const uint16_t* dY, uint16_t* w, 
                          void* ws, int mode, float s, double* acc, int32_t* flag_out, const int32_t* flag_in,
                          hipStream_t st);
 
-// Event timing (lomo_timing.hip): begin returns true iff a start event was recorded.
+// Event timing (lomo_timing.hip).  Contraction kernels attach the events to their own dispatch
+// (no extra packets on the stream); multi-kernel families bracket their launches instead.
+bool timing_slot(int family, hipEvent_t* start, hipEvent_t* stop);
+// begin returns true iff a start event was recorded.
 bool timing_begin(int family, hipStream_t st);
 void timing_end(int family, hipStream_t st);
 struct ScopedTiming {
@@ -76,6 +81,15 @@ struct ScopedTiming {
         if (on) timing_end(family, st);
     }
 };
+
+// Launch with the family's timing events attached when timing is on.
+template <typename Kern, typename... Args>
+inline hipError_t launch_timed(int family, Kern kern, dim3 grid, dim3 block, size_t lds, hipStream_t st, Args... args) {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (timing_slot(family, &e0, &e1)) hipExtLaunchKernelGGL(kern, grid, block, (uint32_t)lds, st, e0, e1, 0, args...);
+    else hipLaunchKernelGGL(kern, grid, block, lds, st, args...);
+    return hipGetLastError();
+}
 
 hipError_t launch_reduce_flags(const int32_t* flags, int64_t n, int32_t* out, hipStream_t st);
 

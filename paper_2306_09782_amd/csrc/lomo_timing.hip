@@ -20,6 +20,28 @@ Pool g_pool[LOMO_KERNEL_FAMILIES];
 constexpr size_t kMaxEventsPerFamily = 1u << 16;
 }  // namespace
 
+// Hands out the next (start, stop) event pair of a family for a launch that records them as part
+// of its own dispatch; the pair counts as used.  False when timing is off.
+bool timing_slot(int family, hipEvent_t* start, hipEvent_t* stop) {
+    if (!g_on) return false;
+    std::lock_guard<std::mutex> lk(g_mu);
+    Pool& p = g_pool[family];
+    if (p.used == p.ev.size()) {
+        if (p.ev.size() >= kMaxEventsPerFamily) return false;
+        hipEvent_t a, b;
+        if (hipEventCreate(&a) != hipSuccess) return false;
+        if (hipEventCreate(&b) != hipSuccess) {
+            (void)hipEventDestroy(a);
+            return false;
+        }
+        p.ev.emplace_back(a, b);
+    }
+    *start = p.ev[p.used].first;
+    *stop = p.ev[p.used].second;
+    p.used++;
+    return true;
+}
+
 bool timing_begin(int family, hipStream_t st) {
     if (!g_on) return false;
     std::lock_guard<std::mutex> lk(g_mu);
