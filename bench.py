@@ -97,6 +97,8 @@ def main():
                     help="llama7b_layer (default), linear1024, llama7b_stack[:layers], llama13b_stack[:n], ...")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dgrad", action="store_true", help="skip dX (diagnostic only; not the metric)")
+    ap.add_argument("--per-tensor-calls", action="store_true",
+                    help="one C call per tensor instead of the whole-pass calls (same results, more launches)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -138,7 +140,7 @@ def main():
         del src, dst
 
     maxH = max(s.K for s in wl.tensors)
-    stepper = LomoStep(dev, max_T=wl.T, max_H=maxH, max_tensors=len(tensors))
+    stepper = LomoStep(dev, max_T=wl.T, max_H=maxH, max_tensors=len(tensors), grouped=not args.per_tensor_calls)
     lr = float(np.float32(wl.lr))
 
     res = None
@@ -177,7 +179,7 @@ def main():
         roofline = {"kernel": "fused wgrad + SGD update (lomo_contract_dma_kernel<true, EPI_UPDATE>)", "bound": "mfma",
                     "achieved": k1["tflops"], "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s",
                     "frac": k1["tflops"] / PEAK_FP16_TFLOPS, "traffic": profiled_traffic(wl.name),
-                    "flops_per_launch": flops_pass / len(lin), "avg_launch_ms": k1["avg_launch_ms"],
+                    "flops_per_launch": flops_pass * args.steps / k1["launches"], "avg_launch_ms": k1["avg_launch_ms"],
                     "launches_timed": k1["launches"]}
 
     out = {
@@ -187,7 +189,8 @@ def main():
         "dtype": "f16", "accumulate": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "tokens": wl.T, "tensors": len(wl.tensors), "params": wl.n_params,
                    "loss_scale": wl.loss_scale, "lr": wl.lr, "max_norm": wl.max_norm,
-                   "gemms_per_linear": gemms_per_step, "weights_restored_between_steps": False},
+                   "gemms_per_linear": gemms_per_step, "weights_restored_between_steps": False,
+                   "calls": "per_tensor" if args.per_tensor_calls else "whole_pass"},
         "params_per_s": wl.n_params / (ms_per_step * 1e-3),
         "frac_fp16_mfma_peak_whole_step": tflops / PEAK_FP16_TFLOPS,
         "kernels": {k: fam_rate(k) for k in ("wgrad_update", "wgrad_sqnorm", "dgrad")},

@@ -125,6 +125,44 @@ lomo_status lomo_vector_update(const lomo_half* Xhat, const lomo_half* dY, lomo_
                                const int32_t* overflow_flag,
                                void* ws, size_t ws_bytes, void* stream);
 
+/* ---------------------------------------------------------------- whole passes over a list of tensors
+ *
+ * The same two passes, taken over all tensors of a step in one call each, so that the library can run
+ * the contractions of many tensors in a few persistent launches (one ramp-up per pass, partial last
+ * rounds of one tensor filled with tiles of the next).  Results are those of the per-tensor calls
+ * above made in list order: within the update pass every dX is computed from pre-update weights
+ * (all dgrads run before any update), and tensors are independent otherwise (Algorithm 1 couples
+ * them only through the clipping coefficient). */
+
+typedef enum { LOMO_TENSOR_LINEAR = 0, LOMO_TENSOR_EMBEDDING = 1, LOMO_TENSOR_VECTOR = 2 } lomo_tensor_kind;
+
+typedef struct {
+    int32_t kind;          /* lomo_tensor_kind                                                     */
+    const lomo_half* X;    /* linear: X [T x K]; vector: xhat [T x K]; embedding: unused (NULL)     */
+    const lomo_half* dY;   /* linear: [T x N]; embedding and vector: [T x K]                        */
+    lomo_half* W;          /* linear: [N x K]; embedding: [N x K] (N = vocabulary); vector: [K]     */
+    lomo_half* dX;         /* linear only, may be NULL                                              */
+    const int32_t* ids;    /* embedding only: [T]                                                   */
+    int64_t T, K, N;       /* linear: K in-features, N out-features; embedding: K = H, N = V;
+                              vector: K = H, N = 1                                                  */
+} lomo_tensor;
+
+/* Device workspace needed by the row kernels of the listed tensors (host function). */
+size_t lomo_step_workspace_bytes(const lomo_tensor* tensors, int64_t n);
+
+/* Pass 1 over tensors[0..n) (host array of descriptors, device buffers inside): acc[0] += the squared
+ * norm of every scaled gradient; flags[i] |= 1 if tensor i's gradient holds inf/NaN; finally
+ * flags[n] = any(flags[0..n)).  acc (device double) and flags (device int32[n + 1]) are zeroed by the
+ * caller.  W and dX members are ignored. */
+lomo_status lomo_step_norm_pass(const lomo_tensor* tensors, int64_t n, double* acc, int32_t* flags,
+                                void* ws, size_t ws_bytes, void* stream);
+
+/* Pass 2 over the same list: dX (where given) and the fused gradient + SGD update of every tensor,
+ * W <- round_fp16(W - lr * clip_coef * inv_loss_scale * G), skipped entirely if step_flag[0] != 0. */
+lomo_status lomo_step_update_pass(const lomo_tensor* tensors, int64_t n,
+                                  float lr, float inv_loss_scale, float clip_coef,
+                                  const int32_t* step_flag, void* ws, size_t ws_bytes, void* stream);
+
 /* ---------------------------------------------------------------- helpers */
 
 /* Workspace sizes in bytes (host functions; 0 for T == 0). */

@@ -9,6 +9,8 @@ from .binding import (LomoError, library_path, load_library, lomo_version, lomo_
                       lomo_reduce_flags, lomo_linear_backward_update, lomo_embedding_update,
                       lomo_vector_update, lomo_embedding_workspace_bytes, lomo_vector_workspace_bytes,
                       lomo_embedding_grouping, lomo_timing_enable, lomo_timing_read, KERNEL_FAMILIES,
+                      lomo_step_workspace_bytes, lomo_step_norm_pass, lomo_step_update_pass, make_tensor_list,
+                      LomoTensor,
                       EXPORTED_SYMBOLS)
 
 __all__ = [n for n in dir() if n.startswith("lomo_")] + ["LomoError", "library_path", "load_library",

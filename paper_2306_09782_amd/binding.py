@@ -17,7 +17,17 @@ EXPORTED_SYMBOLS = (
     "lomo_clip_coef", "lomo_scaler_step", "lomo_reduce_flags", "lomo_linear_backward_update",
     "lomo_embedding_update", "lomo_vector_update", "lomo_embedding_workspace_bytes",
     "lomo_vector_workspace_bytes", "lomo_embedding_grouping", "lomo_timing_enable", "lomo_timing_read",
+    "lomo_step_workspace_bytes", "lomo_step_norm_pass", "lomo_step_update_pass",
 )
+
+
+class LomoTensor(ctypes.Structure):
+    """Mirror of the C struct lomo_tensor."""
+    _fields_ = [("kind", c_int32), ("X", c_void_p), ("dY", c_void_p), ("W", c_void_p), ("dX", c_void_p),
+                ("ids", c_void_p), ("T", c_int64), ("K", c_int64), ("N", c_int64)]
+
+
+KIND_CODES = {"linear": 0, "embedding": 1, "vector": 2}
 
 
 class LomoError(RuntimeError):
@@ -55,6 +65,9 @@ def load_library():
         "lomo_embedding_workspace_bytes": (c_size_t, [I64, I64]),
         "lomo_vector_workspace_bytes": (c_size_t, [I64, I64]),
         "lomo_embedding_grouping": (c_int, [P, I64, I64, P, c_size_t, P, P, P, P, P]),
+        "lomo_step_workspace_bytes": (c_size_t, [POINTER(LomoTensor), I64]),
+        "lomo_step_norm_pass": (c_int, [POINTER(LomoTensor), I64, P, P, P, c_size_t, P]),
+        "lomo_step_update_pass": (c_int, [POINTER(LomoTensor), I64, c_float, c_float, c_float, P, P, c_size_t, P]),
         "lomo_timing_enable": (c_int, [c_int]),
         "lomo_timing_read": (c_int, [c_int, POINTER(c_double), POINTER(c_int64)]),
     }
@@ -175,3 +188,42 @@ def lomo_timing_read(family: int):
     ms, n = c_double(0.0), c_int64(0)
     _check(load_library().lomo_timing_read(family, ctypes.byref(ms), ctypes.byref(n)))
     return ms.value, n.value
+
+
+def make_tensor_list(tensors):
+    """ctypes array of lomo_tensor from records {kind, X / ids, dY, W, dX?} holding torch tensors."""
+    arr = (LomoTensor * len(tensors))()
+    for rec, t in zip(arr, tensors):
+        kind = t["kind"]
+        rec.kind = KIND_CODES[kind]
+        dY, W = t["dY"], t["W"]
+        rec.dY, rec.W = dY.data_ptr(), W.data_ptr()
+        rec.T = dY.shape[0]
+        if kind == "linear":
+            X = t["X"]
+            rec.X, rec.K, rec.N = X.data_ptr(), X.shape[1], dY.shape[1]
+            dX = t.get("dX")
+            rec.dX = dX.data_ptr() if dX is not None else None
+            assert tuple(W.shape) == (rec.N, rec.K) and X.shape[0] == rec.T
+        elif kind == "embedding":
+            rec.ids, rec.K, rec.N = t["ids"].data_ptr(), dY.shape[1], W.shape[0]
+            assert W.shape[1] == rec.K and t["ids"].numel() == rec.T
+        else:
+            rec.X, rec.K, rec.N = t["X"].data_ptr(), dY.shape[1], 1
+            assert W.numel() == rec.K
+    return arr
+
+
+def lomo_step_workspace_bytes(tensor_list) -> int:
+    return load_library().lomo_step_workspace_bytes(tensor_list, len(tensor_list))
+
+
+def lomo_step_norm_pass(tensor_list, acc, flags, ws, stream=None):
+    assert flags.numel() >= len(tensor_list) + 1
+    _check(load_library().lomo_step_norm_pass(tensor_list, len(tensor_list), _ptr(acc), _ptr(flags), _ptr(ws),
+                                              _nbytes(ws), _stream(stream)))
+
+
+def lomo_step_update_pass(tensor_list, lr, inv_loss_scale, clip_coef, step_flag, ws, stream=None):
+    _check(load_library().lomo_step_update_pass(tensor_list, len(tensor_list), lr, inv_loss_scale, clip_coef,
+                                                _ptr(step_flag), _ptr(ws), _nbytes(ws), _stream(stream)))

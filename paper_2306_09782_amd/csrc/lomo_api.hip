@@ -5,6 +5,8 @@
 
 #include <math.h>
 
+#include <vector>
+
 using namespace lomo;
 
 namespace {
@@ -170,6 +172,140 @@ lomo_status lomo_vector_update(const lomo_half* Xhat, const lomo_half* dY, lomo_
     ScopedTiming timing(LOMO_KERNEL_VECTOR, static_cast<hipStream_t>(stream));
     return from_hip(launch_vector(Xhat, dY, w, T, H, ws, 1, step_size(lr, inv_loss_scale, clip_coef), nullptr, nullptr,
                                   overflow_flag, static_cast<hipStream_t>(stream)));
+}
+
+// ---- whole passes ------------------------------------------------------------------------
+
+static lomo_status check_linear(const lomo_tensor& t, bool need_w) {
+    if (t.T < 0 || t.K < 0 || t.N < 0 || (t.K & 7) || (t.N & 7)) return LOMO_ERR_SHAPE;
+    if (t.T == 0 || t.K == 0 || t.N == 0) return LOMO_OK;
+    if (!t.X || !t.dY || (need_w && !t.W)) return LOMO_ERR_NULL;
+    if (misaligned(t.X) || misaligned(t.dY) || (need_w && (misaligned(t.W) || misaligned(t.dX)))) return LOMO_ERR_ALIGN;
+    return LOMO_OK;
+}
+
+size_t lomo_step_workspace_bytes(const lomo_tensor* tensors, int64_t n) {
+    size_t need = 0;
+    if (!tensors) return 0;
+    for (int64_t i = 0; i < n; ++i) {
+        size_t b = 0;
+        if (tensors[i].kind == LOMO_TENSOR_EMBEDDING) b = embedding_ws_bytes(tensors[i].T, tensors[i].K);
+        if (tensors[i].kind == LOMO_TENSOR_VECTOR) b = vector_ws_bytes(tensors[i].T, tensors[i].K);
+        if (b > need) need = b;
+    }
+    return need;
+}
+
+static lomo_status check_step(const lomo_tensor* tensors, int64_t n, bool update, void* ws, size_t ws_bytes) {
+    if (n < 0) return LOMO_ERR_SHAPE;
+    if (n > 0 && !tensors) return LOMO_ERR_NULL;
+    for (int64_t i = 0; i < n; ++i) {
+        const lomo_tensor& t = tensors[i];
+        lomo_status s;
+        if (t.kind == LOMO_TENSOR_LINEAR) {
+            s = check_linear(t, update);
+        } else if (t.kind == LOMO_TENSOR_EMBEDDING) {
+            s = check_embedding(t.ids, t.dY, t.T, t.K, t.N, ws, ws_bytes);
+            if (s == LOMO_OK && update && t.T > 0 && t.K > 0 && t.N > 0 && (!t.W || misaligned(t.W))) s = t.W ? LOMO_ERR_ALIGN : LOMO_ERR_NULL;
+        } else if (t.kind == LOMO_TENSOR_VECTOR) {
+            s = check_vector(t.X, t.dY, t.T, t.K, ws, ws_bytes);
+            if (s == LOMO_OK && update && t.T > 0 && t.K > 0 && !t.W) s = LOMO_ERR_NULL;
+        } else {
+            s = LOMO_ERR_SHAPE;
+        }
+        if (s != LOMO_OK) return s;
+    }
+    return LOMO_OK;
+}
+
+lomo_status lomo_step_norm_pass(const lomo_tensor* tensors, int64_t n, double* acc, int32_t* flags, void* ws,
+                                size_t ws_bytes, void* stream) {
+    lomo_status cs = check_step(tensors, n, false, ws, ws_bytes);
+    if (cs != LOMO_OK) return cs;
+    if (!acc || !flags) return LOMO_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(acc) & 7u) return LOMO_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    std::vector<GemmArgs> grouped;
+    for (int64_t i = 0; i < n; ++i) {
+        const lomo_tensor& t = tensors[i];
+        if (t.T == 0 || t.K == 0 || t.N == 0) continue;
+        if (t.kind == LOMO_TENSOR_LINEAR) {
+            GemmArgs a{};
+            a.A = t.X; a.B = t.dY; a.Out = nullptr;
+            a.M = t.K; a.Nn = t.N; a.C = t.T;
+            a.lda = t.K; a.ldb = t.N; a.ldo = t.K;
+            a.acc = acc; a.flag_out = flags + i;
+            a.family = LOMO_KERNEL_WGRAD_SQNORM;
+            if (dma_eligible(a)) grouped.push_back(a);
+            else if (launch_wgrad_sqnorm(a, st) != hipSuccess) return LOMO_ERR_LAUNCH;
+        } else if (t.kind == LOMO_TENSOR_EMBEDDING) {
+            EmbeddingWs w = carve_embedding_ws(ws, t.T);
+            ScopedTiming timing(LOMO_KERNEL_EMBEDDING, st);
+            if (launch_embedding_grouping(t.ids, t.T, w, st) != hipSuccess) return LOMO_ERR_LAUNCH;
+            if (launch_embedding_rows(t.dY, nullptr, t.T, t.K, w, 0, 0.f, acc, flags + i, nullptr, st) != hipSuccess)
+                return LOMO_ERR_LAUNCH;
+        } else {
+            ScopedTiming timing(LOMO_KERNEL_VECTOR, st);
+            if (launch_vector(t.X, t.dY, nullptr, t.T, t.K, ws, 0, 0.f, acc, flags + i, nullptr, st) != hipSuccess)
+                return LOMO_ERR_LAUNCH;
+        }
+    }
+    if (!grouped.empty() && launch_dma_group<true, EPI_SQNORM>(grouped.data(), (int)grouped.size(), st) != hipSuccess)
+        return LOMO_ERR_LAUNCH;
+    return from_hip(launch_reduce_flags(flags, n, flags + n, st));
+}
+
+lomo_status lomo_step_update_pass(const lomo_tensor* tensors, int64_t n, float lr, float inv_loss_scale,
+                                  float clip_coef, const int32_t* step_flag, void* ws, size_t ws_bytes, void* stream) {
+    lomo_status cs = check_step(tensors, n, true, ws, ws_bytes);
+    if (cs != LOMO_OK) return cs;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const float s = step_size(lr, inv_loss_scale, clip_coef);
+    std::vector<GemmArgs> dgrads, updates, updates_plain;
+    // every dgrad first: dX must come from the pre-update weights
+    for (int64_t i = 0; i < n; ++i) {
+        const lomo_tensor& t = tensors[i];
+        if (t.kind != LOMO_TENSOR_LINEAR || t.T == 0 || t.K == 0 || t.N == 0) continue;
+        if (t.dX) {
+            GemmArgs d{};
+            d.A = t.W; d.B = t.dY; d.Out = t.dX;
+            d.M = t.K; d.Nn = t.T; d.C = t.N;
+            d.lda = t.K; d.ldb = t.N; d.ldo = t.K;
+            d.family = LOMO_KERNEL_DGRAD;
+            if (dma_eligible(d)) dgrads.push_back(d);
+            else if (launch_dgrad(d, st) != hipSuccess) return LOMO_ERR_LAUNCH;
+        }
+        GemmArgs a{};
+        a.A = t.X; a.B = t.dY; a.Out = t.W;
+        a.M = t.K; a.Nn = t.N; a.C = t.T;
+        a.lda = t.K; a.ldb = t.N; a.ldo = t.K;
+        a.s = s; a.flag_in = step_flag;
+        a.family = LOMO_KERNEL_WGRAD_UPDATE;
+        if (dma_eligible(a)) updates.push_back(a);
+        else updates_plain.push_back(a);
+    }
+    if (!dgrads.empty() && launch_dma_group<false, EPI_STORE>(dgrads.data(), (int)dgrads.size(), st) != hipSuccess)
+        return LOMO_ERR_LAUNCH;
+    if (!updates.empty() && launch_dma_group<true, EPI_UPDATE>(updates.data(), (int)updates.size(), st) != hipSuccess)
+        return LOMO_ERR_LAUNCH;
+    for (const GemmArgs& a : updates_plain)
+        if (launch_wgrad_update(a, st) != hipSuccess) return LOMO_ERR_LAUNCH;
+    for (int64_t i = 0; i < n; ++i) {
+        const lomo_tensor& t = tensors[i];
+        if (t.T == 0 || t.K == 0 || t.N == 0) continue;
+        if (t.kind == LOMO_TENSOR_EMBEDDING) {
+            EmbeddingWs w = carve_embedding_ws(ws, t.T);
+            ScopedTiming timing(LOMO_KERNEL_EMBEDDING, st);
+            if (launch_embedding_grouping(t.ids, t.T, w, st) != hipSuccess) return LOMO_ERR_LAUNCH;
+            if (launch_embedding_rows(t.dY, t.W, t.T, t.K, w, 1, s, nullptr, nullptr, step_flag, st) != hipSuccess)
+                return LOMO_ERR_LAUNCH;
+        } else if (t.kind == LOMO_TENSOR_VECTOR) {
+            ScopedTiming timing(LOMO_KERNEL_VECTOR, st);
+            if (launch_vector(t.X, t.dY, t.W, t.T, t.K, ws, 1, s, nullptr, nullptr, step_flag, st) != hipSuccess)
+                return LOMO_ERR_LAUNCH;
+        }
+    }
+    return LOMO_OK;
 }
 
 lomo_status lomo_reduce_flags(const int32_t* flags, int64_t n, int32_t* out, void* stream) {

@@ -1,7 +1,12 @@
-// 256 x 256 MFMA contraction with a four-stage direct-to-LDS pipeline (gfx950).
+// Persistent, grouped 256 x 256 MFMA contraction with a four-stage direct-to-LDS pipeline (gfx950).
 //
 // Same mathematics and epilogues as the other contraction kernels (fused wgrad + SGD update of
-// paper section 3.2 / Algorithm 1, squared-norm pass of section 3.3.1, dgrad).  Data movement:
+// paper section 3.2 / Algorithm 1, squared-norm pass of section 3.3.1, dgrad).  One launch covers
+// the output tiles of up to MAX_GROUP tensors: one workgroup per CU walks the concatenated tile list
+// with a fixed stride, so there is one ramp-up per pass instead of one per tensor and partial last
+// rounds of one tensor are filled with tiles of the next.
+//
+// Data movement per tile:
 //   * global -> LDS without passing through registers: global_load_lds_dwordx4 writes lane L's
 //     16 bytes to M0 + 16 L, and each lane may fetch any global address, so a wave instruction
 //     fills 1 KiB of LDS with the 16-byte chunks of two tile rows in swizzled order;
@@ -12,7 +17,8 @@
 //     operands) or ds_read_b128 (contraction-contiguous operand of dgrad); the fragments of the
 //     next half-slice are read while the current one is multiplied, across the barrier;
 //   * one barrier per slice.  The vector-memory counter is managed by hand because the compiler
-//     would otherwise drain it before every LDS read.
+//     would otherwise drain it before every LDS read;
+//   * the first slices of the next tile are requested before the epilogue of the current one runs.
 #include "lomo_gemm_common.h"
 
 namespace lomo {
@@ -23,6 +29,25 @@ namespace dma {
 
 constexpr int BM = 256, BN = 256, BK = 32, NS = 4;
 constexpr int A_HALVES = BK * BM, B_HALVES = BK * BN, STAGE_HALVES = A_HALVES + B_HALVES;
+constexpr int LDS_BYTES = NS * STAGE_HALVES * 2 + 256;   // four stages + a reduction scratch
+constexpr int MAX_GROUP = 40;
+
+struct GroupTensor {
+    const uint16_t* A;
+    const uint16_t* B;
+    uint16_t* Out;
+    int32_t* flag_out;
+    int M, Nn, C, lda, ldb, ldo;
+    int tiles_m, tiles_n, tile_begin;
+};
+
+struct GroupArgs {
+    double* acc;
+    const int32_t* flag_in;
+    float s;
+    int n, total_tiles;
+    GroupTensor t[MAX_GROUP];
+};
 
 __device__ __forceinline__ int swz_s(int r) { return ((r & 1) * 10) + ((r & 2) * 2); }
 __device__ __forceinline__ int swz_c(int n) { return ((n >> 1) & 3) ^ ((n >> 3) & 1); }
@@ -43,72 +68,93 @@ __device__ __forceinline__ half8 read_tr8(const uint16_t* p0, const uint16_t* p1
 }  // namespace dma
 
 template <bool B_STRIDED, int EPI>
-__global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+__global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga) {
     using namespace dma;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
 
-    if (EPI == EPI_UPDATE && g.flag_in != nullptr && *g.flag_in != 0) return;
+    if (EPI == EPI_UPDATE && ga.flag_in != nullptr && *ga.flag_in != 0) return;   // step dropped
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave & 1, wn = wave >> 1;
+    const int G = gridDim.x;
 
-    int tm, tn;
-    {   // XCD-aware tile assignment: each XCD owns a contiguous range of tiles, walked in 8-wide bands
-        const int total = tiles_m * tiles_n;
-        const int bid = blockIdx.x;
-        const int x = bid & 7, local = bid >> 3;
-        const int q = total >> 3, r = total & 7;
+    // Position of this workgroup inside a window of G consecutive tiles: workgroups of one XCD
+    // (blockIdx % 8) take a contiguous run, which the band order below turns into an 8 x 4 block of
+    // tiles that share operand panels in that XCD's L2.
+    int pos;
+    {
+        const int x = (int)(blockIdx.x & 7), local = (int)(blockIdx.x >> 3);
+        const int q = G >> 3, r = G & 7;
 #ifdef LOMO_EXP_PLAIN_ORDER   // timing experiment: tiles in launch order
-        const int t = bid + 0 * (x + local + q + r);
+        pos = (int)blockIdx.x + 0 * (x + local + q + r);
 #else
-        const int t = x * q + (x < r ? x : r) + local;
+        pos = x * q + (x < r ? x : r) + local;
 #endif
-        constexpr int GM = 8;
-        const int per_band = GM * tiles_n;
-        const int band = t / per_band;
-        const int first_m = band * GM;
-        const int gsz = (tiles_m - first_m < GM) ? (tiles_m - first_m) : GM;
-        const int in_band = t - band * per_band;
-        tm = first_m + in_band % gsz;
-        tn = in_band / gsz;
     }
-    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
 
-    floatx16 acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    // ---- DMA: per-lane source byte offsets inside a slice, and this wave's LDS targets
-    uint32_t a_voff[4], b_voff[4];
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        const int q = wave * 4 + it;
-        {
-            const int r = 2 * q + (lane >> 5), cp = lane & 31;
-            a_voff[it] = (uint32_t)(r * (int)g.lda + ((cp ^ swz_s(r)) * 8)) * 2u;
-        }
-        if constexpr (B_STRIDED) {
-            const int r = 2 * q + (lane >> 5), cp = lane & 31;
-            b_voff[it] = (uint32_t)(r * (int)g.ldb + ((cp ^ swz_s(r)) * 8)) * 2u;
-        } else {
-            const int n = 16 * q + (lane >> 2), cp = lane & 3;
-            b_voff[it] = (uint32_t)(n * (int)g.ldb + ((cp ^ swz_c(n)) * 8)) * 2u;
-        }
-    }
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
     const uint32_t lds_wave = lds0 + (uint32_t)wave * 4096u;   // this wave's first KiB slot in a tile
+    uint16_t* red_scratch = smem + NS * STAGE_HALVES;
 
-    const uint16_t* pa = g.A + m0;
-    const uint16_t* pb = B_STRIDED ? (g.B + n0) : (g.B + n0 * g.ldb);
-    const int64_t a_step = (int64_t)BK * g.lda;
-    const int64_t b_step = B_STRIDED ? (int64_t)BK * g.ldb : (int64_t)BK;
-    const int KT = (int)(g.C / BK);
+    // ---- fragment read offsets (halves): fixed for the whole kernel
+    const int g4 = lane >> 4, j16 = lane & 15;
+    const int mhalf = g4 & 1, kh = g4 >> 1, rib = j16 >> 2, piece = j16 & 3;
+    const int a_rd = (8 * kh + rib) * BM + (((wm * (BM / 16) + 2 * mhalf + (piece >> 1)) ^ swz_s(rib)) * 8) + (piece & 1) * 4;
+    int b_rd;
+    if constexpr (B_STRIDED) {
+        b_rd = (8 * kh + rib) * BN + (((wn * (BN / 16) + 2 * mhalf + (piece >> 1)) ^ swz_s(rib)) * 8) + (piece & 1) * 4;
+    } else {
+        const int nl = wn * (BN / 2) + (lane & 31), lh = lane >> 5;
+        b_rd = nl * BK + ((lh ^ swz_c(nl)) * 8);
+    }
+
+    // ---- per-tile state of the loads
+    uint32_t a_voff[4], b_voff[4];
+    const uint16_t* pa = nullptr;
+    const uint16_t* pb = nullptr;
+    int64_t a_step = 0, b_step = 0;
+    int KT = 0;
+
+    // Locate tile number w of the concatenated list; set up the load state; return its coordinates.
+    auto setup = [&](int w, int& tensor, int64_t& m0, int64_t& n0) {
+        int k = 0;
+        while (k + 1 < ga.n && w >= ga.t[k + 1].tile_begin) ++k;
+        const GroupTensor& T = ga.t[k];
+        const int t = w - T.tile_begin;
+        constexpr int GM = 8;
+        const int per_band = GM * T.tiles_n;
+        const int band = t / per_band;
+        const int first_m = band * GM;
+        const int gsz = (T.tiles_m - first_m < GM) ? (T.tiles_m - first_m) : GM;
+        const int in_band = t - band * per_band;
+        const int tm = first_m + in_band % gsz;
+        const int tn = in_band / gsz;
+        tensor = k;
+        m0 = (int64_t)tm * BM;
+        n0 = (int64_t)tn * BN;
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int q = wave * 4 + it;
+            {
+                const int r = 2 * q + (lane >> 5), cp = lane & 31;
+                a_voff[it] = (uint32_t)(r * T.lda + ((cp ^ swz_s(r)) * 8)) * 2u;
+            }
+            if constexpr (B_STRIDED) {
+                const int r = 2 * q + (lane >> 5), cp = lane & 31;
+                b_voff[it] = (uint32_t)(r * T.ldb + ((cp ^ swz_s(r)) * 8)) * 2u;
+            } else {
+                const int n = 16 * q + (lane >> 2), cp = lane & 3;
+                b_voff[it] = (uint32_t)(n * T.ldb + ((cp ^ swz_c(n)) * 8)) * 2u;
+            }
+        }
+        pa = T.A + m0;
+        pb = B_STRIDED ? (T.B + n0) : (T.B + n0 * (int64_t)T.ldb);
+        a_step = (int64_t)BK * T.lda;
+        b_step = B_STRIDED ? (int64_t)BK * T.ldb : (int64_t)BK;
+        KT = T.C / BK;
+    };
 
     // One DMA instruction: part 0 = A tile, part 1 = B tile; `it` selects this wave's KiB slot.
     auto issue1 = [&](int stage, int buf, int part, int it) {
@@ -121,27 +167,20 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(GemmArgs g, int t
         if (part == 0) dma16(a_voff[it], pa + (int64_t)s * a_step, l);
         else dma16(b_voff[it], pb + (int64_t)s * b_step, l);
     };
-    auto issue = [&](int stage) {
+    // Slices 0..2 and the A part of slice 3 of the tile that `setup` selected.
+    auto issue_prologue = [&] {
 #pragma unroll
-        for (int it = 0; it < 4; ++it) issue1(stage, stage & 3, 0, it);
+        for (int st = 0; st < 3; ++st) {
 #pragma unroll
-        for (int it = 0; it < 4; ++it) issue1(stage, stage & 3, 1, it);
+            for (int it = 0; it < 4; ++it) issue1(st, st, 0, it);
+#pragma unroll
+            for (int it = 0; it < 4; ++it) issue1(st, st, 1, it);
+        }
+#pragma unroll
+        for (int it = 0; it < 4; ++it) issue1(3, 3, 0, it);
     };
 
-    // ---- fragment read offsets (halves), as in the register-staged fast path
-    const int g4 = lane >> 4, j16 = lane & 15;
-    const int mhalf = g4 & 1, kh = g4 >> 1, rib = j16 >> 2, piece = j16 & 3;
-    const int a_rd = (8 * kh + rib) * BM + (((wm * (BM / 16) + 2 * mhalf + (piece >> 1)) ^ swz_s(rib)) * 8) + (piece & 1) * 4;
-    int b_rd;
-    if constexpr (B_STRIDED) {
-        b_rd = (8 * kh + rib) * BN + (((wn * (BN / 16) + 2 * mhalf + (piece >> 1)) ^ swz_s(rib)) * 8) + (piece & 1) * 4;
-    } else {
-        const int nl = wn * (BN / 2) + (lane & 31), lh = lane >> 5;
-        b_rd = nl * BK + ((lh ^ swz_c(nl)) * 8);
-    }
-
-    // Fragment reads, in the order the MFMAs consume them: a0, b0..b3, a1..a3, cut into four
-    // groups so that group q is read while MFMA group q (a[q] x b[0..3]) of the other set runs.
+    // ---- fragment reads, in the order the MFMAs consume them: a0, b0..b3, a1..a3
     auto read_a = [&](half8 (&a)[4], int buf, int kk, int i) {
 #ifdef LOMO_EXP_B128_READS   // timing experiment only: plain 16-byte reads, results are meaningless
         a[i] = *reinterpret_cast<const half8*>(smem + buf * STAGE_HALVES + (lane & 31) * 32 + (lane >> 5) * 8 + kk * 16 + i * 1024);
@@ -183,6 +222,17 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(GemmArgs g, int t
     constexpr int RB = B_STRIDED ? 2 : 1;                       // LDS read instructions per b fragment
     constexpr int READS_EARLY[4] = {2 + 2 * RB, 2 * RB + 2, 4, 0};
     constexpr int READS_EVEN[4] = {2 + RB, 2 * RB, RB + 2, 4};
+
+    floatx16 acc[4][4];
+    auto zero_acc = [&] {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    };
+
     // Half a slice: 16 MFMAs on (ua, ub) in four groups; each group is preceded by the reads of one
     // fragment group of the next half-slice and followed by one direct-to-LDS load, so that LDS reads,
     // global loads and MFMAs overlap instead of queueing behind each other.
@@ -214,70 +264,136 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(GemmArgs g, int t
         }
     };
 
-    // ---- prologue: slices 0..2 and the A part of slice 3 in flight; slice 0 landed and visible
-    issue(0);
-    issue(1);
-    issue(2);
-#pragma unroll
-    for (int it = 0; it < 4; ++it) issue1(3, 3, 0, it);
-    asm volatile("s_waitcnt vmcnt(20)\n\ts_barrier" ::: "memory");
-    half8 fa0[4], fb0[4], fa1[4], fb1[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) read_group(fa0, fb0, 0, 0, q, false);
+    // ---- walk the tile list: tile w = round * G + pos; every workgroup leaves through `break`
+    int w = pos;
+    if (w >= ga.total_tiles) return;   // cannot happen with grid <= total_tiles; nothing was issued yet
+    int tensor;
+    int64_t m0, n0;
+    setup(w, tensor, m0, n0);
+    issue_prologue();
+    zero_acc();
 
-    // KT is a multiple of 4: the body is unrolled over the four LDS stages so that every LDS
-    // address is a register plus an immediate.
-    for (int kt = 0; kt < KT; kt += 4) {
+    while (true) {
+        // every load of this tile's first slices has landed and is visible to all waves
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        half8 fa0[4], fb0[4], fa1[4], fb1[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            // first half of slice kt+u; reads its second half's fragments; loads the B part of slice kt+u+3
-            half_slice(fa0, fb0, fa1, fb1, u, 1, true, kt + u + 3, (u + 3) & 3, 1);
-            // own loads of slice kt+u+1 landed (two younger slices may still fly); own LDS reads done
+        for (int q = 0; q < 4; ++q) read_group(fa0, fb0, 0, 0, q, false);
+
+        // KT is a multiple of 4: the body is unrolled over the four LDS stages so that every LDS
+        // address is a register plus an immediate.
+        for (int kt = 0; kt < KT; kt += 4) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                // first half of slice kt+u; reads its second half's fragments; loads the B part of slice kt+u+3
+                half_slice(fa0, fb0, fa1, fb1, u, 1, true, kt + u + 3, (u + 3) & 3, 1);
+                // own loads of slice kt+u+1 landed (two younger slices may still fly); own LDS reads done
 #ifdef LOMO_EXP_NO_BARRIER   // timing experiment only: waves drift apart, results are meaningless
-            asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
+                asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
 #else
-            asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 #endif
-            __builtin_amdgcn_sched_barrier(0);
-            // second half; reads the first fragments of the next slice; loads the A part of slice
-            // kt+u+4 into the buffer of slice kt+u, which nobody reads any more
-            half_slice(fa1, fb1, fa0, fb0, (u + 1) & 3, 0, false, kt + u + 4, u, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                // second half; reads the first fragments of the next slice; loads the A part of slice
+                // kt+u+4 into the buffer of slice kt+u, which nobody reads any more
+                half_slice(fa1, fb1, fa0, fb0, (u + 1) & 3, 0, false, kt + u + 4, u, 0);
+            }
         }
-    }
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        // drain: the loads past the end (re-reads) have landed, all waves are done with the LDS stages
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
-    epilogue<BM, BN, EPI>(acc, g, smem, m0, n0, BM, BN);
+        // epilogue arguments of the tile just finished
+        GemmArgs g;
+        g.Out = ga.t[tensor].Out;
+        g.ldo = ga.t[tensor].ldo;
+        g.s = ga.s;
+        g.acc = ga.acc;
+        g.flag_out = ga.t[tensor].flag_out;
+        const int64_t em0 = m0, en0 = n0;
+
+        // request the first slices of the next tile, then finish this one
+        w += G;
+        const bool more = w < ga.total_tiles;
+        if (more) {
+            setup(w, tensor, m0, n0);
+            issue_prologue();
+        }
+        epilogue<BM, BN, EPI>(acc, g, red_scratch, em0, en0, BM, BN);
+        if (!more) break;
+        zero_acc();
+    }
+}
+
+// ---- host side ----------------------------------------------------------------------------
+
+static int cu_count() {
+    static const int n = [] {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 256;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) return 256;
+        return v;
+    }();
+    return n;
+}
+
+bool dma_eligible(const GemmArgs& a) {
+    using namespace dma;
+    return a.M > 0 && a.Nn > 0 && a.C >= 4 * BK && a.M % BM == 0 && a.Nn % BN == 0 && a.C % (4 * BK) == 0 &&
+           a.M < (1 << 30) && a.Nn < (1 << 30) && a.C < (1 << 30) &&
+           (int64_t)BK * a.lda < (1 << 30) && (int64_t)BN * a.ldb < (1 << 30) && a.ldo < (1 << 30) &&
+           (a.M / BM) * (a.Nn / BN) < (1 << 24);
 }
 
 template <bool B_STRIDED, int EPI>
-static hipError_t launch_dma_one(const GemmArgs& a, hipStream_t st) {
-    constexpr size_t lds = (size_t)dma::NS * dma::STAGE_HALVES * sizeof(uint16_t);
+hipError_t launch_dma_group(const GemmArgs* list, int n, hipStream_t st) {
+    using namespace dma;
     auto kern = lomo_contract_dma_kernel<B_STRIDED, EPI>;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    const int tiles_m = (int)(a.M / dma::BM), tiles_n = (int)(a.Nn / dma::BN);
-    return launch_timed(a.family, kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(NT), lds, st, a, tiles_m, tiles_n);
+    for (int first = 0; first < n; first += MAX_GROUP) {
+        const int cnt = (n - first < MAX_GROUP) ? (n - first) : MAX_GROUP;
+        GroupArgs ga{};
+        ga.acc = list[first].acc;
+        ga.flag_in = list[first].flag_in;
+        ga.s = list[first].s;
+        ga.n = cnt;
+        int tiles = 0;
+        for (int i = 0; i < cnt; ++i) {
+            const GemmArgs& a = list[first + i];
+            GroupTensor& t = ga.t[i];
+            t.A = a.A; t.B = a.B; t.Out = a.Out; t.flag_out = a.flag_out;
+            t.M = (int)a.M; t.Nn = (int)a.Nn; t.C = (int)a.C;
+            t.lda = (int)a.lda; t.ldb = (int)a.ldb; t.ldo = (int)a.ldo;
+            t.tiles_m = (int)(a.M / BM); t.tiles_n = (int)(a.Nn / BN);
+            t.tile_begin = tiles;
+            tiles += t.tiles_m * t.tiles_n;
+        }
+        ga.total_tiles = tiles;
+        const int grid = tiles < cu_count() ? tiles : cu_count();
+        hipError_t e = launch_timed(list[first].family, kern, dim3((unsigned)grid), dim3(NT), (size_t)LDS_BYTES, st, ga);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
-// Eligible: whole 256 x 256 tiles, contraction a multiple of 128, enough of them to fill the chip, 32-bit slice offsets.
+// Single tensor: worth it when there are enough tiles to fill most of the chip.
 template <bool B_STRIDED, int EPI>
 bool try_launch_dma(const GemmArgs& a, hipStream_t st, hipError_t* err) {
-    using namespace dma;
-    const bool ok = a.M > 0 && a.Nn > 0 && a.C >= 4 * BK && a.M % BM == 0 && a.Nn % BN == 0 && a.C % (4 * BK) == 0 &&
-                    (int64_t)BK * a.lda < (1 << 30) && (int64_t)BN * a.ldb < (1 << 30) &&
-                    (a.M / BM) * (a.Nn / BN) >= 192 && (a.M / BM) * (a.Nn / BN) < (1 << 24);
-    if (!ok) return false;
-    *err = launch_dma_one<B_STRIDED, EPI>(a, st);
+    if (!dma_eligible(a) || (a.M / dma::BM) * (a.Nn / dma::BN) < 192) return false;
+    *err = launch_dma_group<B_STRIDED, EPI>(&a, 1, st);
     return true;
 }
 
 template bool try_launch_dma<true, EPI_UPDATE>(const GemmArgs&, hipStream_t, hipError_t*);
 template bool try_launch_dma<true, EPI_SQNORM>(const GemmArgs&, hipStream_t, hipError_t*);
 template bool try_launch_dma<false, EPI_STORE>(const GemmArgs&, hipStream_t, hipError_t*);
+template hipError_t launch_dma_group<true, EPI_UPDATE>(const GemmArgs*, int, hipStream_t);
+template hipError_t launch_dma_group<true, EPI_SQNORM>(const GemmArgs*, int, hipStream_t);
+template hipError_t launch_dma_group<false, EPI_STORE>(const GemmArgs*, int, hipStream_t);
 
 }  // namespace lomo

@@ -37,9 +37,14 @@ struct GemmArgs {
 template <bool B_STRIDED, int EPI>
 bool try_launch_fast(const GemmArgs& a, hipStream_t st, hipError_t* err);
 
-// 256 x 256 direct-to-LDS pipeline (lomo_gemm_dma.hip): returns false when not eligible.
+// Persistent 256 x 256 direct-to-LDS kernel (lomo_gemm_dma.hip).  try_launch_dma returns false when
+// the tensor is not eligible or too small; launch_dma_group runs a list of eligible tensors (same
+// epilogue, same acc / step flag / step size) in as few launches as the argument space allows.
+bool dma_eligible(const GemmArgs& a);
 template <bool B_STRIDED, int EPI>
 bool try_launch_dma(const GemmArgs& a, hipStream_t st, hipError_t* err);
+template <bool B_STRIDED, int EPI>
+hipError_t launch_dma_group(const GemmArgs* list, int n, hipStream_t st);
 
 hipError_t launch_wgrad_update(const GemmArgs& a, hipStream_t st);
 hipError_t launch_wgrad_sqnorm(const GemmArgs& a, hipStream_t st);

@@ -15,7 +15,13 @@ from . import binding as B
 
 
 class LomoStep:
-    def __init__(self, device="cuda:0", max_T: int = 8192, max_H: int = 8192, max_tensors: int = 1024):
+    """grouped=True (default) hands the whole tensor list to lomo_step_norm_pass / lomo_step_update_pass;
+    grouped=False makes one C call per tensor in list order.  Results are the same."""
+
+    def __init__(self, device="cuda:0", max_T: int = 8192, max_H: int = 8192, max_tensors: int = 1024,
+                 grouped: bool = True):
+        self.grouped = grouped
+        self._lists = {}
         self.device = torch.device(device)
         self.acc = torch.zeros(1, dtype=torch.float64, device=self.device)
         self.flags = torch.zeros(max_tensors + 1, dtype=torch.int32, device=self.device)
@@ -23,11 +29,23 @@ class LomoStep:
         self.ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         assert self.ws.data_ptr() % 256 == 0
 
+    def _list(self, tensors):
+        key = tuple((id(t), t["W"].data_ptr(), t["dY"].data_ptr(), (t.get("dX").data_ptr() if t.get("dX") is not None else 0))
+                    for t in tensors)
+        cached = self._lists.get("k")
+        if cached is None or cached[0] != key:
+            cached = (key, B.make_tensor_list(tensors))
+            self._lists["k"] = cached
+        return cached[1]
+
     def norm_pass(self, tensors: List[Dict], stream=None):
         n = len(tensors)
         assert n < self.flags.numel()
         self.acc.zero_()
         self.flags.zero_()
+        if self.grouped:
+            B.lomo_step_norm_pass(self._list(tensors), self.acc, self.flags, self.ws, stream)
+            return
         for i, t in enumerate(tensors):
             flag = self.flags[i:i + 1]
             if t["kind"] == "linear":
@@ -41,6 +59,9 @@ class LomoStep:
     def update_pass(self, tensors: List[Dict], lr: float, inv_loss_scale: float, clip: float, stream=None):
         n = len(tensors)
         step_flag = self.flags[n:n + 1]
+        if self.grouped:
+            B.lomo_step_update_pass(self._list(tensors), lr, inv_loss_scale, clip, step_flag, self.ws, stream)
+            return
         for t in tensors:
             if t["kind"] == "linear":
                 B.lomo_linear_backward_update(t["X"], t["dY"], t["W"], t.get("dX"), lr, inv_loss_scale, clip,

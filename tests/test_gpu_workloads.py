@@ -63,8 +63,9 @@ def _check_dx(got, dY, W, what):
     assert ((d <= 1) | near).mean() >= 0.999, what
 
 
+@pytest.mark.parametrize("grouped", [True, False], ids=["grouped", "per_tensor"])
 @pytest.mark.parametrize("name", ["linear1024", "llama7b_layer"])
-def test_two_pass_step_matches_oracle(L, name):
+def test_two_pass_step_matches_oracle(L, name, grouped):
     from paper_2306_09782_amd.step import LomoStep
     wl = S.workload(name)
     gpu = _device_tensors(wl)
@@ -72,7 +73,7 @@ def test_two_pass_step_matches_oracle(L, name):
     if name == "linear1024":     # the CPU generator yields the same bits
         np.testing.assert_array_equal(cpu[0]["X"].view(np.uint16), wl.X_np(wl.tensors[0]).view(np.uint16))
     lr = float(np.float32(wl.lr))
-    stepper = LomoStep(DEV, max_T=wl.T, max_H=max(s.K for s in wl.tensors), max_tensors=len(gpu))
+    stepper = LomoStep(DEV, max_T=wl.T, max_H=max(s.K for s in wl.tensors), max_tensors=len(gpu), grouped=grouped)
 
     # oracle, materialised: every gradient of the step is held at once
     grads = [O.tensor_grad(t) for t in cpu]
