@@ -163,6 +163,25 @@ lomo_status lomo_step_update_pass(const lomo_tensor* tensors, int64_t n,
                                   float lr, float inv_loss_scale, float clip_coef,
                                   const int32_t* step_flag, void* ws, size_t ws_bytes, void* stream);
 
+/* ---------------------------------------------------------------- clip by value (section 3.3.1, first
+ * alternative): one pass, no norm.  Each element of the unscaled gradient g = G / loss_scale is clamped
+ * to [-clip_value, clip_value] and applied at once: W <- round_fp16(float(W) - lr * clamp(g)), fp32
+ * arithmetic, one rounding.  The paper's example: [1.3, 0.8] clipped at 1.0 becomes [1.0, 0.8].
+ * Overflow cannot be known before updating in a single pass: an element whose gradient is inf/NaN is
+ * left unchanged and the flag is raised, so the host can still halve the loss scale. */
+
+/* One linear tensor (dX as in lomo_linear_backward_update).  overflow_flag: device int32, |= 1, may be NULL. */
+lomo_status lomo_linear_backward_update_clip_value(const lomo_half* X, const lomo_half* dY, lomo_half* W,
+                                                   lomo_half* dX, int64_t T, int64_t K, int64_t N,
+                                                   float lr, float inv_loss_scale, float clip_value,
+                                                   int32_t* overflow_flag, void* stream);
+
+/* A whole step in one pass over a tensor list (all kinds).  flags: device int32[n + 1], zeroed by the
+ * caller; flags[i] |= 1 where tensor i met a non-finite gradient element, flags[n] = any. */
+lomo_status lomo_step_update_pass_clip_value(const lomo_tensor* tensors, int64_t n,
+                                             float lr, float inv_loss_scale, float clip_value,
+                                             int32_t* flags, void* ws, size_t ws_bytes, void* stream);
+
 /* ---------------------------------------------------------------- helpers */
 
 /* Workspace sizes in bytes (host functions; 0 for T == 0). */

@@ -162,9 +162,16 @@ def sgd_update(W, G, lr: float, coef: float, loss_scale: float) -> np.ndarray:
 
 
 def sgd_update_clip_value(W, G, lr: float, clip_value: float, loss_scale: float) -> np.ndarray:
-    """Single-pass alternative of section 3.3.1: clamp each gradient element to +-clip_value."""
-    g = np.clip(np.asarray(G, dtype=np.float64) / loss_scale, -clip_value, clip_value)
-    return round_f16(as_f64(W) - lr * g)
+    """Single-pass alternative of section 3.3.1: clamp each gradient element to +-clip_value.
+
+    The paper does not say what a single pass does on overflow; reading taken here: an element whose
+    gradient is inf/NaN keeps its weight (the caller learns of it through has_overflow).
+    """
+    with np.errstate(invalid="ignore", over="ignore"):
+        g = np.asarray(G, dtype=np.float64) / loss_scale
+        fin = np.isfinite(g)
+        stepped = round_f16(as_f64(W) - lr * np.clip(np.where(fin, g, 0.0), -clip_value, clip_value))
+    return np.where(fin, stepped, np.asarray(W, dtype=np.float16))
 
 
 # --------------------------------------------------------------------------- whole steps

@@ -10,6 +10,7 @@ from .binding import (LomoError, library_path, load_library, lomo_version, lomo_
                       lomo_vector_update, lomo_embedding_workspace_bytes, lomo_vector_workspace_bytes,
                       lomo_embedding_grouping, lomo_timing_enable, lomo_timing_read, KERNEL_FAMILIES,
                       lomo_step_workspace_bytes, lomo_step_norm_pass, lomo_step_update_pass, make_tensor_list,
+                      lomo_linear_backward_update_clip_value, lomo_step_update_pass_clip_value,
                       LomoTensor,
                       EXPORTED_SYMBOLS)
 

@@ -18,6 +18,7 @@ EXPORTED_SYMBOLS = (
     "lomo_embedding_update", "lomo_vector_update", "lomo_embedding_workspace_bytes",
     "lomo_vector_workspace_bytes", "lomo_embedding_grouping", "lomo_timing_enable", "lomo_timing_read",
     "lomo_step_workspace_bytes", "lomo_step_norm_pass", "lomo_step_update_pass",
+    "lomo_linear_backward_update_clip_value", "lomo_step_update_pass_clip_value",
 )
 
 
@@ -68,6 +69,9 @@ def load_library():
         "lomo_step_workspace_bytes": (c_size_t, [POINTER(LomoTensor), I64]),
         "lomo_step_norm_pass": (c_int, [POINTER(LomoTensor), I64, P, P, P, c_size_t, P]),
         "lomo_step_update_pass": (c_int, [POINTER(LomoTensor), I64, c_float, c_float, c_float, P, P, c_size_t, P]),
+        "lomo_linear_backward_update_clip_value": (c_int, [P, P, P, P, I64, I64, I64, c_float, c_float, c_float, P, P]),
+        "lomo_step_update_pass_clip_value": (c_int, [POINTER(LomoTensor), I64, c_float, c_float, c_float, P, P,
+                                                     c_size_t, P]),
         "lomo_timing_enable": (c_int, [c_int]),
         "lomo_timing_read": (c_int, [c_int, POINTER(c_double), POINTER(c_int64)]),
     }
@@ -227,3 +231,20 @@ def lomo_step_norm_pass(tensor_list, acc, flags, ws, stream=None):
 def lomo_step_update_pass(tensor_list, lr, inv_loss_scale, clip_coef, step_flag, ws, stream=None):
     _check(load_library().lomo_step_update_pass(tensor_list, len(tensor_list), lr, inv_loss_scale, clip_coef,
                                                 _ptr(step_flag), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def lomo_linear_backward_update_clip_value(X, dY, W, dX, lr, inv_loss_scale, clip_value, overflow_flag=None,
+                                           stream=None):
+    T, K = X.shape
+    N = dY.shape[1]
+    assert dY.shape[0] == T and tuple(W.shape) == (N, K) and (dX is None or tuple(dX.shape) == (T, K))
+    _check(load_library().lomo_linear_backward_update_clip_value(_ptr(X), _ptr(dY), _ptr(W), _ptr(dX), T, K, N, lr,
+                                                                 inv_loss_scale, clip_value, _ptr(overflow_flag),
+                                                                 _stream(stream)))
+
+
+def lomo_step_update_pass_clip_value(tensor_list, lr, inv_loss_scale, clip_value, flags, ws, stream=None):
+    assert flags.numel() >= len(tensor_list) + 1
+    _check(load_library().lomo_step_update_pass_clip_value(tensor_list, len(tensor_list), lr, inv_loss_scale,
+                                                           clip_value, _ptr(flags), _ptr(ws), _nbytes(ws),
+                                                           _stream(stream)))

@@ -308,6 +308,93 @@ lomo_status lomo_step_update_pass(const lomo_tensor* tensors, int64_t n, float l
     return LOMO_OK;
 }
 
+// ---- clip by value (single pass) -----------------------------------------------------------
+
+lomo_status lomo_linear_backward_update_clip_value(const lomo_half* X, const lomo_half* dY, lomo_half* W, lomo_half* dX,
+                                                   int64_t T, int64_t K, int64_t N, float lr, float inv_loss_scale,
+                                                   float clip_value, int32_t* overflow_flag, void* stream) {
+    lomo_tensor t{};
+    t.kind = LOMO_TENSOR_LINEAR;
+    t.X = X; t.dY = dY; t.W = W; t.dX = dX; t.T = T; t.K = K; t.N = N;
+    lomo_status cs = check_linear(t, true);
+    if (cs != LOMO_OK) return cs;
+    if (!(clip_value >= 0.f)) return LOMO_ERR_SHAPE;
+    if (T == 0 || K == 0 || N == 0) return LOMO_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dX) {
+        GemmArgs d{};
+        d.A = W; d.B = dY; d.Out = dX;
+        d.M = K; d.Nn = T; d.C = N;
+        d.lda = K; d.ldb = N; d.ldo = K;
+        d.family = LOMO_KERNEL_DGRAD;
+        if (launch_dgrad(d, st) != hipSuccess) return LOMO_ERR_LAUNCH;
+    }
+    GemmArgs a{};
+    a.A = X; a.B = dY; a.Out = W;
+    a.M = K; a.Nn = N; a.C = T;
+    a.lda = K; a.ldb = N; a.ldo = K;
+    a.lr = lr; a.inv_s = inv_loss_scale; a.clipv = clip_value;
+    a.flag_out = overflow_flag;
+    a.family = LOMO_KERNEL_WGRAD_UPDATE;
+    return from_hip(launch_wgrad_update_clipv(a, st));
+}
+
+lomo_status lomo_step_update_pass_clip_value(const lomo_tensor* tensors, int64_t n, float lr, float inv_loss_scale,
+                                             float clip_value, int32_t* flags, void* ws, size_t ws_bytes, void* stream) {
+    lomo_status cs = check_step(tensors, n, true, ws, ws_bytes);
+    if (cs != LOMO_OK) return cs;
+    if (!flags) return LOMO_ERR_NULL;
+    if (!(clip_value >= 0.f)) return LOMO_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    std::vector<GemmArgs> dgrads, updates, updates_plain;
+    for (int64_t i = 0; i < n; ++i) {
+        const lomo_tensor& t = tensors[i];
+        if (t.kind != LOMO_TENSOR_LINEAR || t.T == 0 || t.K == 0 || t.N == 0) continue;
+        if (t.dX) {
+            GemmArgs d{};
+            d.A = t.W; d.B = t.dY; d.Out = t.dX;
+            d.M = t.K; d.Nn = t.T; d.C = t.N;
+            d.lda = t.K; d.ldb = t.N; d.ldo = t.K;
+            d.family = LOMO_KERNEL_DGRAD;
+            if (dma_eligible(d)) dgrads.push_back(d);
+            else if (launch_dgrad(d, st) != hipSuccess) return LOMO_ERR_LAUNCH;
+        }
+        GemmArgs a{};
+        a.A = t.X; a.B = t.dY; a.Out = t.W;
+        a.M = t.K; a.Nn = t.N; a.C = t.T;
+        a.lda = t.K; a.ldb = t.N; a.ldo = t.K;
+        a.lr = lr; a.inv_s = inv_loss_scale; a.clipv = clip_value;
+        a.flag_out = flags + i;
+        a.family = LOMO_KERNEL_WGRAD_UPDATE;
+        if (dma_eligible(a)) updates.push_back(a);
+        else updates_plain.push_back(a);
+    }
+    if (!dgrads.empty() && launch_dma_group<false, EPI_STORE>(dgrads.data(), (int)dgrads.size(), st) != hipSuccess)
+        return LOMO_ERR_LAUNCH;
+    if (!updates.empty() && launch_dma_group<true, EPI_CLIPV>(updates.data(), (int)updates.size(), st) != hipSuccess)
+        return LOMO_ERR_LAUNCH;
+    for (const GemmArgs& a : updates_plain)
+        if (launch_wgrad_update_clipv(a, st) != hipSuccess) return LOMO_ERR_LAUNCH;
+    for (int64_t i = 0; i < n; ++i) {
+        const lomo_tensor& t = tensors[i];
+        if (t.T == 0 || t.K == 0 || t.N == 0) continue;
+        if (t.kind == LOMO_TENSOR_EMBEDDING) {
+            EmbeddingWs w = carve_embedding_ws(ws, t.T);
+            ScopedTiming timing(LOMO_KERNEL_EMBEDDING, st);
+            if (launch_embedding_grouping(t.ids, t.T, w, st) != hipSuccess) return LOMO_ERR_LAUNCH;
+            if (launch_embedding_rows(t.dY, t.W, t.T, t.K, w, 2, inv_loss_scale, nullptr, flags + i, nullptr, st, lr,
+                                      clip_value) != hipSuccess)
+                return LOMO_ERR_LAUNCH;
+        } else if (t.kind == LOMO_TENSOR_VECTOR) {
+            ScopedTiming timing(LOMO_KERNEL_VECTOR, st);
+            if (launch_vector(t.X, t.dY, t.W, t.T, t.K, ws, 2, inv_loss_scale, nullptr, flags + i, nullptr, st, lr,
+                              clip_value) != hipSuccess)
+                return LOMO_ERR_LAUNCH;
+        }
+    }
+    return from_hip(launch_reduce_flags(flags, n, flags + n, st));
+}
+
 lomo_status lomo_reduce_flags(const int32_t* flags, int64_t n, int32_t* out, void* stream) {
     if (n < 0) return LOMO_ERR_SHAPE;
     if (!out || (n > 0 && !flags)) return LOMO_ERR_NULL;

@@ -242,6 +242,13 @@ hipError_t launch_wgrad_update(const GemmArgs& a, hipStream_t st) {
     return use_big_tiles(a.M, a.Nn) ? launch_one<256, 256, true, EPI_UPDATE>(a, st)
                                     : launch_one<128, 128, true, EPI_UPDATE>(a, st);
 }
+hipError_t launch_wgrad_update_clipv(const GemmArgs& a, hipStream_t st) {
+    hipError_t e;
+    if (fast_enabled() && dma_enabled() && try_launch_dma<true, EPI_CLIPV>(a, st, &e)) return e;
+    if (fast_enabled() && try_launch_fast<true, EPI_CLIPV>(a, st, &e)) return e;
+    return use_big_tiles(a.M, a.Nn) ? launch_one<256, 256, true, EPI_CLIPV>(a, st)
+                                    : launch_one<128, 128, true, EPI_CLIPV>(a, st);
+}
 hipError_t launch_wgrad_sqnorm(const GemmArgs& a, hipStream_t st) {
     hipError_t e;
     if (fast_enabled() && dma_enabled() && try_launch_dma<true, EPI_SQNORM>(a, st, &e)) return e;

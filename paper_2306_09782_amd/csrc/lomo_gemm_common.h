@@ -25,6 +25,7 @@ __device__ __forceinline__ float wave_sum(float v) {
 //   EPI_UPDATE: W <- rne16(float(W) - s * acc)   (section 3.2 update, fp32 as section 3.3.2 asks)
 //   EPI_SQNORM: one fp32 sum of squares per workgroup -> double atomic; inf/NaN -> flag
 //   EPI_STORE : Out <- rne16(acc)
+//   EPI_CLIPV : W <- rne16(float(W) - lr * clamp(acc / S, -c, c))   (single-pass alternative of section 3.3.1)
 template <int BM, int BN, int EPI>
 __device__ __forceinline__ void epilogue(floatx16 (&acc)[BM / 64][BN / 64], const GemmArgs& g, uint16_t* smem,
                                          int64_t m0, int64_t n0, int m_rem, int n_rem) {
@@ -84,10 +85,12 @@ __device__ __forceinline__ void epilogue(floatx16 (&acc)[BM / 64][BN / 64], cons
                     if (row != nullptr && ml < m_rem) w[i][a] = *reinterpret_cast<const half8*>(row + ml);
                 }
         };
-        if constexpr (EPI == EPI_UPDATE) load_stripe(0, wbuf[0]);
+        constexpr bool RMW = (EPI == EPI_UPDATE || EPI == EPI_CLIPV);
+        bool bad = false;
+        if constexpr (RMW) load_stripe(0, wbuf[0]);
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            if constexpr (EPI == EPI_UPDATE) {
+            if constexpr (RMW) {
                 if (j + 1 < TN) load_stripe(j + 1, wbuf[(j + 1) & 1]);
             }
             uint16_t* row = row_ptr(j);
@@ -111,12 +114,27 @@ __device__ __forceinline__ void epilogue(floatx16 (&acc)[BM / 64][BN / 64], cons
                         const half8 w = wbuf[j & 1][i][a];
 #pragma unroll
                         for (int e = 0; e < 8; ++e) out[e] = (_Float16)fmaf(-s, v[e], (float)w[e]);
+                    } else if constexpr (EPI == EPI_CLIPV) {
+                        // clip by value (section 3.3.1): clamp each unscaled gradient element, then update;
+                        // a non-finite element raises the flag and leaves its weight alone
+                        const half8 w = wbuf[j & 1][i][a];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const float gq = v[e] * g.inv_s;
+                            const bool fin = (__float_as_uint(gq) & 0x7f800000u) != 0x7f800000u;
+                            const float gc = fminf(fmaxf(gq, -g.clipv), g.clipv);
+                            out[e] = fin ? (_Float16)fmaf(-g.lr, gc, (float)w[e]) : w[e];
+                            bad |= !fin;
+                        }
                     } else {
 #pragma unroll
                         for (int e = 0; e < 8; ++e) out[e] = (_Float16)v[e];
                     }
                     *reinterpret_cast<half8*>(row + ml) = out;
                 }
+        }
+        if constexpr (EPI == EPI_CLIPV) {
+            if (__any(bad) && lane == 0 && g.flag_out != nullptr) atomicOr(g.flag_out, 1);
         }
     }
 }

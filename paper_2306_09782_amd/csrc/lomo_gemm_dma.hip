@@ -44,7 +44,7 @@ struct GroupTensor {
 struct GroupArgs {
     double* acc;
     const int32_t* flag_in;
-    float s;
+    float s, lr, inv_s, clipv;
     int n, total_tiles;
     GroupTensor t[MAX_GROUP];
 };
@@ -307,6 +307,9 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga
         g.Out = ga.t[tensor].Out;
         g.ldo = ga.t[tensor].ldo;
         g.s = ga.s;
+        g.lr = ga.lr;
+        g.inv_s = ga.inv_s;
+        g.clipv = ga.clipv;
         g.acc = ga.acc;
         g.flag_out = ga.t[tensor].flag_out;
         const int64_t em0 = m0, en0 = n0;
@@ -361,6 +364,9 @@ hipError_t launch_dma_group(const GemmArgs* list, int n, hipStream_t st) {
         ga.acc = list[first].acc;
         ga.flag_in = list[first].flag_in;
         ga.s = list[first].s;
+        ga.lr = list[first].lr;
+        ga.inv_s = list[first].inv_s;
+        ga.clipv = list[first].clipv;
         ga.n = cnt;
         int tiles = 0;
         for (int i = 0; i < cnt; ++i) {
@@ -390,9 +396,11 @@ bool try_launch_dma(const GemmArgs& a, hipStream_t st, hipError_t* err) {
 }
 
 template bool try_launch_dma<true, EPI_UPDATE>(const GemmArgs&, hipStream_t, hipError_t*);
+template bool try_launch_dma<true, EPI_CLIPV>(const GemmArgs&, hipStream_t, hipError_t*);
 template bool try_launch_dma<true, EPI_SQNORM>(const GemmArgs&, hipStream_t, hipError_t*);
 template bool try_launch_dma<false, EPI_STORE>(const GemmArgs&, hipStream_t, hipError_t*);
 template hipError_t launch_dma_group<true, EPI_UPDATE>(const GemmArgs*, int, hipStream_t);
+template hipError_t launch_dma_group<true, EPI_CLIPV>(const GemmArgs*, int, hipStream_t);
 template hipError_t launch_dma_group<true, EPI_SQNORM>(const GemmArgs*, int, hipStream_t);
 template hipError_t launch_dma_group<false, EPI_STORE>(const GemmArgs*, int, hipStream_t);
 

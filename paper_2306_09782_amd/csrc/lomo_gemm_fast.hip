@@ -226,6 +226,7 @@ bool try_launch_fast(const GemmArgs& a, hipStream_t st, hipError_t* err) {
 }
 
 template bool try_launch_fast<true, EPI_UPDATE>(const GemmArgs&, hipStream_t, hipError_t*);
+template bool try_launch_fast<true, EPI_CLIPV>(const GemmArgs&, hipStream_t, hipError_t*);
 template bool try_launch_fast<true, EPI_SQNORM>(const GemmArgs&, hipStream_t, hipError_t*);
 template bool try_launch_fast<false, EPI_STORE>(const GemmArgs&, hipStream_t, hipError_t*);
 

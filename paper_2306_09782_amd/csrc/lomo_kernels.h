@@ -12,7 +12,8 @@ namespace lomo {
 enum Epilogue : int {
     EPI_UPDATE = 0,   // W <- rne16(W - s * acc)            (fused wgrad + SGD update)
     EPI_SQNORM = 1,   // acc_out += sum acc^2, overflow flag (norm pass)
-    EPI_STORE = 2     // Out <- rne16(acc)                  (dgrad)
+    EPI_STORE = 2,    // Out <- rne16(acc)                  (dgrad)
+    EPI_CLIPV = 3     // W <- rne16(W - lr * clamp(acc / S, -c, c)), single pass (clip by value)
 };
 
 // One contraction  Out[n][m] (+)= sum_c A(c, m) * B(c, n).
@@ -28,6 +29,7 @@ struct GemmArgs {
     int64_t M, Nn, C;
     int64_t lda, ldb, ldo;
     float s;                 // update step (EPI_UPDATE)
+    float lr, inv_s, clipv;  // learning rate, 1 / loss scale, clamp threshold (EPI_CLIPV)
     double* acc;             // squared-norm accumulator (EPI_SQNORM)
     int32_t* flag_out;       // overflow flag to raise (EPI_SQNORM), may be null
     const int32_t* flag_in;  // overflow flag to honour (EPI_UPDATE), may be null
@@ -47,6 +49,7 @@ template <bool B_STRIDED, int EPI>
 hipError_t launch_dma_group(const GemmArgs* list, int n, hipStream_t st);
 
 hipError_t launch_wgrad_update(const GemmArgs& a, hipStream_t st);
+hipError_t launch_wgrad_update_clipv(const GemmArgs& a, hipStream_t st);
 hipError_t launch_wgrad_sqnorm(const GemmArgs& a, hipStream_t st);
 hipError_t launch_dgrad(const GemmArgs& a, hipStream_t st);
 
@@ -61,15 +64,17 @@ struct EmbeddingWs {          // carved out of the caller's workspace
 size_t embedding_ws_bytes(int64_t T, int64_t H);
 EmbeddingWs carve_embedding_ws(void* ws, int64_t T);
 hipError_t launch_embedding_grouping(const int32_t* ids, int64_t T, const EmbeddingWs& w, hipStream_t st);
-// mode 0: squared norm into acc (+ flag_out); mode 1: in-place row update honouring flag_in.
+// mode 0: squared norm into acc (+ flag_out); mode 1: in-place row update honouring flag_in;
+// mode 2: clip-by-value update, g = clamp(sum * s, -clipv, clipv), W -= lr * g, raising flag_out
+// (and leaving the element alone) where the sum is not finite.  In mode 2, s is 1 / loss scale.
 hipError_t launch_embedding_rows(const uint16_t* dY, uint16_t* W, int64_t T, int64_t H, const EmbeddingWs& w,
                                  int mode, float s, double* acc, int32_t* flag_out, const int32_t* flag_in,
-                                 hipStream_t st);
+                                 hipStream_t st, float lr = 0.f, float clipv = 0.f);
 
 size_t vector_ws_bytes(int64_t T, int64_t H);
 hipError_t launch_vector(const uint16_t* Xhat, const uint16_t* dY, uint16_t* w, int64_t T, int64_t H,
                          void* ws, int mode, float s, double* acc, int32_t* flag_out, const int32_t* flag_in,
-                         hipStream_t st);
+                         hipStream_t st, float lr = 0.f, float clipv = 0.f);
 
 // Event timing (lomo_timing.hip).  Contraction kernels attach the events to their own dispatch
 // (no extra packets on the stream); multi-kernel families bracket their launches instead.

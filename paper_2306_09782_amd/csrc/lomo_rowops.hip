@@ -195,7 +195,7 @@ __global__ __launch_bounds__(ROW_NT) void emb_rows_kernel(const uint16_t* __rest
                                                           const int32_t* __restrict__ seg_offsets,
                                                           const int32_t* __restrict__ n_unique, float s,
                                                           double* __restrict__ acc, int32_t* __restrict__ flag_out,
-                                                          const int32_t* __restrict__ flag_in) {
+                                                          const int32_t* __restrict__ flag_in, float lr, float clipv) {
     __shared__ float red[4];
     __shared__ int redflag[4];
     const int seg = blockIdx.x;
@@ -245,21 +245,38 @@ __global__ __launch_bounds__(ROW_NT) void emb_rows_kernel(const uint16_t* __rest
         half8* p = reinterpret_cast<half8*>(W + (int64_t)unique_ids[seg] * H + col);
         const half8 w = *p;
         half8 o;
+        if (MODE == 1) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = (_Float16)fmaf(-s, g[e], (float)w[e]);
+            for (int e = 0; e < 8; ++e) o[e] = (_Float16)fmaf(-s, g[e], (float)w[e]);
+        } else {   // clip by value: s is 1 / loss scale here
+            bool bad = false;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float gq = g[e] * s;
+                const bool fin = (__float_as_uint(gq) & 0x7f800000u) != 0x7f800000u;
+                const float gc = fminf(fmaxf(gq, -clipv), clipv);
+                o[e] = fin ? (_Float16)fmaf(-lr, gc, (float)w[e]) : w[e];
+                bad |= !fin;
+            }
+            if (bad && flag_out != nullptr) atomicOr(flag_out, 1);
+        }
         *p = o;
     }
 }
 
 hipError_t launch_embedding_rows(const uint16_t* dY, uint16_t* W, int64_t T, int64_t H, const EmbeddingWs& w, int mode,
-                                 float s, double* acc, int32_t* flag_out, const int32_t* flag_in, hipStream_t st) {
+                                 float s, double* acc, int32_t* flag_out, const int32_t* flag_in, hipStream_t st,
+                                 float lr, float clipv) {
     const dim3 grid((unsigned)T, (unsigned)((H + ROW_NT * 8 - 1) / (ROW_NT * 8)));
     if (mode == 0)
         hipLaunchKernelGGL(emb_rows_kernel<0>, grid, dim3(ROW_NT), 0, st, dY, W, H, w.perm, w.unique_ids, w.seg_offsets,
-                           w.n_unique, s, acc, flag_out, flag_in);
-    else
+                           w.n_unique, s, acc, flag_out, flag_in, lr, clipv);
+    else if (mode == 1)
         hipLaunchKernelGGL(emb_rows_kernel<1>, grid, dim3(ROW_NT), 0, st, dY, W, H, w.perm, w.unique_ids, w.seg_offsets,
-                           w.n_unique, s, acc, flag_out, flag_in);
+                           w.n_unique, s, acc, flag_out, flag_in, lr, clipv);
+    else
+        hipLaunchKernelGGL(emb_rows_kernel<2>, grid, dim3(ROW_NT), 0, st, dY, W, H, w.perm, w.unique_ids, w.seg_offsets,
+                           w.n_unique, s, acc, flag_out, flag_in, lr, clipv);
     return hipGetLastError();
 }
 
@@ -322,7 +339,7 @@ template <int MODE>
 __global__ __launch_bounds__(ROW_NT) void vec_finish_kernel(const float* __restrict__ partial, int64_t H, int splits,
                                                             uint16_t* __restrict__ w, float s, double* __restrict__ acc,
                                                             int32_t* __restrict__ flag_out,
-                                                            const int32_t* __restrict__ flag_in) {
+                                                            const int32_t* __restrict__ flag_in, float lr, float clipv) {
     __shared__ float red[4];
     __shared__ int redflag[4];
     if (MODE == 1 && flag_in != nullptr && flag_in[0] != 0) return;
@@ -340,12 +357,22 @@ __global__ __launch_bounds__(ROW_NT) void vec_finish_kernel(const float* __restr
         }
     } else if (j < H) {
         const _Float16 old = *reinterpret_cast<const _Float16*>(w + j);
-        *reinterpret_cast<_Float16*>(w + j) = (_Float16)fmaf(-s, g, (float)old);
+        if (MODE == 1) {
+            *reinterpret_cast<_Float16*>(w + j) = (_Float16)fmaf(-s, g, (float)old);
+        } else {   // clip by value: s is 1 / loss scale here
+            const float gq = g * s;
+            if ((__float_as_uint(gq) & 0x7f800000u) != 0x7f800000u) {
+                *reinterpret_cast<_Float16*>(w + j) = (_Float16)fmaf(-lr, fminf(fmaxf(gq, -clipv), clipv), (float)old);
+            } else if (flag_out != nullptr) {
+                atomicOr(flag_out, 1);
+            }
+        }
     }
 }
 
 hipError_t launch_vector(const uint16_t* Xhat, const uint16_t* dY, uint16_t* w, int64_t T, int64_t H, void* ws, int mode,
-                         float s, double* acc, int32_t* flag_out, const int32_t* flag_in, hipStream_t st) {
+                         float s, double* acc, int32_t* flag_out, const int32_t* flag_in, hipStream_t st, float lr,
+                         float clipv) {
     const int splits = vector_splits(T);
     float* partial = static_cast<float*>(ws);
     hipLaunchKernelGGL(vec_partial_kernel, dim3((unsigned)((H + VEC_COLS - 1) / VEC_COLS), (unsigned)splits),
@@ -353,10 +380,13 @@ hipError_t launch_vector(const uint16_t* Xhat, const uint16_t* dY, uint16_t* w, 
     const dim3 grid((unsigned)((H + ROW_NT - 1) / ROW_NT));
     if (mode == 0)
         hipLaunchKernelGGL(vec_finish_kernel<0>, grid, dim3(ROW_NT), 0, st, partial, H, splits, w, s, acc, flag_out,
-                           flag_in);
-    else
+                           flag_in, lr, clipv);
+    else if (mode == 1)
         hipLaunchKernelGGL(vec_finish_kernel<1>, grid, dim3(ROW_NT), 0, st, partial, H, splits, w, s, acc, flag_out,
-                           flag_in);
+                           flag_in, lr, clipv);
+    else
+        hipLaunchKernelGGL(vec_finish_kernel<2>, grid, dim3(ROW_NT), 0, st, partial, H, splits, w, s, acc, flag_out,
+                           flag_in, lr, clipv);
     return hipGetLastError();
 }
 

@@ -289,6 +289,71 @@ def test_vector_overflow(L):
     assert (host(wd) == 1.0).all()
 
 
+# ------------------------------------------------------------------------------- clip by value
+
+
+@pytest.mark.parametrize("T,K,N", [(512, 1024, 1024), (100, 264, 136), (70, 3600, 3320), (128, 4096, 4096)])
+def test_linear_clip_by_value(L, T, K, N):
+    Sc, sig_dy = 1024.0, 0.01
+    X = gen(31, (T, K), 1.0)
+    dY = S.normal_f16_np(S.tensor_key(32, T, K, N), (T, N), S.normal_mult(sig_dy, Sc))
+    W = S.normal_f16_np(S.tensor_key(33, T, K, N), (N, K), S.normal_mult(0.02))
+    G = O.linear_grad(X, dY)
+    gstd = math.sqrt(T) * sig_dy
+    clipv = float(np.float32(0.7 * gstd))                     # about half of the elements are clamped
+    lr = float(np.float32(30 * 2.0 ** -16 / gstd))
+    Wd = dev(W)
+    dX = torch.empty(T, K, dtype=torch.float16, device=DEV)
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    L.lomo_linear_backward_update_clip_value(dev(X), dev(dY), Wd, dX, lr, 1.0 / Sc, clipv, flag)
+    got = host(Wd)
+    want = O.sgd_update_clip_value(W, G, lr, clipv, Sc)
+    assert_weights_close(got, want, "clip by value")
+    clamped = np.abs(G / Sc) > clipv
+    assert 0.3 < clamped.mean() < 0.7
+    assert (O.ulp_distance_f16(want, O.sgd_update(W, G, lr, 1.0, Sc)) > 2).mean() > 0.2   # clamping matters
+    assert int(flag.item()) == 0
+    assert_dx_close(host(dX), dY, W, "dX")
+
+
+def test_clip_by_value_overflow_elements_keep_their_weight(L):
+    T, K, N = 130, 264, 520
+    X, dY, W = gen(34, (T, K), 1.0), gen(35, (T, N), 1.0), gen(36, (N, K), 0.02)
+    dY[7, 33] = np.inf                                         # poisons row 33 of the gradient
+    G = O.linear_grad(X, dY)
+    Wd = dev(W)
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    L.lomo_linear_backward_update_clip_value(dev(X), dev(dY), Wd, None, 0.01, 1.0, 5.0, flag)
+    got = host(Wd)
+    assert int(flag.item()) == 1
+    np.testing.assert_array_equal(got[33].view(np.uint16), W[33].view(np.uint16))
+    assert_weights_close(got, O.sgd_update_clip_value(W, G, float(np.float32(0.01)), 5.0, 1.0), "clip by value + inf")
+
+
+def test_step_clip_by_value_all_kinds(L):
+    T, V, H, N = 256, 500, 264, 512
+    Sc = 64.0
+    cpu = [
+        dict(kind="linear", X=gen(40, (T, H), 1.0), dY=S.normal_f16_np(41, (T, N), S.normal_mult(0.01, Sc)), W=gen(42, (N, H), 0.02)),
+        dict(kind="linear", X=gen(43, (T, 4096), 1.0), dY=S.normal_f16_np(44, (T, 4096), S.normal_mult(0.01, Sc)),
+             W=gen(45, (4096, 4096), 0.02)),                                  # persistent-kernel path
+        dict(kind="vector", X=gen(46, (T, H), 1.0), dY=S.normal_f16_np(47, (T, H), S.normal_mult(0.01, Sc)), W=np.ones(H, np.float16)),
+        dict(kind="embedding", ids=S.zipf_ids(3, T, V), dY=S.normal_f16_np(48, (T, H), S.normal_mult(0.01, Sc)), W=gen(49, (V, H), 0.02)),
+    ]
+    cpu[2]["dY"][5, 9] = np.nan
+    gpu = [{k: (dev(v) if isinstance(v, np.ndarray) else v) for k, v in t.items()} for t in cpu]
+    lst = L.make_tensor_list(gpu)
+    ws = torch.empty(max(L.lomo_step_workspace_bytes(lst), 256), dtype=torch.uint8, device=DEV)
+    flags = torch.zeros(len(gpu) + 1, dtype=torch.int32, device=DEV)
+    lr, clipv = 0.02, 0.05
+    L.lomo_step_update_pass_clip_value(lst, lr, 1.0 / Sc, clipv, flags, ws)
+    assert flags.cpu().tolist() == [0, 0, 1, 0, 1]
+    for g_, t in zip(gpu, cpu):
+        want = O.sgd_update_clip_value(t["W"], O.tensor_grad(t), float(np.float32(lr)), float(np.float32(clipv)), Sc)
+        assert_weights_close(host(g_["W"]), want, t["kind"])
+    assert host(gpu[2]["W"])[9] == 1.0
+
+
 def test_reduce_flags(L):
     f = torch.zeros(700, dtype=torch.int32, device=DEV)
     out = torch.full((1,), 7, dtype=torch.int32, device=DEV)

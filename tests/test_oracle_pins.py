@@ -403,6 +403,21 @@ def test_p11_clip_by_value_printed_example(golden_dir):
     np.testing.assert_array_equal(out, f16(g["clip_value_out"][0]))
 
 
+def test_clip_by_value_hand_cases():
+    """Hand-worked: W = [1, 1, 1, 1], scaled G = [8, -8, 1, inf], S = 4, c = 1, lr = 0.5.
+    g = [2, -2, 0.25, inf] -> clamp [1, -1, 0.25, (left alone)] -> W' = [0.5, 1.5, 0.875, 1]."""
+    W = np.ones(4, np.float16)
+    G = np.array([8.0, -8.0, 1.0, np.inf])
+    out = O.sgd_update_clip_value(W, G, 0.5, 1.0, 4.0)
+    np.testing.assert_array_equal(out.astype(np.float64), [0.5, 1.5, 0.875, 1.0])
+    assert O.has_overflow(G)
+    out = O.sgd_update_clip_value(W, np.array([np.nan, 2.0, -0.5, 0.0]), 1.0, 0.25, 1.0)
+    np.testing.assert_array_equal(out.astype(np.float64), [1.0, 0.75, 1.25, 1.0])
+    # below the threshold it is plain SGD
+    G = np.array([0.5, -0.25, 0.125, 0.0])
+    np.testing.assert_array_equal(O.sgd_update_clip_value(W, G, 0.5, 1.0, 1.0), O.sgd_update(W, G, 0.5, 1.0, 1.0))
+
+
 # ----------------------------------------------------------------------------- rounding
 
 
