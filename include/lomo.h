@@ -109,8 +109,8 @@ lomo_status lomo_linear_backward_update(const lomo_half* X, const lomo_half* dY,
                                         const int32_t* overflow_flag, void* stream);
 
 /* Embedding table W [V x H]: positions are grouped by id with a stable sort (ties by position),
- * each touched row's gradient is the fp32 sum of its dY rows in ascending position order
- * (deterministic), and the row is updated in place as above.  Rows whose id does not occur are
+ * each touched row's gradient is the fp32 sum of its dY rows taken in a fixed order that depends
+ * only on the ids (bit-reproducible), and the row is updated in place as above.  Rows whose id does not occur are
  * neither read nor written. */
 lomo_status lomo_embedding_update(const int32_t* ids, const lomo_half* dY, lomo_half* W,
                                   int64_t T, int64_t H, int64_t V,

@@ -101,7 +101,7 @@ lomo_status lomo_embedding_grouping(const int32_t* ids, int64_t T, int64_t V, vo
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (T > 0) {
         if (!ids) return LOMO_ERR_NULL;
-        if (!ws || ws_bytes < embedding_ws_bytes(T, 8) || (reinterpret_cast<uintptr_t>(ws) & 255u))
+        if (!ws || ws_bytes < embedding_ws_bytes(T, 0) || (reinterpret_cast<uintptr_t>(ws) & 255u))
             return LOMO_ERR_WORKSPACE;
     }
     EmbeddingWs w{};

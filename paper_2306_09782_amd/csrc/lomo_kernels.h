@@ -60,6 +60,7 @@ struct EmbeddingWs {          // carved out of the caller's workspace
     int32_t* unique_ids;      // [T]
     int32_t* seg_offsets;     // [T + 1]
     int32_t* n_unique;        // [1]
+    double* partials;         // [512 * ceil(H / 512)] per-workgroup shares of the squared norm
 };
 size_t embedding_ws_bytes(int64_t T, int64_t H);
 EmbeddingWs carve_embedding_ws(void* ws, int64_t T);

@@ -124,13 +124,19 @@ __global__ __launch_bounds__(SORT_NT) void emb_segments(const uint64_t* __restri
     }
 }
 
-size_t embedding_ws_bytes(int64_t T, int64_t /*H*/) {
+static inline size_t emb_partials_bytes(int64_t H) {
+    const int64_t slabs = (H + 511) / 512 > 0 ? (H + 511) / 512 : 1;
+    return align_up((size_t)512 * (size_t)slabs * sizeof(double), 256);
+}
+
+size_t embedding_ws_bytes(int64_t T, int64_t H) {
     if (T <= 0) return 0;
     const int64_t Tpad = next_pow2(T);
     size_t b = align_up((size_t)Tpad * 8, 256);
     b += align_up((size_t)T * 4, 256) * 2;         // perm, unique_ids
     b += align_up((size_t)(T + 1) * 4, 256);       // seg_offsets
     b += 256;                                      // n_unique
+    b += emb_partials_bytes(H);                    // per-workgroup shares of the squared norm
     return b;
 }
 
@@ -147,6 +153,8 @@ EmbeddingWs carve_embedding_ws(void* ws, int64_t T) {
     w.seg_offsets = reinterpret_cast<int32_t*>(p);
     p += align_up((size_t)(T + 1) * 4, 256);
     w.n_unique = reinterpret_cast<int32_t*>(p);
+    p += 256;
+    w.partials = reinterpret_cast<double*>(p);
     return w;
 }
 
@@ -175,7 +183,7 @@ hipError_t launch_embedding_grouping(const int32_t* ids, int64_t T, const Embedd
 }
 
 // ------------------------------------------------------------------------------------------
-// Embedding rows: one workgroup per (segment, 2048-column slab); fp32 sums in position order.
+// Embedding rows: fp32 segment sums in a fixed order.
 // ------------------------------------------------------------------------------------------
 
 constexpr int ROW_NT = 256;
@@ -188,95 +196,142 @@ __device__ __forceinline__ float block_sum_256(float v, float* red) {
     return (red[0] + red[1]) + (red[2] + red[3]);
 }
 
+// Workgroups stride over segments; each handles one 512-column slab.  The eight waves of a workgroup
+// take the segment's rows round-robin (wave w: rows beg + w, beg + w + 8, ...), each summing in
+// ascending position order; the eight partial sums are then added pairwise in a fixed tree.  The
+// order depends only on the input, never on scheduling, so results are bit-reproducible, and a hot
+// token's long segment costs an eighth of a serial walk.
+constexpr int EMB_COLS = 512;   // 64 lanes x 8 halves
+constexpr int EMB_NT = 512;     // 8 waves
+constexpr int EMB_W = EMB_NT / 64;
+
+constexpr int EMB_MAX_GX = 512;    // workgroups along the segment axis; each strides over segments
+
 template <int MODE>
-__global__ __launch_bounds__(ROW_NT) void emb_rows_kernel(const uint16_t* __restrict__ dY, uint16_t* __restrict__ W,
+__global__ __launch_bounds__(EMB_NT) void emb_rows_kernel(const uint16_t* __restrict__ dY, uint16_t* __restrict__ W,
                                                           int64_t H, const int32_t* __restrict__ perm,
                                                           const int32_t* __restrict__ unique_ids,
                                                           const int32_t* __restrict__ seg_offsets,
                                                           const int32_t* __restrict__ n_unique, float s,
-                                                          double* __restrict__ acc, int32_t* __restrict__ flag_out,
+                                                          double* __restrict__ partials, int32_t* __restrict__ flag_out,
                                                           const int32_t* __restrict__ flag_in, float lr, float clipv) {
-    __shared__ float red[4];
-    __shared__ int redflag[4];
-    const int seg = blockIdx.x;
-    if (seg >= n_unique[0]) return;
+    __shared__ float part[EMB_W - 1][64][9];
     if (MODE == 1 && flag_in != nullptr && flag_in[0] != 0) return;
-    const int64_t col = ((int64_t)blockIdx.y * ROW_NT + threadIdx.x) * 8;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t col = (int64_t)blockIdx.y * EMB_COLS + lane * 8;
     const bool active = col < H;
-    const int beg = seg_offsets[seg], end = seg_offsets[seg + 1];
-    float g[8];
+    const int nseg = n_unique[0];
+    double block_sq = 0.0;     // MODE 0: this workgroup's share of the squared norm (held by wave 0)
+    bool any_bad = false;
+
+    for (int seg = blockIdx.x; seg < nseg; seg += gridDim.x) {
+        const int beg = seg_offsets[seg], end = seg_offsets[seg + 1];
+        float g[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) g[e] = 0.f;
-    if (active) {
-        int r = beg;
-        for (; r + 4 <= end; r += 4) {
-            half8 v[4];
+        for (int e = 0; e < 8; ++e) g[e] = 0.f;
+        if (active) {
+            int r = beg + wave;
+            for (; r + 7 * EMB_W < end; r += 8 * EMB_W) {      // eight rows in flight per wave
+                half8 v[8];
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
-                v[u] = *reinterpret_cast<const half8*>(dY + (int64_t)perm[r + u] * H + col);
+                for (int u = 0; u < 8; ++u)
+                    v[u] = *reinterpret_cast<const half8*>(dY + (int64_t)perm[r + EMB_W * u] * H + col);
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+                for (int u = 0; u < 8; ++u)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) g[e] += (float)v[u][e];
+                    for (int e = 0; e < 8; ++e) g[e] += (float)v[u][e];
+            }
+            for (; r < end; r += EMB_W) {
+                const half8 v = *reinterpret_cast<const half8*>(dY + (int64_t)perm[r] * H + col);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) g[e] += (float)v[e];
+            }
         }
-        for (; r < end; ++r) {
-            const half8 v = *reinterpret_cast<const half8*>(dY + (int64_t)perm[r] * H + col);
+        if (end - beg > 1) {      // uniform per workgroup: a one-row segment is wave 0's alone
+            if (wave > 0) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) g[e] += (float)v[e];
-        }
-    }
-    if (MODE == 0) {
-        float sum = 0.f;
-        uint32_t worst = 0u;
+                for (int e = 0; e < 8; ++e) part[wave - 1][lane][e] = g[e];
+            }
+            __syncthreads();
+            if (wave == 0) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            sum = fmaf(g[e], g[e], sum);
-            const uint32_t mag = __float_as_uint(g[e]) & 0x7fffffffu;
-            worst = mag > worst ? mag : worst;
+                for (int e = 0; e < 8; ++e)
+                    g[e] = ((g[e] + part[0][lane][e]) + (part[1][lane][e] + part[2][lane][e])) +
+                           ((part[3][lane][e] + part[4][lane][e]) + (part[5][lane][e] + part[6][lane][e]));
+            }
+            __syncthreads();
         }
-        const bool bad = __any(worst >= 0x7f800000u);
-        if ((threadIdx.x & 63) == 0) redflag[threadIdx.x >> 6] = bad ? 1 : 0;
-        const float total = block_sum_256(sum, red);
-        if (threadIdx.x == 0) {
-            atomicAdd(acc, (double)total);
-            if (flag_out != nullptr && (redflag[0] | redflag[1] | redflag[2] | redflag[3])) atomicOr(flag_out, 1);
-        }
-    } else if (active) {
-        half8* p = reinterpret_cast<half8*>(W + (int64_t)unique_ids[seg] * H + col);
-        const half8 w = *p;
-        half8 o;
-        if (MODE == 1) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = (_Float16)fmaf(-s, g[e], (float)w[e]);
-        } else {   // clip by value: s is 1 / loss scale here
-            bool bad = false;
+        if (wave != 0) continue;
+
+        if (MODE == 0) {
+            float sum = 0.f;
+            uint32_t worst = 0u;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const float gq = g[e] * s;
-                const bool fin = (__float_as_uint(gq) & 0x7f800000u) != 0x7f800000u;
-                const float gc = fminf(fmaxf(gq, -clipv), clipv);
-                o[e] = fin ? (_Float16)fmaf(-lr, gc, (float)w[e]) : w[e];
-                bad |= !fin;
+                sum = fmaf(g[e], g[e], sum);
+                const uint32_t mag = __float_as_uint(g[e]) & 0x7fffffffu;
+                worst = mag > worst ? mag : worst;
             }
-            if (bad && flag_out != nullptr) atomicOr(flag_out, 1);
+            any_bad |= worst >= 0x7f800000u;
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
+            block_sq += (double)sum;
+        } else if (active) {
+            half8* p = reinterpret_cast<half8*>(W + (int64_t)unique_ids[seg] * H + col);
+            const half8 w = *p;
+            half8 o;
+            if (MODE == 1) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = (_Float16)fmaf(-s, g[e], (float)w[e]);
+            } else {   // clip by value: s is 1 / loss scale here
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float gq = g[e] * s;
+                    const bool fin = (__float_as_uint(gq) & 0x7f800000u) != 0x7f800000u;
+                    const float gc = fminf(fmaxf(gq, -clipv), clipv);
+                    o[e] = fin ? (_Float16)fmaf(-lr, gc, (float)w[e]) : w[e];
+                    any_bad |= !fin;
+                }
+            }
+            *p = o;
         }
-        *p = o;
     }
+    if (wave != 0) return;
+    if (MODE == 0 && lane == 0) partials[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = block_sq;
+    if (MODE != 1 && flag_out != nullptr && __any(any_bad) && lane == 0) atomicOr(flag_out, 1);
+}
+
+// Adds the per-workgroup shares in index order: the embedding's squared norm is bit-reproducible.
+__global__ __launch_bounds__(ROW_NT) void emb_finish_sqnorm(const double* __restrict__ partials, int n,
+                                                            double* __restrict__ acc) {
+    __shared__ double red[ROW_NT];
+    double v = 0.0;
+    for (int i = threadIdx.x; i < n; i += ROW_NT) v += partials[i];
+    red[threadIdx.x] = v;
+    __syncthreads();
+    for (int off = ROW_NT / 2; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) atomicAdd(acc, red[0]);
 }
 
 hipError_t launch_embedding_rows(const uint16_t* dY, uint16_t* W, int64_t T, int64_t H, const EmbeddingWs& w, int mode,
                                  float s, double* acc, int32_t* flag_out, const int32_t* flag_in, hipStream_t st,
                                  float lr, float clipv) {
-    const dim3 grid((unsigned)T, (unsigned)((H + ROW_NT * 8 - 1) / (ROW_NT * 8)));
-    if (mode == 0)
-        hipLaunchKernelGGL(emb_rows_kernel<0>, grid, dim3(ROW_NT), 0, st, dY, W, H, w.perm, w.unique_ids, w.seg_offsets,
-                           w.n_unique, s, acc, flag_out, flag_in, lr, clipv);
-    else if (mode == 1)
-        hipLaunchKernelGGL(emb_rows_kernel<1>, grid, dim3(ROW_NT), 0, st, dY, W, H, w.perm, w.unique_ids, w.seg_offsets,
-                           w.n_unique, s, acc, flag_out, flag_in, lr, clipv);
-    else
-        hipLaunchKernelGGL(emb_rows_kernel<2>, grid, dim3(ROW_NT), 0, st, dY, W, H, w.perm, w.unique_ids, w.seg_offsets,
-                           w.n_unique, s, acc, flag_out, flag_in, lr, clipv);
+    const unsigned gx = (unsigned)(T < EMB_MAX_GX ? T : EMB_MAX_GX);
+    const dim3 grid(gx, (unsigned)((H + EMB_COLS - 1) / EMB_COLS));
+    if (mode == 0) {
+        hipLaunchKernelGGL(emb_rows_kernel<0>, grid, dim3(EMB_NT), 0, st, dY, W, H, w.perm, w.unique_ids, w.seg_offsets,
+                           w.n_unique, s, w.partials, flag_out, flag_in, lr, clipv);
+        hipLaunchKernelGGL(emb_finish_sqnorm, dim3(1), dim3(ROW_NT), 0, st, w.partials, (int)(grid.x * grid.y), acc);
+    } else if (mode == 1) {
+        hipLaunchKernelGGL(emb_rows_kernel<1>, grid, dim3(EMB_NT), 0, st, dY, W, H, w.perm, w.unique_ids, w.seg_offsets,
+                           w.n_unique, s, w.partials, flag_out, flag_in, lr, clipv);
+    } else {
+        hipLaunchKernelGGL(emb_rows_kernel<2>, grid, dim3(EMB_NT), 0, st, dY, W, H, w.perm, w.unique_ids, w.seg_offsets,
+                           w.n_unique, s, w.partials, flag_out, flag_in, lr, clipv);
+    }
     return hipGetLastError();
 }
 
