@@ -199,9 +199,23 @@ lomo_status lomo_embedding_grouping(const int32_t* ids, int64_t T, int64_t V,
 
 /* ---------------------------------------------------------------- diagnostics */
 
+/* How the norm pass (paper section 3.3.1) obtains ||dY^T X||^2 of a linear tensor.
+ *   LOMO_NORM_DIRECT  contract the gradient tile by tile and square it (2 T N K flop).  Default.
+ *   LOMO_NORM_GRAM    sum over token pairs of (x_t . x_t')(dy_t . dy_t'), lower triangle only
+ *                     (T^2 (K + N) flop); needs T % 256 == 0, K % 128 == 0, N % 128 == 0 and dense
+ *                     rows, other tensors take the direct route.  Same value up to rounding, same
+ *                     overflow flag; its rounding error is relative to sum_t |x_t|^2 |dy_t|^2 instead
+ *                     of ||G||^2, so it loses accuracy when per-token gradients cancel in the sum.
+ *   LOMO_NORM_AUTO    per tensor, whichever the cost model says is faster.
+ * Applies to lomo_wgrad_sqnorm and lomo_step_norm_pass; process-wide host-side setting, not
+ * thread-safe against concurrent launches.  Returns LOMO_ERR_SHAPE for an unknown value. */
+enum { LOMO_NORM_DIRECT = 0, LOMO_NORM_AUTO = 1, LOMO_NORM_GRAM = 2 };
+lomo_status lomo_set_norm_algorithm(int algorithm);
+int lomo_get_norm_algorithm(void);
+
 /* Kernel families for lomo_timing_read. */
 enum { LOMO_KERNEL_WGRAD_UPDATE = 0, LOMO_KERNEL_WGRAD_SQNORM = 1, LOMO_KERNEL_DGRAD = 2,
-       LOMO_KERNEL_EMBEDDING = 3, LOMO_KERNEL_VECTOR = 4, LOMO_KERNEL_FAMILIES = 5 };
+       LOMO_KERNEL_EMBEDDING = 3, LOMO_KERNEL_VECTOR = 4, LOMO_KERNEL_GRAM_SQNORM = 5, LOMO_KERNEL_FAMILIES = 6 };
 
 /* Per-kernel timing for benchmarks: while enabled, each launch of a kernel family is bracketed
  * by two HIP events recorded on the launch stream (the only host-side state the library keeps;

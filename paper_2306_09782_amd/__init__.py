@@ -11,7 +11,7 @@ from .binding import (LomoError, library_path, load_library, lomo_version, lomo_
                       lomo_embedding_grouping, lomo_timing_enable, lomo_timing_read, KERNEL_FAMILIES,
                       lomo_step_workspace_bytes, lomo_step_norm_pass, lomo_step_update_pass, make_tensor_list,
                       lomo_linear_backward_update_clip_value, lomo_step_update_pass_clip_value,
-                      LomoTensor,
+                      lomo_set_norm_algorithm, lomo_get_norm_algorithm, NORM_ALGORITHMS, LomoTensor,
                       EXPORTED_SYMBOLS)
 
 __all__ = [n for n in dir() if n.startswith("lomo_")] + ["LomoError", "library_path", "load_library",

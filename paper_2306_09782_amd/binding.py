@@ -19,6 +19,7 @@ EXPORTED_SYMBOLS = (
     "lomo_vector_workspace_bytes", "lomo_embedding_grouping", "lomo_timing_enable", "lomo_timing_read",
     "lomo_step_workspace_bytes", "lomo_step_norm_pass", "lomo_step_update_pass",
     "lomo_linear_backward_update_clip_value", "lomo_step_update_pass_clip_value",
+    "lomo_set_norm_algorithm", "lomo_get_norm_algorithm",
 )
 
 
@@ -72,6 +73,8 @@ def load_library():
         "lomo_linear_backward_update_clip_value": (c_int, [P, P, P, P, I64, I64, I64, c_float, c_float, c_float, P, P]),
         "lomo_step_update_pass_clip_value": (c_int, [POINTER(LomoTensor), I64, c_float, c_float, c_float, P, P,
                                                      c_size_t, P]),
+        "lomo_set_norm_algorithm": (c_int, [c_int]),
+        "lomo_get_norm_algorithm": (c_int, []),
         "lomo_timing_enable": (c_int, [c_int]),
         "lomo_timing_read": (c_int, [c_int, POINTER(c_double), POINTER(c_int64)]),
     }
@@ -180,7 +183,18 @@ def lomo_embedding_grouping(ids, V, ws, unique_ids, seg_offsets, perm, n_unique,
                                                   _ptr(seg_offsets), _ptr(perm), _ptr(n_unique), _stream(stream)))
 
 
-KERNEL_FAMILIES = ("wgrad_update", "wgrad_sqnorm", "dgrad", "embedding", "vector")
+KERNEL_FAMILIES = ("wgrad_update", "wgrad_sqnorm", "dgrad", "embedding", "vector", "gram_sqnorm")
+NORM_ALGORITHMS = {"direct": 0, "auto": 1, "gram": 2}
+
+
+def lomo_set_norm_algorithm(algorithm):
+    """'direct' (default), 'auto' or 'gram' (or the integer code): route of the norm pass for linear tensors."""
+    code = NORM_ALGORITHMS[algorithm] if isinstance(algorithm, str) else int(algorithm)
+    _check(load_library().lomo_set_norm_algorithm(code))
+
+
+def lomo_get_norm_algorithm() -> int:
+    return load_library().lomo_get_norm_algorithm()
 
 
 def lomo_timing_enable(on: bool):

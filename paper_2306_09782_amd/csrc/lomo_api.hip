@@ -250,7 +250,10 @@ lomo_status lomo_step_norm_pass(const lomo_tensor* tensors, int64_t n, double* a
                 return LOMO_ERR_LAUNCH;
         }
     }
-    if (!grouped.empty() && launch_dma_group<true, EPI_SQNORM>(grouped.data(), (int)grouped.size(), st) != hipSuccess)
+    std::vector<GemmArgs> gram, direct;
+    choose_norm_route(grouped, gram, direct);
+    if (!gram.empty() && launch_gram_group(gram.data(), (int)gram.size(), st) != hipSuccess) return LOMO_ERR_LAUNCH;
+    if (!direct.empty() && launch_dma_group<true, EPI_SQNORM>(direct.data(), (int)direct.size(), st) != hipSuccess)
         return LOMO_ERR_LAUNCH;
     return from_hip(launch_reduce_flags(flags, n, flags + n, st));
 }
@@ -394,6 +397,13 @@ lomo_status lomo_step_update_pass_clip_value(const lomo_tensor* tensors, int64_t
     }
     return from_hip(launch_reduce_flags(flags, n, flags + n, st));
 }
+
+lomo_status lomo_set_norm_algorithm(int algorithm) {
+    if (algorithm != LOMO_NORM_DIRECT && algorithm != LOMO_NORM_AUTO && algorithm != LOMO_NORM_GRAM) return LOMO_ERR_SHAPE;
+    set_norm_algorithm(algorithm);
+    return LOMO_OK;
+}
+int lomo_get_norm_algorithm(void) { return norm_algorithm(); }
 
 lomo_status lomo_reduce_flags(const int32_t* flags, int64_t n, int32_t* out, void* stream) {
     if (n < 0) return LOMO_ERR_SHAPE;

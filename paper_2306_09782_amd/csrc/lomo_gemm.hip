@@ -251,6 +251,11 @@ hipError_t launch_wgrad_update_clipv(const GemmArgs& a, hipStream_t st) {
 }
 hipError_t launch_wgrad_sqnorm(const GemmArgs& a, hipStream_t st) {
     hipError_t e;
+    if (norm_algorithm() != LOMO_NORM_DIRECT && fast_enabled() && dma_enabled()) {
+        std::vector<GemmArgs> one(1, a), gram, direct;
+        choose_norm_route(one, gram, direct);
+        if (!gram.empty()) return launch_gram_group(gram.data(), 1, st);
+    }
     if (fast_enabled() && dma_enabled() && try_launch_dma<true, EPI_SQNORM>(a, st, &e)) return e;
     if (fast_enabled() && try_launch_fast<true, EPI_SQNORM>(a, st, &e)) return e;
     return use_big_tiles(a.M, a.Nn) ? launch_one<256, 256, true, EPI_SQNORM>(a, st)

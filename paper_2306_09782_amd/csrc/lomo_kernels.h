@@ -4,6 +4,8 @@
 #include <hip/hip_ext.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "lomo.h"
 
 namespace lomo {
@@ -47,6 +49,17 @@ template <bool B_STRIDED, int EPI>
 bool try_launch_dma(const GemmArgs& a, hipStream_t st, hipError_t* err);
 template <bool B_STRIDED, int EPI>
 hipError_t launch_dma_group(const GemmArgs* list, int n, hipStream_t st);
+
+// Gram route of the norm pass (lomo_gram.hip): ||dY^T X||^2 from X X^T and dY dY^T.  `a` is a norm-pass
+// contraction (A = X, B = dY, C = T).  Costs are in units of one 256 x 256 x 32 slice on one CU.
+bool gram_eligible(const GemmArgs& a);
+double gram_cost(const GemmArgs& a);
+double direct_cost(const GemmArgs& a);
+hipError_t launch_gram_group(const GemmArgs* list, int n, hipStream_t st);
+int norm_algorithm();
+void set_norm_algorithm(int v);
+// Splits the eligible tensors of `all` between the two routes according to the current setting.
+void choose_norm_route(const std::vector<GemmArgs>& all, std::vector<GemmArgs>& gram, std::vector<GemmArgs>& direct);
 
 hipError_t launch_wgrad_update(const GemmArgs& a, hipStream_t st);
 hipError_t launch_wgrad_update_clipv(const GemmArgs& a, hipStream_t st);

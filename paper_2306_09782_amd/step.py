@@ -71,14 +71,18 @@ class LomoStep:
             else:
                 B.lomo_vector_update(t["X"], t["dY"], t["W"], lr, inv_loss_scale, clip, self.ws, step_flag, stream)
 
+    def read_back(self, n: int) -> Dict:
+        """The one host read-back of a step: scaled squared norm, per-tensor flags, step flag."""
+        host = torch.cat([self.acc.view(torch.int32), self.flags[:n + 1]]).cpu()
+        return {"total_sqnorm": float(host[:2].view(torch.float64)[0]),
+                "flags": [bool(v) for v in host[2:2 + n].tolist()], "overflow": bool(host[2 + n])}
+
     def run(self, tensors: List[Dict], lr: float, loss_scale: float, max_norm: float = 1.0, eps: float = 1e-6,
             stream=None, clip_override: Optional[float] = None) -> Dict:
         n = len(tensors)
         self.norm_pass(tensors, stream)
-        host = torch.cat([self.acc.view(torch.int32), self.flags[:n + 1]]).cpu()   # one read-back
-        sq = float(host[:2].view(torch.float64)[0])
-        flags = [bool(v) for v in host[2:2 + n].tolist()]
-        overflow = bool(host[2 + n])
+        back = self.read_back(n)
+        sq, flags, overflow = back["total_sqnorm"], back["flags"], back["overflow"]
         clip = B.lomo_clip_coef(sq, loss_scale, max_norm, eps) if clip_override is None else clip_override
         if not overflow:
             self.update_pass(tensors, lr, 1.0 / loss_scale, clip, stream)
