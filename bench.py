@@ -99,6 +99,11 @@ def main():
     ap.add_argument("--no-dgrad", action="store_true", help="skip dX (diagnostic only; not the metric)")
     ap.add_argument("--per-tensor-calls", action="store_true",
                     help="one C call per tensor instead of the whole-pass calls (same results, more launches)")
+    ap.add_argument("--norm-pass", choices=["direct", "auto", "gram"], default="direct",
+                    help="route of the norm pass for linear tensors in the timed steps (default: direct, the one the "
+                         "metric's flop count describes)")
+    ap.add_argument("--no-norm-compare", action="store_true",
+                    help="skip the extra timing of pass 1 alone on each route after the timed steps")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -143,6 +148,7 @@ def main():
     stepper = LomoStep(dev, max_T=wl.T, max_H=maxH, max_tensors=len(tensors), grouped=not args.per_tensor_calls)
     lr = float(np.float32(wl.lr))
 
+    L.lomo_set_norm_algorithm(args.norm_pass)
     res = None
     for _ in range(args.warmup):
         res = stepper.run(tensors, lr, wl.loss_scale, wl.max_norm, wl.eps)
@@ -157,6 +163,24 @@ def main():
     dt = time.perf_counter() - t0
     fam = {name: L.lomo_timing_read(i) for i, name in enumerate(L.KERNEL_FAMILIES)}
     L.lomo_timing_enable(False)
+
+    # Pass 1 alone on each route (same inputs, same result up to rounding): not part of `value`.
+    norm_compare = None
+    if not args.no_norm_compare:
+        norm_compare = {}
+        for route in ("direct", "gram", "auto"):
+            L.lomo_set_norm_algorithm(route)
+            for _ in range(2):
+                stepper.norm_pass(tensors)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            reps = max(3, min(10, args.steps))
+            for _ in range(reps):
+                stepper.norm_pass(tensors)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t1) / reps * 1e3
+            norm_compare[route] = {"ms": ms, "total_sqnorm": stepper.read_back(len(tensors))["total_sqnorm"]}
+        L.lomo_set_norm_algorithm(args.norm_pass)
 
     ms_per_step = dt / args.steps * 1e3
     lin = [s for s in wl.tensors if s.kind == "linear"]
@@ -190,7 +214,7 @@ def main():
         "config": {"workload": wl.name, "tokens": wl.T, "tensors": len(wl.tensors), "params": wl.n_params,
                    "loss_scale": wl.loss_scale, "lr": wl.lr, "max_norm": wl.max_norm,
                    "gemms_per_linear": gemms_per_step, "weights_restored_between_steps": False,
-                   "calls": "per_tensor" if args.per_tensor_calls else "whole_pass"},
+                   "calls": "per_tensor" if args.per_tensor_calls else "whole_pass", "norm_pass": args.norm_pass},
         "params_per_s": wl.n_params / (ms_per_step * 1e-3),
         "frac_fp16_mfma_peak_whole_step": tflops / PEAK_FP16_TFLOPS,
         "kernels": {k: fam_rate(k) for k in ("wgrad_update", "wgrad_sqnorm", "dgrad")},
@@ -198,6 +222,11 @@ def main():
         "grad_norm": res["norm"], "clip_coef": res["clip_coef"], "overflow": res["overflow"],
         "roofline": roofline,
     }
+    if fam["gram_sqnorm"][1]:
+        out["kernels"]["gram_sqnorm"] = {"ms_per_step": fam["gram_sqnorm"][0] / args.steps, "launches": fam["gram_sqnorm"][1],
+                                         "avg_launch_ms": fam["gram_sqnorm"][0] / fam["gram_sqnorm"][1]}
+    if norm_compare:
+        out["norm_pass_alone"] = norm_compare
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))
