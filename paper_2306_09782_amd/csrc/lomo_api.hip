@@ -169,6 +169,7 @@ lomo_status lomo_vector_update(const lomo_half* Xhat, const lomo_half* dY, lomo_
     if (s != LOMO_OK) return s;
     if (T == 0 || H == 0) return LOMO_OK;
     if (!w) return LOMO_ERR_NULL;
+    if (misaligned(w)) return LOMO_ERR_ALIGN;
     ScopedTiming timing(LOMO_KERNEL_VECTOR, static_cast<hipStream_t>(stream));
     return from_hip(launch_vector(Xhat, dY, w, T, H, ws, 1, step_size(lr, inv_loss_scale, clip_coef), nullptr, nullptr,
                                   overflow_flag, static_cast<hipStream_t>(stream)));
@@ -209,7 +210,7 @@ static lomo_status check_step(const lomo_tensor* tensors, int64_t n, bool update
             if (s == LOMO_OK && update && t.T > 0 && t.K > 0 && t.N > 0 && (!t.W || misaligned(t.W))) s = t.W ? LOMO_ERR_ALIGN : LOMO_ERR_NULL;
         } else if (t.kind == LOMO_TENSOR_VECTOR) {
             s = check_vector(t.X, t.dY, t.T, t.K, ws, ws_bytes);
-            if (s == LOMO_OK && update && t.T > 0 && t.K > 0 && !t.W) s = LOMO_ERR_NULL;
+            if (s == LOMO_OK && update && t.T > 0 && t.K > 0 && (!t.W || misaligned(t.W))) s = t.W ? LOMO_ERR_ALIGN : LOMO_ERR_NULL;
         } else {
             s = LOMO_ERR_SHAPE;
         }

@@ -10,6 +10,7 @@
 namespace lomo {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 
 static inline int64_t next_pow2(int64_t v) {
     int64_t p = 1;
@@ -340,13 +341,17 @@ hipError_t launch_embedding_rows(const uint16_t* dY, uint16_t* W, int64_t T, int
 // row split, stage 2 adds the splits in order and finishes (norm or update).
 // ------------------------------------------------------------------------------------------
 
-constexpr int VEC_COLS = 64;        // columns per workgroup: 8 lanes x 8 halves = 128 bytes per row
-constexpr int VEC_ROWS = ROW_NT / 8;
+constexpr int VEC_COLS = 512;       // columns per workgroup: 64 lanes x 8 halves = 1 KiB per row and wave
+constexpr int VEC_NT = 512;         // 8 waves
+constexpr int VEC_W = VEC_NT / 64;
+constexpr int VEC_U = 8;            // rows a wave has in flight: 16 independent 16-byte loads per lane
+constexpr int VEC_BLOCK = VEC_W * VEC_U;   // rows a workgroup consumes per iteration
+constexpr int VEC_MAX_SPLITS = 128;
 
 static inline int vector_splits(int64_t T) {
-    int64_t s = (T + 255) / 256;
+    int64_t s = (T + VEC_BLOCK - 1) / VEC_BLOCK;
     if (s < 1) s = 1;
-    if (s > 64) s = 64;
+    if (s > VEC_MAX_SPLITS) s = VEC_MAX_SPLITS;
     return (int)s;
 }
 
@@ -355,73 +360,147 @@ size_t vector_ws_bytes(int64_t T, int64_t H) {
     return align_up((size_t)vector_splits(T) * (size_t)H * sizeof(float), 256);
 }
 
-__global__ __launch_bounds__(ROW_NT) void vec_partial_kernel(const uint16_t* __restrict__ Xh,
+// Stage 1.  Workgroup (slab, split) sums rows [t0, t1) of its 512-column slab.  Per iteration every wave
+// takes eight consecutive rows and issues all sixteen loads before using any, so a CU keeps about
+// 256 KiB in flight; a wave adds its rows in ascending order, the eight waves are then added in a
+// fixed tree: the result depends on T and H only, not on scheduling.
+__global__ __launch_bounds__(VEC_NT) void vec_partial_kernel(const uint16_t* __restrict__ Xh,
                                                              const uint16_t* __restrict__ dY, int64_t T, int64_t H,
                                                              int splits, float* __restrict__ partial) {
-    __shared__ float red[VEC_ROWS][VEC_COLS + 1];
-    const int cx = threadIdx.x & 7, ry = threadIdx.x >> 3;
-    const int64_t col = (int64_t)blockIdx.x * VEC_COLS + cx * 8;
+    __shared__ float part[VEC_W - 1][64][9];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t col = (int64_t)blockIdx.x * VEC_COLS + lane * 8;
+    const bool active = col < H;
     const int split = blockIdx.y;
-    const int64_t rows_per = (T + splits - 1) / splits;
+    int64_t rows_per = (T + splits - 1) / splits;
+    rows_per = (rows_per + VEC_BLOCK - 1) / VEC_BLOCK * VEC_BLOCK;
     const int64_t t0 = (int64_t)split * rows_per;
     const int64_t t1 = (t0 + rows_per < T) ? (t0 + rows_per) : T;
     float g[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) g[e] = 0.f;
-    if (col < H) {
-        for (int64_t t = t0 + ry; t < t1; t += VEC_ROWS) {
+    if (active) {
+        int64_t base = t0 + wave * VEC_U;
+        for (; base + VEC_U <= t1; base += VEC_BLOCK) {          // eight whole rows: no per-row test
+            half8 a[VEC_U], b[VEC_U];
+#pragma unroll
+            for (int u = 0; u < VEC_U; ++u) {
+                a[u] = *reinterpret_cast<const half8*>(Xh + (base + u) * H + col);
+                b[u] = *reinterpret_cast<const half8*>(dY + (base + u) * H + col);
+            }
+#pragma unroll
+            for (int u = 0; u < VEC_U; ++u)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) g[e] = fmaf((float)a[u][e], (float)b[u][e], g[e]);
+        }
+        for (int64_t t = base; t < t1 && t < base + VEC_U; ++t) {   // ragged end of the split
             const half8 a = *reinterpret_cast<const half8*>(Xh + t * H + col);
             const half8 b = *reinterpret_cast<const half8*>(dY + t * H + col);
 #pragma unroll
             for (int e = 0; e < 8; ++e) g[e] = fmaf((float)a[e], (float)b[e], g[e]);
         }
     }
+    if (wave > 0) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) red[ry][cx * 8 + e] = g[e];
+        for (int e = 0; e < 8; ++e) part[wave - 1][lane][e] = g[e];
+    }
     __syncthreads();
-    if (threadIdx.x < VEC_COLS) {
-        const int64_t c = (int64_t)blockIdx.x * VEC_COLS + threadIdx.x;
-        if (c < H) {
-            float sum = 0.f;
+    if (wave == 0 && active) {
+        float4 lo, hi;
+        float o[8];
 #pragma unroll
-            for (int r = 0; r < VEC_ROWS; ++r) sum += red[r][threadIdx.x];
-            partial[(int64_t)split * H + c] = sum;
-        }
+        for (int e = 0; e < 8; ++e)
+            o[e] = ((g[e] + part[0][lane][e]) + (part[1][lane][e] + part[2][lane][e])) +
+                   ((part[3][lane][e] + part[4][lane][e]) + (part[5][lane][e] + part[6][lane][e]));
+        lo = make_float4(o[0], o[1], o[2], o[3]);
+        hi = make_float4(o[4], o[5], o[6], o[7]);
+        float4* dst = reinterpret_cast<float4*>(partial + (int64_t)split * H + col);
+        dst[0] = lo;
+        dst[1] = hi;
     }
 }
+
+// Stage 2.  A workgroup finishes 128 columns: eight groups of 32 lanes take the splits round-robin
+// (group q: splits q, q + 8, ...), four columns per lane, every load independent of the others; the
+// eight group sums are then added in a fixed tree.  Then the squared norm or the update.
+constexpr int FIN_COLS = 128;
+constexpr int FIN_GROUPS = ROW_NT / 32;
 
 template <int MODE>
 __global__ __launch_bounds__(ROW_NT) void vec_finish_kernel(const float* __restrict__ partial, int64_t H, int splits,
                                                             uint16_t* __restrict__ w, float s, double* __restrict__ acc,
                                                             int32_t* __restrict__ flag_out,
                                                             const int32_t* __restrict__ flag_in, float lr, float clipv) {
+    __shared__ float4 part[FIN_GROUPS - 1][32];
     __shared__ float red[4];
     __shared__ int redflag[4];
     if (MODE == 1 && flag_in != nullptr && flag_in[0] != 0) return;
-    const int64_t j = (int64_t)blockIdx.x * ROW_NT + threadIdx.x;
-    float g = 0.f;
-    if (j < H)
-        for (int sp = 0; sp < splits; ++sp) g += partial[(int64_t)sp * H + j];
+    const int c4 = threadIdx.x & 31, grp = threadIdx.x >> 5;
+    const int64_t j = (int64_t)blockIdx.x * FIN_COLS + c4 * 4;
+    const bool active = j < H;                     // H is a multiple of 8: four whole columns or none
+    float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (active) {
+        int sp = grp;
+        for (; sp + 3 * FIN_GROUPS < splits; sp += 4 * FIN_GROUPS) {
+            float4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                v[u] = *reinterpret_cast<const float4*>(partial + (int64_t)(sp + u * FIN_GROUPS) * H + j);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                g.x += v[u].x; g.y += v[u].y; g.z += v[u].z; g.w += v[u].w;
+            }
+        }
+        for (; sp < splits; sp += FIN_GROUPS) {
+            const float4 v = *reinterpret_cast<const float4*>(partial + (int64_t)sp * H + j);
+            g.x += v.x; g.y += v.y; g.z += v.z; g.w += v.w;
+        }
+    }
+    if (grp > 0) part[grp - 1][c4] = g;
+    __syncthreads();
+    float gs[4] = {0.f, 0.f, 0.f, 0.f};
+    if (grp == 0) {
+        const float4 p0 = part[0][c4], p1 = part[1][c4], p2 = part[2][c4], p3 = part[3][c4], p4 = part[4][c4],
+                     p5 = part[5][c4], p6 = part[6][c4];
+        gs[0] = ((g.x + p0.x) + (p1.x + p2.x)) + ((p3.x + p4.x) + (p5.x + p6.x));
+        gs[1] = ((g.y + p0.y) + (p1.y + p2.y)) + ((p3.y + p4.y) + (p5.y + p6.y));
+        gs[2] = ((g.z + p0.z) + (p1.z + p2.z)) + ((p3.z + p4.z) + (p5.z + p6.z));
+        gs[3] = ((g.w + p0.w) + (p1.w + p2.w)) + ((p3.w + p4.w) + (p5.w + p6.w));
+    }
     if (MODE == 0) {
-        const bool bad = __any((__float_as_uint(g) & 0x7fffffffu) >= 0x7f800000u);
+        float sq = 0.f;
+        bool badv = false;
+        if (grp == 0 && active) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                sq = fmaf(gs[e], gs[e], sq);
+                badv |= (__float_as_uint(gs[e]) & 0x7fffffffu) >= 0x7f800000u;
+            }
+        }
+        const bool bad = __any(badv);
         if ((threadIdx.x & 63) == 0) redflag[threadIdx.x >> 6] = bad ? 1 : 0;
-        const float total = block_sum_256(g * g, red);
+        const float total = block_sum_256(sq, red);
         if (threadIdx.x == 0) {
             atomicAdd(acc, (double)total);
             if (flag_out != nullptr && (redflag[0] | redflag[1] | redflag[2] | redflag[3])) atomicOr(flag_out, 1);
         }
-    } else if (j < H) {
-        const _Float16 old = *reinterpret_cast<const _Float16*>(w + j);
-        if (MODE == 1) {
-            *reinterpret_cast<_Float16*>(w + j) = (_Float16)fmaf(-s, g, (float)old);
-        } else {   // clip by value: s is 1 / loss scale here
-            const float gq = g * s;
-            if ((__float_as_uint(gq) & 0x7f800000u) != 0x7f800000u) {
-                *reinterpret_cast<_Float16*>(w + j) = (_Float16)fmaf(-lr, fminf(fmaxf(gq, -clipv), clipv), (float)old);
-            } else if (flag_out != nullptr) {
-                atomicOr(flag_out, 1);
+    } else if (grp == 0 && active) {
+        half4 old = *reinterpret_cast<const half4*>(w + j);
+        bool badv = false;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (MODE == 1) {
+                old[e] = (_Float16)fmaf(-s, gs[e], (float)old[e]);
+            } else {   // clip by value: s is 1 / loss scale here
+                const float gq = gs[e] * s;
+                if ((__float_as_uint(gq) & 0x7f800000u) != 0x7f800000u)
+                    old[e] = (_Float16)fmaf(-lr, fminf(fmaxf(gq, -clipv), clipv), (float)old[e]);
+                else
+                    badv = true;
             }
         }
+        *reinterpret_cast<half4*>(w + j) = old;
+        if (MODE == 2 && badv && flag_out != nullptr) atomicOr(flag_out, 1);
     }
 }
 
@@ -431,8 +510,8 @@ hipError_t launch_vector(const uint16_t* Xhat, const uint16_t* dY, uint16_t* w, 
     const int splits = vector_splits(T);
     float* partial = static_cast<float*>(ws);
     hipLaunchKernelGGL(vec_partial_kernel, dim3((unsigned)((H + VEC_COLS - 1) / VEC_COLS), (unsigned)splits),
-                       dim3(ROW_NT), 0, st, Xhat, dY, T, H, splits, partial);
-    const dim3 grid((unsigned)((H + ROW_NT - 1) / ROW_NT));
+                       dim3(VEC_NT), 0, st, Xhat, dY, T, H, splits, partial);
+    const dim3 grid((unsigned)((H + FIN_COLS - 1) / FIN_COLS));
     if (mode == 0)
         hipLaunchKernelGGL(vec_finish_kernel<0>, grid, dim3(ROW_NT), 0, st, partial, H, splits, w, s, acc, flag_out,
                            flag_in, lr, clipv);
