@@ -1,10 +1,11 @@
 #!/usr/bin/env python3
-"""Benchmark of the two-pass LOMO step (norm pass, host coefficient, fused update pass).
+"""Benchmark of the two-pass LOMO step (norm pass, clipping coefficient, fused update pass).
 
 A step = pass 1 over every tensor of the workload (squared gradient norm + overflow flags),
-one host read-back, pass 2 over every tensor (dgrad from the pre-update W, then the fused
-weight-gradient + SGD update).  Inputs are synthetic, seeded and resident in HBM before the
-timed region.  W is not restored between iterations: the clipped updates are far below one
+the coefficient (a one-thread kernel by default; --host-coefficient reads the norm back and
+forms it on the host, one synchronisation per step), pass 2 over every tensor (dgrad from the
+pre-update W, then the fused weight-gradient + SGD update) and a copy of the step's scalars to
+pinned host memory.  Inputs are synthetic, seeded and resident in HBM before the timed region.  W is not restored between iterations: the clipped updates are far below one
 fp16 ulp for these workloads, so the weights drift by at most a few ulps over a run.
 
 Prints ONE JSON line: whole-step throughput, the roofline of the dominant kernel (the fused
@@ -99,6 +100,9 @@ def main():
     ap.add_argument("--no-dgrad", action="store_true", help="skip dX (diagnostic only; not the metric)")
     ap.add_argument("--per-tensor-calls", action="store_true",
                     help="one C call per tensor instead of the whole-pass calls (same results, more launches)")
+    ap.add_argument("--host-coefficient", action="store_true",
+                    help="form the clipping coefficient on the host after a read-back between the passes (one "
+                         "synchronisation per step) instead of on the device")
     ap.add_argument("--norm-pass", choices=["direct", "auto", "gram"], default="direct",
                     help="route of the norm pass for linear tensors in the timed steps (default: direct, the one the "
                          "metric's flop count describes)")
@@ -149,18 +153,28 @@ def main():
     lr = float(np.float32(wl.lr))
 
     L.lomo_set_norm_algorithm(args.norm_pass)
+    device_coef = not args.host_coefficient and not args.per_tensor_calls
+
+    def one_step():
+        if device_coef:      # pass 1, coefficient kernel, pass 2, scalars to pinned memory: no host wait
+            stepper.run_async(tensors, lr, wl.loss_scale, wl.max_norm, wl.eps)
+            return None
+        return stepper.run(tensors, lr, wl.loss_scale, wl.max_norm, wl.eps)
+
     res = None
     for _ in range(args.warmup):
-        res = stepper.run(tensors, lr, wl.loss_scale, wl.max_norm, wl.eps)
+        res = one_step()
     torch.cuda.synchronize()
 
     L.lomo_timing_enable(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        res = stepper.run(tensors, lr, wl.loss_scale, wl.max_norm, wl.eps)
+        res = one_step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    if device_coef:
+        res = stepper.result()
     fam = {name: L.lomo_timing_read(i) for i, name in enumerate(L.KERNEL_FAMILIES)}
     L.lomo_timing_enable(False)
 
@@ -214,7 +228,8 @@ def main():
         "config": {"workload": wl.name, "tokens": wl.T, "tensors": len(wl.tensors), "params": wl.n_params,
                    "loss_scale": wl.loss_scale, "lr": wl.lr, "max_norm": wl.max_norm,
                    "gemms_per_linear": gemms_per_step, "weights_restored_between_steps": False,
-                   "calls": "per_tensor" if args.per_tensor_calls else "whole_pass", "norm_pass": args.norm_pass},
+                   "calls": "per_tensor" if args.per_tensor_calls else "whole_pass", "norm_pass": args.norm_pass,
+                   "coefficient": "device" if device_coef else "host"},
         "params_per_s": wl.n_params / (ms_per_step * 1e-3),
         "frac_fp16_mfma_peak_whole_step": tflops / PEAK_FP16_TFLOPS,
         "kernels": {k: fam_rate(k) for k in ("wgrad_update", "wgrad_sqnorm", "dgrad")},

@@ -163,6 +163,28 @@ lomo_status lomo_step_update_pass(const lomo_tensor* tensors, int64_t n,
                                   float lr, float inv_loss_scale, float clip_coef,
                                   const int32_t* step_flag, void* ws, size_t ws_bytes, void* stream);
 
+/* The coefficient of a step without a host round trip (sections 3.3.1 and 3.3.2, appendix A): a one-thread
+ * kernel reads the scaled squared norm acc[0] and the step flag that pass 1 left on the device and
+ * writes, to device memory,
+ *     grad_norm = sqrt(acc) / loss_scale,  clip_coef = min(1, max_norm / (grad_norm + eps)),
+ *     step = (float)(lr * clip_coef / loss_scale)   (formed in double, rounded once),
+ *     overflow = step_flag[0] != 0;   clip_coef = step = 0 if overflow or grad_norm is not finite.
+ * lomo_step_update_pass_device is lomo_step_update_pass with the step size read from scalars->step by
+ * the kernels themselves, so norm pass, coefficient and update pass can be queued back to back on one
+ * stream (or captured into a graph) and the host reads `scalars` whenever it likes.
+ * scalars: device memory, 8-byte aligned, caller-owned. */
+typedef struct lomo_step_scalars {
+    double clip_coef;
+    double grad_norm;
+    float step;
+    int32_t overflow;
+} lomo_step_scalars;
+
+lomo_status lomo_step_scalars_device(const double* acc, const int32_t* step_flag, double loss_scale, double max_norm,
+                                     double eps, double lr, lomo_step_scalars* scalars, void* stream);
+lomo_status lomo_step_update_pass_device(const lomo_tensor* tensors, int64_t n, const lomo_step_scalars* scalars,
+                                         const int32_t* step_flag, void* ws, size_t ws_bytes, void* stream);
+
 /* ---------------------------------------------------------------- clip by value (section 3.3.1, first
  * alternative): one pass, no norm.  Each element of the unscaled gradient g = G / loss_scale is clamped
  * to [-clip_value, clip_value] and applied at once: W <- round_fp16(float(W) - lr * clamp(g)), fp32

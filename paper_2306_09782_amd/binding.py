@@ -19,7 +19,7 @@ EXPORTED_SYMBOLS = (
     "lomo_vector_workspace_bytes", "lomo_embedding_grouping", "lomo_timing_enable", "lomo_timing_read",
     "lomo_step_workspace_bytes", "lomo_step_norm_pass", "lomo_step_update_pass",
     "lomo_linear_backward_update_clip_value", "lomo_step_update_pass_clip_value",
-    "lomo_set_norm_algorithm", "lomo_get_norm_algorithm",
+    "lomo_set_norm_algorithm", "lomo_get_norm_algorithm", "lomo_step_scalars_device", "lomo_step_update_pass_device",
 )
 
 
@@ -73,6 +73,8 @@ def load_library():
         "lomo_linear_backward_update_clip_value": (c_int, [P, P, P, P, I64, I64, I64, c_float, c_float, c_float, P, P]),
         "lomo_step_update_pass_clip_value": (c_int, [POINTER(LomoTensor), I64, c_float, c_float, c_float, P, P,
                                                      c_size_t, P]),
+        "lomo_step_scalars_device": (c_int, [P, P, c_double, c_double, c_double, c_double, P, P]),
+        "lomo_step_update_pass_device": (c_int, [POINTER(LomoTensor), I64, P, P, P, c_size_t, P]),
         "lomo_set_norm_algorithm": (c_int, [c_int]),
         "lomo_get_norm_algorithm": (c_int, []),
         "lomo_timing_enable": (c_int, [c_int]),
@@ -245,6 +247,28 @@ def lomo_step_norm_pass(tensor_list, acc, flags, ws, stream=None):
 def lomo_step_update_pass(tensor_list, lr, inv_loss_scale, clip_coef, step_flag, ws, stream=None):
     _check(load_library().lomo_step_update_pass(tensor_list, len(tensor_list), lr, inv_loss_scale, clip_coef,
                                                 _ptr(step_flag), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+SCALARS_BYTES = 24   # sizeof(lomo_step_scalars): double clip_coef, double grad_norm, float step, int32 overflow
+
+
+def lomo_step_scalars_device(acc, step_flag, loss_scale, max_norm, eps, lr, scalars, stream=None):
+    """scalars: device uint8 tensor of at least SCALARS_BYTES bytes, 8-byte aligned."""
+    assert _nbytes(scalars) >= SCALARS_BYTES
+    _check(load_library().lomo_step_scalars_device(_ptr(acc), _ptr(step_flag), loss_scale, max_norm, eps, lr,
+                                                   _ptr(scalars), _stream(stream)))
+
+
+def lomo_step_update_pass_device(tensor_list, scalars, step_flag, ws, stream=None):
+    _check(load_library().lomo_step_update_pass_device(tensor_list, len(tensor_list), _ptr(scalars), _ptr(step_flag),
+                                                       _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def unpack_step_scalars(host_bytes):
+    """{clip_coef, norm, step, overflow} from the SCALARS_BYTES bytes of a lomo_step_scalars (host uint8 tensor)."""
+    import struct
+    clip, norm, step, ovf = struct.unpack("<ddfi", bytes(host_bytes[:SCALARS_BYTES].tolist()))
+    return {"clip_coef": clip, "norm": norm, "step": step, "overflow": bool(ovf)}
 
 
 def lomo_linear_backward_update_clip_value(X, dY, W, dX, lr, inv_loss_scale, clip_value, overflow_flag=None,

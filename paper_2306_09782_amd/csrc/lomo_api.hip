@@ -259,12 +259,12 @@ lomo_status lomo_step_norm_pass(const lomo_tensor* tensors, int64_t n, double* a
     return from_hip(launch_reduce_flags(flags, n, flags + n, st));
 }
 
-lomo_status lomo_step_update_pass(const lomo_tensor* tensors, int64_t n, float lr, float inv_loss_scale,
-                                  float clip_coef, const int32_t* step_flag, void* ws, size_t ws_bytes, void* stream) {
+// Pass 2 with the step size given by value (s_dev == nullptr) or read by the kernels from device memory.
+static lomo_status update_pass(const lomo_tensor* tensors, int64_t n, float s, const float* s_dev,
+                               const int32_t* step_flag, void* ws, size_t ws_bytes, void* stream) {
     lomo_status cs = check_step(tensors, n, true, ws, ws_bytes);
     if (cs != LOMO_OK) return cs;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const float s = step_size(lr, inv_loss_scale, clip_coef);
     std::vector<GemmArgs> dgrads, updates, updates_plain;
     // every dgrad first: dX must come from the pre-update weights
     for (int64_t i = 0; i < n; ++i) {
@@ -283,7 +283,7 @@ lomo_status lomo_step_update_pass(const lomo_tensor* tensors, int64_t n, float l
         a.A = t.X; a.B = t.dY; a.Out = t.W;
         a.M = t.K; a.Nn = t.N; a.C = t.T;
         a.lda = t.K; a.ldb = t.N; a.ldo = t.K;
-        a.s = s; a.flag_in = step_flag;
+        a.s = s; a.s_dev = s_dev; a.flag_in = step_flag;
         a.family = LOMO_KERNEL_WGRAD_UPDATE;
         if (dma_eligible(a)) updates.push_back(a);
         else updates_plain.push_back(a);
@@ -301,15 +301,38 @@ lomo_status lomo_step_update_pass(const lomo_tensor* tensors, int64_t n, float l
             EmbeddingWs w = carve_embedding_ws(ws, t.T);
             ScopedTiming timing(LOMO_KERNEL_EMBEDDING, st);
             if (launch_embedding_grouping(t.ids, t.T, w, st) != hipSuccess) return LOMO_ERR_LAUNCH;
-            if (launch_embedding_rows(t.dY, t.W, t.T, t.K, w, 1, s, nullptr, nullptr, step_flag, st) != hipSuccess)
+            if (launch_embedding_rows(t.dY, t.W, t.T, t.K, w, 1, s, nullptr, nullptr, step_flag, st, 0.f, 0.f, s_dev) !=
+                hipSuccess)
                 return LOMO_ERR_LAUNCH;
         } else if (t.kind == LOMO_TENSOR_VECTOR) {
             ScopedTiming timing(LOMO_KERNEL_VECTOR, st);
-            if (launch_vector(t.X, t.dY, t.W, t.T, t.K, ws, 1, s, nullptr, nullptr, step_flag, st) != hipSuccess)
+            if (launch_vector(t.X, t.dY, t.W, t.T, t.K, ws, 1, s, nullptr, nullptr, step_flag, st, 0.f, 0.f, s_dev) !=
+                hipSuccess)
                 return LOMO_ERR_LAUNCH;
         }
     }
     return LOMO_OK;
+}
+
+lomo_status lomo_step_update_pass(const lomo_tensor* tensors, int64_t n, float lr, float inv_loss_scale,
+                                  float clip_coef, const int32_t* step_flag, void* ws, size_t ws_bytes, void* stream) {
+    return update_pass(tensors, n, step_size(lr, inv_loss_scale, clip_coef), nullptr, step_flag, ws, ws_bytes, stream);
+}
+
+lomo_status lomo_step_scalars_device(const double* acc, const int32_t* step_flag, double loss_scale, double max_norm,
+                                     double eps, double lr, lomo_step_scalars* scalars, void* stream) {
+    if (!acc || !scalars) return LOMO_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(acc) & 7u) || (reinterpret_cast<uintptr_t>(scalars) & 7u)) return LOMO_ERR_ALIGN;
+    if (!(loss_scale > 0.0)) return LOMO_ERR_SHAPE;
+    return from_hip(launch_step_scalars(acc, step_flag, loss_scale, max_norm, eps, lr, scalars,
+                                        static_cast<hipStream_t>(stream)));
+}
+
+lomo_status lomo_step_update_pass_device(const lomo_tensor* tensors, int64_t n, const lomo_step_scalars* scalars,
+                                         const int32_t* step_flag, void* ws, size_t ws_bytes, void* stream) {
+    if (!scalars) return LOMO_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(scalars) & 7u) return LOMO_ERR_ALIGN;
+    return update_pass(tensors, n, 0.f, &scalars->step, step_flag, ws, ws_bytes, stream);
 }
 
 // ---- clip by value (single pass) -----------------------------------------------------------

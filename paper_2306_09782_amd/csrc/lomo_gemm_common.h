@@ -68,7 +68,7 @@ __device__ __forceinline__ void epilogue(floatx16 (&acc)[BM / 64][BN / 64], cons
         // lane half lh covers m = 32 i + 16 a + 8 lh .. + 7.  All W loads of a 32-row stripe are issued
         // before any of them is used, and the next stripe is loaded while the current one is updated.
         typedef uint32_t u32x2v __attribute__((ext_vector_type(2)));
-        const float s = g.s;
+        const float s = g.s_dev != nullptr ? *g.s_dev : g.s;
         auto row_ptr = [&](int j) -> uint16_t* {
             const int nl = wn * (BN / 2) + 32 * j + l32;
             return (nl < n_rem) ? g.Out + (n0 + nl) * g.ldo + m0 : nullptr;

@@ -45,6 +45,7 @@ struct GroupArgs {
     double* acc;
     const int32_t* flag_in;
     float s, lr, inv_s, clipv;
+    const float* s_dev;
     int n, total_tiles;
     GroupTensor t[MAX_GROUP];
 };
@@ -307,6 +308,7 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga
         g.Out = ga.t[tensor].Out;
         g.ldo = ga.t[tensor].ldo;
         g.s = ga.s;
+        g.s_dev = ga.s_dev;
         g.lr = ga.lr;
         g.inv_s = ga.inv_s;
         g.clipv = ga.clipv;
@@ -364,6 +366,7 @@ hipError_t launch_dma_group(const GemmArgs* list, int n, hipStream_t st) {
         ga.acc = list[first].acc;
         ga.flag_in = list[first].flag_in;
         ga.s = list[first].s;
+        ga.s_dev = list[first].s_dev;
         ga.lr = list[first].lr;
         ga.inv_s = list[first].inv_s;
         ga.clipv = list[first].clipv;

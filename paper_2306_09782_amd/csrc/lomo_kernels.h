@@ -31,6 +31,7 @@ struct GemmArgs {
     int64_t M, Nn, C;
     int64_t lda, ldb, ldo;
     float s;                 // update step (EPI_UPDATE)
+    const float* s_dev;      // when not null the update step is read from device memory instead
     float lr, inv_s, clipv;  // learning rate, 1 / loss scale, clamp threshold (EPI_CLIPV)
     double* acc;             // squared-norm accumulator (EPI_SQNORM)
     int32_t* flag_out;       // overflow flag to raise (EPI_SQNORM), may be null
@@ -83,12 +84,18 @@ hipError_t launch_embedding_grouping(const int32_t* ids, int64_t T, const Embedd
 // (and leaving the element alone) where the sum is not finite.  In mode 2, s is 1 / loss scale.
 hipError_t launch_embedding_rows(const uint16_t* dY, uint16_t* W, int64_t T, int64_t H, const EmbeddingWs& w,
                                  int mode, float s, double* acc, int32_t* flag_out, const int32_t* flag_in,
-                                 hipStream_t st, float lr = 0.f, float clipv = 0.f);
+                                 hipStream_t st, float lr = 0.f, float clipv = 0.f, const float* s_dev = nullptr);
 
 size_t vector_ws_bytes(int64_t T, int64_t H);
 hipError_t launch_vector(const uint16_t* Xhat, const uint16_t* dY, uint16_t* w, int64_t T, int64_t H,
                          void* ws, int mode, float s, double* acc, int32_t* flag_out, const int32_t* flag_in,
-                         hipStream_t st, float lr = 0.f, float clipv = 0.f);
+                         hipStream_t st, float lr = 0.f, float clipv = 0.f, const float* s_dev = nullptr);
+// mode 1 with s_dev: the step is read from device memory (written by launch_step_scalars earlier on the stream).
+
+// Device-side form of the host coefficient: reads the scaled squared norm and the step flag, writes
+// {clip, norm, step = lr * clip / S, overflow} to `out`.
+hipError_t launch_step_scalars(const double* acc, const int32_t* step_flag, double loss_scale, double max_norm, double eps,
+                               double lr, lomo_step_scalars* out, hipStream_t st);
 
 // Event timing (lomo_timing.hip).  Contraction kernels attach the events to their own dispatch
 // (no extra packets on the stream); multi-kernel families bracket their launches instead.

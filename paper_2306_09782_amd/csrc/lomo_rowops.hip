@@ -215,9 +215,11 @@ __global__ __launch_bounds__(EMB_NT) void emb_rows_kernel(const uint16_t* __rest
                                                           const int32_t* __restrict__ seg_offsets,
                                                           const int32_t* __restrict__ n_unique, float s,
                                                           double* __restrict__ partials, int32_t* __restrict__ flag_out,
-                                                          const int32_t* __restrict__ flag_in, float lr, float clipv) {
+                                                          const int32_t* __restrict__ flag_in, float lr, float clipv,
+                                                          const float* __restrict__ s_dev) {
     __shared__ float part[EMB_W - 1][64][9];
     if (MODE == 1 && flag_in != nullptr && flag_in[0] != 0) return;
+    if (MODE == 1 && s_dev != nullptr) s = s_dev[0];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t col = (int64_t)blockIdx.y * EMB_COLS + lane * 8;
     const bool active = col < H;
@@ -319,19 +321,19 @@ __global__ __launch_bounds__(ROW_NT) void emb_finish_sqnorm(const double* __rest
 
 hipError_t launch_embedding_rows(const uint16_t* dY, uint16_t* W, int64_t T, int64_t H, const EmbeddingWs& w, int mode,
                                  float s, double* acc, int32_t* flag_out, const int32_t* flag_in, hipStream_t st,
-                                 float lr, float clipv) {
+                                 float lr, float clipv, const float* s_dev) {
     const unsigned gx = (unsigned)(T < EMB_MAX_GX ? T : EMB_MAX_GX);
     const dim3 grid(gx, (unsigned)((H + EMB_COLS - 1) / EMB_COLS));
     if (mode == 0) {
         hipLaunchKernelGGL(emb_rows_kernel<0>, grid, dim3(EMB_NT), 0, st, dY, W, H, w.perm, w.unique_ids, w.seg_offsets,
-                           w.n_unique, s, w.partials, flag_out, flag_in, lr, clipv);
+                           w.n_unique, s, w.partials, flag_out, flag_in, lr, clipv, s_dev);
         hipLaunchKernelGGL(emb_finish_sqnorm, dim3(1), dim3(ROW_NT), 0, st, w.partials, (int)(grid.x * grid.y), acc);
     } else if (mode == 1) {
         hipLaunchKernelGGL(emb_rows_kernel<1>, grid, dim3(EMB_NT), 0, st, dY, W, H, w.perm, w.unique_ids, w.seg_offsets,
-                           w.n_unique, s, w.partials, flag_out, flag_in, lr, clipv);
+                           w.n_unique, s, w.partials, flag_out, flag_in, lr, clipv, s_dev);
     } else {
         hipLaunchKernelGGL(emb_rows_kernel<2>, grid, dim3(EMB_NT), 0, st, dY, W, H, w.perm, w.unique_ids, w.seg_offsets,
-                           w.n_unique, s, w.partials, flag_out, flag_in, lr, clipv);
+                           w.n_unique, s, w.partials, flag_out, flag_in, lr, clipv, s_dev);
     }
     return hipGetLastError();
 }
@@ -430,11 +432,13 @@ template <int MODE>
 __global__ __launch_bounds__(ROW_NT) void vec_finish_kernel(const float* __restrict__ partial, int64_t H, int splits,
                                                             uint16_t* __restrict__ w, float s, double* __restrict__ acc,
                                                             int32_t* __restrict__ flag_out,
-                                                            const int32_t* __restrict__ flag_in, float lr, float clipv) {
+                                                            const int32_t* __restrict__ flag_in, float lr, float clipv,
+                                                            const float* __restrict__ s_dev) {
     __shared__ float4 part[FIN_GROUPS - 1][32];
     __shared__ float red[4];
     __shared__ int redflag[4];
     if (MODE == 1 && flag_in != nullptr && flag_in[0] != 0) return;
+    if (MODE == 1 && s_dev != nullptr) s = s_dev[0];
     const int c4 = threadIdx.x & 31, grp = threadIdx.x >> 5;
     const int64_t j = (int64_t)blockIdx.x * FIN_COLS + c4 * 4;
     const bool active = j < H;                     // H is a multiple of 8: four whole columns or none
@@ -506,7 +510,7 @@ __global__ __launch_bounds__(ROW_NT) void vec_finish_kernel(const float* __restr
 
 hipError_t launch_vector(const uint16_t* Xhat, const uint16_t* dY, uint16_t* w, int64_t T, int64_t H, void* ws, int mode,
                          float s, double* acc, int32_t* flag_out, const int32_t* flag_in, hipStream_t st, float lr,
-                         float clipv) {
+                         float clipv, const float* s_dev) {
     const int splits = vector_splits(T);
     float* partial = static_cast<float*>(ws);
     hipLaunchKernelGGL(vec_partial_kernel, dim3((unsigned)((H + VEC_COLS - 1) / VEC_COLS), (unsigned)splits),
@@ -514,17 +518,43 @@ hipError_t launch_vector(const uint16_t* Xhat, const uint16_t* dY, uint16_t* w, 
     const dim3 grid((unsigned)((H + FIN_COLS - 1) / FIN_COLS));
     if (mode == 0)
         hipLaunchKernelGGL(vec_finish_kernel<0>, grid, dim3(ROW_NT), 0, st, partial, H, splits, w, s, acc, flag_out,
-                           flag_in, lr, clipv);
+                           flag_in, lr, clipv, s_dev);
     else if (mode == 1)
         hipLaunchKernelGGL(vec_finish_kernel<1>, grid, dim3(ROW_NT), 0, st, partial, H, splits, w, s, acc, flag_out,
-                           flag_in, lr, clipv);
+                           flag_in, lr, clipv, s_dev);
     else
         hipLaunchKernelGGL(vec_finish_kernel<2>, grid, dim3(ROW_NT), 0, st, partial, H, splits, w, s, acc, flag_out,
-                           flag_in, lr, clipv);
+                           flag_in, lr, clipv, s_dev);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------
+
+// Clipping coefficient of the step on the device (section 3.3.1 with the loss scale of section 3.3.2):
+// norm = sqrt(acc) / S, clip = min(1, max_norm / (norm + eps)), step = lr * clip / S in double, rounded
+// once to float.  An overflowed or non-finite step gets clip = step = 0.
+__global__ void step_scalars_kernel(const double* __restrict__ acc, const int32_t* __restrict__ step_flag,
+                                    double loss_scale, double max_norm, double eps, double lr,
+                                    lomo_step_scalars* __restrict__ out) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const int overflow = (step_flag != nullptr && step_flag[0] != 0) ? 1 : 0;
+    const double norm = sqrt(acc[0]) / loss_scale;
+    double clip = 0.0;
+    if (!overflow && norm == norm && norm - norm == 0.0) {      // finite
+        const double c = max_norm / (norm + eps);
+        clip = c < 1.0 ? c : 1.0;
+    }
+    out->clip_coef = clip;
+    out->grad_norm = norm;
+    out->step = (float)(lr * clip / loss_scale);
+    out->overflow = overflow;
+}
+
+hipError_t launch_step_scalars(const double* acc, const int32_t* step_flag, double loss_scale, double max_norm, double eps,
+                               double lr, lomo_step_scalars* out, hipStream_t st) {
+    hipLaunchKernelGGL(step_scalars_kernel, dim3(1), dim3(64), 0, st, acc, step_flag, loss_scale, max_norm, eps, lr, out);
+    return hipGetLastError();
+}
 
 __global__ void reduce_flags_kernel(const int32_t* __restrict__ flags, int64_t n, int32_t* __restrict__ out) {
     __shared__ int any_s;

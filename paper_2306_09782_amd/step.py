@@ -28,6 +28,8 @@ class LomoStep:
         nbytes = max(B.lomo_embedding_workspace_bytes(max_T, max_H), B.lomo_vector_workspace_bytes(max_T, max_H), 256)
         self.ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         assert self.ws.data_ptr() % 256 == 0
+        self.scalars = torch.zeros(32, dtype=torch.uint8, device=self.device)      # lomo_step_scalars
+        self._scalars_host = torch.zeros(32, dtype=torch.uint8).pin_memory() if self.device.type == "cuda" else None
 
     def _list(self, tensors):
         key = tuple((id(t), t["W"].data_ptr(), t["dY"].data_ptr(), (t.get("dX").data_ptr() if t.get("dX") is not None else 0))
@@ -88,3 +90,24 @@ class LomoStep:
             self.update_pass(tensors, lr, 1.0 / loss_scale, clip, stream)
         return {"total_sqnorm": sq, "flags": flags, "overflow": overflow, "clip_coef": clip,
                 "norm": (sq ** 0.5) / loss_scale if sq == sq else float("nan")}
+
+    def run_async(self, tensors: List[Dict], lr: float, loss_scale: float, max_norm: float = 1.0, eps: float = 1e-6,
+                  stream=None) -> None:
+        """The same step with the coefficient formed on the device: pass 1, coefficient kernel, pass 2 and
+        a copy of the step scalars to pinned host memory are queued without any host wait.  Call
+        :meth:`result` after synchronising to read norm, coefficient and overflow of the last step."""
+        assert self.grouped, "run_async uses the whole-pass calls"
+        n = len(tensors)
+        self.norm_pass(tensors, stream)
+        step_flag = self.flags[n:n + 1]
+        B.lomo_step_scalars_device(self.acc, step_flag, loss_scale, max_norm, eps, lr, self.scalars, stream)
+        B.lomo_step_update_pass_device(self._list(tensors), self.scalars, step_flag, self.ws, stream)
+        if stream is None:
+            self._scalars_host.copy_(self.scalars, non_blocking=True)
+        else:
+            with torch.cuda.stream(stream):
+                self._scalars_host.copy_(self.scalars, non_blocking=True)
+
+    def result(self) -> Dict:
+        """Scalars of the last run_async step (synchronise the stream first)."""
+        return B.unpack_step_scalars(self._scalars_host)

@@ -107,3 +107,48 @@ def test_two_pass_step_matches_oracle(L, name, grouped):
         changed_o = want.view(np.uint16) != t["W"].view(np.uint16)
         changed_g = got.view(np.uint16) != t["W"].view(np.uint16)
         assert changed_o.mean() > 0.9 and (changed_o != changed_g).mean() < 1e-3
+
+
+@pytest.mark.parametrize("name", ["linear1024", "llama7b_layer"])
+def test_device_coefficient_step_matches_oracle(L, name):
+    """Norm pass, coefficient kernel and update pass queued without a host wait (LomoStep.run_async)."""
+    from paper_2306_09782_amd.step import LomoStep
+    wl = S.workload(name)
+    gpu = _device_tensors(wl)
+    cpu = [_host(t) for t in gpu]
+    stepper = LomoStep(DEV, max_T=wl.T, max_H=max(s.K for s in wl.tensors), max_tensors=len(gpu))
+    grads = [O.tensor_grad(t) for t in cpu]
+    total = math.fsum(O.sqnorm(g) for g in grads)
+    norm = O.grad_norm(total, wl.loss_scale)
+    coef = O.clip_coef(norm, wl.max_norm, wl.eps)
+    sig = wl.tensors[0].sigma_dy
+    lr_vis = 30 * 2.0 ** -16 / (math.sqrt(wl.T) * sig)
+
+    # clipped step made visible: lr such that lr * coef is the visible step size
+    lr = float(np.float32(lr_vis / coef))
+    stepper.run_async(gpu, lr, wl.loss_scale, wl.max_norm, wl.eps)
+    torch.cuda.synchronize()
+    res = stepper.result()
+    assert res["overflow"] is False
+    assert abs(res["norm"] / norm - 1) < 1e-5 and abs(res["clip_coef"] / coef - 1) < 1e-5
+    assert abs(res["step"] / (lr * coef / wl.loss_scale) - 1) < 1e-5
+    assert res["clip_coef"] == pytest.approx(L.lomo_clip_coef(stepper.read_back(len(gpu))["total_sqnorm"], wl.loss_scale,
+                                                              wl.max_norm, wl.eps), rel=1e-14)
+    for g, t, G in zip(gpu, cpu, grads):
+        want = O.sgd_update(t["W"], G, lr, res["clip_coef"], wl.loss_scale)
+        got = g["W"].cpu().numpy()
+        exact = _check_ulps(got, want, f"{name}/{g['name']} device coefficient")
+        assert exact > 0.98
+        changed_o = want.view(np.uint16) != t["W"].view(np.uint16)
+        assert changed_o.mean() > 0.9 and (changed_o != (got.view(np.uint16) != t["W"].view(np.uint16))).mean() < 1e-3
+        _check_dx(g["dX"].cpu().numpy(), t["dY"], t["W"], g["name"])
+
+    # overflow: pass 2 is queued anyway and must leave every weight alone; the scalars say why
+    before = [g["W"].clone() for g in gpu]
+    gpu[-1]["dY"][0, 0] = float("inf")
+    stepper.run_async(gpu, lr, wl.loss_scale, wl.max_norm, wl.eps)
+    torch.cuda.synchronize()
+    res = stepper.result()
+    assert res["overflow"] is True and res["clip_coef"] == 0.0 and res["step"] == 0.0
+    for g, b in zip(gpu, before):
+        assert torch.equal(g["W"].view(torch.int16), b.view(torch.int16))
