@@ -491,11 +491,186 @@ def test_ulp_distance():
 def test_oracle_does_not_import_the_hip_path():
     import ast
     import oracle.lomo_oracle as mod
-    tree = ast.parse(open(mod.__file__).read())
-    names = set()
-    for node in ast.walk(tree):
-        if isinstance(node, ast.Import):
-            names |= {a.name.split(".")[0] for a in node.names}
-        elif isinstance(node, ast.ImportFrom):
-            names.add((node.module or "").split(".")[0])
-    assert names <= {"__future__", "math", "typing", "numpy"}, names
+    import oracle.mlp_chain as chain
+    for m in (mod, chain):
+        tree = ast.parse(open(m.__file__).read())
+        names = set()
+        for node in ast.walk(tree):
+            if isinstance(node, ast.Import):
+                names |= {a.name.split(".")[0] for a in node.names}
+            elif isinstance(node, ast.ImportFrom):
+                names.add((node.module or "").split(".")[0] if node.level == 0 else "oracle")
+        assert names <= {"__future__", "math", "typing", "numpy", "oracle"}, names
+
+
+# --------------------------------------------------------------------------- feed-forward block chain
+
+from oracle import mlp_chain as M
+
+
+def _block_inputs(rng, T=3, H=4, F=5):
+    h = rng.normal(size=(T, H))
+    w = 1.0 + 0.3 * rng.normal(size=H)
+    W_gu = 0.7 * rng.normal(size=(2 * F, H))
+    W_d = 0.7 * rng.normal(size=(H, F))
+    R = rng.normal(size=(T, H))
+    return h, w, W_gu, W_d, R
+
+
+def _block_grads_f64(h, w, W_gu, W_d, dy, eps):
+    """The chain's formulas composed in fp64 without any storage rounding."""
+    F = W_d.shape[1]
+    xhat, r, xn = M.rmsnorm_forward(h, w, eps)
+    gu = xn @ W_gu.T
+    a = M.silu(gu[:, :F]) * gu[:, F:]
+    da = O.input_grad_f64(dy, W_d)
+    dgu = M.swiglu_backward(da, gu)
+    dxn = O.input_grad_f64(dgu, W_gu)
+    return {"G_d": O.linear_grad(a, dy), "G_gu": O.linear_grad(xn, dgu), "g_w": O.vector_grad(xhat, dxn),
+            "dh": M.rmsnorm_backward(dxn, xhat, r, w, dres=dy)}
+
+
+def test_block_chain_finite_differences():
+    rng = np.random.default_rng(5)
+    eps = 1e-3
+    h, w, W_gu, W_d, R = _block_inputs(rng)
+    got = _block_grads_f64(h, w, W_gu, W_d, R, eps)          # loss = sum(y * R)  =>  dy = R
+    loss = lambda h_, w_, Wgu_, Wd_: float((M.block_forward_f64(h_, w_, Wgu_, Wd_, eps) * R).sum())
+    d = 1e-6
+
+    def fd(arr, idx, which):
+        p, m = arr.copy(), arr.copy()
+        p[idx] += d
+        m[idx] -= d
+        args_p = {"h": h, "w": w, "W_gu": W_gu, "W_d": W_d}
+        args_m = dict(args_p)
+        args_p[which], args_m[which] = p, m
+        return (loss(args_p["h"], args_p["w"], args_p["W_gu"], args_p["W_d"]) -
+                loss(args_m["h"], args_m["w"], args_m["W_gu"], args_m["W_d"])) / (2 * d)
+
+    for which, arr, grad in (("W_d", W_d, got["G_d"]), ("W_gu", W_gu, got["G_gu"]), ("w", w, got["g_w"]),
+                             ("h", h, got["dh"])):
+        for idx in np.ndindex(arr.shape):
+            assert fd(arr, idx, which) == pytest.approx(grad[idx], rel=2e-6, abs=2e-7), (which, idx)
+
+
+@pytest.mark.parametrize("mut", ["silu_prime_without_product_term", "rms_without_projection", "gain_uses_xn",
+                                 "dup_uses_sigmoid_only"])
+def test_block_chain_finite_differences_catch_planted_mistakes(mut):
+    """The same check must fail for plausible wrong formulas (planted here, in CPU code only)."""
+    rng = np.random.default_rng(6)
+    eps = 1e-3
+    h, w, W_gu, W_d, R = _block_inputs(rng)
+    F = W_d.shape[1]
+    xhat, r, xn = M.rmsnorm_forward(h, w, eps)
+    gu = xn @ W_gu.T
+    g, u = gu[:, :F], gu[:, F:]
+    s = M.sigmoid(g)
+    da = R @ W_d
+    good = _block_grads_f64(h, w, W_gu, W_d, R, eps)
+    if mut == "silu_prime_without_product_term":
+        dgu = np.concatenate((da * u * s, da * g * s), axis=1)
+        bad, ref = O.linear_grad(xn, dgu), good["G_gu"]
+    elif mut == "dup_uses_sigmoid_only":
+        dgu = np.concatenate((da * u * (s * (1 + g * (1 - s))), da * s), axis=1)
+        bad, ref = O.linear_grad(xn, dgu), good["G_gu"]
+    elif mut == "rms_without_projection":
+        dxn = M.swiglu_backward(da, gu) @ W_gu
+        bad, ref = r[:, None] * (dxn * w) + R, good["dh"]
+    else:
+        dxn = M.swiglu_backward(da, gu) @ W_gu
+        bad, ref = (dxn * xn).sum(0), good["g_w"]
+    assert np.abs(bad - ref).max() > 1e-3 * np.abs(ref).max()
+
+
+def test_block_hand_example(golden_dir):
+    g = read_golden(os.path.join(golden_dir, "hand_mlp_block.txt"))
+    h, w, W_gu, W_d, dy = g["h"], g["w"][0], g["W_gu"], g["W_d"], g["dy"]
+    np.testing.assert_allclose(M.block_forward_f64(h, w, W_gu, W_d, g["eps"]), g["y"], rtol=1e-14)
+    xhat, r, xn = M.rmsnorm_forward(h, w, g["eps"])
+    gu = xn @ W_gu.T
+    a = M.silu(gu[:, :1]) * gu[:, 1:]
+    da = O.input_grad_f64(dy, W_d)
+    np.testing.assert_allclose(da, g["da"], rtol=1e-14)
+    dgu = M.swiglu_backward(da, gu)
+    np.testing.assert_allclose(dgu, g["dgu"], rtol=1e-14)
+    dxn = O.input_grad_f64(dgu, W_gu)
+    np.testing.assert_allclose(dxn, g["dxn"], rtol=1e-14)
+    np.testing.assert_allclose(O.linear_grad(a, dy), g["G_d"], rtol=1e-14)
+    np.testing.assert_allclose(O.linear_grad(xn, dgu), g["G_gu"], rtol=1e-14)
+    np.testing.assert_allclose(O.vector_grad(xhat, dxn), g["g_w"][0], rtol=1e-14)
+    np.testing.assert_allclose(M.rmsnorm_backward(dxn, xhat, r, w, dres=dy), g["dh"], rtol=1e-14)
+
+
+def test_swiglu_backward_closed_forms():
+    one = np.ones((1, 1))
+    for gate, dgate_want, dup_want in ((0.0, 0.5, 0.0), (40.0, 1.0, 40.0), (-40.0, 0.0, 0.0)):
+        out = M.swiglu_backward(one, np.array([[gate, 1.0]]))
+        assert out[0, 0] == pytest.approx(dgate_want, abs=1e-12) and out[0, 1] == pytest.approx(dup_want, abs=1e-12)
+    # silu'(g) against a difference quotient of silu itself
+    for gate in (-3.0, -0.5, 0.3, 2.0):
+        fdq = (M.silu(np.array(gate + 1e-6)) - M.silu(np.array(gate - 1e-6))) / 2e-6
+        assert M.swiglu_backward(one, np.array([[gate, 1.0]]))[0, 0] == pytest.approx(float(fdq), rel=1e-8)
+
+
+def test_rmsnorm_backward_is_orthogonal_to_its_input():
+    """RMSNorm ignores the scale of h (eps = 0), so the gradient through it has no component along h."""
+    rng = np.random.default_rng(7)
+    h = rng.normal(size=(5, 16))
+    w = rng.normal(size=16)
+    xhat, r, _ = M.rmsnorm_forward(h, w, 0.0)
+    dxn = rng.normal(size=(5, 16))
+    dh = M.rmsnorm_backward(dxn, xhat, r, w)
+    assert np.abs((dh * h).sum(1)).max() < 1e-12 * np.abs(dh).max() * np.abs(h).max() * 16
+    assert np.allclose((xhat * xhat).mean(1), 1.0)
+    # all-equal row, unit gain: xhat = 1, any dxn is projected onto the zero-mean subspace
+    dh1 = M.rmsnorm_backward(np.array([[1.0, 2.0, 3.0, 6.0]]), np.ones((1, 4)), np.array([0.5]), np.ones(4))
+    np.testing.assert_allclose(dh1, 0.5 * (np.array([[1.0, 2.0, 3.0, 6.0]]) - 3.0))
+
+
+def _stored_block(seed, T=24, H=16, F=24, scale=256.0):
+    rng = np.random.default_rng(seed)
+    h = rng.normal(size=(T, H)).astype(np.float16)
+    w = (1.0 + 0.1 * rng.normal(size=H)).astype(np.float16)
+    W_gu = (0.3 * rng.normal(size=(2 * F, H))).astype(np.float16)
+    W_d = (0.3 * rng.normal(size=(H, F))).astype(np.float16)
+    dy = (0.01 * scale * rng.normal(size=(T, H))).astype(np.float16)
+    return h, w, W_gu, W_d, dy, M.block_forward_stored(h, w, W_gu, W_d, 1e-5)
+
+
+def test_block_step_fused_order_equals_materialised():
+    h, w, W_gu, W_d, dy, saved = _stored_block(8)
+    a = M.block_step(dy, saved, w, W_gu, W_d, 0.5, 256.0, max_norm=1e9)
+    b = M.block_step_fused_order(dy, saved, w, W_gu, W_d, 0.5, 256.0, max_norm=1e9)
+    for k in ("W_d", "W_gu", "w", "dh"):
+        np.testing.assert_array_equal(a[k].view(np.uint16), b[k].view(np.uint16))
+    assert (a["W_gu"].view(np.uint16) != W_gu.view(np.uint16)).mean() > 0.5       # the step is visible
+    assert a["clip_coef"] == 1.0 and a["overflow"] is False
+
+
+def test_block_step_matches_generic_step_on_its_three_tensors():
+    """The block step is the generic materialised step applied to (W_d, W_gu, w) with the chain's hand-ons."""
+    h, w, W_gu, W_d, dy, saved = _stored_block(9)
+    a = M.block_step(dy, saved, w, W_gu, W_d, 0.05, 256.0)
+    recs = [dict(kind="linear", X=saved["a"], dY=dy, W=W_d), dict(kind="linear", X=saved["xn"], dY=a["dgu"], W=W_gu),
+            dict(kind="vector", X=saved["xhat"], dY=a["dxn"], W=w)]
+    b = O.step_materialised(recs, 0.05, 256.0)
+    assert a["clip_coef"] == b["clip_coef"] and a["norm"] == b["norm"] and a["clip_coef"] < 1.0
+    for got, want in zip((a["W_d"], a["W_gu"], a["w"]), b["W"]):
+        np.testing.assert_array_equal(got.view(np.uint16), want.view(np.uint16))
+    np.testing.assert_array_equal(a["da"].view(np.uint16), b["dX"][0].view(np.uint16))
+
+
+def test_block_step_overflow_and_scale_invariance():
+    h, w, W_gu, W_d, dy, saved = _stored_block(10)
+    bad = dy.copy()
+    bad[3, 2] = np.inf
+    r = M.block_step(bad, saved, w, W_gu, W_d, 0.05, 256.0)
+    assert r["overflow"] is True
+    for k, p in (("W_d", W_d), ("W_gu", W_gu), ("w", w)):
+        np.testing.assert_array_equal(r[k].view(np.uint16), p.view(np.uint16))
+    # doubling the loss scale doubles dy exactly and changes no parameter bit
+    a = M.block_step(dy, saved, w, W_gu, W_d, 0.05, 256.0)
+    b = M.block_step((dy.astype(np.float32) * 2).astype(np.float16), saved, w, W_gu, W_d, 0.05, 512.0)
+    for k in ("W_d", "W_gu", "w"):
+        np.testing.assert_array_equal(a[k].view(np.uint16), b[k].view(np.uint16))
