@@ -221,6 +221,34 @@ lomo_status lomo_embedding_grouping(const int32_t* ids, int64_t T, int64_t V,
 
 /* ---------------------------------------------------------------- diagnostics */
 
+/* ---------------------------------------------------------------- backward loop through a feed-forward block
+ * Algorithm 1 of the paper walks back through the layers: each parameter's gradient is formed and applied,
+ * and the gradient of the layer input is handed to the layer below (section 3.2).  These calls are the
+ * steps between the linear tensors of a LLaMA feed-forward block (the models of section 4):
+ *     xhat = h * rstd (per token), xn = xhat * gain, [gate | up] = xn W_gu^T, a = silu(gate) * up,
+ *     y = h + a W_d^T.
+ * All buffers device memory, row-major fp16 unless stated, caller-owned, 16-byte aligned; asynchronous on
+ * `stream`; fp32 arithmetic, each stored element rounded once. */
+
+/* dX = dY W alone (dY [T x N], W [N x K], dX [T x K]): pass 1 of a chained step needs the hand-on gradient
+ * but must not touch W.  Same kernel and shape rules as the dgrad inside lomo_linear_backward_update. */
+lomo_status lomo_linear_dgrad(const lomo_half* dY, const lomo_half* W, lomo_half* dX,
+                              int64_t T, int64_t K, int64_t N, void* stream);
+
+/* SwiGLU backward.  da [T x F]; gate_up and dgate_up [T x 2F], each row [gate | up]:
+ *   dgate = da * up * s * (1 + gate * (1 - s)),  dup = da * gate * s,  s = 1 / (1 + exp(-gate)).
+ * F % 8 == 0.  dgate_up may not alias the inputs. */
+lomo_status lomo_swiglu_backward(const lomo_half* da, const lomo_half* gate_up, lomo_half* dgate_up,
+                                 int64_t T, int64_t F, void* stream);
+
+/* RMSNorm backward.  dxn, xhat, dh [T x H]; rstd [T] fp32 (1 / sqrt(mean(h^2) + eps) from the forward pass);
+ * gain [H]; dres [T x H] or NULL (gradient arriving through the residual connection, added in):
+ *   dh = dres + rstd * (dxn * gain - xhat * mean_j(dxn * gain * xhat)).
+ * H % 8 == 0.  dh may alias dres (each element is read before it is written by the same thread), nothing else. */
+lomo_status lomo_rmsnorm_backward(const lomo_half* dxn, const lomo_half* xhat, const float* rstd,
+                                  const lomo_half* gain, const lomo_half* dres, lomo_half* dh,
+                                  int64_t T, int64_t H, void* stream);
+
 /* How the norm pass (paper section 3.3.1) obtains ||dY^T X||^2 of a linear tensor.
  *   LOMO_NORM_DIRECT  contract the gradient tile by tile and square it (2 T N K flop).  Default.
  *   LOMO_NORM_GRAM    sum over token pairs of (x_t . x_t')(dy_t . dy_t'), lower triangle only
@@ -237,7 +265,8 @@ int lomo_get_norm_algorithm(void);
 
 /* Kernel families for lomo_timing_read. */
 enum { LOMO_KERNEL_WGRAD_UPDATE = 0, LOMO_KERNEL_WGRAD_SQNORM = 1, LOMO_KERNEL_DGRAD = 2,
-       LOMO_KERNEL_EMBEDDING = 3, LOMO_KERNEL_VECTOR = 4, LOMO_KERNEL_GRAM_SQNORM = 5, LOMO_KERNEL_FAMILIES = 6 };
+       LOMO_KERNEL_EMBEDDING = 3, LOMO_KERNEL_VECTOR = 4, LOMO_KERNEL_GRAM_SQNORM = 5, LOMO_KERNEL_CHAIN = 6,
+       LOMO_KERNEL_FAMILIES = 7 };
 
 /* Per-kernel timing for benchmarks: while enabled, each launch of a kernel family is bracketed
  * by two HIP events recorded on the launch stream (the only host-side state the library keeps;

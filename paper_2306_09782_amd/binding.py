@@ -20,6 +20,7 @@ EXPORTED_SYMBOLS = (
     "lomo_step_workspace_bytes", "lomo_step_norm_pass", "lomo_step_update_pass",
     "lomo_linear_backward_update_clip_value", "lomo_step_update_pass_clip_value",
     "lomo_set_norm_algorithm", "lomo_get_norm_algorithm", "lomo_step_scalars_device", "lomo_step_update_pass_device",
+    "lomo_linear_dgrad", "lomo_swiglu_backward", "lomo_rmsnorm_backward",
 )
 
 
@@ -75,6 +76,9 @@ def load_library():
                                                      c_size_t, P]),
         "lomo_step_scalars_device": (c_int, [P, P, c_double, c_double, c_double, c_double, P, P]),
         "lomo_step_update_pass_device": (c_int, [POINTER(LomoTensor), I64, P, P, P, c_size_t, P]),
+        "lomo_linear_dgrad": (c_int, [P, P, P, I64, I64, I64, P]),
+        "lomo_swiglu_backward": (c_int, [P, P, P, I64, I64, P]),
+        "lomo_rmsnorm_backward": (c_int, [P, P, P, P, P, P, I64, I64, P]),
         "lomo_set_norm_algorithm": (c_int, [c_int]),
         "lomo_get_norm_algorithm": (c_int, []),
         "lomo_timing_enable": (c_int, [c_int]),
@@ -185,7 +189,7 @@ def lomo_embedding_grouping(ids, V, ws, unique_ids, seg_offsets, perm, n_unique,
                                                   _ptr(seg_offsets), _ptr(perm), _ptr(n_unique), _stream(stream)))
 
 
-KERNEL_FAMILIES = ("wgrad_update", "wgrad_sqnorm", "dgrad", "embedding", "vector", "gram_sqnorm")
+KERNEL_FAMILIES = ("wgrad_update", "wgrad_sqnorm", "dgrad", "embedding", "vector", "gram_sqnorm", "chain")
 NORM_ALGORITHMS = {"direct": 0, "auto": 1, "gram": 2}
 
 
@@ -247,6 +251,27 @@ def lomo_step_norm_pass(tensor_list, acc, flags, ws, stream=None):
 def lomo_step_update_pass(tensor_list, lr, inv_loss_scale, clip_coef, step_flag, ws, stream=None):
     _check(load_library().lomo_step_update_pass(tensor_list, len(tensor_list), lr, inv_loss_scale, clip_coef,
                                                 _ptr(step_flag), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def lomo_linear_dgrad(dY, W, dX, stream=None):
+    T, N = dY.shape
+    K = W.shape[1]
+    assert W.shape[0] == N and tuple(dX.shape) == (T, K)
+    _check(load_library().lomo_linear_dgrad(_ptr(dY), _ptr(W), _ptr(dX), T, K, N, _stream(stream)))
+
+
+def lomo_swiglu_backward(da, gate_up, dgate_up, stream=None):
+    T, F = da.shape
+    assert tuple(gate_up.shape) == (T, 2 * F) and tuple(dgate_up.shape) == (T, 2 * F)
+    _check(load_library().lomo_swiglu_backward(_ptr(da), _ptr(gate_up), _ptr(dgate_up), T, F, _stream(stream)))
+
+
+def lomo_rmsnorm_backward(dxn, xhat, rstd, gain, dres, dh, stream=None):
+    T, H = dxn.shape
+    assert tuple(xhat.shape) == (T, H) and rstd.numel() == T and gain.numel() == H and tuple(dh.shape) == (T, H)
+    assert dres is None or tuple(dres.shape) == (T, H)
+    _check(load_library().lomo_rmsnorm_backward(_ptr(dxn), _ptr(xhat), _ptr(rstd), _ptr(gain), _ptr(dres), _ptr(dh),
+                                                T, H, _stream(stream)))
 
 
 SCALARS_BYTES = 24   # sizeof(lomo_step_scalars): double clip_coef, double grad_norm, float step, int32 overflow

@@ -422,6 +422,46 @@ lomo_status lomo_step_update_pass_clip_value(const lomo_tensor* tensors, int64_t
     return from_hip(launch_reduce_flags(flags, n, flags + n, st));
 }
 
+lomo_status lomo_linear_dgrad(const lomo_half* dY, const lomo_half* W, lomo_half* dX, int64_t T, int64_t K, int64_t N,
+                              void* stream) {
+    if (T < 0 || K < 0 || N < 0 || (K & 7) || (N & 7)) return LOMO_ERR_SHAPE;
+    if (T == 0 || K == 0) return LOMO_OK;
+    if (!dX) return LOMO_ERR_NULL;
+    if (N > 0 && (!dY || !W)) return LOMO_ERR_NULL;
+    if (misaligned(dY) || misaligned(W) || misaligned(dX)) return LOMO_ERR_ALIGN;
+    if (N == 0) return LOMO_ERR_SHAPE;   // an empty contraction would leave dX undefined
+    GemmArgs d{};
+    d.A = W; d.B = dY; d.Out = dX;
+    d.M = K; d.Nn = T; d.C = N;
+    d.lda = K; d.ldb = N; d.ldo = K;
+    d.family = LOMO_KERNEL_DGRAD;
+    return from_hip(launch_dgrad(d, static_cast<hipStream_t>(stream)));
+}
+
+lomo_status lomo_swiglu_backward(const lomo_half* da, const lomo_half* gate_up, lomo_half* dgate_up, int64_t T, int64_t F,
+                                 void* stream) {
+    if (T < 0 || F < 0 || (F & 7)) return LOMO_ERR_SHAPE;
+    if (T == 0 || F == 0) return LOMO_OK;
+    if (!da || !gate_up || !dgate_up) return LOMO_ERR_NULL;
+    if (misaligned(da) || misaligned(gate_up) || misaligned(dgate_up)) return LOMO_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ScopedTiming timing(LOMO_KERNEL_CHAIN, st);
+    return from_hip(launch_swiglu_backward(da, gate_up, dgate_up, T, F, st));
+}
+
+lomo_status lomo_rmsnorm_backward(const lomo_half* dxn, const lomo_half* xhat, const float* rstd, const lomo_half* gain,
+                                  const lomo_half* dres, lomo_half* dh, int64_t T, int64_t H, void* stream) {
+    if (T < 0 || H < 0 || (H & 7) || T > 0x7fffffff) return LOMO_ERR_SHAPE;
+    if (T == 0 || H == 0) return LOMO_OK;
+    if (!dxn || !xhat || !rstd || !gain || !dh) return LOMO_ERR_NULL;
+    if (misaligned(dxn) || misaligned(xhat) || misaligned(gain) || misaligned(dres) || misaligned(dh) ||
+        (reinterpret_cast<uintptr_t>(rstd) & 3u))
+        return LOMO_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ScopedTiming timing(LOMO_KERNEL_CHAIN, st);
+    return from_hip(launch_rmsnorm_backward(dxn, xhat, rstd, gain, dres, dh, T, H, st));
+}
+
 lomo_status lomo_set_norm_algorithm(int algorithm) {
     if (algorithm != LOMO_NORM_DIRECT && algorithm != LOMO_NORM_AUTO && algorithm != LOMO_NORM_GRAM) return LOMO_ERR_SHAPE;
     set_norm_algorithm(algorithm);

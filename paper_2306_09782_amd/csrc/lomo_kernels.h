@@ -122,6 +122,12 @@ inline hipError_t launch_timed(int family, Kern kern, dim3 grid, dim3 block, siz
     return hipGetLastError();
 }
 
+// Feed-forward block chain (lomo_chain.hip): rows of gate_up / dgate_up are [gate | up], 2F wide.
+hipError_t launch_swiglu_backward(const uint16_t* da, const uint16_t* gate_up, uint16_t* dgate_up, int64_t T, int64_t F,
+                                  hipStream_t st);
+hipError_t launch_rmsnorm_backward(const uint16_t* dxn, const uint16_t* xhat, const float* rstd, const uint16_t* gain,
+                                   const uint16_t* dres, uint16_t* dh, int64_t T, int64_t H, hipStream_t st);
+
 hipError_t launch_reduce_flags(const int32_t* flags, int64_t n, int32_t* out, hipStream_t st);
 
 }  // namespace lomo
