@@ -89,6 +89,59 @@ def hbm_kernels(wl, fam, steps):
     return out
 
 
+def chain_bench(L, torch, np, dev, steps, warmup):
+    """Two-pass step through the feed-forward block of the 7B layer (T = 4096, H = 4096, F = 11008) with the
+    hand-on gradients produced by the kernels themselves: 4 GEMMs per linear tensor, as in the paper's
+    two backward passes.  Synthetic saved activations (the chain's arithmetic does not care)."""
+    from paper_2306_09782_amd.chain import LomoMlpBlock
+    import lomo_synth as S
+    T, H, F = 4096, 4096, 11008
+    key = lambda i: S.tensor_key(0, 99, i, 0)
+    gen = lambda i, shape, sigma: S.normal_f16_torch(key(i), shape, S.normal_mult(sigma), dev)
+    saved = {"a": gen(0, (T, F), 0.3), "xn": gen(1, (T, H), 1.0), "xhat": gen(2, (T, H), 1.0),
+             "gate_up": gen(3, (T, 2 * F), 1.0), "rstd": torch.ones(T, dtype=torch.float32, device=dev)}
+    w = torch.ones(H, dtype=torch.float16, device=dev)
+    W_gu, W_d = gen(4, (2 * F, H), 0.02), gen(5, (H, F), 0.02)
+    dy = gen(6, (T, H), 1e-3 * 65536.0)
+    dh = torch.empty(T, H, dtype=torch.float16, device=dev)
+    blk = LomoMlpBlock(dev, T, H, F)
+    run = lambda: blk.step(dy, saved, w, W_gu, W_d, dh, 1e-2, 65536.0)
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    L.lomo_timing_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    fam = {name: L.lomo_timing_read(i) for i, name in enumerate(L.KERNEL_FAMILIES)}
+    L.lomo_timing_enable(False)
+    res = blk.result()
+
+    def timed(fn, reps=20):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+    sw_ms = timed(lambda: L.lomo_swiglu_backward(blk.da, saved["gate_up"], blk.dgu))
+    rn_ms = timed(lambda: L.lomo_rmsnorm_backward(blk.dxn, saved["xhat"], saved["rstd"], w, dy, dh))
+    sw_bytes, rn_bytes = 5 * T * F * 2, 4 * T * H * 2 + 4 * T + 2 * H
+    flops = 4 * (2 * T * H * F + 2 * T * H * 2 * F)
+    return {"workload": "feed-forward block of the 7B layer, chained (T 4096, H 4096, F 11008)", "ms_per_step": ms,
+            "gemms_per_linear": 4, "tflops": flops / (ms * 1e-3) / 1e12, "grad_norm": res["norm"], "overflow": res["overflow"],
+            "family_ms_per_step": {k: v[0] / steps for k, v in fam.items() if v[1]},
+            "swiglu_backward": {"ms": sw_ms, "algorithmic_bytes": sw_bytes, "gb_per_s": sw_bytes / sw_ms / 1e6,
+                                "frac_hbm_peak": sw_bytes / sw_ms / 1e6 / 8000.0},
+            "rmsnorm_backward": {"ms": rn_ms, "algorithmic_bytes": rn_bytes, "gb_per_s": rn_bytes / rn_ms / 1e6,
+                                 "frac_hbm_peak": rn_bytes / rn_ms / 1e6 / 8000.0}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -108,6 +161,8 @@ def main():
                          "metric's flop count describes)")
     ap.add_argument("--no-norm-compare", action="store_true",
                     help="skip the extra timing of pass 1 alone on each route after the timed steps")
+    ap.add_argument("--chain", action="store_true",
+                    help="also time the chained two-pass step through the 7B feed-forward block (extra key `chain`)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -242,6 +297,10 @@ def main():
                                          "avg_launch_ms": fam["gram_sqnorm"][0] / fam["gram_sqnorm"][1]}
     if norm_compare:
         out["norm_pass_alone"] = norm_compare
+    if args.chain:
+        del tensors
+        torch.cuda.empty_cache()
+        out["chain"] = chain_bench(L, torch, np, dev, max(3, args.steps // 2), 2)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))
