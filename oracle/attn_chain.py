@@ -1,0 +1,225 @@
+"""CPU oracle for the attention half of LOMO's backward loop through a decoder layer -- TEST INFRASTRUCTURE.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import this file; the HIP path
+never does, and this file imports nothing from it (it builds on oracle/lomo_oracle.py and oracle/mlp_chain.py).
+
+What it computes.  Algorithm 1 of the paper walks the layers backwards, updating each parameter as soon as
+its gradient exists and handing the gradient of the layer input down (section 3.2).  Here the walk goes
+through the self-attention block of the models the paper fine-tunes (LLaMA, section 4): RMSNorm with gain
+w, fused projection W_qkv [3H x H], rotary position embedding on q and k, causal softmax attention over
+n_heads heads of width d, output projection W_o [H x H], residual connection.  Tokens are laid out
+t = b * s + pos (B sequences of length s); head n owns columns [n d, (n + 1) d) of q, k, v and o.
+
+    xhat = h * r,  xn = xhat * w,  [q | k | v] = xn W_qkv^T
+    rotary: for c < d/2 and angle a = pos * theta_c:  q'_c = q_c cos a - q_{c+d/2} sin a,
+                                                      q'_{c+d/2} = q_{c+d/2} cos a + q_c sin a   (same for k)
+    S_ij = (q'_i . k'_j) / sqrt(d) for j <= i (same sequence),  P = softmax_j(S),  o_i = sum_j P_ij v_j
+    y = h + o W_o^T
+
+Backward, given dy (carrying the loss scale), with lse_i = log sum_j exp(S_ij) saved by the forward pass:
+    do = dy W_o                               G_o = dy^T o
+    P_ij = exp(S_ij - lse_i),  dP_ij = do_i . v_j,  delta_i = do_i . o_i
+    dS = P * (dP - delta) / sqrt(d)           dv_j = sum_i P_ij do_i
+    dq'_i = sum_j dS_ij k'_j                  dk'_j = sum_i dS_ij q'_i
+    rotary backward = rotation by -a:  dq_c = dq'_c cos a + dq'_{c+d/2} sin a,  dq_{c+d/2} = dq'_{c+d/2} cos a - dq'_c sin a
+    dxn = [dq | dk | dv] W_qkv                G_qkv = [dq | dk | dv]^T xn
+    g_w = sum_t dxn * xhat                    dh = dy + rmsnorm_backward(dxn)
+
+Precision (section 3.3.2: fp16 storage, full-precision computation): every tensor the mixed-precision run
+keeps in fp16 is rounded once where it is stored -- do, [dq|dk|dv] (after the rotary step), dxn, dh, and
+also the attention probabilities P and their gradients dS, which fp16 training holds as fp16 tensors before
+they enter the next matrix product.  dS is formed from the unrounded P.  The cos / sin table and lse are
+fp32 inputs.  All arithmetic in between is fp64.
+
+Pins (tests/test_oracle_pins.py): central finite differences of a scalar loss through the forward block for
+dq, dk, dv (before the rotary step) and through the whole block for G_o, G_qkv, g_w, dh; softmax rows sum
+to one and delta equals sum_j P dP; causality (the last key receives gradient from the last query only);
+the rotary step is a rotation (norm preserving, backward = inverse); a hand-worked two-token example.
+"""
+from __future__ import annotations
+
+import math
+from typing import Dict
+
+import numpy as np
+
+from . import lomo_oracle as O
+from . import mlp_chain as M
+
+
+# --------------------------------------------------------------------------- rotary embedding
+
+
+def rope_tables(s: int, d: int, base: float = 10000.0):
+    """cos, sin [s x d/2] in fp32: angle(pos, c) = pos * base^(-2c/d).  The stored table is the input."""
+    c = np.arange(d // 2, dtype=np.float64)
+    ang = np.arange(s, dtype=np.float64)[:, None] * base ** (-2.0 * c / d)[None, :]
+    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+
+
+def _heads(x, n_heads: int):
+    T, H = x.shape
+    return x.reshape(T, n_heads, H // n_heads)
+
+
+def rope_rotate(x, cos, sin, s: int, n_heads: int, inverse: bool = False) -> np.ndarray:
+    """Rotary step on x [T x H] (fp64 out).  inverse=True rotates by the negative angle (the backward step)."""
+    x64 = _heads(O.as_f64(x) if x.dtype == np.float16 else np.asarray(x, dtype=np.float64), n_heads)
+    T, _, d = x64.shape
+    pos = np.arange(T) % s
+    co = np.asarray(cos, dtype=np.float64)[pos][:, None, :]
+    si = np.asarray(sin, dtype=np.float64)[pos][:, None, :]
+    if inverse:
+        si = -si
+    x1, x2 = x64[..., : d // 2], x64[..., d // 2:]
+    out = np.concatenate((x1 * co - x2 * si, x2 * co + x1 * si), axis=-1)
+    return out.reshape(T, -1)
+
+
+# --------------------------------------------------------------------------- attention
+
+
+def _scores(qh, kh, d):
+    """Causal scaled scores of one sequence and head: [s x s] with -inf above the diagonal."""
+    S = (qh @ kh.T) / math.sqrt(d)
+    s = S.shape[0]
+    S[np.triu_indices(s, 1)] = -np.inf
+    return S
+
+
+def attention_forward_f64(q, k, v, s: int, n_heads: int):
+    """o [T x H] and lse [T x n_heads] in plain fp64 (q, k already rotated)."""
+    T, H = q.shape
+    d = H // n_heads
+    qh, kh, vh = (_heads(np.asarray(a, dtype=np.float64), n_heads) for a in (q, k, v))
+    o = np.zeros((T, n_heads, d))
+    lse = np.zeros((T, n_heads))
+    for b in range(T // s):
+        sl = slice(b * s, (b + 1) * s)
+        for n in range(n_heads):
+            S = _scores(qh[sl, n], kh[sl, n], d)
+            m = S.max(axis=1, keepdims=True)
+            e = np.exp(S - m)
+            z = e.sum(axis=1, keepdims=True)
+            lse[sl, n] = (m + np.log(z))[:, 0]
+            o[sl, n] = (e / z) @ vh[sl, n]
+    return o.reshape(T, H), lse
+
+
+def attention_forward_stored(qkv, s: int, n_heads: int) -> Dict:
+    """What the forward pass leaves behind: o in fp16 (from fp16 probabilities) and lse in fp32."""
+    T, H3 = qkv.shape
+    H = H3 // 3
+    d = H // n_heads
+    q, k, v = (O.as_f64(qkv[:, i * H:(i + 1) * H]) for i in range(3))
+    qh, kh, vh = (_heads(a, n_heads) for a in (q, k, v))
+    o = np.zeros((T, n_heads, d))
+    lse = np.zeros((T, n_heads), dtype=np.float32)
+    for b in range(T // s):
+        sl = slice(b * s, (b + 1) * s)
+        for n in range(n_heads):
+            S = _scores(qh[sl, n], kh[sl, n], d)
+            m = S.max(axis=1, keepdims=True)
+            l = (m + np.log(np.exp(S - m).sum(axis=1, keepdims=True)))[:, 0].astype(np.float32)
+            lse[sl, n] = l
+            P16 = O.round_f16(np.exp(S - l.astype(np.float64)[:, None]))
+            o[sl, n] = O.as_f64(P16) @ vh[sl, n]
+    return {"o": O.round_f16(o.reshape(T, H)), "lse": lse}
+
+
+def attention_backward(qkv, o, do, lse, s: int, n_heads: int, round_probabilities: bool = True) -> np.ndarray:
+    """[dq' | dk' | dv] in fp64 (before the rotary backward step) from the saved fp16 qkv (rotated q and k),
+    fp16 o, fp32 lse and the incoming do.  With round_probabilities the probabilities P and their scaled
+    gradients dS pass through fp16 before the matrix products that consume them."""
+    T, H3 = qkv.shape
+    H = H3 // 3
+    d = H // n_heads
+    cast = (lambda a: O.as_f64(a)) if qkv.dtype == np.float16 else (lambda a: np.asarray(a, dtype=np.float64))
+    q, k, v = (_heads(cast(qkv[:, i * H:(i + 1) * H]), n_heads) for i in range(3))
+    oh = _heads(cast(o), n_heads)
+    doh = _heads(cast(do), n_heads)
+    rnd = (lambda a: O.as_f64(O.round_f16(a))) if round_probabilities else (lambda a: a)
+    out = np.zeros((T, 3, n_heads, d))
+    with np.errstate(invalid="ignore", over="ignore"):
+        for b in range(T // s):
+            sl = slice(b * s, (b + 1) * s)
+            for n in range(n_heads):
+                S = _scores(q[sl, n], k[sl, n], d)
+                P = np.exp(S - np.asarray(lse[sl, n], dtype=np.float64)[:, None])
+                dP = doh[sl, n] @ v[sl, n].T
+                delta = (doh[sl, n] * oh[sl, n]).sum(axis=1, keepdims=True)
+                dS = np.where(P > 0, P * (dP - delta), 0.0) / math.sqrt(d)
+                out[sl, 0, n] = rnd(dS) @ k[sl, n]
+                out[sl, 1, n] = rnd(dS).T @ q[sl, n]
+                out[sl, 2, n] = rnd(P).T @ doh[sl, n]
+    return out.reshape(T, 3 * H)
+
+
+def attention_rope_backward(qkv, o, do, lse, cos, sin, s: int, n_heads: int) -> np.ndarray:
+    """[dq | dk | dv] as stored (fp16): attention backward, rotary backward on the q and k parts, one rounding."""
+    T, H3 = qkv.shape
+    H = H3 // 3
+    g = attention_backward(qkv, o, do, lse, s, n_heads)
+    dq = rope_rotate(g[:, :H], cos, sin, s, n_heads, inverse=True)
+    dk = rope_rotate(g[:, H:2 * H], cos, sin, s, n_heads, inverse=True)
+    return O.round_f16(np.concatenate((dq, dk, g[:, 2 * H:]), axis=1))
+
+
+# --------------------------------------------------------------------------- the block
+
+
+def block_forward_f64(h, w, W_qkv, W_o, cos, sin, s: int, n_heads: int, eps: float) -> np.ndarray:
+    """y of the attention block in plain fp64 (finite-difference pin)."""
+    H = h.shape[1]
+    _, _, xn = M.rmsnorm_forward(h, w, eps)
+    qkv = xn @ np.asarray(W_qkv, dtype=np.float64).T
+    q = rope_rotate(qkv[:, :H], cos, sin, s, n_heads)
+    k = rope_rotate(qkv[:, H:2 * H], cos, sin, s, n_heads)
+    o, _ = attention_forward_f64(q, k, qkv[:, 2 * H:], s, n_heads)
+    return np.asarray(h, dtype=np.float64) + o @ np.asarray(W_o, dtype=np.float64).T
+
+
+def block_forward_stored(h, w, W_qkv, W_o, cos, sin, s: int, n_heads: int, eps: float) -> Dict:
+    """Saved activations of the forward pass, each rounded to its storage type."""
+    H = h.shape[1]
+    xhat64, r64, _ = M.rmsnorm_forward(h, w, eps)
+    xhat = O.round_f16(xhat64)
+    xn = O.round_f16(O.as_f64(xhat) * O.as_f64(w)[None, :])
+    qkv = O.round_f16(O.as_f64(xn) @ O.as_f64(W_qkv).T)
+    q = O.round_f16(rope_rotate(qkv[:, :H], cos, sin, s, n_heads))
+    k = O.round_f16(rope_rotate(qkv[:, H:2 * H], cos, sin, s, n_heads))
+    qkv_rot = np.concatenate((q, k, qkv[:, 2 * H:]), axis=1)
+    att = attention_forward_stored(qkv_rot, s, n_heads)
+    return {"xhat": xhat, "r": r64.astype(np.float32), "xn": xn, "qkv": qkv_rot, "o": att["o"], "lse": att["lse"]}
+
+
+def chain_gradients(dy, saved: Dict, w, W_qkv, W_o, cos, sin, s: int, n_heads: int) -> Dict:
+    do = O.input_grad(dy, W_o)
+    G_o = O.linear_grad(saved["o"], dy)
+    dqkv = attention_rope_backward(saved["qkv"], saved["o"], do, saved["lse"], cos, sin, s, n_heads)
+    dxn = O.input_grad(dqkv, W_qkv)
+    G_qkv = O.linear_grad(saved["xn"], dqkv)
+    g_w = O.vector_grad(saved["xhat"], dxn)
+    dh = O.round_f16(M.rmsnorm_backward(dxn, saved["xhat"], saved["r"], w, dres=dy))
+    return {"do": do, "dqkv": dqkv, "dxn": dxn, "dh": dh, "G_o": G_o, "G_qkv": G_qkv, "g_w": g_w}
+
+
+def block_step(dy, saved: Dict, w, W_qkv, W_o, cos, sin, s: int, n_heads: int, lr: float, loss_scale: float,
+               max_norm: float = 1.0, eps_clip: float = 1e-6) -> Dict:
+    """Two-pass LOMO step over the attention block, parameters in backward order W_o, W_qkv, w.  As in the
+    feed-forward block no hand-on gradient depends on an updated parameter, so the fused order of
+    Algorithm 1 gives the materialised result computed here."""
+    c = chain_gradients(dy, saved, w, W_qkv, W_o, cos, sin, s, n_heads)
+    grads = [c["G_o"], c["G_qkv"], c["g_w"]]
+    flags = [O.has_overflow(g) for g in grads]
+    sq = [O.sqnorm(g) for g in grads]
+    overflow = any(flags)
+    total = math.fsum(sq) if not overflow else float("nan")
+    norm = O.grad_norm(total, loss_scale) if not overflow else float("nan")
+    coef = O.clip_coef(norm, max_norm, eps_clip) if not overflow else float("nan")
+    params = [W_o, W_qkv, w]
+    new = [np.array(p, copy=True) if overflow else O.sgd_update(p, g, lr, coef, loss_scale)
+           for p, g in zip(params, grads)]
+    return {"W_o": new[0], "W_qkv": new[1], "w": new[2], "dh": c["dh"], "do": c["do"], "dqkv": c["dqkv"],
+            "dxn": c["dxn"], "flags": flags, "sqnorms": sq, "overflow": overflow, "total_sqnorm": total,
+            "norm": norm, "clip_coef": coef}

@@ -492,7 +492,8 @@ def test_oracle_does_not_import_the_hip_path():
     import ast
     import oracle.lomo_oracle as mod
     import oracle.mlp_chain as chain
-    for m in (mod, chain):
+    import oracle.attn_chain as attn
+    for m in (mod, chain, attn):
         tree = ast.parse(open(m.__file__).read())
         names = set()
         for node in ast.walk(tree):
@@ -674,3 +675,177 @@ def test_block_step_overflow_and_scale_invariance():
     b = M.block_step((dy.astype(np.float32) * 2).astype(np.float16), saved, w, W_gu, W_d, 0.05, 512.0)
     for k in ("W_d", "W_gu", "w"):
         np.testing.assert_array_equal(a[k].view(np.uint16), b[k].view(np.uint16))
+
+
+# --------------------------------------------------------------------------- attention block chain
+
+from oracle import attn_chain as A
+
+
+def test_attention_hand_example(golden_dir):
+    g = read_golden(os.path.join(golden_dir, "hand_attention_2tok.txt"))
+    o, lse = A.attention_forward_f64(g["q"], g["k"], g["v"], 2, 1)
+    np.testing.assert_allclose(o, g["o"], rtol=1e-14)
+    np.testing.assert_allclose(lse, g["lse"], rtol=1e-14)
+    qkv = np.concatenate((g["q"], g["k"], g["v"]), axis=1)
+    d = A.attention_backward(qkv, o, g["do"], lse, 2, 1, round_probabilities=False)
+    np.testing.assert_allclose(d[:, 0:2], g["dq"], rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(d[:, 2:4], g["dk"], rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(d[:, 4:6], g["dv"], rtol=1e-13, atol=1e-15)
+
+
+def test_attention_backward_finite_differences():
+    rng = np.random.default_rng(11)
+    s, nh, dd, B = 5, 2, 4, 2
+    T, H = B * s, nh * dd
+    q, k, v, R = (rng.normal(size=(T, H)) for _ in range(4))
+    o, lse = A.attention_forward_f64(q, k, v, s, nh)
+    got = A.attention_backward(np.concatenate((q, k, v), axis=1), o, R, lse, s, nh, round_probabilities=False)
+    loss = lambda q_, k_, v_: float((A.attention_forward_f64(q_, k_, v_, s, nh)[0] * R).sum())
+    e = 1e-6
+    for part, arr in enumerate((q, k, v)):
+        for idx in np.ndindex(arr.shape):
+            p, m = arr.copy(), arr.copy()
+            p[idx] += e
+            m[idx] -= e
+            args_p, args_m = [q, k, v], [q, k, v]
+            args_p[part], args_m[part] = p, m
+            fd = (loss(*args_p) - loss(*args_m)) / (2 * e)
+            assert fd == pytest.approx(got[idx[0], part * H + idx[1]], rel=1e-6, abs=1e-8), (part, idx)
+    # structure: rows of P sum to one; delta equals sum_j P dP; the last key hears the last query only
+    for b in range(B):
+        sl = slice(b * s, (b + 1) * s)
+        for n in range(nh):
+            hs = slice(n * dd, (n + 1) * dd)
+            S = (q[sl, hs] @ k[sl, hs].T) / math.sqrt(dd)
+            S[np.triu_indices(s, 1)] = -np.inf
+            P = np.exp(S - lse[sl, n][:, None])
+            np.testing.assert_allclose(P.sum(1), 1.0, rtol=1e-13)
+            dP = R[sl, hs] @ v[sl, hs].T
+            np.testing.assert_allclose((P * dP).sum(1), (R[sl, hs] * o[sl, hs]).sum(1), rtol=1e-12)
+            np.testing.assert_allclose(got[sl, 2 * H + n * dd:2 * H + (n + 1) * dd][-1], P[-1, -1] * R[sl, hs][-1], rtol=1e-12)
+
+
+def test_rope_is_a_rotation():
+    rng = np.random.default_rng(12)
+    s, nh, dd = 7, 3, 8
+    cos, sin = A.rope_tables(s, dd)
+    x = rng.normal(size=(2 * s, nh * dd))
+    y = A.rope_rotate(x, cos, sin, s, nh)
+    np.testing.assert_allclose(A.rope_rotate(y, cos, sin, s, nh, inverse=True), x, atol=1e-6)   # fp32 table
+    np.testing.assert_allclose((y.reshape(2 * s, nh, dd) ** 2).sum(-1), (x.reshape(2 * s, nh, dd) ** 2).sum(-1), rtol=1e-6)
+    np.testing.assert_array_equal(y[0], x[0])                      # position 0: angle 0
+    np.testing.assert_array_equal(y[s], x[s])                      # first token of the second sequence
+    # d = 2, position 1, theta_0 = 1: the textbook plane rotation by one radian
+    c1, s1 = A.rope_tables(2, 2)
+    r = A.rope_rotate(np.array([[0.0, 0.0], [3.0, 4.0]]), c1, s1, 2, 1)
+    np.testing.assert_allclose(r[1], [3 * math.cos(1) - 4 * math.sin(1), 4 * math.cos(1) + 3 * math.sin(1)], rtol=1e-6)
+    # the backward step is the transpose of the forward one: <rotate(x), g> == <x, rotate^-1(g)>
+    gq = rng.normal(size=x.shape)
+    assert float((y * gq).sum()) == pytest.approx(float((x * A.rope_rotate(gq, cos, sin, s, nh, inverse=True)).sum()), rel=1e-12)
+
+
+def _attn_block_inputs(rng, B=2, s=4, nh=2, dd=4):
+    T, H = B * s, nh * dd
+    h = rng.normal(size=(T, H))
+    w = 1.0 + 0.3 * rng.normal(size=H)
+    W_qkv = 0.6 * rng.normal(size=(3 * H, H))
+    W_o = 0.6 * rng.normal(size=(H, H))
+    R = rng.normal(size=(T, H))
+    return h, w, W_qkv, W_o, R, s, nh
+
+
+def test_attention_block_chain_finite_differences():
+    rng = np.random.default_rng(13)
+    eps = 1e-3
+    h, w, W_qkv, W_o, R, s, nh = _attn_block_inputs(rng)
+    T, H = h.shape
+    cos, sin = A.rope_tables(s, H // nh)
+    # the chain's formulas composed in fp64 without storage rounding
+    xhat, r, xn = M.rmsnorm_forward(h, w, eps)
+    qkv = xn @ W_qkv.T
+    q = A.rope_rotate(qkv[:, :H], cos, sin, s, nh)
+    k = A.rope_rotate(qkv[:, H:2 * H], cos, sin, s, nh)
+    o, lse = A.attention_forward_f64(q, k, qkv[:, 2 * H:], s, nh)
+    do = O.input_grad_f64(R, W_o)
+    g = A.attention_backward(np.concatenate((q, k, qkv[:, 2 * H:]), axis=1), o, do, lse, s, nh, round_probabilities=False)
+    dqkv = np.concatenate((A.rope_rotate(g[:, :H], cos, sin, s, nh, inverse=True),
+                           A.rope_rotate(g[:, H:2 * H], cos, sin, s, nh, inverse=True), g[:, 2 * H:]), axis=1)
+    dxn = O.input_grad_f64(dqkv, W_qkv)
+    got = {"W_o": O.linear_grad(o, R), "W_qkv": O.linear_grad(xn, dqkv), "w": O.vector_grad(xhat, dxn),
+           "h": M.rmsnorm_backward(dxn, xhat, r, w, dres=R)}
+    base = {"h": h, "w": w, "W_qkv": W_qkv, "W_o": W_o}
+    loss = lambda a: float((A.block_forward_f64(a["h"], a["w"], a["W_qkv"], a["W_o"], cos, sin, s, nh, eps) * R).sum())
+    e = 1e-6
+    for which in ("W_o", "W_qkv", "w", "h"):
+        arr = base[which]
+        for idx in list(np.ndindex(arr.shape))[::3]:
+            p, m = dict(base), dict(base)
+            p[which], m[which] = arr.copy(), arr.copy()
+            p[which][idx] += e
+            m[which][idx] -= e
+            fd = (loss(p) - loss(m)) / (2 * e)
+            assert fd == pytest.approx(got[which][idx], rel=5e-6, abs=1e-7), (which, idx)
+
+
+def test_attention_block_step_is_the_generic_step_on_its_tensors():
+    rng = np.random.default_rng(14)
+    B, s, nh, dd = 2, 8, 2, 8
+    T, H = B * s, nh * dd
+    f16 = lambda shape, sig: (sig * rng.normal(size=shape)).astype(np.float16)
+    h, w = f16((T, H), 1.0), (1.0 + 0.1 * rng.normal(size=H)).astype(np.float16)
+    W_qkv, W_o, dy = f16((3 * H, H), 0.3), f16((H, H), 0.3), f16((T, H), 2.0)
+    cos, sin = A.rope_tables(s, dd)
+    saved = A.block_forward_stored(h, w, W_qkv, W_o, cos, sin, s, nh, 1e-5)
+    a = A.block_step(dy, saved, w, W_qkv, W_o, cos, sin, s, nh, 0.05, 256.0)
+    recs = [dict(kind="linear", X=saved["o"], dY=dy, W=W_o), dict(kind="linear", X=saved["xn"], dY=a["dqkv"], W=W_qkv),
+            dict(kind="vector", X=saved["xhat"], dY=a["dxn"], W=w)]
+    b = O.step_materialised(recs, 0.05, 256.0)
+    assert a["clip_coef"] == b["clip_coef"] and a["overflow"] is False
+    for got, want in zip((a["W_o"], a["W_qkv"], a["w"]), b["W"]):
+        np.testing.assert_array_equal(got.view(np.uint16), want.view(np.uint16))
+    # storage rounding of P and dS matters little but is there: the unrounded route differs slightly
+    g16 = A.attention_backward(saved["qkv"], saved["o"], a["do"], saved["lse"], s, nh)
+    g64 = A.attention_backward(saved["qkv"], saved["o"], a["do"], saved["lse"], s, nh, round_probabilities=False)
+    rel = np.abs(g16 - g64).max() / np.abs(g64).max()
+    assert 0 < rel < 2e-3
+    bad = dy.copy()
+    bad[5, 1] = np.nan
+    r = A.block_step(bad, saved, w, W_qkv, W_o, cos, sin, s, nh, 0.05, 256.0)
+    assert r["overflow"] is True
+    np.testing.assert_array_equal(r["W_qkv"].view(np.uint16), W_qkv.view(np.uint16))
+
+
+@pytest.mark.parametrize("mut", ["no_delta", "no_scale", "rope_forward_instead_of_inverse", "no_causal_mask"])
+def test_attention_finite_differences_catch_planted_mistakes(mut):
+    """Wrong formulas planted in CPU code must disagree with the difference quotients."""
+    rng = np.random.default_rng(15)
+    s, nh, dd = 4, 1, 4
+    cos, sin = A.rope_tables(s, dd)
+    qp, kp, v, R = (rng.normal(size=(s, dd)) for _ in range(4))          # before the rotary step
+
+    def fwd(q_, k_, v_):
+        return A.attention_forward_f64(A.rope_rotate(q_, cos, sin, s, nh), A.rope_rotate(k_, cos, sin, s, nh), v_, s, nh)
+
+    loss = lambda q_, k_, v_: float((fwd(q_, k_, v_)[0] * R).sum())
+    e = 1e-6
+    fd = np.zeros((s, dd))
+    for idx in np.ndindex(qp.shape):
+        p, m = qp.copy(), qp.copy()
+        p[idx] += e
+        m[idx] -= e
+        fd[idx] = (loss(p, kp, v) - loss(m, kp, v)) / (2 * e)
+    q, k = A.rope_rotate(qp, cos, sin, s, nh), A.rope_rotate(kp, cos, sin, s, nh)
+    o, lse = fwd(qp, kp, v)
+    S = (q @ k.T) / math.sqrt(dd)
+    if mut != "no_causal_mask":
+        S[np.triu_indices(s, 1)] = -np.inf
+    P = np.exp(S - lse[:, 0][:, None])
+    dP = R @ v.T
+    delta = 0.0 if mut == "no_delta" else (R * o).sum(1, keepdims=True)
+    dS = P * (dP - delta) / (1.0 if mut == "no_scale" else math.sqrt(dd))
+    dq_rot = dS @ k
+    bad = A.rope_rotate(dq_rot, cos, sin, s, nh, inverse=(mut != "rope_forward_instead_of_inverse"))
+    good = A.rope_rotate(A.attention_backward(np.concatenate((q, k, v), 1), o, R, lse, s, nh, False)[:, :dd], cos, sin, s, nh, True)
+    np.testing.assert_allclose(good, fd, rtol=1e-5, atol=1e-8)
+    assert np.abs(bad - fd).max() > 1e-3 * np.abs(fd).max()
