@@ -249,6 +249,22 @@ lomo_status lomo_rmsnorm_backward(const lomo_half* dxn, const lomo_half* xhat, c
                                   const lomo_half* gain, const lomo_half* dres, lomo_half* dh,
                                   int64_t T, int64_t H, void* stream);
 
+/* Causal self-attention backward with the rotary position step, for the hand-on gradient through the
+ * attention block of a LLaMA layer.  Tokens t = b * s + pos (B sequences of length s); head n owns columns
+ * [n d, (n + 1) d) of q, k, v, o; d = head_dim must be 128 and s a multiple of 64 (else LOMO_ERR_SHAPE).
+ *   qkv   [T x 3H] rotated q | rotated k | v as saved by the forward pass (H = n_heads * d)
+ *   o     [T x H]  attention output;  dO [T x H] its gradient
+ *   lse   [T x n_heads] fp32, log sum_j exp(q_i . k_j / sqrt(d)) over the keys j <= i
+ *   rope_cos, rope_sin [s x d/2] fp32 (angle pos * theta_c), or both NULL for no rotary step
+ *   delta_ws [T x n_heads] fp32 scratch (receives do_i . o_i)
+ *   dqkv  [T x 3H] out: dq | dk | dv, the gradient of the fused projection's output
+ * P = exp(S - lse), dP = dO v^T, dS = P (dP - delta) / sqrt(d), dv = P^T dO, dk = dS^T q, dq = dS k, then
+ * dq and dk are rotated by the negative angle (pairs (c, c + d/2)).  fp32 accumulation; P and dS pass through
+ * fp16 before the products that consume them; outputs rounded once.  Deterministic (no atomics). */
+lomo_status lomo_attention_backward(const lomo_half* qkv, const lomo_half* o, const lomo_half* dO, const float* lse,
+                                    const float* rope_cos, const float* rope_sin, float* delta_ws, lomo_half* dqkv,
+                                    int64_t B, int64_t s, int64_t n_heads, int64_t head_dim, void* stream);
+
 /* How the norm pass (paper section 3.3.1) obtains ||dY^T X||^2 of a linear tensor.
  *   LOMO_NORM_DIRECT  contract the gradient tile by tile and square it (2 T N K flop).  Default.
  *   LOMO_NORM_GRAM    sum over token pairs of (x_t . x_t')(dy_t . dy_t'), lower triangle only
@@ -266,7 +282,7 @@ int lomo_get_norm_algorithm(void);
 /* Kernel families for lomo_timing_read. */
 enum { LOMO_KERNEL_WGRAD_UPDATE = 0, LOMO_KERNEL_WGRAD_SQNORM = 1, LOMO_KERNEL_DGRAD = 2,
        LOMO_KERNEL_EMBEDDING = 3, LOMO_KERNEL_VECTOR = 4, LOMO_KERNEL_GRAM_SQNORM = 5, LOMO_KERNEL_CHAIN = 6,
-       LOMO_KERNEL_FAMILIES = 7 };
+       LOMO_KERNEL_ATTENTION = 7, LOMO_KERNEL_FAMILIES = 8 };
 
 /* Per-kernel timing for benchmarks: while enabled, each launch of a kernel family is bracketed
  * by two HIP events recorded on the launch stream (the only host-side state the library keeps;

@@ -13,7 +13,7 @@ from .binding import (LomoError, library_path, load_library, lomo_version, lomo_
                       lomo_linear_backward_update_clip_value, lomo_step_update_pass_clip_value,
                       lomo_set_norm_algorithm, lomo_get_norm_algorithm, NORM_ALGORITHMS, LomoTensor,
                       lomo_step_scalars_device, lomo_step_update_pass_device, unpack_step_scalars, SCALARS_BYTES,
-                      lomo_linear_dgrad, lomo_swiglu_backward, lomo_rmsnorm_backward,
+                      lomo_linear_dgrad, lomo_swiglu_backward, lomo_rmsnorm_backward, lomo_attention_backward,
                       EXPORTED_SYMBOLS)
 
 __all__ = [n for n in dir() if n.startswith("lomo_")] + ["LomoError", "library_path", "load_library",

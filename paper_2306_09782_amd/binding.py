@@ -20,7 +20,7 @@ EXPORTED_SYMBOLS = (
     "lomo_step_workspace_bytes", "lomo_step_norm_pass", "lomo_step_update_pass",
     "lomo_linear_backward_update_clip_value", "lomo_step_update_pass_clip_value",
     "lomo_set_norm_algorithm", "lomo_get_norm_algorithm", "lomo_step_scalars_device", "lomo_step_update_pass_device",
-    "lomo_linear_dgrad", "lomo_swiglu_backward", "lomo_rmsnorm_backward",
+    "lomo_linear_dgrad", "lomo_swiglu_backward", "lomo_rmsnorm_backward", "lomo_attention_backward",
 )
 
 
@@ -79,6 +79,7 @@ def load_library():
         "lomo_linear_dgrad": (c_int, [P, P, P, I64, I64, I64, P]),
         "lomo_swiglu_backward": (c_int, [P, P, P, I64, I64, P]),
         "lomo_rmsnorm_backward": (c_int, [P, P, P, P, P, P, I64, I64, P]),
+        "lomo_attention_backward": (c_int, [P, P, P, P, P, P, P, P, I64, I64, I64, I64, P]),
         "lomo_set_norm_algorithm": (c_int, [c_int]),
         "lomo_get_norm_algorithm": (c_int, []),
         "lomo_timing_enable": (c_int, [c_int]),
@@ -189,7 +190,7 @@ def lomo_embedding_grouping(ids, V, ws, unique_ids, seg_offsets, perm, n_unique,
                                                   _ptr(seg_offsets), _ptr(perm), _ptr(n_unique), _stream(stream)))
 
 
-KERNEL_FAMILIES = ("wgrad_update", "wgrad_sqnorm", "dgrad", "embedding", "vector", "gram_sqnorm", "chain")
+KERNEL_FAMILIES = ("wgrad_update", "wgrad_sqnorm", "dgrad", "embedding", "vector", "gram_sqnorm", "chain", "attention")
 NORM_ALGORITHMS = {"direct": 0, "auto": 1, "gram": 2}
 
 
@@ -272,6 +273,14 @@ def lomo_rmsnorm_backward(dxn, xhat, rstd, gain, dres, dh, stream=None):
     assert dres is None or tuple(dres.shape) == (T, H)
     _check(load_library().lomo_rmsnorm_backward(_ptr(dxn), _ptr(xhat), _ptr(rstd), _ptr(gain), _ptr(dres), _ptr(dh),
                                                 T, H, _stream(stream)))
+
+
+def lomo_attention_backward(qkv, o, dO, lse, rope_cos, rope_sin, delta_ws, dqkv, B, s, n_heads, stream=None):
+    T, H = o.shape
+    assert T == B * s and H % n_heads == 0 and tuple(qkv.shape) == (T, 3 * H) and tuple(dqkv.shape) == (T, 3 * H)
+    assert tuple(dO.shape) == (T, H) and lse.numel() == T * n_heads and delta_ws.numel() >= T * n_heads
+    _check(load_library().lomo_attention_backward(_ptr(qkv), _ptr(o), _ptr(dO), _ptr(lse), _ptr(rope_cos), _ptr(rope_sin),
+                                                  _ptr(delta_ws), _ptr(dqkv), B, s, n_heads, H // n_heads, _stream(stream)))
 
 
 SCALARS_BYTES = 24   # sizeof(lomo_step_scalars): double clip_coef, double grad_norm, float step, int32 overflow

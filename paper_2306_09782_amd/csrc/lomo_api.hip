@@ -462,6 +462,23 @@ lomo_status lomo_rmsnorm_backward(const lomo_half* dxn, const lomo_half* xhat, c
     return from_hip(launch_rmsnorm_backward(dxn, xhat, rstd, gain, dres, dh, T, H, st));
 }
 
+lomo_status lomo_attention_backward(const lomo_half* qkv, const lomo_half* o, const lomo_half* dO, const float* lse,
+                                    const float* rope_cos, const float* rope_sin, float* delta_ws, lomo_half* dqkv,
+                                    int64_t B, int64_t s, int64_t n_heads, int64_t head_dim, void* stream) {
+    if (B < 0 || s < 0 || n_heads < 0 || head_dim != 128 || (s & 63) || s > (1 << 20) || n_heads > 65535 || B > 65535)
+        return LOMO_ERR_SHAPE;
+    if (B == 0 || s == 0 || n_heads == 0) return LOMO_OK;
+    if (!qkv || !o || !dO || !lse || !delta_ws || !dqkv) return LOMO_ERR_NULL;
+    if ((rope_cos == nullptr) != (rope_sin == nullptr)) return LOMO_ERR_NULL;
+    if (misaligned(qkv) || misaligned(o) || misaligned(dO) || misaligned(dqkv) || (reinterpret_cast<uintptr_t>(lse) & 3u) ||
+        (reinterpret_cast<uintptr_t>(delta_ws) & 3u) || (reinterpret_cast<uintptr_t>(rope_cos) & 3u) ||
+        (reinterpret_cast<uintptr_t>(rope_sin) & 3u))
+        return LOMO_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ScopedTiming timing(LOMO_KERNEL_ATTENTION, st);
+    return from_hip(launch_attention_backward(qkv, o, dO, lse, rope_cos, rope_sin, delta_ws, dqkv, B, s, n_heads, st));
+}
+
 lomo_status lomo_set_norm_algorithm(int algorithm) {
     if (algorithm != LOMO_NORM_DIRECT && algorithm != LOMO_NORM_AUTO && algorithm != LOMO_NORM_GRAM) return LOMO_ERR_SHAPE;
     set_norm_algorithm(algorithm);

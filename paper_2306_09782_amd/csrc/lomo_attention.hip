@@ -1,0 +1,316 @@
+// Backward of causal softmax attention with the rotary step, for the hand-on gradient of Algorithm 1
+// (paper section 3.2) through the self-attention block of a LLaMA layer (the models of section 4), gfx950.
+//
+// Tokens t = b * s + pos; head n owns columns [128 n, 128 n + 128) of q, k, v, o.  qkv holds the rotated
+// q and k and v side by side ([T x 3H]); lse[t][n] = log sum_j exp(S_tj) is saved by the forward pass.
+//
+//   P_ij = exp(q_i . k_j / sqrt(d) - lse_i)  (j <= i),   dP_ij = do_i . v_j,   delta_i = do_i . o_i
+//   dS = P (dP - delta) / sqrt(d);   dv_j = sum_i P_ij do_i;   dk_j = sum_i dS_ij q_i;   dq_i = sum_j dS_ij k_j
+//   then the rotary step backwards (rotation by the negative angle) on dq and dk.
+//
+// fp16 storage, fp32 accumulation on the MFMA units; P and dS pass through fp16 before the products that
+// consume them (fp16 training holds them as fp16 tensors); dq, dk, dv are rounded once, after the rotation.
+//
+// Two deterministic kernels, no atomics: one workgroup per (sequence, head, block of 64 keys) walks the query
+// blocks at or below it and accumulates dk, dv; one per (sequence, head, block of 64 queries) walks the key
+// blocks up to it and accumulates dq.  Both recompute S, P, dP, dS per 64 x 64 block (32x32x16 MFMA, four
+// waves in 2 x 2); the loop operand of the next block is fetched into registers while the current one is
+// multiplied.  Transposed operands come from LDS through ds_read_b64_tr_b16.
+#include "lomo_gemm_common.h"
+
+namespace lomo {
+
+typedef short short4a __attribute__((ext_vector_type(4)));
+
+namespace attn {
+
+constexpr int D = 128;        // head width
+constexpr int BLK = 64;       // queries / keys per block
+constexpr int PD = D + 8;     // LDS pitch of a [64 x 128] fp16 tile (halves)
+constexpr int PS = BLK + 8;   // LDS pitch of a [64 x 64] fp16 tile
+constexpr int PO = D + 4;     // LDS pitch of the fp32 output tile (floats)
+constexpr int TILE = BLK * PD;
+constexpr int LDS_BYTES = 4 * TILE * 2 + 2 * BLK * PS * 2 + 2 * BLK * 4;
+
+struct Args {
+    const uint16_t* qkv;   // [T x 3H]
+    const uint16_t* o;     // [T x H]
+    const uint16_t* dO;    // [T x H]
+    const float* lse;      // [T x nh]
+    const float* delta;    // [T x nh]
+    const float* cosv;     // [s x 64] or null
+    const float* sinv;
+    uint16_t* dqkv;        // [T x 3H]
+    int s, nh, H;
+};
+
+__device__ __forceinline__ half8 read_tr8(const uint16_t* p0, const uint16_t* p1) {
+    typedef __attribute__((address_space(3))) short4a* lds_p;
+    const short4a lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p0));
+    const short4a hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p1));
+    return __builtin_bit_cast(half8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// A [64 x 128] fp16 tile: thread tid owns the 16-byte chunks tid, tid + 256, tid + 512, tid + 768
+// (row = chunk / 16, column = 8 * (chunk % 16)).
+__device__ __forceinline__ void fetch_tile(u32x4 (&r)[4], const uint16_t* g, int64_t ld) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int c = threadIdx.x + 256 * u;
+        r[u] = *reinterpret_cast<const u32x4*>(g + (int64_t)(c >> 4) * ld + (c & 15) * 8);
+    }
+}
+__device__ __forceinline__ void stash_tile(const u32x4 (&r)[4], uint16_t* s) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int c = threadIdx.x + 256 * u;
+        *reinterpret_cast<u32x4*>(s + (c >> 4) * PD + (c & 15) * 8) = r[u];
+    }
+}
+
+}  // namespace attn
+
+// delta[t][n] = sum_c dO[t][128 n + c] * o[t][128 n + c]: sixteen lanes per (token, head), eight columns each.
+__global__ __launch_bounds__(256) void attention_delta_kernel(const uint16_t* __restrict__ o, const uint16_t* __restrict__ dO,
+                                                              float* __restrict__ delta, int64_t rows) {
+    const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);     // row = t * nh + n
+    const int part = threadIdx.x & 15;
+    float sum = 0.f;
+    if (row < rows) {
+        const half8 a = *reinterpret_cast<const half8*>(o + row * attn::D + part * 8);
+        const half8 b = *reinterpret_cast<const half8*>(dO + row * attn::D + part * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sum = fmaf((float)a[e], (float)b[e], sum);
+    }
+#pragma unroll
+    for (int off = 8; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
+    if (row < rows && part == 0) delta[row] = sum;
+}
+
+// MODE 0: workgroup = (key block j, head, sequence): dk, dv.  MODE 1: workgroup = (query block i, head, sequence): dq.
+template <int MODE>
+__global__ __launch_bounds__(256) void attention_backward_kernel(attn::Args a) {
+    using namespace attn;
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    uint16_t* sQ = smem;
+    uint16_t* sDO = sQ + TILE;
+    uint16_t* sK = sDO + TILE;
+    uint16_t* sV = sK + TILE;
+    uint16_t* sP = sV + TILE;
+    uint16_t* sDS = sP + BLK * PS;
+    float* sL = reinterpret_cast<float*>(sDS + BLK * PS);
+    float* sDelta = sL + BLK;
+    float* sOut = reinterpret_cast<float*>(smem);     // [64 x PO] fp32, after the loop (over sQ and sDO)
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wr = wave & 1, wc = wave >> 1;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int g4 = lane >> 4, j16 = lane & 15;
+    const int mhalf = g4 & 1, kh = g4 >> 1, rib = j16 >> 2, piece = j16 & 3;
+    const int tr_row = 8 * kh + rib, tr_col = 16 * mhalf + 4 * piece;
+
+    const int nb = a.s / BLK;
+    const int n = blockIdx.y, b = blockIdx.z;
+    const int fixed = (MODE == 0) ? (int)blockIdx.x : nb - 1 - (int)blockIdx.x;   // heaviest blocks first
+    const int64_t ld3 = 3 * (int64_t)a.H, ldh = a.H;
+    const int64_t t0 = (int64_t)b * a.s;
+    const uint16_t* gq = a.qkv + (int64_t)n * D;
+    const uint16_t* gk = gq + a.H;
+    const uint16_t* gv = gk + a.H;
+    const uint16_t* gdo = a.dO + (int64_t)n * D;
+    const float scale = 0.08838834764831845f;     // 1 / sqrt(128)
+
+    // the operand that stays: K_j, V_j (MODE 0) or Q_i, dO_i with lse and delta (MODE 1)
+    u32x4 r0[4], r1[4];
+    if (MODE == 0) {
+        fetch_tile(r0, gk + (t0 + (int64_t)fixed * BLK) * ld3, ld3);
+        fetch_tile(r1, gv + (t0 + (int64_t)fixed * BLK) * ld3, ld3);
+        stash_tile(r0, sK);
+        stash_tile(r1, sV);
+    } else {
+        fetch_tile(r0, gq + (t0 + (int64_t)fixed * BLK) * ld3, ld3);
+        fetch_tile(r1, gdo + (t0 + (int64_t)fixed * BLK) * ldh, ldh);
+        stash_tile(r0, sQ);
+        stash_tile(r1, sDO);
+        if (tid < BLK) {
+            sL[tid] = a.lse[(t0 + (int64_t)fixed * BLK + tid) * a.nh + n];
+            sDelta[tid] = a.delta[(t0 + (int64_t)fixed * BLK + tid) * a.nh + n];
+        }
+    }
+
+    floatx16 acc0[2], acc1[2];     // MODE 0: dv, dk;  MODE 1: dq (acc1 unused)
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            acc0[i][r] = 0.f;
+            acc1[i][r] = 0.f;
+        }
+
+    const int first = (MODE == 0) ? fixed : 0;
+    const int last = (MODE == 0) ? nb - 1 : fixed;
+    float rl = 0.f, rd = 0.f;
+    auto fetch_moving = [&](int blk) {
+        const int64_t row0 = t0 + (int64_t)blk * BLK;
+        if (MODE == 0) {
+            fetch_tile(r0, gq + row0 * ld3, ld3);
+            fetch_tile(r1, gdo + row0 * ldh, ldh);
+            if (tid < BLK) {
+                rl = a.lse[(row0 + tid) * a.nh + n];
+                rd = a.delta[(row0 + tid) * a.nh + n];
+            }
+        } else {
+            fetch_tile(r0, gk + row0 * ld3, ld3);
+            fetch_tile(r1, gv + row0 * ld3, ld3);
+        }
+    };
+    fetch_moving(first);
+
+    for (int blk = first; blk <= last; ++blk) {
+        __syncthreads();     // everybody is done with the tiles of the previous block
+        if (MODE == 0) {
+            stash_tile(r0, sQ);
+            stash_tile(r1, sDO);
+            if (tid < BLK) {
+                sL[tid] = rl;
+                sDelta[tid] = rd;
+            }
+        } else {
+            stash_tile(r0, sK);
+            stash_tile(r1, sV);
+        }
+        __syncthreads();
+        if (blk < last) fetch_moving(blk + 1);     // in flight while this block is multiplied
+
+        // ---- S = Q K^T and dP = dO V^T for this wave's 32 queries x 32 keys
+        floatx16 accS, accP;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            accS[r] = 0.f;
+            accP[r] = 0.f;
+        }
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) {
+            const int off = 16 * ks + 8 * lh;
+            const half8 aq = *reinterpret_cast<const half8*>(sQ + (32 * wr + l32) * PD + off);
+            const half8 bk = *reinterpret_cast<const half8*>(sK + (32 * wc + l32) * PD + off);
+            accS = __builtin_amdgcn_mfma_f32_32x32x16_f16(aq, bk, accS, 0, 0, 0);
+            const half8 ad = *reinterpret_cast<const half8*>(sDO + (32 * wr + l32) * PD + off);
+            const half8 bv = *reinterpret_cast<const half8*>(sV + (32 * wc + l32) * PD + off);
+            accP = __builtin_amdgcn_mfma_f32_32x32x16_f16(ad, bv, accP, 0, 0, 0);
+        }
+        // ---- P and dS in fp16, [query][key]
+        const bool diag = (MODE == 0) ? (blk == fixed) : (blk == fixed);
+        const int key = 32 * wc + l32;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int qrow = 32 * wr + 8 * (r >> 2) + 4 * lh + (r & 3);
+            float p = expf(fmaf(scale, accS[r], -sL[qrow]));
+            float ds = scale * p * (accP[r] - sDelta[qrow]);
+            if (diag && key > qrow) {
+                p = 0.f;
+                ds = 0.f;
+            }
+            reinterpret_cast<_Float16*>(sP)[qrow * PS + key] = (_Float16)p;
+            reinterpret_cast<_Float16*>(sDS)[qrow * PS + key] = (_Float16)ds;
+        }
+        __syncthreads();
+
+        if (MODE == 0) {
+            // dv^T[dcol][key] += dO^T P,  dk^T[dcol][key] += Q^T dS   (contraction over the 64 queries)
+#pragma unroll
+            for (int ks = 0; ks < BLK / 16; ++ks) {
+                const uint16_t* pp = sP + (16 * ks + tr_row) * PS + 32 * wc + tr_col;
+                const uint16_t* pd = sDS + (16 * ks + tr_row) * PS + 32 * wc + tr_col;
+                const half8 bP = read_tr8(pp, pp + 4 * PS);
+                const half8 bD = read_tr8(pd, pd + 4 * PS);
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const uint16_t* po = sDO + (16 * ks + tr_row) * PD + 64 * wr + 32 * i + tr_col;
+                    const uint16_t* pq = sQ + (16 * ks + tr_row) * PD + 64 * wr + 32 * i + tr_col;
+                    acc0[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(read_tr8(po, po + 4 * PD), bP, acc0[i], 0, 0, 0);
+                    acc1[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(read_tr8(pq, pq + 4 * PD), bD, acc1[i], 0, 0, 0);
+                }
+            }
+        } else {
+            // dq^T[dcol][query] += K^T dS^T   (contraction over the 64 keys)
+#pragma unroll
+            for (int ks = 0; ks < BLK / 16; ++ks) {
+                const half8 bD = *reinterpret_cast<const half8*>(sDS + (32 * wc + l32) * PS + 16 * ks + 8 * lh);
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const uint16_t* pk = sK + (16 * ks + tr_row) * PD + 64 * wr + 32 * i + tr_col;
+                    acc0[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(read_tr8(pk, pk + 4 * PD), bD, acc0[i], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    // ---- results: through LDS as fp32 so that the rotary pairs (c, c + 64) meet and stores are 16 bytes wide
+    const int64_t orow0 = t0 + (int64_t)fixed * BLK;
+    auto emit = [&](floatx16 (&acc)[2], int64_t colbase, bool rotate) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                sOut[(32 * wc + l32) * PO + 64 * wr + 32 * i + 8 * (r >> 2) + 4 * lh + (r & 3)] = acc[i][r];
+        __syncthreads();
+        // thread: row = tid / 4, sixteen pairs (c, c + 64) with c = 16 * (tid % 4) ...
+        const int row = tid >> 2, c0 = 16 * (tid & 3);
+        const float* src = sOut + row * PO;
+        const int pos = fixed * BLK + row;
+        half8 lo[2], hi[2];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const float x1 = src[c0 + e], x2 = src[c0 + e + 64];
+            float y1 = x1, y2 = x2;
+            if (rotate) {
+                const float co = a.cosv[pos * 64 + c0 + e], si = a.sinv[pos * 64 + c0 + e];
+                y1 = fmaf(x2, si, x1 * co);
+                y2 = fmaf(-x1, si, x2 * co);
+            }
+            lo[e >> 3][e & 7] = (_Float16)y1;
+            hi[e >> 3][e & 7] = (_Float16)y2;
+        }
+        uint16_t* dst = a.dqkv + (orow0 + row) * ld3 + colbase + (int64_t)n * D + c0;
+        *reinterpret_cast<half8*>(dst) = lo[0];
+        *reinterpret_cast<half8*>(dst + 8) = lo[1];
+        *reinterpret_cast<half8*>(dst + 64) = hi[0];
+        *reinterpret_cast<half8*>(dst + 72) = hi[1];
+    };
+    const bool rot = a.cosv != nullptr;
+    if (MODE == 0) {
+        emit(acc0, 2 * (int64_t)a.H, false);    // dv
+        emit(acc1, (int64_t)a.H, rot);          // dk
+    } else {
+        emit(acc0, 0, rot);                     // dq
+    }
+}
+
+hipError_t launch_attention_backward(const uint16_t* qkv, const uint16_t* o, const uint16_t* dO, const float* lse,
+                                     const float* cosv, const float* sinv, float* delta, uint16_t* dqkv, int64_t B, int64_t s,
+                                     int64_t nh, hipStream_t st) {
+    using namespace attn;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attention_backward_kernel<0>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(attention_backward_kernel<1>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int64_t rows = B * s * nh;
+    hipLaunchKernelGGL(attention_delta_kernel, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, o, dO, delta, rows);
+    Args a;
+    a.qkv = qkv; a.o = o; a.dO = dO; a.lse = lse; a.delta = delta; a.cosv = cosv; a.sinv = sinv; a.dqkv = dqkv;
+    a.s = (int)s; a.nh = (int)nh; a.H = (int)(nh * D);
+    const dim3 grid((unsigned)(s / BLK), (unsigned)nh, (unsigned)B);
+    hipLaunchKernelGGL(attention_backward_kernel<0>, grid, dim3(256), LDS_BYTES, st, a);
+    hipLaunchKernelGGL(attention_backward_kernel<1>, grid, dim3(256), LDS_BYTES, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace lomo

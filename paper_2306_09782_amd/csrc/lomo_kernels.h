@@ -128,6 +128,11 @@ hipError_t launch_swiglu_backward(const uint16_t* da, const uint16_t* gate_up, u
 hipError_t launch_rmsnorm_backward(const uint16_t* dxn, const uint16_t* xhat, const float* rstd, const uint16_t* gain,
                                    const uint16_t* dres, uint16_t* dh, int64_t T, int64_t H, hipStream_t st);
 
+// Causal attention backward with the rotary step (lomo_attention.hip): head width 128, s % 64 == 0.
+hipError_t launch_attention_backward(const uint16_t* qkv, const uint16_t* o, const uint16_t* dO, const float* lse,
+                                     const float* cosv, const float* sinv, float* delta, uint16_t* dqkv, int64_t B, int64_t s,
+                                     int64_t nh, hipStream_t st);
+
 hipError_t launch_reduce_flags(const int32_t* flags, int64_t n, int32_t* out, hipStream_t st);
 
 }  // namespace lomo
