@@ -155,6 +155,37 @@ def attention_backward(qkv, o, do, lse, s: int, n_heads: int, round_probabilitie
     return out.reshape(T, 3 * H)
 
 
+def attention_rounding_sensitivity(qkv, o, do, lse, s: int, n_heads: int) -> np.ndarray:
+    """How far one fp16 ulp of a single entry of P or dS can move each element of [dq | dk | dv] (after the
+    rotary step, where a pair shares its two bounds): 2^-11 * max_j |dS_ij| * max_j |k_jc| for dq, and likewise
+    for dk and dv.  The probabilities are recomputed in fp32 by an implementation and in fp64 here, so an entry
+    that sits on a rounding boundary may legitimately round either way; tests allow two such flips."""
+    T, H3 = qkv.shape
+    H = H3 // 3
+    d = H // n_heads
+    q, k, v = (_heads(O.as_f64(qkv[:, i * H:(i + 1) * H]), n_heads) for i in range(3))
+    oh, doh = _heads(O.as_f64(o), n_heads), _heads(O.as_f64(do), n_heads)
+    out = np.zeros((T, 3, n_heads, d))
+    with np.errstate(invalid="ignore", over="ignore"):
+        for b in range(T // s):
+            sl = slice(b * s, (b + 1) * s)
+            for n in range(n_heads):
+                S = _scores(q[sl, n], k[sl, n], d)
+                P = np.exp(S - np.asarray(lse[sl, n], dtype=np.float64)[:, None])
+                dP = doh[sl, n] @ v[sl, n].T
+                delta = (doh[sl, n] * oh[sl, n]).sum(axis=1, keepdims=True)
+                dS = np.abs(np.where(P > 0, P * (dP - delta), 0.0)) / math.sqrt(d)
+                out[sl, 0, n] = dS.max(axis=1)[:, None] * np.abs(k[sl, n]).max(axis=0)[None, :]
+                out[sl, 1, n] = dS.max(axis=0)[:, None] * np.abs(q[sl, n]).max(axis=0)[None, :]
+                out[sl, 2, n] = P.max(axis=0)[:, None] * np.abs(doh[sl, n]).max(axis=0)[None, :]
+    # the rotary step mixes columns c and c + d/2 with weights of magnitude <= 1
+    for part in (0, 1):
+        pair = out[:, part, :, : d // 2] + out[:, part, :, d // 2:]
+        out[:, part, :, : d // 2] = pair
+        out[:, part, :, d // 2:] = pair
+    return 2.0 ** -11 * out.reshape(T, 3 * H)
+
+
 def attention_rope_backward(qkv, o, do, lse, cos, sin, s: int, n_heads: int) -> np.ndarray:
     """[dq | dk | dv] as stored (fp16): attention backward, rotary backward on the q and k parts, one rounding."""
     T, H3 = qkv.shape
@@ -190,7 +221,8 @@ def block_forward_stored(h, w, W_qkv, W_o, cos, sin, s: int, n_heads: int, eps: 
     k = O.round_f16(rope_rotate(qkv[:, H:2 * H], cos, sin, s, n_heads))
     qkv_rot = np.concatenate((q, k, qkv[:, 2 * H:]), axis=1)
     att = attention_forward_stored(qkv_rot, s, n_heads)
-    return {"xhat": xhat, "r": r64.astype(np.float32), "xn": xn, "qkv": qkv_rot, "o": att["o"], "lse": att["lse"]}
+    y = O.round_f16(O.as_f64(h) + O.as_f64(att["o"]) @ O.as_f64(W_o).T)
+    return {"xhat": xhat, "r": r64.astype(np.float32), "xn": xn, "qkv": qkv_rot, "o": att["o"], "lse": att["lse"], "y": y}
 
 
 def chain_gradients(dy, saved: Dict, w, W_qkv, W_o, cos, sin, s: int, n_heads: int) -> Dict:
@@ -223,3 +255,42 @@ def block_step(dy, saved: Dict, w, W_qkv, W_o, cos, sin, s: int, n_heads: int, l
     return {"W_o": new[0], "W_qkv": new[1], "w": new[2], "dh": c["dh"], "do": c["do"], "dqkv": c["dqkv"],
             "dxn": c["dxn"], "flags": flags, "sqnorms": sq, "overflow": overflow, "total_sqnorm": total,
             "norm": norm, "clip_coef": coef}
+
+
+# --------------------------------------------------------------------------- the whole decoder layer
+
+
+def layer_forward_f64(h, p: Dict, cos, sin, s: int, n_heads: int, eps: float) -> np.ndarray:
+    """Output of the decoder layer (attention block, then feed-forward block) in plain fp64."""
+    y1 = block_forward_f64(h, p["w1"], p["W_qkv"], p["W_o"], cos, sin, s, n_heads, eps)
+    return M.block_forward_f64(y1, p["w2"], p["W_gu"], p["W_d"], eps)
+
+
+def layer_forward_stored(h, p: Dict, cos, sin, s: int, n_heads: int, eps: float):
+    """Saved activations of both blocks; the feed-forward block reads the stored (fp16) attention-block output."""
+    sa = block_forward_stored(h, p["w1"], p["W_qkv"], p["W_o"], cos, sin, s, n_heads, eps)
+    sm = M.block_forward_stored(sa["y"], p["w2"], p["W_gu"], p["W_d"], eps)
+    return sa, sm
+
+
+LAYER_ORDER = ("W_d", "W_gu", "w2", "W_o", "W_qkv", "w1")      # backward order of the six parameters
+
+
+def layer_step(dy, saved_attn: Dict, saved_mlp: Dict, p: Dict, cos, sin, s: int, n_heads: int, lr: float,
+               loss_scale: float, max_norm: float = 1.0, eps_clip: float = 1e-6) -> Dict:
+    """Two-pass LOMO step over one decoder layer: the walk of Algorithm 1 goes through the feed-forward block,
+    hands its input gradient to the attention block, and one global norm over the six parameters sets the
+    clipping coefficient (section 3.3.1)."""
+    cm = M.chain_gradients(dy, saved_mlp, p["w2"], p["W_gu"], p["W_d"])
+    ca = chain_gradients(cm["dh"], saved_attn, p["w1"], p["W_qkv"], p["W_o"], cos, sin, s, n_heads)
+    grads = [cm["G_d"], cm["G_gu"], cm["g_w"], ca["G_o"], ca["G_qkv"], ca["g_w"]]
+    flags = [O.has_overflow(g) for g in grads]
+    sq = [O.sqnorm(g) for g in grads]
+    overflow = any(flags)
+    total = math.fsum(sq) if not overflow else float("nan")
+    norm = O.grad_norm(total, loss_scale) if not overflow else float("nan")
+    coef = O.clip_coef(norm, max_norm, eps_clip) if not overflow else float("nan")
+    new = {k: (np.array(p[k], copy=True) if overflow else O.sgd_update(p[k], g, lr, coef, loss_scale))
+           for k, g in zip(LAYER_ORDER, grads)}
+    return {"params": new, "dh": ca["dh"], "dh_mid": cm["dh"], "mlp": cm, "attn": ca, "flags": flags, "sqnorms": sq,
+            "overflow": overflow, "total_sqnorm": total, "norm": norm, "clip_coef": coef}

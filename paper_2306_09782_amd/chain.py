@@ -1,11 +1,15 @@
-"""LOMO's backward loop through one LLaMA feed-forward block: sequencing of C-ABI calls only.
+"""LOMO's backward loop through a LLaMA decoder layer: sequencing of C-ABI calls only (no arithmetic).
 
-Algorithm 1 of the paper, with the two passes of section 3.3, over the block's parameters in backward
-order (W_d, fused W_gu, RMSNorm gain w).  Each pass walks the chain from the block's output gradient dy
-down to the gradient of its input: the dX of one linear tensor is the dY of the next.  Pass 1 only
-accumulates squared norms and overflow flags; the coefficient is formed on the device; pass 2 walks
-the chain again (the hand-on gradients are not kept between the passes) and updates every parameter
-right after the gradient of its input has been taken from the old value.  No host wait anywhere.
+Algorithm 1 of the paper with the two passes of section 3.3.  Each pass walks the chain from the layer's
+output gradient dy down to the gradient of its input: the dX of one linear tensor, passed through the
+element-wise / attention backward kernels, is the dY of the next.  Pass 1 only accumulates squared norms
+and overflow flags; the coefficient is formed on the device; pass 2 walks the chain again (the hand-on
+gradients are not kept between the passes) and updates every parameter right after the gradient of its
+input has been taken from the old value.  Nothing waits on the host.
+
+  feed-forward block:  dy -> W_d -> SwiGLU backward -> fused W_gu -> gain w -> RMSNorm backward (+ dy) -> dh
+  attention block:     dy -> W_o -> attention + rotary backward -> fused W_qkv -> gain w -> RMSNorm backward (+ dy) -> dh
+  decoder layer:       feed-forward block, then the attention block on its dh; one norm over all six parameters
 """
 from __future__ import annotations
 
@@ -16,55 +20,30 @@ import torch
 from . import binding as B
 
 
-class LomoMlpBlock:
-    """Scratch for the hand-on gradients of one block (da [T x F], [dgate|dup] [T x 2F], dxn [T x H]) plus
-    the step state (accumulator, flags, workspace, scalars).  `saved` holds the forward activations the
-    backward needs: a [T x F], xn and xhat [T x H], rstd [T] fp32, gate_up [T x 2F]."""
+class StepState:
+    """Accumulator, per-parameter flags (+ the step flag), workspace and scalars of one chained step."""
 
-    def __init__(self, device, T: int, H: int, F: int):
-        self.device = torch.device(device)
-        f16 = dict(dtype=torch.float16, device=self.device)
-        self.da = torch.empty(T, F, **f16)
-        self.dgu = torch.empty(T, 2 * F, **f16)
-        self.dxn = torch.empty(T, H, **f16)
-        self.acc = torch.zeros(1, dtype=torch.float64, device=self.device)
-        self.flags = torch.zeros(4, dtype=torch.int32, device=self.device)     # W_d, W_gu, w, any
-        self.ws = torch.empty(max(B.lomo_vector_workspace_bytes(T, H), 256), dtype=torch.uint8, device=self.device)
-        self.scalars = torch.zeros(32, dtype=torch.uint8, device=self.device)
+    def __init__(self, device, n_params: int, T: int, H: int):
+        self.n = n_params
+        self.acc = torch.zeros(1, dtype=torch.float64, device=device)
+        self.flags = torch.zeros(n_params + 1, dtype=torch.int32, device=device)
+        self.ws = torch.empty(max(B.lomo_vector_workspace_bytes(T, H), 256), dtype=torch.uint8, device=device)
+        self.scalars = torch.zeros(32, dtype=torch.uint8, device=device)
         self._scalars_host = torch.zeros(32, dtype=torch.uint8).pin_memory()
-        self._lists = None
 
-    def _tensor_lists(self, dy, saved, w, W_gu, W_d):
-        key = tuple(t.data_ptr() for t in (dy, saved["a"], saved["xn"], saved["xhat"], w, W_gu, W_d))
-        if self._lists is None or self._lists[0] != key:
-            down = B.make_tensor_list([{"kind": "linear", "X": saved["a"], "dY": dy, "W": W_d, "dX": self.da}])
-            gu = B.make_tensor_list([{"kind": "linear", "X": saved["xn"], "dY": self.dgu, "W": W_gu, "dX": self.dxn}])
-            gain = B.make_tensor_list([{"kind": "vector", "X": saved["xhat"], "dY": self.dxn, "W": w}])
-            self._lists = (key, down, gu, gain)
-        return self._lists[1:]
+    @property
+    def step_flag(self):
+        return self.flags[self.n:self.n + 1]
 
-    def step(self, dy, saved: Dict, w, W_gu, W_d, dh, lr: float, loss_scale: float, max_norm: float = 1.0,
-             eps: float = 1e-6, stream=None) -> None:
-        """Queues the whole two-pass step; dh receives the gradient of the block input (residual included)."""
-        down, gu, gain = self._tensor_lists(dy, saved, w, W_gu, W_d)
-        f = self.flags
+    def begin(self):
         self.acc.zero_()
-        f.zero_()
-        # ---- pass 1: walk the chain, keep only norms and flags
-        B.lomo_linear_dgrad(dy, W_d, self.da, stream)
-        B.lomo_wgrad_sqnorm(saved["a"], dy, self.acc, f[0:1], stream)
-        B.lomo_swiglu_backward(self.da, saved["gate_up"], self.dgu, stream)
-        B.lomo_linear_dgrad(self.dgu, W_gu, self.dxn, stream)
-        B.lomo_wgrad_sqnorm(saved["xn"], self.dgu, self.acc, f[1:2], stream)
-        B.lomo_vector_sqnorm(saved["xhat"], self.dxn, self.ws, self.acc, f[2:3], stream)
-        B.lomo_reduce_flags(f[0:3], f[3:4], stream)
-        B.lomo_step_scalars_device(self.acc, f[3:4], loss_scale, max_norm, eps, lr, self.scalars, stream)
-        # ---- pass 2: walk it again; every parameter is updated right after its input gradient is taken
-        B.lomo_step_update_pass_device(down, self.scalars, f[3:4], self.ws, stream)       # da, then W_d
-        B.lomo_swiglu_backward(self.da, saved["gate_up"], self.dgu, stream)
-        B.lomo_step_update_pass_device(gu, self.scalars, f[3:4], self.ws, stream)         # dxn, then W_gu
-        B.lomo_rmsnorm_backward(self.dxn, saved["xhat"], saved["rstd"], w, dy, dh, stream)  # old gain
-        B.lomo_step_update_pass_device(gain, self.scalars, f[3:4], self.ws, stream)       # then the gain
+        self.flags.zero_()
+
+    def coefficient(self, lr, loss_scale, max_norm, eps, stream):
+        B.lomo_reduce_flags(self.flags[:self.n], self.step_flag, stream)
+        B.lomo_step_scalars_device(self.acc, self.step_flag, loss_scale, max_norm, eps, lr, self.scalars, stream)
+
+    def finish(self, stream):
         if stream is None:
             self._scalars_host.copy_(self.scalars, non_blocking=True)
         else:
@@ -76,5 +55,142 @@ class LomoMlpBlock:
         out = B.unpack_step_scalars(self._scalars_host)
         host = torch.cat([self.acc.view(torch.int32), self.flags]).cpu()
         out["total_sqnorm"] = float(host[:2].view(torch.float64)[0])
-        out["flags"] = [bool(v) for v in host[2:5].tolist()]
+        out["flags"] = [bool(v) for v in host[2:2 + self.n].tolist()]
         return out
+
+
+def _linear(state: StepState, slot: int, X, dY, W, dX, tensor_list, update: bool, stream):
+    """One linear tensor of the walk: hand-on gradient from the old W, then norm (pass 1) or fused update (pass 2)."""
+    if update:
+        B.lomo_step_update_pass_device(tensor_list, state.scalars, state.step_flag, state.ws, stream)
+    else:
+        B.lomo_linear_dgrad(dY, W, dX, stream)
+        B.lomo_wgrad_sqnorm(X, dY, state.acc, state.flags[slot:slot + 1], stream)
+
+
+def _gain(state: StepState, slot: int, xhat, dxn, w, tensor_list, update: bool, stream):
+    if update:
+        B.lomo_step_update_pass_device(tensor_list, state.scalars, state.step_flag, state.ws, stream)
+    else:
+        B.lomo_vector_sqnorm(xhat, dxn, state.ws, state.acc, state.flags[slot:slot + 1], stream)
+
+
+class LomoMlpBlock:
+    """Hand-on buffers of the feed-forward block: da [T x F], [dgate|dup] [T x 2F], dxn [T x H].
+    `saved`: a [T x F], xn and xhat [T x H], rstd [T] fp32, gate_up [T x 2F]."""
+
+    def __init__(self, device, T: int, H: int, F: int, state: StepState = None, slot0: int = 0):
+        self.device = torch.device(device)
+        f16 = dict(dtype=torch.float16, device=self.device)
+        self.da = torch.empty(T, F, **f16)
+        self.dgu = torch.empty(T, 2 * F, **f16)
+        self.dxn = torch.empty(T, H, **f16)
+        self.state = state if state is not None else StepState(self.device, 3, T, H)
+        self.slot0 = slot0
+        self._lists = None
+
+    def _tensor_lists(self, dy, saved, w, W_gu, W_d):
+        key = tuple(t.data_ptr() for t in (dy, saved["a"], saved["xn"], saved["xhat"], w, W_gu, W_d))
+        if self._lists is None or self._lists[0] != key:
+            down = B.make_tensor_list([{"kind": "linear", "X": saved["a"], "dY": dy, "W": W_d, "dX": self.da}])
+            gu = B.make_tensor_list([{"kind": "linear", "X": saved["xn"], "dY": self.dgu, "W": W_gu, "dX": self.dxn}])
+            gain = B.make_tensor_list([{"kind": "vector", "X": saved["xhat"], "dY": self.dxn, "W": w}])
+            self._lists = (key, down, gu, gain)
+        return self._lists[1:]
+
+    def walk(self, dy, saved: Dict, w, W_gu, W_d, dh, update: bool, stream=None):
+        down, gu, gain = self._tensor_lists(dy, saved, w, W_gu, W_d)
+        st, k = self.state, self.slot0
+        _linear(st, k, saved["a"], dy, W_d, self.da, down, update, stream)
+        B.lomo_swiglu_backward(self.da, saved["gate_up"], self.dgu, stream)
+        _linear(st, k + 1, saved["xn"], self.dgu, W_gu, self.dxn, gu, update, stream)
+        B.lomo_rmsnorm_backward(self.dxn, saved["xhat"], saved["rstd"], w, dy, dh, stream)     # old gain
+        _gain(st, k + 2, saved["xhat"], self.dxn, w, gain, update, stream)
+
+    def step(self, dy, saved: Dict, w, W_gu, W_d, dh, lr: float, loss_scale: float, max_norm: float = 1.0,
+             eps: float = 1e-6, stream=None) -> None:
+        """Queues the whole two-pass step of this block alone; dh receives the gradient of the block input."""
+        self.state.begin()
+        self.walk(dy, saved, w, W_gu, W_d, dh, False, stream)
+        self.state.coefficient(lr, loss_scale, max_norm, eps, stream)
+        self.walk(dy, saved, w, W_gu, W_d, dh, True, stream)
+        self.state.finish(stream)
+
+    def result(self) -> Dict:
+        return self.state.result()
+
+
+class LomoAttentionBlock:
+    """Hand-on buffers of the attention block: do [T x H], [dq|dk|dv] [T x 3H], dxn [T x H], delta [T x heads].
+    `saved`: o, xn, xhat [T x H], rstd [T] fp32, qkv [T x 3H] (rotated q and k, v), lse [T x heads] fp32."""
+
+    def __init__(self, device, batch: int, seq: int, H: int, n_heads: int, state: StepState = None, slot0: int = 0):
+        self.device = torch.device(device)
+        T = batch * seq
+        self.batch, self.seq, self.n_heads = batch, seq, n_heads
+        f16 = dict(dtype=torch.float16, device=self.device)
+        self.do = torch.empty(T, H, **f16)
+        self.dqkv = torch.empty(T, 3 * H, **f16)
+        self.dxn = torch.empty(T, H, **f16)
+        self.delta = torch.empty(T * n_heads, dtype=torch.float32, device=self.device)
+        self.state = state if state is not None else StepState(self.device, 3, T, H)
+        self.slot0 = slot0
+        self._lists = None
+
+    def _tensor_lists(self, dy, saved, w, W_qkv, W_o):
+        key = tuple(t.data_ptr() for t in (dy, saved["o"], saved["xn"], saved["xhat"], w, W_qkv, W_o))
+        if self._lists is None or self._lists[0] != key:
+            out = B.make_tensor_list([{"kind": "linear", "X": saved["o"], "dY": dy, "W": W_o, "dX": self.do}])
+            qkv = B.make_tensor_list([{"kind": "linear", "X": saved["xn"], "dY": self.dqkv, "W": W_qkv, "dX": self.dxn}])
+            gain = B.make_tensor_list([{"kind": "vector", "X": saved["xhat"], "dY": self.dxn, "W": w}])
+            self._lists = (key, out, qkv, gain)
+        return self._lists[1:]
+
+    def walk(self, dy, saved: Dict, w, W_qkv, W_o, rope_cos, rope_sin, dh, update: bool, stream=None):
+        out, qkv, gain = self._tensor_lists(dy, saved, w, W_qkv, W_o)
+        st, k = self.state, self.slot0
+        _linear(st, k, saved["o"], dy, W_o, self.do, out, update, stream)
+        B.lomo_attention_backward(saved["qkv"], saved["o"], self.do, saved["lse"], rope_cos, rope_sin, self.delta,
+                                  self.dqkv, self.batch, self.seq, self.n_heads, stream)
+        _linear(st, k + 1, saved["xn"], self.dqkv, W_qkv, self.dxn, qkv, update, stream)
+        B.lomo_rmsnorm_backward(self.dxn, saved["xhat"], saved["rstd"], w, dy, dh, stream)
+        _gain(st, k + 2, saved["xhat"], self.dxn, w, gain, update, stream)
+
+    def step(self, dy, saved: Dict, w, W_qkv, W_o, rope_cos, rope_sin, dh, lr: float, loss_scale: float,
+             max_norm: float = 1.0, eps: float = 1e-6, stream=None) -> None:
+        self.state.begin()
+        self.walk(dy, saved, w, W_qkv, W_o, rope_cos, rope_sin, dh, False, stream)
+        self.state.coefficient(lr, loss_scale, max_norm, eps, stream)
+        self.walk(dy, saved, w, W_qkv, W_o, rope_cos, rope_sin, dh, True, stream)
+        self.state.finish(stream)
+
+    def result(self) -> Dict:
+        return self.state.result()
+
+
+class LomoDecoderLayer:
+    """Both blocks under one step: flags in backward order W_d, W_gu, w2, W_o, W_qkv, w1."""
+
+    def __init__(self, device, batch: int, seq: int, H: int, F: int, n_heads: int):
+        self.device = torch.device(device)
+        T = batch * seq
+        self.state = StepState(self.device, 6, T, H)
+        self.mlp = LomoMlpBlock(self.device, T, H, F, self.state, 0)
+        self.attn = LomoAttentionBlock(self.device, batch, seq, H, n_heads, self.state, 3)
+        self.dh_mid = torch.empty(T, H, dtype=torch.float16, device=self.device)
+
+    def _walk(self, dy, saved_attn, saved_mlp, p, rope_cos, rope_sin, dh, update, stream):
+        self.mlp.walk(dy, saved_mlp, p["w2"], p["W_gu"], p["W_d"], self.dh_mid, update, stream)
+        self.attn.walk(self.dh_mid, saved_attn, p["w1"], p["W_qkv"], p["W_o"], rope_cos, rope_sin, dh, update, stream)
+
+    def step(self, dy, saved_attn: Dict, saved_mlp: Dict, p: Dict, rope_cos, rope_sin, dh, lr: float, loss_scale: float,
+             max_norm: float = 1.0, eps: float = 1e-6, stream=None) -> None:
+        """p: {"w1", "W_qkv", "W_o", "w2", "W_gu", "W_d"} device tensors, updated in place; dh: gradient of the layer input."""
+        self.state.begin()
+        self._walk(dy, saved_attn, saved_mlp, p, rope_cos, rope_sin, dh, False, stream)
+        self.state.coefficient(lr, loss_scale, max_norm, eps, stream)
+        self._walk(dy, saved_attn, saved_mlp, p, rope_cos, rope_sin, dh, True, stream)
+        self.state.finish(stream)
+
+    def result(self) -> Dict:
+        return self.state.result()

@@ -4,8 +4,9 @@ block and the whole decoder layer as chained two-pass LOMO steps.
 The kernel recomputes the probabilities in fp32 where the oracle uses fp64, and both round P and dS to fp16
 before the products that consume them; a probability that sits within 1e-6 of a rounding boundary may
 therefore round differently, which moves an output by about 2^-11 of one term of its sum.  Bar for dq, dk,
-dv on the same input bits: within 1 fp16 ulp on >= 99 % of the elements and everywhere within 2 ulp or
-2^-9 of the root-mean-square of the tensor's row (floored at 2^-6 of the tensor's, for rows that cancel).
+dv on the same input bits: within 1 fp16 ulp on >= 99 % of the elements and everywhere within 2 ulp, or
+2^-9 of the root-mean-square of the tensor's row (floored at 2^-6 of the tensor's, for rows that cancel), or
+two fp16 roundings of the largest P / dS entry that feeds the element (oracle: attention_rounding_sensitivity).
 """
 import math
 import os
@@ -40,14 +41,17 @@ def f16(rng, shape, sigma):
     return (sigma * rng.standard_normal(size=shape)).astype(np.float16)
 
 
-def close_rows(got, want64, what, frac=0.99):
+def close_rows(got, want64, what, frac=0.99, flip=None):
     """1 ulp on `frac`, everywhere 2 ulp or 2^-9 of the row's rms (rows that cancel to nothing, like the first
-    token's dq, which is exactly zero, are measured against 2^-6 of the whole tensor's rms instead)."""
+    token's dq, which is exactly zero, are measured against 2^-6 of the whole tensor's rms instead), or within
+    two fp16 roundings of the largest probability(-gradient) entry that feeds the element (`flip`)."""
     want16 = O.round_f16(want64)
     d = O.ulp_distance_f16(got, want16)
     rms = np.sqrt((want64 ** 2).mean(axis=1, keepdims=True))
     rms = np.maximum(rms, 2.0 ** -6 * math.sqrt(float((want64 ** 2).mean())))
     near = np.abs(got.astype(np.float64) - want64) <= 2.0 ** -9 * rms
+    if flip is not None:
+        near |= np.abs(got.astype(np.float64) - want64) <= 2.0 * flip + 2.0 ** -11 * np.abs(want64)
     assert ((d <= 2) | near).all(), f"{what}: {d[~((d <= 2) | near)].max()} ulp"
     assert ((d <= 1) | (np.abs(got.astype(np.float64) - want64) <= 2.0 ** -12 * rms)).mean() >= frac, what
 
@@ -80,8 +84,9 @@ def test_attention_backward(L, B, s, nh, rope, sharp):
     got = out.cpu().numpy()
     want_delta = (O.as_f64(do) * O.as_f64(o)).reshape(T, nh, 128).sum(-1).reshape(-1)
     np.testing.assert_allclose(delta.cpu().numpy(), want_delta, rtol=2e-5, atol=2e-4)
+    flip = A.attention_rounding_sensitivity(qkv, o, do, lse, s, nh)
     for name, sl in (("dq", slice(0, H)), ("dk", slice(H, 2 * H)), ("dv", slice(2 * H, 3 * H))):
-        close_rows(got[:, sl], g[:, sl], f"{name} B={B} s={s} nh={nh}")
+        close_rows(got[:, sl], g[:, sl], f"{name} B={B} s={s} nh={nh}", flip=flip[:, sl])
 
 
 def test_attention_backward_is_causal_and_per_sequence(L):
@@ -125,3 +130,202 @@ def test_attention_backward_propagates_non_finite_and_rejects_bad_shapes(L):
     assert lib.lomo_attention_backward(z, z, z, z, z, z, z, z, 1, 64, 1, 64, z) == 2      # head width 64: shape error
     assert lib.lomo_attention_backward(z, z, z, z, z, z, z, z, 1, 100, 1, 128, z) == 2    # s not a multiple of 64
     assert lib.lomo_attention_backward(z, z, z, z, z, z, z, z, 1, 64, 1, 128, z) == 1     # null pointers
+
+
+# --------------------------------------------------------------------------- attention block and decoder layer
+
+
+def ulps_ok(got, want, what, frac=0.999, worst=2, near=None):
+    assert got.shape == want.shape
+    d = O.ulp_distance_f16(got, want)
+    ok1, okw = d <= 1, d <= worst
+    if near is not None:
+        ok1, okw = ok1 | near, okw | near
+    assert okw.all(), f"{what}: {d[~okw].max()} ulp"
+    assert ok1.mean() >= frac, f"{what}: only {ok1.mean():.5f} within 1 ulp"
+
+
+f64 = lambda a: a.astype(np.float64)
+
+
+def dgrad_ok(got, dY, W, what):
+    ref = O.input_grad_f64(dY, W)
+    near = np.abs(f64(got) - ref) <= 2.0 ** -20 * (np.abs(f64(dY)) @ np.abs(f64(W)))
+    ulps_ok(got, O.round_f16(ref), what, near=near)
+
+
+def rms_ok(got, dxn, saved, w, dres, what):
+    ref = M.rmsnorm_backward(dxn, saved["xhat"], saved["r"], w, dres=dres)
+    mag = f64(saved["r"])[:, None] * (np.abs(f64(dxn) * f64(w)) + np.abs(f64(saved["xhat"])) *
+                                       np.abs((f64(dxn) * f64(w) * f64(saved["xhat"])).mean(1))[:, None]) + np.abs(f64(dres))
+    ulps_ok(got, O.round_f16(ref), what, near=np.abs(f64(got) - ref) <= 2.0 ** -20 * mag)
+
+
+def frob_ok(got, want, what, tol=2.0 ** -11):
+    rel = np.linalg.norm(f64(got) - f64(want)) / np.linalg.norm(f64(want))
+    assert rel < tol, (what, rel)
+
+
+def weights_ok(got, want_chain, old, what, X=None, dY_dev=None, lr=None, coef=None, S=None, kind="linear"):
+    """Updated parameter against the oracle's chain, and against the oracle's update formed from the hand-on the
+    device actually used.  The second is held to the strict bar.  For the first, the device's hand-on differs
+    from the oracle's by a few parts in 10^4 in places, which moves an update by that fraction of itself:
+    more than an ulp where a large update lands on a small value; hence the guard 2^-9 |update|."""
+    near = np.abs(f64(got) - f64(want_chain)) <= 2.0 ** -9 * np.abs(f64(want_chain) - f64(old))
+    ulps_ok(got, want_chain, what + " (oracle chain)", near=near)
+    if X is not None:
+        G = O.linear_grad(X, dY_dev) if kind == "linear" else O.vector_grad(X, dY_dev)
+        ulps_ok(got, O.sgd_update(old, G, lr, coef, S), what + " (oracle update from the device's hand-on)")
+
+
+def to_dev_saved(saved):
+    g = {k: dev(v) for k, v in saved.items() if k not in ("r", "y")}
+    g["rstd"] = dev(saved["r"])
+    return g
+
+
+def check_attention_hand_ons(blk, dh, want, saved, w, W_qkv, W_o, dy, cos, sin, s, nh):
+    """Each stage against the oracle on the bits it read; the chain as a whole in the Frobenius norm."""
+    do, dqkv, dxn = blk.do.cpu().numpy(), blk.dqkv.cpu().numpy(), blk.dxn.cpu().numpy()
+    H = do.shape[1]
+    dgrad_ok(do, dy, W_o, "do from dy")
+    g = A.attention_backward(saved["qkv"], saved["o"], do, saved["lse"], s, nh)
+    g = np.concatenate((A.rope_rotate(g[:, :H], cos, sin, s, nh, inverse=True),
+                        A.rope_rotate(g[:, H:2 * H], cos, sin, s, nh, inverse=True), g[:, 2 * H:]), axis=1)
+    flip = A.attention_rounding_sensitivity(saved["qkv"], saved["o"], do, saved["lse"], s, nh)
+    for name, sl in (("dq", slice(0, H)), ("dk", slice(H, 2 * H)), ("dv", slice(2 * H, 3 * H))):
+        close_rows(dqkv[:, sl], g[:, sl], f"{name} from the device's do", flip=flip[:, sl])
+    dgrad_ok(dxn, dqkv, W_qkv, "dxn from the device's dqkv")
+    rms_ok(dh.cpu().numpy(), dxn, saved, w, dy, "dh from the device's dxn")
+    for name, gg, r in (("do", do, want["do"]), ("dqkv", dqkv, want["dqkv"]), ("dxn", dxn, want["dxn"]),
+                        ("dh", dh.cpu().numpy(), want["dh"])):
+        frob_ok(gg, r, name)
+
+
+def make_attention_block(rng, B, s, nh, scale):
+    H = nh * 128
+    T = B * s
+    h = f16(rng, (T, H), 1.0)
+    w = (1.0 + 0.05 * rng.standard_normal(H)).astype(np.float16)
+    W_qkv, W_o = f16(rng, (3 * H, H), 0.03), f16(rng, (H, H), 0.03)
+    dy = f16(rng, (T, H), 1e-3 * scale)
+    cos, sin = A.rope_tables(s, 128)
+    return h, w, W_qkv, W_o, dy, cos, sin, A.block_forward_stored(h, w, W_qkv, W_o, cos, sin, s, nh, 1e-5)
+
+
+@pytest.mark.parametrize("visible", [True, False], ids=["visible", "clipped"])
+@pytest.mark.parametrize("B,s,nh", [(2, 128, 2), (1, 192, 1)])
+def test_attention_block_step_matches_oracle(L, B, s, nh, visible):
+    from paper_2306_09782_amd.chain import LomoAttentionBlock
+    rng = np.random.default_rng(B * 100 + s + nh)
+    scale = 4096.0
+    h, w, W_qkv, W_o, dy, cos, sin, saved = make_attention_block(rng, B, s, nh, scale)
+    T, H = h.shape
+    max_norm = 1e30 if visible else 1.0
+    probe = A.block_step(dy, saved, w, W_qkv, W_o, cos, sin, s, nh, 1.0, scale, max_norm=1e30)
+    typical = math.sqrt(probe["sqnorms"][1] / W_qkv.size) / scale
+    lr = float(np.float32(30 * 2.0 ** -16 / typical)) if visible else 1e-2
+    want = A.block_step(dy, saved, w, W_qkv, W_o, cos, sin, s, nh, lr, scale, max_norm=max_norm)
+    blk = LomoAttentionBlock(DEV, B, s, H, nh)
+    dw, dWqkv, dWo = dev(w), dev(W_qkv), dev(W_o)
+    dh = torch.empty(T, H, dtype=torch.float16, device=DEV)
+    blk.step(dev(dy), to_dev_saved(saved), dw, dWqkv, dWo, dev(cos), dev(sin), dh, lr, scale, max_norm)
+    torch.cuda.synchronize()
+    res = blk.result()
+    assert res["flags"] == want["flags"] == [False] * 3 and res["overflow"] is False
+    assert abs(res["norm"] / want["norm"] - 1) < 1e-3 and abs(res["clip_coef"] / want["clip_coef"] - 1) < 1e-3
+    hand = dict(lr=lr, coef=res["clip_coef"], S=scale)
+    ulps_ok(dWo.cpu().numpy(), want["W_o"], "W_o")
+    weights_ok(dWqkv.cpu().numpy(), want["W_qkv"], W_qkv, "W_qkv", saved["xn"], blk.dqkv.cpu().numpy(), **hand)
+    weights_ok(dw.cpu().numpy(), want["w"], w, "gain", saved["xhat"], blk.dxn.cpu().numpy(), kind="vector", **hand)
+    if visible:
+        changed_o = want["W_qkv"].view(np.uint16) != W_qkv.view(np.uint16)
+        changed_g = dWqkv.cpu().numpy().view(np.uint16) != W_qkv.view(np.uint16)
+        assert changed_o.mean() > 0.8 and (changed_o != changed_g).mean() < 2e-3
+    check_attention_hand_ons(blk, dh, want, saved, w, W_qkv, W_o, dy, cos, sin, s, nh)
+
+
+def run_layer(L, rng, B, s, nh, F, scale, lr, max_norm=1.0, poison=None):
+    from paper_2306_09782_amd.chain import LomoDecoderLayer
+    H, T = nh * 128, B * s
+    p = {"w1": (1.0 + 0.05 * rng.standard_normal(H)).astype(np.float16), "W_qkv": f16(rng, (3 * H, H), 0.02),
+         "W_o": f16(rng, (H, H), 0.02), "w2": (1.0 + 0.05 * rng.standard_normal(H)).astype(np.float16),
+         "W_gu": f16(rng, (2 * F, H), 0.02), "W_d": f16(rng, (H, F), 0.02)}
+    h = f16(rng, (T, H), 1.0)
+    dy = f16(rng, (T, H), 1e-3 * scale)
+    if poison is not None:
+        dy[poison] = np.inf
+    cos, sin = A.rope_tables(s, 128)
+    sa, sm = A.layer_forward_stored(h, p, cos, sin, s, nh, 1e-5)
+    if lr is None:      # a step that moves most weights by tens of ulps
+        probe = A.layer_step(dy, sa, sm, p, cos, sin, s, nh, 1.0, scale, max_norm=1e30)
+        lr = float(np.float32(30 * 2.0 ** -16 / (math.sqrt(probe["sqnorms"][1] / p["W_gu"].size) / scale)))
+    want = A.layer_step(dy, sa, sm, p, cos, sin, s, nh, lr, scale, max_norm=max_norm)
+    layer = LomoDecoderLayer(DEV, B, s, H, F, nh)
+    dp = {k: dev(v) for k, v in p.items()}
+    dh = torch.empty(T, H, dtype=torch.float16, device=DEV)
+    layer.step(dev(dy), to_dev_saved(sa), to_dev_saved(sm), dp, dev(cos), dev(sin), dh, lr, scale, max_norm)
+    torch.cuda.synchronize()
+    return layer, dp, dh, want, p, sa, sm, dy, cos, sin, lr, scale
+
+
+def check_layer(layer, dp, dh, want, p, sa, sm, dy, cos, sin, lr, scale, s, nh):
+    res = layer.result()
+    assert res["flags"] == want["flags"] and res["overflow"] is False
+    assert abs(res["norm"] / want["norm"] - 1) < 1e-3 and abs(res["clip_coef"] / want["clip_coef"] - 1) < 1e-3
+    da, dgu, dxn = layer.mlp.da.cpu().numpy(), layer.mlp.dgu.cpu().numpy(), layer.mlp.dxn.cpu().numpy()
+    mid_, dqkv_, adxn_ = layer.dh_mid.cpu().numpy(), layer.attn.dqkv.cpu().numpy(), layer.attn.dxn.cpu().numpy()
+    hand = dict(lr=lr, coef=res["clip_coef"], S=scale)
+    got = {k: v.cpu().numpy() for k, v in dp.items()}
+    ulps_ok(got["W_d"], want["params"]["W_d"], "W_d")
+    weights_ok(got["W_gu"], want["params"]["W_gu"], p["W_gu"], "W_gu", sm["xn"], dgu, **hand)
+    weights_ok(got["w2"], want["params"]["w2"], p["w2"], "w2", sm["xhat"], dxn, kind="vector", **hand)
+    weights_ok(got["W_o"], want["params"]["W_o"], p["W_o"], "W_o", sa["o"], mid_, **hand)
+    weights_ok(got["W_qkv"], want["params"]["W_qkv"], p["W_qkv"], "W_qkv", sa["xn"], dqkv_, **hand)
+    weights_ok(got["w1"], want["params"]["w1"], p["w1"], "w1", sa["xhat"], adxn_, kind="vector", **hand)
+    # feed-forward half: stages on the device's own bits
+    dgrad_ok(da, dy, p["W_d"], "da")
+    ulps_ok(dgu, O.round_f16(M.swiglu_backward(da, sm["gate_up"])), "dgu from the device's da")
+    dgrad_ok(dxn, dgu, p["W_gu"], "mlp dxn")
+    mid = layer.dh_mid.cpu().numpy()
+    rms_ok(mid, dxn, sm, p["w2"], dy, "dh between the blocks")
+    frob_ok(mid, want["dh_mid"], "dh_mid")
+    # attention half, fed by the device's dh_mid
+    check_attention_hand_ons(layer.attn, dh, want["attn"] | {"dh": want["dh"]}, sa, p["w1"], p["W_qkv"], p["W_o"], mid,
+                             cos, sin, s, nh)
+
+
+def test_decoder_layer_step_matches_oracle(L):
+    rng = np.random.default_rng(31)
+    B, s, nh, F = 2, 128, 2, 688
+    out = run_layer(L, rng, B, s, nh, F, 4096.0, 1e-2)
+    check_layer(*out, s, nh)
+
+
+def test_decoder_layer_visible_step(L):
+    rng = np.random.default_rng(32)
+    B, s, nh, F = 1, 256, 2, 344
+    layer, dp, dh, want, p, sa, sm, dy, cos, sin, lr, scale = run_layer(L, rng, B, s, nh, F, 4096.0, None, max_norm=1e30)
+    check_layer(layer, dp, dh, want, p, sa, sm, dy, cos, sin, lr, scale, s, nh)
+    for name in ("W_qkv", "W_gu", "W_d", "W_o"):
+        changed_o = want["params"][name].view(np.uint16) != p[name].view(np.uint16)
+        changed_g = dp[name].cpu().numpy().view(np.uint16) != p[name].view(np.uint16)
+        assert changed_o.mean() > 0.5 and (changed_o != changed_g).mean() < 2e-3, name
+
+
+def test_decoder_layer_overflow_leaves_parameters_alone(L):
+    rng = np.random.default_rng(33)
+    layer, dp, dh, want, p, *_ = run_layer(L, rng, 1, 128, 1, 344, 4096.0, 1e-2, poison=(77, 5))
+    res = layer.result()
+    assert want["overflow"] is True and res["overflow"] is True and res["step"] == 0.0
+    assert res["flags"] == want["flags"]
+    for name in A.LAYER_ORDER:
+        np.testing.assert_array_equal(dp[name].cpu().numpy().view(np.uint16), p[name].view(np.uint16))
+
+
+@pytest.mark.timeout(900)
+def test_decoder_layer_llama7b_shape(L):
+    """8 sequences of 512 tokens, H = 4096 (32 heads), F = 11008: one 7B decoder layer against the full oracle."""
+    rng = np.random.default_rng(34)
+    out = run_layer(L, rng, 8, 512, 32, 11008, 65536.0, 1e-2)
+    check_layer(*out, 512, 32)

@@ -849,3 +849,94 @@ def test_attention_finite_differences_catch_planted_mistakes(mut):
     good = A.rope_rotate(A.attention_backward(np.concatenate((q, k, v), 1), o, R, lse, s, nh, False)[:, :dd], cos, sin, s, nh, True)
     np.testing.assert_allclose(good, fd, rtol=1e-5, atol=1e-8)
     assert np.abs(bad - fd).max() > 1e-3 * np.abs(fd).max()
+
+
+def _layer_params(rng, H, F, sig=0.5, dtype=np.float64):
+    mk = lambda shape, s_: (s_ * rng.normal(size=shape)).astype(dtype)
+    return {"w1": (1.0 + 0.2 * rng.normal(size=H)).astype(dtype), "W_qkv": mk((3 * H, H), sig), "W_o": mk((H, H), sig),
+            "w2": (1.0 + 0.2 * rng.normal(size=H)).astype(dtype), "W_gu": mk((2 * F, H), sig), "W_d": mk((H, F), sig)}
+
+
+def test_layer_chain_finite_differences_across_both_blocks():
+    """The hand-on between the blocks (residuals included): gradients of attention-block parameters taken
+    through the feed-forward block must match difference quotients of the whole layer."""
+    rng = np.random.default_rng(21)
+    B, s, nh, dd, F, eps = 1, 4, 1, 4, 6, 1e-3
+    T, H = B * s, nh * dd
+    p = _layer_params(rng, H, F)
+    h, R = rng.normal(size=(T, H)), rng.normal(size=(T, H))
+    cos, sin = A.rope_tables(s, dd)
+    # unrounded chain, composed from the pieces
+    y1 = A.block_forward_f64(h, p["w1"], p["W_qkv"], p["W_o"], cos, sin, s, nh, eps)
+    mg = _block_grads_f64(y1, p["w2"], p["W_gu"], p["W_d"], R, eps)
+    dmid = mg["dh"]
+    xhat, r, xn = M.rmsnorm_forward(h, p["w1"], eps)
+    qkv = xn @ p["W_qkv"].T
+    q, k = A.rope_rotate(qkv[:, :H], cos, sin, s, nh), A.rope_rotate(qkv[:, H:2 * H], cos, sin, s, nh)
+    o, lse = A.attention_forward_f64(q, k, qkv[:, 2 * H:], s, nh)
+    do = O.input_grad_f64(dmid, p["W_o"])
+    g = A.attention_backward(np.concatenate((q, k, qkv[:, 2 * H:]), 1), o, do, lse, s, nh, round_probabilities=False)
+    dqkv = np.concatenate((A.rope_rotate(g[:, :H], cos, sin, s, nh, True), A.rope_rotate(g[:, H:2 * H], cos, sin, s, nh, True),
+                           g[:, 2 * H:]), 1)
+    dxn = O.input_grad_f64(dqkv, p["W_qkv"])
+    got = {"W_o": O.linear_grad(o, dmid), "W_qkv": O.linear_grad(xn, dqkv), "w1": O.vector_grad(xhat, dxn),
+           "h": M.rmsnorm_backward(dxn, xhat, r, p["w1"], dres=dmid), "W_d": mg["G_d"], "w2": mg["g_w"]}
+    loss = lambda h_, p_: float((A.layer_forward_f64(h_, p_, cos, sin, s, nh, eps) * R).sum())
+    e = 1e-6
+    for which in ("W_o", "W_qkv", "w1", "W_d", "w2"):
+        for idx in list(np.ndindex(p[which].shape))[::2]:
+            pp, pm = dict(p), dict(p)
+            pp[which], pm[which] = p[which].copy(), p[which].copy()
+            pp[which][idx] += e
+            pm[which][idx] -= e
+            assert (loss(h, pp) - loss(h, pm)) / (2 * e) == pytest.approx(got[which][idx], rel=1e-5, abs=1e-7), (which, idx)
+    for idx in np.ndindex(h.shape):
+        hp, hm = h.copy(), h.copy()
+        hp[idx] += e
+        hm[idx] -= e
+        assert (loss(hp, p) - loss(hm, p)) / (2 * e) == pytest.approx(got["h"][idx], rel=1e-5, abs=1e-7), idx
+
+
+def test_layer_step_is_the_generic_step_on_six_tensors():
+    rng = np.random.default_rng(22)
+    B, s, nh, dd, F = 2, 8, 2, 8, 24
+    T, H = B * s, nh * dd
+    p = _layer_params(rng, H, F, sig=0.3, dtype=np.float16)
+    h = rng.normal(size=(T, H)).astype(np.float16)
+    dy = (2.0 * rng.normal(size=(T, H))).astype(np.float16)
+    cos, sin = A.rope_tables(s, dd)
+    sa, sm = A.layer_forward_stored(h, p, cos, sin, s, nh, 1e-5)
+    a = A.layer_step(dy, sa, sm, p, cos, sin, s, nh, 0.05, 256.0)
+    recs = [dict(kind="linear", X=sm["a"], dY=dy, W=p["W_d"]), dict(kind="linear", X=sm["xn"], dY=a["mlp"]["dgu"], W=p["W_gu"]),
+            dict(kind="vector", X=sm["xhat"], dY=a["mlp"]["dxn"], W=p["w2"]),
+            dict(kind="linear", X=sa["o"], dY=a["dh_mid"], W=p["W_o"]), dict(kind="linear", X=sa["xn"], dY=a["attn"]["dqkv"], W=p["W_qkv"]),
+            dict(kind="vector", X=sa["xhat"], dY=a["attn"]["dxn"], W=p["w1"])]
+    b = O.step_materialised(recs, 0.05, 256.0)
+    assert a["clip_coef"] == b["clip_coef"] and a["clip_coef"] < 1.0 and a["flags"] == b["flags"]
+    for name, want in zip(A.LAYER_ORDER, b["W"]):
+        np.testing.assert_array_equal(a["params"][name].view(np.uint16), want.view(np.uint16))
+    # the feed-forward block saw the stored output of the attention block
+    np.testing.assert_array_equal(sm["xhat"].shape, sa["y"].shape)
+
+
+def test_attention_rounding_sensitivity_bounds_a_single_flip():
+    """Moving one entry of dS or P by one fp16 ulp moves no output by more than the stated sensitivity."""
+    rng = np.random.default_rng(16)
+    s, nh, dd = 16, 1, 8
+    f16 = lambda shape, sig: (sig * rng.normal(size=shape)).astype(np.float16)
+    qkv = np.concatenate((f16((s, dd), 1.0), f16((s, dd), 1.0), f16((s, dd), 1.0)), axis=1)
+    att = A.attention_forward_stored(qkv, s, nh)
+    do = f16((s, dd), 3.0)
+    bound = A.attention_rounding_sensitivity(qkv, att["o"], do, att["lse"], s, nh)
+    q, k, v = (O.as_f64(qkv[:, i * dd:(i + 1) * dd]) for i in range(3))
+    S = (q @ k.T) / math.sqrt(dd)
+    S[np.triu_indices(s, 1)] = -np.inf
+    P = np.exp(S - att["lse"].astype(np.float64))
+    dS = P * (O.as_f64(do) @ v.T - (O.as_f64(do) * O.as_f64(att["o"])).sum(1, keepdims=True)) / math.sqrt(dd)
+    for (i, j) in ((5, 2), (15, 15), (9, 0)):
+        bump = np.zeros_like(dS)
+        bump[i, j] = abs(dS[i, j]) * 2.0 ** -11                 # at most one ulp of that entry
+        assert (np.abs(bump @ k) <= bound[:, :dd] + 1e-300).all() and (np.abs(bump.T @ q) <= bound[:, dd:2 * dd] + 1e-300).all()
+        bumpP = np.zeros_like(P)
+        bumpP[i, j] = P[i, j] * 2.0 ** -11
+        assert (np.abs(bumpP.T @ O.as_f64(do)) <= bound[:, 2 * dd:] + 1e-300).all()
