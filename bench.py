@@ -90,22 +90,28 @@ def hbm_kernels(wl, fam, steps):
 
 
 def chain_bench(L, torch, np, dev, steps, warmup):
-    """Two-pass step through the feed-forward block of the 7B layer (T = 4096, H = 4096, F = 11008) with the
-    hand-on gradients produced by the kernels themselves: 4 GEMMs per linear tensor, as in the paper's
-    two backward passes.  Synthetic saved activations (the chain's arithmetic does not care)."""
-    from paper_2306_09782_amd.chain import LomoMlpBlock
+    """Two-pass step through one whole 7B decoder layer (8 x 512 tokens, H = 4096, 32 heads, F = 11008) with the
+    hand-on gradients produced by the kernels themselves: 4 GEMMs per linear tensor, as in the paper's two
+    backward passes.  Synthetic saved activations (the chain's arithmetic does not care what they hold)."""
+    from paper_2306_09782_amd.chain import LomoDecoderLayer
     import lomo_synth as S
-    T, H, F = 4096, 4096, 11008
+    Bt, s, nh, H, F = 8, 512, 32, 4096, 11008
+    T = Bt * s
     key = lambda i: S.tensor_key(0, 99, i, 0)
     gen = lambda i, shape, sigma: S.normal_f16_torch(key(i), shape, S.normal_mult(sigma), dev)
-    saved = {"a": gen(0, (T, F), 0.3), "xn": gen(1, (T, H), 1.0), "xhat": gen(2, (T, H), 1.0),
-             "gate_up": gen(3, (T, 2 * F), 1.0), "rstd": torch.ones(T, dtype=torch.float32, device=dev)}
-    w = torch.ones(H, dtype=torch.float16, device=dev)
-    W_gu, W_d = gen(4, (2 * F, H), 0.02), gen(5, (H, F), 0.02)
+    ones = lambda n, dt: torch.ones(n, dtype=dt, device=dev)
+    sm = {"a": gen(0, (T, F), 0.3), "xn": gen(1, (T, H), 1.0), "xhat": gen(2, (T, H), 1.0),
+          "gate_up": gen(3, (T, 2 * F), 1.0), "rstd": ones(T, torch.float32)}
+    sa = {"o": gen(7, (T, H), 0.2), "xn": gen(8, (T, H), 1.0), "xhat": gen(9, (T, H), 1.0), "qkv": gen(10, (T, 3 * H), 1.0),
+          "rstd": ones(T, torch.float32), "lse": torch.full((T, nh), 4.0, dtype=torch.float32, device=dev)}
+    p = {"w1": ones(H, torch.float16), "w2": ones(H, torch.float16), "W_qkv": gen(11, (3 * H, H), 0.02),
+         "W_o": gen(12, (H, H), 0.02), "W_gu": gen(4, (2 * F, H), 0.02), "W_d": gen(5, (H, F), 0.02)}
+    ang = torch.arange(s, device=dev, dtype=torch.float64)[:, None] * (10000.0 ** (-torch.arange(64, device=dev, dtype=torch.float64) / 64.0))[None, :]
+    cos, sin = torch.cos(ang).float().contiguous(), torch.sin(ang).float().contiguous()
     dy = gen(6, (T, H), 1e-3 * 65536.0)
     dh = torch.empty(T, H, dtype=torch.float16, device=dev)
-    blk = LomoMlpBlock(dev, T, H, F)
-    run = lambda: blk.step(dy, saved, w, W_gu, W_d, dh, 1e-2, 65536.0)
+    layer = LomoDecoderLayer(dev, Bt, s, H, F, nh)
+    run = lambda: layer.step(dy, sa, sm, p, cos, sin, dh, 1e-2, 65536.0)
     for _ in range(warmup):
         run()
     torch.cuda.synchronize()
@@ -117,7 +123,7 @@ def chain_bench(L, torch, np, dev, steps, warmup):
     ms = (time.perf_counter() - t0) / steps * 1e3
     fam = {name: L.lomo_timing_read(i) for i, name in enumerate(L.KERNEL_FAMILIES)}
     L.lomo_timing_enable(False)
-    res = blk.result()
+    res = layer.result()
 
     def timed(fn, reps=20):
         fn()
@@ -129,17 +135,28 @@ def chain_bench(L, torch, np, dev, steps, warmup):
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps
-    sw_ms = timed(lambda: L.lomo_swiglu_backward(blk.da, saved["gate_up"], blk.dgu))
-    rn_ms = timed(lambda: L.lomo_rmsnorm_backward(blk.dxn, saved["xhat"], saved["rstd"], w, dy, dh))
+    m, at = layer.mlp, layer.attn
+    sw_ms = timed(lambda: L.lomo_swiglu_backward(m.da, sm["gate_up"], m.dgu))
+    rn_ms = timed(lambda: L.lomo_rmsnorm_backward(m.dxn, sm["xhat"], sm["rstd"], p["w2"], dy, dh))
+    at_ms = timed(lambda: L.lomo_attention_backward(sa["qkv"], sa["o"], at.do, sa["lse"], cos, sin, at.delta, at.dqkv, Bt, s, nh))
     sw_bytes, rn_bytes = 5 * T * F * 2, 4 * T * H * 2 + 4 * T + 2 * H
-    flops = 4 * (2 * T * H * F + 2 * T * H * 2 * F)
-    return {"workload": "feed-forward block of the 7B layer, chained (T 4096, H 4096, F 11008)", "ms_per_step": ms,
+    # attention backward: 7 block products of 2 * 64 * 64 * 128 flop per (query block, key block) pair at or below
+    # the diagonal (S and dP in both kernels, dv, dk, dq once); bytes: qkv, o, dO read, dqkv written, once each
+    nb = s // 64
+    at_flops = Bt * nh * (nb * (nb + 1) // 2) * 7 * 2 * 64 * 64 * 128
+    at_bytes = (3 * T * H + T * H + T * H + 3 * T * H) * 2
+    lin_flops = 2 * T * H * (3 * H + H + 2 * F + F)
+    flops = 4 * lin_flops + 2 * at_flops
+    return {"workload": "one 7B decoder layer, chained (8 x 512 tokens, H 4096, 32 heads, F 11008)", "ms_per_step": ms,
             "gemms_per_linear": 4, "tflops": flops / (ms * 1e-3) / 1e12, "grad_norm": res["norm"], "overflow": res["overflow"],
             "family_ms_per_step": {k: v[0] / steps for k, v in fam.items() if v[1]},
             "swiglu_backward": {"ms": sw_ms, "algorithmic_bytes": sw_bytes, "gb_per_s": sw_bytes / sw_ms / 1e6,
                                 "frac_hbm_peak": sw_bytes / sw_ms / 1e6 / 8000.0},
             "rmsnorm_backward": {"ms": rn_ms, "algorithmic_bytes": rn_bytes, "gb_per_s": rn_bytes / rn_ms / 1e6,
-                                 "frac_hbm_peak": rn_bytes / rn_ms / 1e6 / 8000.0}}
+                                 "frac_hbm_peak": rn_bytes / rn_ms / 1e6 / 8000.0},
+            "attention_backward": {"ms": at_ms, "flops": at_flops, "tflops": at_flops / (at_ms * 1e-3) / 1e12,
+                                   "frac_fp16_mfma_peak": at_flops / (at_ms * 1e-3) / 1e12 / PEAK_FP16_TFLOPS,
+                                   "algorithmic_bytes": at_bytes, "gb_per_s": at_bytes / at_ms / 1e6}}
 
 
 def main():
@@ -162,7 +179,7 @@ def main():
     ap.add_argument("--no-norm-compare", action="store_true",
                     help="skip the extra timing of pass 1 alone on each route after the timed steps")
     ap.add_argument("--chain", action="store_true",
-                    help="also time the chained two-pass step through the 7B feed-forward block (extra key `chain`)")
+                    help="also time the chained two-pass step through one whole 7B decoder layer (extra key `chain`)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference for rocprofv3 byte counters)")
     args = ap.parse_args()

@@ -30,7 +30,7 @@ constexpr int PD = D + 8;     // LDS pitch of a [64 x 128] fp16 tile (halves)
 constexpr int PS = BLK + 8;   // LDS pitch of a [64 x 64] fp16 tile
 constexpr int PO = D + 4;     // LDS pitch of the fp32 output tile (floats)
 constexpr int TILE = BLK * PD;
-constexpr int LDS_BYTES = 4 * TILE * 2 + 2 * BLK * PS * 2 + 2 * BLK * 4;
+constexpr int LDS_BYTES = 2 * TILE * 2 + 2 * BLK * PS * 2 + 2 * BLK * 4;
 
 struct Args {
     const uint16_t* qkv;   // [T x 3H]
@@ -89,18 +89,18 @@ __global__ __launch_bounds__(256) void attention_delta_kernel(const uint16_t* __
 
 // MODE 0: workgroup = (key block j, head, sequence): dk, dv.  MODE 1: workgroup = (query block i, head, sequence): dq.
 template <int MODE>
-__global__ __launch_bounds__(256) void attention_backward_kernel(attn::Args a) {
+__global__ __launch_bounds__(256, 2) void attention_backward_kernel(attn::Args a) {
     using namespace attn;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-    uint16_t* sQ = smem;
-    uint16_t* sDO = sQ + TILE;
-    uint16_t* sK = sDO + TILE;
-    uint16_t* sV = sK + TILE;
-    uint16_t* sP = sV + TILE;
+    // Two [64 x 128] tiles for the operand pair that moves with the loop (MODE 0: Q_i and dO_i; MODE 1: K_j and
+    // V_j); the pair that stays is held as MFMA fragments in registers.  Less LDS, two workgroups per CU.
+    uint16_t* sA = smem;
+    uint16_t* sB = sA + TILE;
+    uint16_t* sP = sB + TILE;
     uint16_t* sDS = sP + BLK * PS;
     float* sL = reinterpret_cast<float*>(sDS + BLK * PS);
     float* sDelta = sL + BLK;
-    float* sOut = reinterpret_cast<float*>(smem);     // [64 x PO] fp32, after the loop (over sQ and sDO)
+    float* sOut = reinterpret_cast<float*>(smem);     // [64 x PO] fp32, after the loop (over both tiles)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wr = wave & 1, wc = wave >> 1;
@@ -119,22 +119,34 @@ __global__ __launch_bounds__(256) void attention_backward_kernel(attn::Args a) {
     const uint16_t* gv = gk + a.H;
     const uint16_t* gdo = a.dO + (int64_t)n * D;
     const float scale = 0.08838834764831845f;     // 1 / sqrt(128)
+    // exp(x) as the hardware's 2^y with y = x log2(e): its relative error (about 1e-6 for |x| < 30) is far
+    // below half an fp16 ulp, and the softmax phase is bound by vector ALU work, not by the matrix cores
+    const float log2e = 1.4426950408889634f, scale_log2e = scale * log2e;
 
-    // the operand that stays: K_j, V_j (MODE 0) or Q_i, dO_i with lse and delta (MODE 1)
+    // the operand pair that stays: K_j, V_j (MODE 0) or Q_i, dO_i with lse and delta (MODE 1), through LDS
+    // once into the registers of the wave that multiplies with them
     u32x4 r0[4], r1[4];
     if (MODE == 0) {
         fetch_tile(r0, gk + (t0 + (int64_t)fixed * BLK) * ld3, ld3);
         fetch_tile(r1, gv + (t0 + (int64_t)fixed * BLK) * ld3, ld3);
-        stash_tile(r0, sK);
-        stash_tile(r1, sV);
     } else {
         fetch_tile(r0, gq + (t0 + (int64_t)fixed * BLK) * ld3, ld3);
         fetch_tile(r1, gdo + (t0 + (int64_t)fixed * BLK) * ldh, ldh);
-        stash_tile(r0, sQ);
-        stash_tile(r1, sDO);
         if (tid < BLK) {
-            sL[tid] = a.lse[(t0 + (int64_t)fixed * BLK + tid) * a.nh + n];
+            sL[tid] = a.lse[(t0 + (int64_t)fixed * BLK + tid) * a.nh + n] * log2e;
             sDelta[tid] = a.delta[(t0 + (int64_t)fixed * BLK + tid) * a.nh + n];
+        }
+    }
+    stash_tile(r0, sA);
+    stash_tile(r1, sB);
+    __syncthreads();
+    half8 fx[D / 16], fy[D / 16];
+    {
+        const int row = ((MODE == 0) ? 32 * wc : 32 * wr) + l32;     // keys are MFMA columns, queries MFMA rows
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) {
+            fx[ks] = *reinterpret_cast<const half8*>(sA + row * PD + 16 * ks + 8 * lh);
+            fy[ks] = *reinterpret_cast<const half8*>(sB + row * PD + 16 * ks + 8 * lh);
         }
     }
 
@@ -168,16 +180,11 @@ __global__ __launch_bounds__(256) void attention_backward_kernel(attn::Args a) {
 
     for (int blk = first; blk <= last; ++blk) {
         __syncthreads();     // everybody is done with the tiles of the previous block
-        if (MODE == 0) {
-            stash_tile(r0, sQ);
-            stash_tile(r1, sDO);
-            if (tid < BLK) {
-                sL[tid] = rl;
-                sDelta[tid] = rd;
-            }
-        } else {
-            stash_tile(r0, sK);
-            stash_tile(r1, sV);
+        stash_tile(r0, sA);
+        stash_tile(r1, sB);
+        if (MODE == 0 && tid < BLK) {
+            sL[tid] = rl * log2e;
+            sDelta[tid] = rd;
         }
         __syncthreads();
         if (blk < last) fetch_moving(blk + 1);     // in flight while this block is multiplied
@@ -192,12 +199,17 @@ __global__ __launch_bounds__(256) void attention_backward_kernel(attn::Args a) {
 #pragma unroll
         for (int ks = 0; ks < D / 16; ++ks) {
             const int off = 16 * ks + 8 * lh;
-            const half8 aq = *reinterpret_cast<const half8*>(sQ + (32 * wr + l32) * PD + off);
-            const half8 bk = *reinterpret_cast<const half8*>(sK + (32 * wc + l32) * PD + off);
-            accS = __builtin_amdgcn_mfma_f32_32x32x16_f16(aq, bk, accS, 0, 0, 0);
-            const half8 ad = *reinterpret_cast<const half8*>(sDO + (32 * wr + l32) * PD + off);
-            const half8 bv = *reinterpret_cast<const half8*>(sV + (32 * wc + l32) * PD + off);
-            accP = __builtin_amdgcn_mfma_f32_32x32x16_f16(ad, bv, accP, 0, 0, 0);
+            if (MODE == 0) {      // moving Q_i, dO_i are the MFMA rows; K_j, V_j come from registers
+                const half8 aq = *reinterpret_cast<const half8*>(sA + (32 * wr + l32) * PD + off);
+                const half8 ad = *reinterpret_cast<const half8*>(sB + (32 * wr + l32) * PD + off);
+                accS = __builtin_amdgcn_mfma_f32_32x32x16_f16(aq, fx[ks], accS, 0, 0, 0);
+                accP = __builtin_amdgcn_mfma_f32_32x32x16_f16(ad, fy[ks], accP, 0, 0, 0);
+            } else {              // moving K_j, V_j are the MFMA columns; Q_i, dO_i come from registers
+                const half8 bk = *reinterpret_cast<const half8*>(sA + (32 * wc + l32) * PD + off);
+                const half8 bv = *reinterpret_cast<const half8*>(sB + (32 * wc + l32) * PD + off);
+                accS = __builtin_amdgcn_mfma_f32_32x32x16_f16(fx[ks], bk, accS, 0, 0, 0);
+                accP = __builtin_amdgcn_mfma_f32_32x32x16_f16(fy[ks], bv, accP, 0, 0, 0);
+            }
         }
         // ---- P and dS in fp16, [query][key]
         const bool diag = (MODE == 0) ? (blk == fixed) : (blk == fixed);
@@ -205,7 +217,7 @@ __global__ __launch_bounds__(256) void attention_backward_kernel(attn::Args a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int qrow = 32 * wr + 8 * (r >> 2) + 4 * lh + (r & 3);
-            float p = expf(fmaf(scale, accS[r], -sL[qrow]));
+            float p = __builtin_amdgcn_exp2f(fmaf(scale_log2e, accS[r], -sL[qrow]));
             float ds = scale * p * (accP[r] - sDelta[qrow]);
             if (diag && key > qrow) {
                 p = 0.f;
@@ -226,8 +238,8 @@ __global__ __launch_bounds__(256) void attention_backward_kernel(attn::Args a) {
                 const half8 bD = read_tr8(pd, pd + 4 * PS);
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
-                    const uint16_t* po = sDO + (16 * ks + tr_row) * PD + 64 * wr + 32 * i + tr_col;
-                    const uint16_t* pq = sQ + (16 * ks + tr_row) * PD + 64 * wr + 32 * i + tr_col;
+                    const uint16_t* po = sB + (16 * ks + tr_row) * PD + 64 * wr + 32 * i + tr_col;
+                    const uint16_t* pq = sA + (16 * ks + tr_row) * PD + 64 * wr + 32 * i + tr_col;
                     acc0[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(read_tr8(po, po + 4 * PD), bP, acc0[i], 0, 0, 0);
                     acc1[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(read_tr8(pq, pq + 4 * PD), bD, acc1[i], 0, 0, 0);
                 }
@@ -239,7 +251,7 @@ __global__ __launch_bounds__(256) void attention_backward_kernel(attn::Args a) {
                 const half8 bD = *reinterpret_cast<const half8*>(sDS + (32 * wc + l32) * PS + 16 * ks + 8 * lh);
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
-                    const uint16_t* pk = sK + (16 * ks + tr_row) * PD + 64 * wr + 32 * i + tr_col;
+                    const uint16_t* pk = sA + (16 * ks + tr_row) * PD + 64 * wr + 32 * i + tr_col;
                     acc0[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(read_tr8(pk, pk + 4 * PD), bD, acc0[i], 0, 0, 0);
                 }
             }
@@ -249,6 +261,17 @@ __global__ __launch_bounds__(256) void attention_backward_kernel(attn::Args a) {
     // ---- results: through LDS as fp32 so that the rotary pairs (c, c + 64) meet and stores are 16 bytes wide
     const int64_t orow0 = t0 + (int64_t)fixed * BLK;
     auto emit = [&](floatx16 (&acc)[2], int64_t colbase, bool rotate) {
+        // thread: row = tid / 4, sixteen pairs (c, c + 64) with c = 16 * (tid % 4) ...
+        const int row = tid >> 2, c0 = 16 * (tid & 3);
+        const int pos = fixed * BLK + row;
+        float4 co[4], si[4];
+        if (rotate) {      // the table rows of this thread, requested before the exchange through LDS
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                co[u] = *reinterpret_cast<const float4*>(a.cosv + pos * 64 + c0 + 4 * u);
+                si[u] = *reinterpret_cast<const float4*>(a.sinv + pos * 64 + c0 + 4 * u);
+            }
+        }
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < 2; ++i)
@@ -256,22 +279,28 @@ __global__ __launch_bounds__(256) void attention_backward_kernel(attn::Args a) {
             for (int r = 0; r < 16; ++r)
                 sOut[(32 * wc + l32) * PO + 64 * wr + 32 * i + 8 * (r >> 2) + 4 * lh + (r & 3)] = acc[i][r];
         __syncthreads();
-        // thread: row = tid / 4, sixteen pairs (c, c + 64) with c = 16 * (tid % 4) ...
-        const int row = tid >> 2, c0 = 16 * (tid & 3);
         const float* src = sOut + row * PO;
-        const int pos = fixed * BLK + row;
         half8 lo[2], hi[2];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const float x1 = src[c0 + e], x2 = src[c0 + e + 64];
-            float y1 = x1, y2 = x2;
+        for (int u = 0; u < 4; ++u) {
+            const float4 x1 = *reinterpret_cast<const float4*>(src + c0 + 4 * u);
+            const float4 x2 = *reinterpret_cast<const float4*>(src + c0 + 64 + 4 * u);
+            const float a1[4] = {x1.x, x1.y, x1.z, x1.w}, a2[4] = {x2.x, x2.y, x2.z, x2.w};
+            float cc[4] = {1.f, 1.f, 1.f, 1.f}, ss[4] = {0.f, 0.f, 0.f, 0.f};
             if (rotate) {
-                const float co = a.cosv[pos * 64 + c0 + e], si = a.sinv[pos * 64 + c0 + e];
-                y1 = fmaf(x2, si, x1 * co);
-                y2 = fmaf(-x1, si, x2 * co);
+                cc[0] = co[u].x; cc[1] = co[u].y; cc[2] = co[u].z; cc[3] = co[u].w;
+                ss[0] = si[u].x; ss[1] = si[u].y; ss[2] = si[u].z; ss[3] = si[u].w;
             }
-            lo[e >> 3][e & 7] = (_Float16)y1;
-            hi[e >> 3][e & 7] = (_Float16)y2;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float y1 = a1[e], y2 = a2[e];
+                if (rotate) {
+                    y1 = fmaf(a2[e], ss[e], a1[e] * cc[e]);
+                    y2 = fmaf(-a1[e], ss[e], a2[e] * cc[e]);
+                }
+                lo[u >> 1][4 * (u & 1) + e] = (_Float16)y1;
+                hi[u >> 1][4 * (u & 1) + e] = (_Float16)y2;
+            }
         }
         uint16_t* dst = a.dqkv + (orow0 + row) * ld3 + colbase + (int64_t)n * D + c0;
         *reinterpret_cast<half8*>(dst) = lo[0];
