@@ -465,7 +465,8 @@ lomo_status lomo_rmsnorm_backward(const lomo_half* dxn, const lomo_half* xhat, c
 lomo_status lomo_attention_backward(const lomo_half* qkv, const lomo_half* o, const lomo_half* dO, const float* lse,
                                     const float* rope_cos, const float* rope_sin, float* delta_ws, lomo_half* dqkv,
                                     int64_t B, int64_t s, int64_t n_heads, int64_t head_dim, void* stream) {
-    if (B < 0 || s < 0 || n_heads < 0 || head_dim != 128 || (s & 63) || s > (1 << 20) || n_heads > 65535 || B > 65535)
+    if (B < 0 || s < 0 || n_heads < 0 || head_dim != 128 || (s & 63) || s > (1 << 20) || n_heads > 65535 || B > 65535 ||
+        (s / 64) * n_heads * B >= (1ll << 31))
         return LOMO_ERR_SHAPE;
     if (B == 0 || s == 0 || n_heads == 0) return LOMO_OK;
     if (!qkv || !o || !dO || !lse || !delta_ws || !dqkv) return LOMO_ERR_NULL;

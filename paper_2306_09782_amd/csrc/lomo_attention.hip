@@ -109,9 +109,18 @@ __global__ __launch_bounds__(256, 2) void attention_backward_kernel(attn::Args a
     const int mhalf = g4 & 1, kh = g4 >> 1, rib = j16 >> 2, piece = j16 & 3;
     const int tr_row = 8 * kh + rib, tr_col = 16 * mhalf + 4 * piece;
 
+    // Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous run of (sequence, head) pairs so
+    // that the blocks of one head, which re-read the same q, k, v, dO rows, meet in one L2.
     const int nb = a.s / BLK;
-    const int n = blockIdx.y, b = blockIdx.z;
-    const int fixed = (MODE == 0) ? (int)blockIdx.x : nb - 1 - (int)blockIdx.x;   // heaviest blocks first
+    int pos;
+    {
+        const int G = gridDim.x, x = (int)(blockIdx.x & 7), local = (int)(blockIdx.x >> 3);
+        const int q = G >> 3, r = G & 7;
+        pos = x * q + (x < r ? x : r) + local;
+    }
+    const int head = pos / nb, within = pos - head * nb;
+    const int n = head % a.nh, b = head / a.nh;
+    const int fixed = (MODE == 0) ? within : nb - 1 - within;   // heaviest blocks first
     const int64_t ld3 = 3 * (int64_t)a.H, ldh = a.H;
     const int64_t t0 = (int64_t)b * a.s;
     const uint16_t* gq = a.qkv + (int64_t)n * D;
@@ -142,7 +151,7 @@ __global__ __launch_bounds__(256, 2) void attention_backward_kernel(attn::Args a
     __syncthreads();
     half8 fx[D / 16], fy[D / 16];
     {
-        const int row = ((MODE == 0) ? 32 * wc : 32 * wr) + l32;     // keys are MFMA columns, queries MFMA rows
+        const int row = ((MODE == 0) ? 32 * wc : 32 * wr) + l32;     // MODE 0: this wave's keys; MODE 1: its queries
 #pragma unroll
         for (int ks = 0; ks < D / 16; ++ks) {
             fx[ks] = *reinterpret_cast<const half8*>(sA + row * PD + 16 * ks + 8 * lh);
@@ -189,7 +198,8 @@ __global__ __launch_bounds__(256, 2) void attention_backward_kernel(attn::Args a
         __syncthreads();
         if (blk < last) fetch_moving(blk + 1);     // in flight while this block is multiplied
 
-        // ---- S = Q K^T and dP = dO V^T for this wave's 32 queries x 32 keys
+        // ---- S^T = K Q^T and dP^T = V dO^T for this wave's 32 keys x 32 queries: the keys are the MFMA rows, so a
+        // lane owns one query (one lse, one delta) and four consecutive keys per register group
         floatx16 accS, accP;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -199,32 +209,42 @@ __global__ __launch_bounds__(256, 2) void attention_backward_kernel(attn::Args a
 #pragma unroll
         for (int ks = 0; ks < D / 16; ++ks) {
             const int off = 16 * ks + 8 * lh;
-            if (MODE == 0) {      // moving Q_i, dO_i are the MFMA rows; K_j, V_j come from registers
-                const half8 aq = *reinterpret_cast<const half8*>(sA + (32 * wr + l32) * PD + off);
-                const half8 ad = *reinterpret_cast<const half8*>(sB + (32 * wr + l32) * PD + off);
-                accS = __builtin_amdgcn_mfma_f32_32x32x16_f16(aq, fx[ks], accS, 0, 0, 0);
-                accP = __builtin_amdgcn_mfma_f32_32x32x16_f16(ad, fy[ks], accP, 0, 0, 0);
-            } else {              // moving K_j, V_j are the MFMA columns; Q_i, dO_i come from registers
-                const half8 bk = *reinterpret_cast<const half8*>(sA + (32 * wc + l32) * PD + off);
-                const half8 bv = *reinterpret_cast<const half8*>(sB + (32 * wc + l32) * PD + off);
-                accS = __builtin_amdgcn_mfma_f32_32x32x16_f16(fx[ks], bk, accS, 0, 0, 0);
-                accP = __builtin_amdgcn_mfma_f32_32x32x16_f16(fy[ks], bv, accP, 0, 0, 0);
+            if (MODE == 0) {      // moving Q_i, dO_i come from LDS; K_j, V_j from registers
+                const half8 fq = *reinterpret_cast<const half8*>(sA + (32 * wr + l32) * PD + off);
+                const half8 fd = *reinterpret_cast<const half8*>(sB + (32 * wr + l32) * PD + off);
+                accS = __builtin_amdgcn_mfma_f32_32x32x16_f16(fx[ks], fq, accS, 0, 0, 0);
+                accP = __builtin_amdgcn_mfma_f32_32x32x16_f16(fy[ks], fd, accP, 0, 0, 0);
+            } else {              // moving K_j, V_j come from LDS; Q_i, dO_i from registers
+                const half8 fk = *reinterpret_cast<const half8*>(sA + (32 * wc + l32) * PD + off);
+                const half8 fv = *reinterpret_cast<const half8*>(sB + (32 * wc + l32) * PD + off);
+                accS = __builtin_amdgcn_mfma_f32_32x32x16_f16(fk, fx[ks], accS, 0, 0, 0);
+                accP = __builtin_amdgcn_mfma_f32_32x32x16_f16(fv, fy[ks], accP, 0, 0, 0);
             }
         }
-        // ---- P and dS in fp16, [query][key]
-        const bool diag = (MODE == 0) ? (blk == fixed) : (blk == fixed);
-        const int key = 32 * wc + l32;
+        // ---- P and dS in fp16, [query][key]: four consecutive keys per 8-byte store
+        {
+            const bool diag = blk == fixed;
+            const int qrow = 32 * wr + l32;
+            const float lq = sL[qrow], dq = sDelta[qrow];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int qrow = 32 * wr + 8 * (r >> 2) + 4 * lh + (r & 3);
-            float p = __builtin_amdgcn_exp2f(fmaf(scale_log2e, accS[r], -sL[qrow]));
-            float ds = scale * p * (accP[r] - sDelta[qrow]);
-            if (diag && key > qrow) {
-                p = 0.f;
-                ds = 0.f;
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int key0 = 32 * wc + 8 * q4 + 4 * lh;
+                half4 hp, hd;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int r = 4 * q4 + e;
+                    float p = __builtin_amdgcn_exp2f(fmaf(scale_log2e, accS[r], -lq));
+                    float ds = scale * p * (accP[r] - dq);
+                    if (diag && key0 + e > qrow) {
+                        p = 0.f;
+                        ds = 0.f;
+                    }
+                    hp[e] = (_Float16)p;
+                    hd[e] = (_Float16)ds;
+                }
+                *reinterpret_cast<half4*>(sP + qrow * PS + key0) = hp;
+                *reinterpret_cast<half4*>(sDS + qrow * PS + key0) = hd;
             }
-            reinterpret_cast<_Float16*>(sP)[qrow * PS + key] = (_Float16)p;
-            reinterpret_cast<_Float16*>(sDS)[qrow * PS + key] = (_Float16)ds;
         }
         __syncthreads();
 
@@ -336,7 +356,7 @@ hipError_t launch_attention_backward(const uint16_t* qkv, const uint16_t* o, con
     Args a;
     a.qkv = qkv; a.o = o; a.dO = dO; a.lse = lse; a.delta = delta; a.cosv = cosv; a.sinv = sinv; a.dqkv = dqkv;
     a.s = (int)s; a.nh = (int)nh; a.H = (int)(nh * D);
-    const dim3 grid((unsigned)(s / BLK), (unsigned)nh, (unsigned)B);
+    const dim3 grid((unsigned)((s / BLK) * nh * B));
     hipLaunchKernelGGL(attention_backward_kernel<0>, grid, dim3(256), LDS_BYTES, st, a);
     hipLaunchKernelGGL(attention_backward_kernel<1>, grid, dim3(256), LDS_BYTES, st, a);
     return hipGetLastError();
