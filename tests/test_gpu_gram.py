@@ -169,3 +169,27 @@ def test_norm_algorithm_setting(L):
     L.lomo_set_norm_algorithm("direct")
     with pytest.raises(L.LomoError):
         L.lomo_set_norm_algorithm(7)
+
+
+@pytest.mark.parametrize("K,N", [(8192, 8192), (8192, 22016), (22016, 8192)])
+def test_gram_llama65b_tensor_shapes(gram, K, N):
+    """The linear tensors of the 65B layer at its token count (T = 2048), where the Gram route pays most:
+    same inputs as the workload (device generator), norm against the oracle's materialised gradient."""
+    L = gram
+    T = 2048
+    X = S.normal_f16_torch(S.tensor_key(0, 3, 1, 0), (T, K), S.normal_mult(1.0), DEV)
+    dY = S.normal_f16_torch(S.tensor_key(0, 3, 1, 1), (T, N), S.normal_mult(1e-3, 65536.0), DEV)
+    acc = torch.zeros(2, dtype=torch.float64, device=DEV)
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    L.lomo_timing_enable(True)
+    L.lomo_wgrad_sqnorm(X, dY, acc[0:1], flag)
+    used = L.lomo_timing_read(L.KERNEL_FAMILIES.index("gram_sqnorm"))[1]
+    L.lomo_timing_enable(False)
+    L.lomo_set_norm_algorithm("direct")
+    L.lomo_wgrad_sqnorm(X, dY, acc[1:2], flag)
+    torch.cuda.synchronize()
+    want = O.sqnorm(O.linear_grad(X.cpu().numpy(), dY.cpu().numpy()))
+    g, d = acc.cpu().numpy()
+    assert used == 1 and int(flag.item()) == 0
+    assert abs(g / want - 1) < 1e-3 and abs(g / want - 1) < 2e-5
+    assert abs(d / want - 1) < 2e-5
