@@ -26,7 +26,7 @@ namespace attn {
 
 constexpr int D = 128;        // head width
 constexpr int BLK = 64;       // queries / keys per block
-constexpr int PD = D + 8;     // LDS pitch of a [64 x 128] fp16 tile (halves)
+constexpr int PD = D;         // LDS pitch of a [64 x 128] fp16 tile (halves): unpadded, 16-byte chunks swizzled
 constexpr int PS = BLK + 8;   // LDS pitch of a [64 x 64] fp16 tile
 constexpr int PO = D + 4;     // LDS pitch of the fp32 output tile (floats)
 constexpr int TILE = BLK * PD;
@@ -60,11 +60,17 @@ __device__ __forceinline__ void fetch_tile(u32x4 (&r)[4], const uint16_t* g, int
         r[u] = *reinterpret_cast<const u32x4*>(g + (int64_t)(c >> 4) * ld + (c & 15) * 8);
     }
 }
+// Chunk swizzle of the [64 x 128] tiles: 16-byte chunk c of row r sits at position c ^ swz(r).  Rows that
+// differ in their low two bits are 4 chunks apart (the four rows of a transposing read fall on disjoint banks,
+// and so do its two 16-column halves), rows that differ in the next two bits are 1..3 chunks apart (sixteen
+// consecutive rows read at the same column hit sixteen different chunks).
+__device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+
 __device__ __forceinline__ void stash_tile(const u32x4 (&r)[4], uint16_t* s) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int c = threadIdx.x + 256 * u;
-        *reinterpret_cast<u32x4*>(s + (c >> 4) * PD + (c & 15) * 8) = r[u];
+        *reinterpret_cast<u32x4*>(s + (c >> 4) * PD + (((c & 15) ^ swz(c >> 4)) * 8)) = r[u];
     }
 }
 
@@ -100,7 +106,7 @@ __global__ __launch_bounds__(256, 2) void attention_backward_kernel(attn::Args a
     uint16_t* sDS = sP + BLK * PS;
     float* sL = reinterpret_cast<float*>(sDS + BLK * PS);
     float* sDelta = sL + BLK;
-    float* sOut = reinterpret_cast<float*>(smem);     // [64 x PO] fp32, after the loop (over both tiles)
+    float* sOut = reinterpret_cast<float*>(smem);     // [64 x PO] fp32, after the loop (over both tiles and into sP)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wr = wave & 1, wc = wave >> 1;
@@ -108,6 +114,8 @@ __global__ __launch_bounds__(256, 2) void attention_backward_kernel(attn::Args a
     const int g4 = lane >> 4, j16 = lane & 15;
     const int mhalf = g4 & 1, kh = g4 >> 1, rib = j16 >> 2, piece = j16 & 3;
     const int tr_row = 8 * kh + rib, tr_col = 16 * mhalf + 4 * piece;
+    // swizzles of the rows a transposing read touches in the big tiles: rows 16 ks + tr_row and + 4
+    const int tr_sw0 = ((rib << 2) | (2 * kh)) << 3, tr_sw1 = ((rib << 2) | (2 * kh + 1)) << 3;
 
     // Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous run of (sequence, head) pairs so
     // that the blocks of one head, which re-read the same q, k, v, dO rows, meet in one L2.
@@ -154,8 +162,8 @@ __global__ __launch_bounds__(256, 2) void attention_backward_kernel(attn::Args a
         const int row = ((MODE == 0) ? 32 * wc : 32 * wr) + l32;     // MODE 0: this wave's keys; MODE 1: its queries
 #pragma unroll
         for (int ks = 0; ks < D / 16; ++ks) {
-            fx[ks] = *reinterpret_cast<const half8*>(sA + row * PD + 16 * ks + 8 * lh);
-            fy[ks] = *reinterpret_cast<const half8*>(sB + row * PD + 16 * ks + 8 * lh);
+            fx[ks] = *reinterpret_cast<const half8*>(sA + row * PD + ((16 * ks + 8 * lh) ^ (swz(row) << 3)));
+            fy[ks] = *reinterpret_cast<const half8*>(sB + row * PD + ((16 * ks + 8 * lh) ^ (swz(row) << 3)));
         }
     }
 
@@ -208,15 +216,16 @@ __global__ __launch_bounds__(256, 2) void attention_backward_kernel(attn::Args a
         }
 #pragma unroll
         for (int ks = 0; ks < D / 16; ++ks) {
-            const int off = 16 * ks + 8 * lh;
+            const int mrow = ((MODE == 0) ? 32 * wr : 32 * wc) + l32;
+            const int off = mrow * PD + ((16 * ks + 8 * lh) ^ (swz(mrow) << 3));
             if (MODE == 0) {      // moving Q_i, dO_i come from LDS; K_j, V_j from registers
-                const half8 fq = *reinterpret_cast<const half8*>(sA + (32 * wr + l32) * PD + off);
-                const half8 fd = *reinterpret_cast<const half8*>(sB + (32 * wr + l32) * PD + off);
+                const half8 fq = *reinterpret_cast<const half8*>(sA + off);
+                const half8 fd = *reinterpret_cast<const half8*>(sB + off);
                 accS = __builtin_amdgcn_mfma_f32_32x32x16_f16(fx[ks], fq, accS, 0, 0, 0);
                 accP = __builtin_amdgcn_mfma_f32_32x32x16_f16(fy[ks], fd, accP, 0, 0, 0);
             } else {              // moving K_j, V_j come from LDS; Q_i, dO_i from registers
-                const half8 fk = *reinterpret_cast<const half8*>(sA + (32 * wc + l32) * PD + off);
-                const half8 fv = *reinterpret_cast<const half8*>(sB + (32 * wc + l32) * PD + off);
+                const half8 fk = *reinterpret_cast<const half8*>(sA + off);
+                const half8 fv = *reinterpret_cast<const half8*>(sB + off);
                 accS = __builtin_amdgcn_mfma_f32_32x32x16_f16(fk, fx[ks], accS, 0, 0, 0);
                 accP = __builtin_amdgcn_mfma_f32_32x32x16_f16(fv, fy[ks], accP, 0, 0, 0);
             }
@@ -258,10 +267,10 @@ __global__ __launch_bounds__(256, 2) void attention_backward_kernel(attn::Args a
                 const half8 bD = read_tr8(pd, pd + 4 * PS);
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
-                    const uint16_t* po = sB + (16 * ks + tr_row) * PD + 64 * wr + 32 * i + tr_col;
-                    const uint16_t* pq = sA + (16 * ks + tr_row) * PD + 64 * wr + 32 * i + tr_col;
-                    acc0[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(read_tr8(po, po + 4 * PD), bP, acc0[i], 0, 0, 0);
-                    acc1[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(read_tr8(pq, pq + 4 * PD), bD, acc1[i], 0, 0, 0);
+                    const int col = 64 * wr + 32 * i + tr_col;
+                    const int o0 = (16 * ks + tr_row) * PD + (col ^ tr_sw0), o1 = (16 * ks + tr_row + 4) * PD + (col ^ tr_sw1);
+                    acc0[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(read_tr8(sB + o0, sB + o1), bP, acc0[i], 0, 0, 0);
+                    acc1[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(read_tr8(sA + o0, sA + o1), bD, acc1[i], 0, 0, 0);
                 }
             }
         } else {
@@ -271,8 +280,9 @@ __global__ __launch_bounds__(256, 2) void attention_backward_kernel(attn::Args a
                 const half8 bD = *reinterpret_cast<const half8*>(sDS + (32 * wc + l32) * PS + 16 * ks + 8 * lh);
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
-                    const uint16_t* pk = sA + (16 * ks + tr_row) * PD + 64 * wr + 32 * i + tr_col;
-                    acc0[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(read_tr8(pk, pk + 4 * PD), bD, acc0[i], 0, 0, 0);
+                    const int col = 64 * wr + 32 * i + tr_col;
+                    const int o0 = (16 * ks + tr_row) * PD + (col ^ tr_sw0), o1 = (16 * ks + tr_row + 4) * PD + (col ^ tr_sw1);
+                    acc0[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(read_tr8(sA + o0, sA + o1), bD, acc0[i], 0, 0, 0);
                 }
             }
         }
