@@ -107,7 +107,7 @@ lomo_status lomo_embedding_grouping(const int32_t* ids, int64_t T, int64_t V, vo
     EmbeddingWs w{};
     if (T > 0) w = carve_embedding_ws(ws, T);
     w.perm = perm; w.unique_ids = unique_ids; w.seg_offsets = seg_offsets; w.n_unique = n_unique;
-    return from_hip(launch_embedding_grouping(ids, T, w, st));
+    return from_hip(launch_embedding_grouping(ids, T, V, w, st));
 }
 
 lomo_status lomo_embedding_sqnorm(const int32_t* ids, const lomo_half* dY, int64_t T, int64_t H, int64_t V, void* ws,
@@ -119,7 +119,7 @@ lomo_status lomo_embedding_sqnorm(const int32_t* ids, const lomo_half* dY, int64
     hipStream_t st = static_cast<hipStream_t>(stream);
     EmbeddingWs w = carve_embedding_ws(ws, T);
     ScopedTiming timing(LOMO_KERNEL_EMBEDDING, st);
-    hipError_t e = launch_embedding_grouping(ids, T, w, st);
+    hipError_t e = launch_embedding_grouping(ids, T, V, w, st);
     if (e != hipSuccess) return LOMO_ERR_LAUNCH;
     return from_hip(launch_embedding_rows(dY, nullptr, T, H, w, 0, 0.f, acc, overflow_flag, nullptr, st));
 }
@@ -135,7 +135,7 @@ lomo_status lomo_embedding_update(const int32_t* ids, const lomo_half* dY, lomo_
     hipStream_t st = static_cast<hipStream_t>(stream);
     EmbeddingWs w = carve_embedding_ws(ws, T);
     ScopedTiming timing(LOMO_KERNEL_EMBEDDING, st);
-    hipError_t e = launch_embedding_grouping(ids, T, w, st);
+    hipError_t e = launch_embedding_grouping(ids, T, V, w, st);
     if (e != hipSuccess) return LOMO_ERR_LAUNCH;
     return from_hip(launch_embedding_rows(dY, W, T, H, w, 1, step_size(lr, inv_loss_scale, clip_coef), nullptr, nullptr,
                                           overflow_flag, st));
@@ -242,7 +242,7 @@ lomo_status lomo_step_norm_pass(const lomo_tensor* tensors, int64_t n, double* a
         } else if (t.kind == LOMO_TENSOR_EMBEDDING) {
             EmbeddingWs w = carve_embedding_ws(ws, t.T);
             ScopedTiming timing(LOMO_KERNEL_EMBEDDING, st);
-            if (launch_embedding_grouping(t.ids, t.T, w, st) != hipSuccess) return LOMO_ERR_LAUNCH;
+            if (launch_embedding_grouping(t.ids, t.T, t.N, w, st) != hipSuccess) return LOMO_ERR_LAUNCH;
             if (launch_embedding_rows(t.dY, nullptr, t.T, t.K, w, 0, 0.f, acc, flags + i, nullptr, st) != hipSuccess)
                 return LOMO_ERR_LAUNCH;
         } else {
@@ -300,7 +300,7 @@ static lomo_status update_pass(const lomo_tensor* tensors, int64_t n, float s, c
         if (t.kind == LOMO_TENSOR_EMBEDDING) {
             EmbeddingWs w = carve_embedding_ws(ws, t.T);
             ScopedTiming timing(LOMO_KERNEL_EMBEDDING, st);
-            if (launch_embedding_grouping(t.ids, t.T, w, st) != hipSuccess) return LOMO_ERR_LAUNCH;
+            if (launch_embedding_grouping(t.ids, t.T, t.N, w, st) != hipSuccess) return LOMO_ERR_LAUNCH;
             if (launch_embedding_rows(t.dY, t.W, t.T, t.K, w, 1, s, nullptr, nullptr, step_flag, st, 0.f, 0.f, s_dev) !=
                 hipSuccess)
                 return LOMO_ERR_LAUNCH;
@@ -408,7 +408,7 @@ lomo_status lomo_step_update_pass_clip_value(const lomo_tensor* tensors, int64_t
         if (t.kind == LOMO_TENSOR_EMBEDDING) {
             EmbeddingWs w = carve_embedding_ws(ws, t.T);
             ScopedTiming timing(LOMO_KERNEL_EMBEDDING, st);
-            if (launch_embedding_grouping(t.ids, t.T, w, st) != hipSuccess) return LOMO_ERR_LAUNCH;
+            if (launch_embedding_grouping(t.ids, t.T, t.N, w, st) != hipSuccess) return LOMO_ERR_LAUNCH;
             if (launch_embedding_rows(t.dY, t.W, t.T, t.K, w, 2, inv_loss_scale, nullptr, flags + i, nullptr, st, lr,
                                       clip_value) != hipSuccess)
                 return LOMO_ERR_LAUNCH;

@@ -78,7 +78,7 @@ struct EmbeddingWs {          // carved out of the caller's workspace
 };
 size_t embedding_ws_bytes(int64_t T, int64_t H);
 EmbeddingWs carve_embedding_ws(void* ws, int64_t T);
-hipError_t launch_embedding_grouping(const int32_t* ids, int64_t T, const EmbeddingWs& w, hipStream_t st);
+hipError_t launch_embedding_grouping(const int32_t* ids, int64_t T, int64_t V, const EmbeddingWs& w, hipStream_t st);
 // mode 0: squared norm into acc (+ flag_out); mode 1: in-place row update honouring flag_in;
 // mode 2: clip-by-value update, g = clamp(sum * s, -clipv, clipv), W -= lr * g, raising flag_out
 // (and leaving the element alone) where the sum is not finite.  In mode 2, s is 1 / loss scale.

@@ -125,6 +125,124 @@ __global__ __launch_bounds__(SORT_NT) void emb_segments(const uint64_t* __restri
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Small batches (at most 8192 positions, id * 8192 below 2^32): keys, sort and segments in ONE workgroup.
+// 32-bit keys id << shift | position; every thread keeps 8 consecutive elements in registers.  The sort is a
+// least-significant-bit-first radix sort over the id bits, one stable split per bit: elements whose bit is 0
+// keep their order and move to the front, the others follow in order (a workgroup-wide exclusive scan of the
+// per-thread zero counts gives every element its new index; the exchange goes through LDS).  Positions start
+// in ascending order and every split is stable, so equal ids end up in ascending position order.
+// ------------------------------------------------------------------------------------------
+
+constexpr int GS_KPT = 8;
+constexpr int GS_MAX = 8192;
+
+__global__ __launch_bounds__(1024) void emb_group_small(const int32_t* __restrict__ ids, int T, int N, int shift,
+                                                        int id_bits, int32_t* __restrict__ perm,
+                                                        int32_t* __restrict__ unique_ids, int32_t* __restrict__ seg_offsets,
+                                                        int32_t* __restrict__ n_unique) {
+    __shared__ uint32_t sk[GS_MAX];
+    __shared__ int32_t wsum[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nw = (int)(blockDim.x >> 6);
+    const int e0 = tid * GS_KPT;
+    uint32_t key[GS_KPT];
+#pragma unroll
+    for (int r = 0; r < GS_KPT; ++r) {
+        const int e = e0 + r;
+        key[r] = (e < T) ? (((uint32_t)ids[e] << shift) | (uint32_t)e) : 0xffffffffu;   // padding: every bit set
+    }
+    for (int bit = shift; bit < shift + id_bits; ++bit) {
+        int zeros = 0;
+#pragma unroll
+        for (int r = 0; r < GS_KPT; ++r) zeros += ((key[r] >> bit) & 1u) ? 0 : 1;
+        int v = zeros;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_up(v, off, 64);
+            if (lane >= off) v += o;
+        }
+        if (lane == 63) wsum[wave] = v;
+        __syncthreads();     // also: everybody has read its keys of the previous split out of sk
+        int zbase = v - zeros, total_zeros = 0;
+        for (int w = 0; w < nw; ++w) {
+            zbase += w < wave ? wsum[w] : 0;
+            total_zeros += wsum[w];
+        }
+        int z = zbase;       // zeros before the current element
+#pragma unroll
+        for (int r = 0; r < GS_KPT; ++r) {
+            const bool one = (key[r] >> bit) & 1u;
+            sk[one ? total_zeros + (e0 + r - z) : z] = key[r];
+            z += one ? 0 : 1;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < GS_KPT; ++r) key[r] = sk[e0 + r];
+    }
+    __syncthreads();
+    // ---- segments: head flags, exclusive scan, outputs
+    const uint32_t mask = (1u << shift) - 1u;
+    uint32_t prev = (uint32_t)__shfl_up((int)key[GS_KPT - 1], 1, 64);
+    if (lane == 63) sk[wave] = key[GS_KPT - 1];
+    __syncthreads();
+    if (lane == 0) prev = wave > 0 ? sk[wave - 1] : 0u;
+    int heads = 0;
+    bool head[GS_KPT];
+#pragma unroll
+    for (int r = 0; r < GS_KPT; ++r) {
+        const int e = e0 + r;
+        const uint32_t before = r == 0 ? prev : key[r - 1];
+        head[r] = e < T && (e == 0 || (before >> shift) != (key[r] >> shift));
+        heads += head[r] ? 1 : 0;
+    }
+    int v = heads;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(v, off, 64);
+        if (lane >= off) v += o;
+    }
+    if (lane == 63) wsum[wave] = v;
+    __syncthreads();
+    int base = 0, total = 0;
+    for (int w = 0; w < nw; ++w) {
+        base += w < wave ? wsum[w] : 0;
+        total += wsum[w];
+    }
+    int idx = base + v - heads;
+#pragma unroll
+    for (int r = 0; r < GS_KPT; ++r) {
+        const int e = e0 + r;
+        if (e < T) perm[e] = (int32_t)(key[r] & mask);
+        if (head[r]) {
+            unique_ids[idx] = (int32_t)(key[r] >> shift);
+            seg_offsets[idx] = e;
+            ++idx;
+        }
+    }
+    if (tid == 0) {
+        n_unique[0] = total;
+        seg_offsets[total] = T;
+    }
+}
+
+// Whether the one-workgroup route applies: N = padded size (power of two, 512..8192), ids < V fit above `shift` bits.
+static inline bool group_small_plan(int64_t T, int64_t V, int* N, int* shift, int* id_bits) {
+    if (T <= 0 || T > GS_MAX || V <= 0) return false;
+    int64_t n = next_pow2(T);
+    if (n < GS_KPT * 64) n = GS_KPT * 64;
+    int sh = 0;
+    while ((1ll << sh) < n) ++sh;
+    if ((V - 1) >> (32 - sh) != 0) return false;                  // id << shift must stay below 2^32
+    if ((((V - 1) << sh) | (n - 1)) >= 0xffffffffll) return false;   // all-ones is the padding key
+    int ib = 1;
+    while ((1ll << ib) < V) ++ib;
+    *N = (int)n;
+    *shift = sh;
+    *id_bits = ib;
+    return true;
+}
+
 static inline size_t emb_partials_bytes(int64_t H) {
     const int64_t slabs = (H + 511) / 512 > 0 ? (H + 511) / 512 : 1;
     return align_up((size_t)512 * (size_t)slabs * sizeof(double), 256);
@@ -159,7 +277,13 @@ EmbeddingWs carve_embedding_ws(void* ws, int64_t T) {
     return w;
 }
 
-hipError_t launch_embedding_grouping(const int32_t* ids, int64_t T, const EmbeddingWs& w, hipStream_t st) {
+hipError_t launch_embedding_grouping(const int32_t* ids, int64_t T, int64_t V, const EmbeddingWs& w, hipStream_t st) {
+    int N = 0, shift = 0, id_bits = 0;
+    if (group_small_plan(T, V, &N, &shift, &id_bits)) {
+        hipLaunchKernelGGL(emb_group_small, dim3(1), dim3((unsigned)(N / GS_KPT)), 0, st, ids, (int)T, N, shift, id_bits,
+                           w.perm, w.unique_ids, w.seg_offsets, w.n_unique);
+        return hipGetLastError();
+    }
     if (T == 0) {   // empty batch: zero segments
         hipLaunchKernelGGL(emb_segments, dim3(1), dim3(SORT_NT), 0, st, w.keys, T, w.perm, w.unique_ids, w.seg_offsets,
                            w.n_unique);
