@@ -105,7 +105,7 @@ lomo_status lomo_embedding_grouping(const int32_t* ids, int64_t T, int64_t V, vo
             return LOMO_ERR_WORKSPACE;
     }
     EmbeddingWs w{};
-    if (T > 0) w = carve_embedding_ws(ws, T);
+    if (T > 0) w = carve_embedding_ws(ws, T, 0);
     w.perm = perm; w.unique_ids = unique_ids; w.seg_offsets = seg_offsets; w.n_unique = n_unique;
     return from_hip(launch_embedding_grouping(ids, T, V, w, st));
 }
@@ -117,11 +117,11 @@ lomo_status lomo_embedding_sqnorm(const int32_t* ids, const lomo_half* dY, int64
     if (!acc) return LOMO_ERR_NULL;
     if (T == 0 || H == 0) return LOMO_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    EmbeddingWs w = carve_embedding_ws(ws, T);
+    EmbeddingWs w = carve_embedding_ws(ws, T, H);
     ScopedTiming timing(LOMO_KERNEL_EMBEDDING, st);
     hipError_t e = launch_embedding_grouping(ids, T, V, w, st);
     if (e != hipSuccess) return LOMO_ERR_LAUNCH;
-    return from_hip(launch_embedding_rows(dY, nullptr, T, H, w, 0, 0.f, acc, overflow_flag, nullptr, st));
+    return from_hip(launch_embedding_rows(ids, dY, nullptr, T, H, w, 0, 0.f, acc, overflow_flag, nullptr, st));
 }
 
 lomo_status lomo_embedding_update(const int32_t* ids, const lomo_half* dY, lomo_half* W, int64_t T, int64_t H, int64_t V,
@@ -133,11 +133,11 @@ lomo_status lomo_embedding_update(const int32_t* ids, const lomo_half* dY, lomo_
     if (!W) return LOMO_ERR_NULL;
     if (misaligned(W)) return LOMO_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    EmbeddingWs w = carve_embedding_ws(ws, T);
+    EmbeddingWs w = carve_embedding_ws(ws, T, H);
     ScopedTiming timing(LOMO_KERNEL_EMBEDDING, st);
     hipError_t e = launch_embedding_grouping(ids, T, V, w, st);
     if (e != hipSuccess) return LOMO_ERR_LAUNCH;
-    return from_hip(launch_embedding_rows(dY, W, T, H, w, 1, step_size(lr, inv_loss_scale, clip_coef), nullptr, nullptr,
+    return from_hip(launch_embedding_rows(ids, dY, W, T, H, w, 1, step_size(lr, inv_loss_scale, clip_coef), nullptr, nullptr,
                                           overflow_flag, st));
 }
 
@@ -240,10 +240,10 @@ lomo_status lomo_step_norm_pass(const lomo_tensor* tensors, int64_t n, double* a
             if (dma_eligible(a)) grouped.push_back(a);
             else if (launch_wgrad_sqnorm(a, st) != hipSuccess) return LOMO_ERR_LAUNCH;
         } else if (t.kind == LOMO_TENSOR_EMBEDDING) {
-            EmbeddingWs w = carve_embedding_ws(ws, t.T);
+            EmbeddingWs w = carve_embedding_ws(ws, t.T, t.K);
             ScopedTiming timing(LOMO_KERNEL_EMBEDDING, st);
             if (launch_embedding_grouping(t.ids, t.T, t.N, w, st) != hipSuccess) return LOMO_ERR_LAUNCH;
-            if (launch_embedding_rows(t.dY, nullptr, t.T, t.K, w, 0, 0.f, acc, flags + i, nullptr, st) != hipSuccess)
+            if (launch_embedding_rows(t.ids, t.dY, nullptr, t.T, t.K, w, 0, 0.f, acc, flags + i, nullptr, st) != hipSuccess)
                 return LOMO_ERR_LAUNCH;
         } else {
             ScopedTiming timing(LOMO_KERNEL_VECTOR, st);
@@ -298,10 +298,10 @@ static lomo_status update_pass(const lomo_tensor* tensors, int64_t n, float s, c
         const lomo_tensor& t = tensors[i];
         if (t.T == 0 || t.K == 0 || t.N == 0) continue;
         if (t.kind == LOMO_TENSOR_EMBEDDING) {
-            EmbeddingWs w = carve_embedding_ws(ws, t.T);
+            EmbeddingWs w = carve_embedding_ws(ws, t.T, t.K);
             ScopedTiming timing(LOMO_KERNEL_EMBEDDING, st);
             if (launch_embedding_grouping(t.ids, t.T, t.N, w, st) != hipSuccess) return LOMO_ERR_LAUNCH;
-            if (launch_embedding_rows(t.dY, t.W, t.T, t.K, w, 1, s, nullptr, nullptr, step_flag, st, 0.f, 0.f, s_dev) !=
+            if (launch_embedding_rows(t.ids, t.dY, t.W, t.T, t.K, w, 1, s, nullptr, nullptr, step_flag, st, 0.f, 0.f, s_dev) !=
                 hipSuccess)
                 return LOMO_ERR_LAUNCH;
         } else if (t.kind == LOMO_TENSOR_VECTOR) {
@@ -406,10 +406,10 @@ lomo_status lomo_step_update_pass_clip_value(const lomo_tensor* tensors, int64_t
         const lomo_tensor& t = tensors[i];
         if (t.T == 0 || t.K == 0 || t.N == 0) continue;
         if (t.kind == LOMO_TENSOR_EMBEDDING) {
-            EmbeddingWs w = carve_embedding_ws(ws, t.T);
+            EmbeddingWs w = carve_embedding_ws(ws, t.T, t.K);
             ScopedTiming timing(LOMO_KERNEL_EMBEDDING, st);
             if (launch_embedding_grouping(t.ids, t.T, t.N, w, st) != hipSuccess) return LOMO_ERR_LAUNCH;
-            if (launch_embedding_rows(t.dY, t.W, t.T, t.K, w, 2, inv_loss_scale, nullptr, flags + i, nullptr, st, lr,
+            if (launch_embedding_rows(t.ids, t.dY, t.W, t.T, t.K, w, 2, inv_loss_scale, nullptr, flags + i, nullptr, st, lr,
                                       clip_value) != hipSuccess)
                 return LOMO_ERR_LAUNCH;
         } else if (t.kind == LOMO_TENSOR_VECTOR) {

@@ -74,16 +74,17 @@ struct EmbeddingWs {          // carved out of the caller's workspace
     int32_t* unique_ids;      // [T]
     int32_t* seg_offsets;     // [T + 1]
     int32_t* n_unique;        // [1]
-    double* partials;         // [512 * ceil(H / 512)] per-workgroup shares of the squared norm
+    double* partials;         // per-wave / per-workgroup shares of the squared norm
+    float* chunk_rows;        // [2 * ceil(T / 16)][H] fp32 partial sums of runs that cross chunk boundaries
 };
 size_t embedding_ws_bytes(int64_t T, int64_t H);
-EmbeddingWs carve_embedding_ws(void* ws, int64_t T);
+EmbeddingWs carve_embedding_ws(void* ws, int64_t T, int64_t H);
 hipError_t launch_embedding_grouping(const int32_t* ids, int64_t T, int64_t V, const EmbeddingWs& w, hipStream_t st);
 // mode 0: squared norm into acc (+ flag_out); mode 1: in-place row update honouring flag_in;
 // mode 2: clip-by-value update, g = clamp(sum * s, -clipv, clipv), W -= lr * g, raising flag_out
 // (and leaving the element alone) where the sum is not finite.  In mode 2, s is 1 / loss scale.
-hipError_t launch_embedding_rows(const uint16_t* dY, uint16_t* W, int64_t T, int64_t H, const EmbeddingWs& w,
-                                 int mode, float s, double* acc, int32_t* flag_out, const int32_t* flag_in,
+hipError_t launch_embedding_rows(const int32_t* ids, const uint16_t* dY, uint16_t* W, int64_t T, int64_t H,
+                                 const EmbeddingWs& w, int mode, float s, double* acc, int32_t* flag_out, const int32_t* flag_in,
                                  hipStream_t st, float lr = 0.f, float clipv = 0.f, const float* s_dev = nullptr);
 
 size_t vector_ws_bytes(int64_t T, int64_t H);

@@ -243,9 +243,17 @@ static inline bool group_small_plan(int64_t T, int64_t V, int* N, int* shift, in
     return true;
 }
 
-static inline size_t emb_partials_bytes(int64_t H) {
-    const int64_t slabs = (H + 511) / 512 > 0 ? (H + 511) / 512 : 1;
-    return align_up((size_t)512 * (size_t)slabs * sizeof(double), 256);
+// Rows are summed in chunks of EMB_CHUNK sorted positions (one wave per chunk and 512-column slab).
+constexpr int EMB_CHUNK = 16;
+constexpr int EMB_COLS = 512;      // 64 lanes x 8 halves
+constexpr int EMB_FIX_GX = 128;    // workgroups of the fix-up kernel along the segment axis (64 segments per trip)
+
+static inline int64_t emb_chunks(int64_t T) { return (T + EMB_CHUNK - 1) / EMB_CHUNK; }
+static inline int64_t emb_slabs(int64_t H) { return H > 0 ? (H + EMB_COLS - 1) / EMB_COLS : 1; }
+static inline int64_t emb_chunk_blocks(int64_t T) { return (emb_chunks(T) + 3) / 4; }     // four waves per workgroup
+
+static inline size_t emb_partials_bytes(int64_t T, int64_t H) {
+    return align_up((size_t)(emb_chunk_blocks(T) + EMB_FIX_GX) * (size_t)emb_slabs(H) * sizeof(double), 256);
 }
 
 size_t embedding_ws_bytes(int64_t T, int64_t H) {
@@ -255,11 +263,12 @@ size_t embedding_ws_bytes(int64_t T, int64_t H) {
     b += align_up((size_t)T * 4, 256) * 2;         // perm, unique_ids
     b += align_up((size_t)(T + 1) * 4, 256);       // seg_offsets
     b += 256;                                      // n_unique
-    b += emb_partials_bytes(H);                    // per-workgroup shares of the squared norm
+    b += emb_partials_bytes(T, H);                 // per-wave / per-workgroup shares of the squared norm
+    b += align_up((size_t)emb_chunks(T) * 2 * (size_t)H * sizeof(float), 256);   // partial sums of runs that cross chunks
     return b;
 }
 
-EmbeddingWs carve_embedding_ws(void* ws, int64_t T) {
+EmbeddingWs carve_embedding_ws(void* ws, int64_t T, int64_t H) {
     EmbeddingWs w;
     char* p = static_cast<char*>(ws);
     const int64_t Tpad = next_pow2(T);
@@ -274,6 +283,8 @@ EmbeddingWs carve_embedding_ws(void* ws, int64_t T) {
     w.n_unique = reinterpret_cast<int32_t*>(p);
     p += 256;
     w.partials = reinterpret_cast<double*>(p);
+    p += emb_partials_bytes(T, H);
+    w.chunk_rows = reinterpret_cast<float*>(p);
     return w;
 }
 
@@ -308,7 +319,15 @@ hipError_t launch_embedding_grouping(const int32_t* ids, int64_t T, int64_t V, c
 }
 
 // ------------------------------------------------------------------------------------------
-// Embedding rows: fp32 segment sums in a fixed order.
+// Embedding rows: fp32 segment sums in a fixed order, independent of how skewed the token ids are.
+//
+// Pass A (emb_chunk_kernel): the sorted positions are cut into chunks of 16; one wave owns a chunk and a
+// 512-column slab, requests its 16 rows at once and adds them in order.  A run of equal ids that lies inside
+// the chunk is a whole segment and is finished on the spot (norm share or row update).  A run that reaches
+// the chunk's first or last position and continues in the neighbouring chunk is stored as an fp32 partial row:
+// slot 0 for the run that came from the previous chunk, slot 1 for the run that goes on into the next one.
+// Pass B (emb_fixup_kernel): every segment that spans chunks adds its partial rows in chunk order (eight waves
+// interleaved, then a fixed tree) and is finished.  The order of every sum depends on the ids alone.
 // ------------------------------------------------------------------------------------------
 
 constexpr int ROW_NT = 256;
@@ -321,26 +340,125 @@ __device__ __forceinline__ float block_sum_256(float v, float* red) {
     return (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-// Workgroups stride over segments; each handles one 512-column slab.  The eight waves of a workgroup
-// take the segment's rows round-robin (wave w: rows beg + w, beg + w + 8, ...), each summing in
-// ascending position order; the eight partial sums are then added pairwise in a fixed tree.  The
-// order depends only on the input, never on scheduling, so results are bit-reproducible, and a hot
-// token's long segment costs an eighth of a serial walk.
-constexpr int EMB_COLS = 512;   // 64 lanes x 8 halves
+// What happens to a finished segment sum g (8 columns of this lane): MODE 0 squared norm + overflow test,
+// MODE 1 row update W <- rne16(W - s g), MODE 2 clip-by-value update (s = 1 / loss scale).
+template <int MODE>
+__device__ __forceinline__ void emb_finish_row(const float (&g)[8], uint16_t* __restrict__ W, int64_t row_off, bool active,
+                                               float s, float lr, float clipv, float& sq, bool& bad) {
+    if (MODE == 0) {
+        uint32_t worst = 0u;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            sq = fmaf(g[e], g[e], sq);
+            const uint32_t mag = __float_as_uint(g[e]) & 0x7fffffffu;
+            worst = mag > worst ? mag : worst;
+        }
+        bad |= worst >= 0x7f800000u;
+    } else if (active) {
+        half8* p = reinterpret_cast<half8*>(W + row_off);
+        const half8 w = *p;
+        half8 o;
+        if (MODE == 1) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (_Float16)fmaf(-s, g[e], (float)w[e]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float gq = g[e] * s;
+                const bool fin = (__float_as_uint(gq) & 0x7f800000u) != 0x7f800000u;
+                const float gc = fminf(fmaxf(gq, -clipv), clipv);
+                o[e] = fin ? (_Float16)fmaf(-lr, gc, (float)w[e]) : w[e];
+                bad |= !fin;
+            }
+        }
+        *p = o;
+    }
+}
+
+template <int MODE>
+__global__ __launch_bounds__(ROW_NT) void emb_chunk_kernel(const int32_t* __restrict__ ids, const uint16_t* __restrict__ dY,
+                                                           uint16_t* __restrict__ W, int T, int64_t H,
+                                                           const int32_t* __restrict__ perm, float s,
+                                                           float* __restrict__ chunk_rows, double* __restrict__ partials,
+                                                           int32_t* __restrict__ flag_out, const int32_t* __restrict__ flag_in,
+                                                           float lr, float clipv, const float* __restrict__ s_dev) {
+    if (MODE == 1 && flag_in != nullptr && flag_in[0] != 0) return;
+    if (MODE == 1 && s_dev != nullptr) s = s_dev[0];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int chunk = blockIdx.x * 4 + wave;
+    const int64_t col = (int64_t)blockIdx.y * EMB_COLS + lane * 8;
+    const bool active = col < H;
+    const int nchunks = (T + EMB_CHUNK - 1) / EMB_CHUNK;
+    float sq = 0.f;
+    bool bad = false;
+    if (chunk < nchunks) {
+        const int r0 = chunk * EMB_CHUNK;
+        const int n = (T - r0 < EMB_CHUNK) ? (T - r0) : EMB_CHUNK;
+        // lanes 0..17 look up (position, id) of the sorted entries r0 - 1 .. r0 + 16; -1 where there is none
+        int myp = -1, myid = -1;
+        {
+            const int idx = r0 - 1 + lane;
+            if (lane < EMB_CHUNK + 2 && idx >= 0 && idx < T) {
+                myp = perm[idx];
+                myid = ids[myp];
+            }
+        }
+        half8 v[EMB_CHUNK];
+#pragma unroll
+        for (int u = 0; u < EMB_CHUNK; ++u) {
+            const int p = __builtin_amdgcn_readlane(myp, u + 1);
+            if (u < n && active) v[u] = *reinterpret_cast<const half8*>(dY + (int64_t)p * H + col);
+        }
+        const int id_prev = __builtin_amdgcn_readlane(myid, 0);
+        float g[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) g[e] = 0.f;
+        bool first = true;
+#pragma unroll
+        for (int u = 0; u < EMB_CHUNK; ++u) {
+            if (u < n) {      // uniform
+                if (active) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) g[e] += (float)v[u][e];
+                }
+                const int id_u = __builtin_amdgcn_readlane(myid, u + 1);
+                const int id_n = __builtin_amdgcn_readlane(myid, u + 2);      // -1 past the end of the batch
+                if (u == n - 1 || id_n != id_u) {                             // the run ends here
+                    const bool from_prev = first && id_prev == id_u;
+                    const bool to_next = u == n - 1 && id_n == id_u;
+                    if (!from_prev && !to_next) {
+                        emb_finish_row<MODE>(g, W, (int64_t)id_u * H + col, active, s, lr, clipv, sq, bad);
+                    } else if (active) {
+                        float4* dst = reinterpret_cast<float4*>(chunk_rows + ((int64_t)chunk * 2 + (from_prev ? 0 : 1)) * H + col);
+                        dst[0] = make_float4(g[0], g[1], g[2], g[3]);
+                        dst[1] = make_float4(g[4], g[5], g[6], g[7]);
+                    }
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) g[e] = 0.f;
+                    first = false;
+                }
+            }
+        }
+    }
+    if (MODE == 0) {      // one share per workgroup: the four waves added in order
+        __shared__ float red[4];
+        const float total = block_sum_256(sq, red);
+        if (threadIdx.x == 0) partials[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = (double)total;
+    }
+    if (MODE != 1 && flag_out != nullptr && __any(bad) && lane == 0) atomicOr(flag_out, 1);
+}
+
 constexpr int EMB_NT = 512;     // 8 waves
 constexpr int EMB_W = EMB_NT / 64;
 
-constexpr int EMB_MAX_GX = 512;    // workgroups along the segment axis; each strides over segments
-
 template <int MODE>
-__global__ __launch_bounds__(EMB_NT) void emb_rows_kernel(const uint16_t* __restrict__ dY, uint16_t* __restrict__ W,
-                                                          int64_t H, const int32_t* __restrict__ perm,
-                                                          const int32_t* __restrict__ unique_ids,
-                                                          const int32_t* __restrict__ seg_offsets,
-                                                          const int32_t* __restrict__ n_unique, float s,
-                                                          double* __restrict__ partials, int32_t* __restrict__ flag_out,
-                                                          const int32_t* __restrict__ flag_in, float lr, float clipv,
-                                                          const float* __restrict__ s_dev) {
+__global__ __launch_bounds__(EMB_NT) void emb_fixup_kernel(const float* __restrict__ chunk_rows, uint16_t* __restrict__ W,
+                                                           int64_t H, const int32_t* __restrict__ unique_ids,
+                                                           const int32_t* __restrict__ seg_offsets,
+                                                           const int32_t* __restrict__ n_unique, float s,
+                                                           double* __restrict__ partials, int32_t* __restrict__ flag_out,
+                                                           const int32_t* __restrict__ flag_in, float lr, float clipv,
+                                                           const float* __restrict__ s_dev) {
     __shared__ float part[EMB_W - 1][64][9];
     if (MODE == 1 && flag_in != nullptr && flag_in[0] != 0) return;
     if (MODE == 1 && s_dev != nullptr) s = s_dev[0];
@@ -348,84 +466,72 @@ __global__ __launch_bounds__(EMB_NT) void emb_rows_kernel(const uint16_t* __rest
     const int64_t col = (int64_t)blockIdx.y * EMB_COLS + lane * 8;
     const bool active = col < H;
     const int nseg = n_unique[0];
-    double block_sq = 0.0;     // MODE 0: this workgroup's share of the squared norm (held by wave 0)
-    bool any_bad = false;
-
-    for (int seg = blockIdx.x; seg < nseg; seg += gridDim.x) {
-        const int beg = seg_offsets[seg], end = seg_offsets[seg + 1];
+    float sq = 0.f;
+    bool bad = false;
+    // 64 segments per trip: every lane looks at one segment's offsets, a ballot names the few that span chunks
+    for (int base = blockIdx.x * 64; base < nseg; base += gridDim.x * 64) {
+      int lbeg = 0, lend = 1;
+      if (base + lane < nseg) {
+          lbeg = seg_offsets[base + lane];
+          lend = seg_offsets[base + lane + 1];
+      }
+      unsigned long long spanning = __ballot(lbeg / EMB_CHUNK != (lend - 1) / EMB_CHUNK);
+      while (spanning != 0ull) {        // uniform across the workgroup: every wave computed the same mask
+        const int bit = __builtin_ctzll(spanning);
+        spanning &= spanning - 1ull;
+        const int seg = base + bit;
+        const int beg = __shfl(lbeg, bit, 64), end = __shfl(lend, bit, 64);
+        const int cf = beg / EMB_CHUNK, cl = (end - 1) / EMB_CHUNK;
         float g[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) g[e] = 0.f;
         if (active) {
-            int r = beg + wave;
-            for (; r + 7 * EMB_W < end; r += 8 * EMB_W) {      // eight rows in flight per wave
-                half8 v[8];
+            // the first chunk holds the segment's run in slot 1 (it goes on), every later chunk in slot 0
+            auto row = [&](int c) { return chunk_rows + ((int64_t)c * 2 + (c == cf ? 1 : 0)) * H + col; };
+            int c = cf + wave;
+            for (; c + 3 * EMB_W <= cl; c += 4 * EMB_W) {
+                float4 a[4][2];
 #pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    v[u] = *reinterpret_cast<const half8*>(dY + (int64_t)perm[r + EMB_W * u] * H + col);
+                for (int u = 0; u < 4; ++u) {
+                    const float4* src = reinterpret_cast<const float4*>(row(c + u * EMB_W));
+                    a[u][0] = src[0];
+                    a[u][1] = src[1];
+                }
 #pragma unroll
-                for (int u = 0; u < 8; ++u)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) g[e] += (float)v[u][e];
-            }
-            for (; r < end; r += EMB_W) {
-                const half8 v = *reinterpret_cast<const half8*>(dY + (int64_t)perm[r] * H + col);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) g[e] += (float)v[e];
-            }
-        }
-        if (end - beg > 1) {      // uniform per workgroup: a one-row segment is wave 0's alone
-            if (wave > 0) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) part[wave - 1][lane][e] = g[e];
-            }
-            __syncthreads();
-            if (wave == 0) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    g[e] = ((g[e] + part[0][lane][e]) + (part[1][lane][e] + part[2][lane][e])) +
-                           ((part[3][lane][e] + part[4][lane][e]) + (part[5][lane][e] + part[6][lane][e]));
-            }
-            __syncthreads();
-        }
-        if (wave != 0) continue;
-
-        if (MODE == 0) {
-            float sum = 0.f;
-            uint32_t worst = 0u;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                sum = fmaf(g[e], g[e], sum);
-                const uint32_t mag = __float_as_uint(g[e]) & 0x7fffffffu;
-                worst = mag > worst ? mag : worst;
-            }
-            any_bad |= worst >= 0x7f800000u;
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
-            block_sq += (double)sum;
-        } else if (active) {
-            half8* p = reinterpret_cast<half8*>(W + (int64_t)unique_ids[seg] * H + col);
-            const half8 w = *p;
-            half8 o;
-            if (MODE == 1) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) o[e] = (_Float16)fmaf(-s, g[e], (float)w[e]);
-            } else {   // clip by value: s is 1 / loss scale here
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float gq = g[e] * s;
-                    const bool fin = (__float_as_uint(gq) & 0x7f800000u) != 0x7f800000u;
-                    const float gc = fminf(fmaxf(gq, -clipv), clipv);
-                    o[e] = fin ? (_Float16)fmaf(-lr, gc, (float)w[e]) : w[e];
-                    any_bad |= !fin;
+                for (int u = 0; u < 4; ++u) {
+                    g[0] += a[u][0].x; g[1] += a[u][0].y; g[2] += a[u][0].z; g[3] += a[u][0].w;
+                    g[4] += a[u][1].x; g[5] += a[u][1].y; g[6] += a[u][1].z; g[7] += a[u][1].w;
                 }
             }
-            *p = o;
+            for (; c <= cl; c += EMB_W) {
+                const float4* src = reinterpret_cast<const float4*>(row(c));
+                const float4 a0 = src[0], a1 = src[1];
+                g[0] += a0.x; g[1] += a0.y; g[2] += a0.z; g[3] += a0.w;
+                g[4] += a1.x; g[5] += a1.y; g[6] += a1.z; g[7] += a1.w;
+            }
         }
+        if (wave > 0) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) part[wave - 1][lane][e] = g[e];
+        }
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                g[e] = ((g[e] + part[0][lane][e]) + (part[1][lane][e] + part[2][lane][e])) +
+                       ((part[3][lane][e] + part[4][lane][e]) + (part[5][lane][e] + part[6][lane][e]));
+            emb_finish_row<MODE>(g, W, (int64_t)unique_ids[seg] * H + col, active, s, lr, clipv, sq, bad);
+        }
+        __syncthreads();
+      }
     }
     if (wave != 0) return;
-    if (MODE == 0 && lane == 0) partials[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = block_sq;
-    if (MODE != 1 && flag_out != nullptr && __any(any_bad) && lane == 0) atomicOr(flag_out, 1);
+    if (MODE == 0) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) sq += __shfl_xor(sq, off, 64);
+        if (lane == 0) partials[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = (double)sq;
+    }
+    if (MODE != 1 && flag_out != nullptr && __any(bad) && lane == 0) atomicOr(flag_out, 1);
 }
 
 // Adds the per-workgroup shares in index order: the embedding's squared norm is bit-reproducible.
@@ -443,22 +549,28 @@ __global__ __launch_bounds__(ROW_NT) void emb_finish_sqnorm(const double* __rest
     if (threadIdx.x == 0) atomicAdd(acc, red[0]);
 }
 
-hipError_t launch_embedding_rows(const uint16_t* dY, uint16_t* W, int64_t T, int64_t H, const EmbeddingWs& w, int mode,
-                                 float s, double* acc, int32_t* flag_out, const int32_t* flag_in, hipStream_t st,
-                                 float lr, float clipv, const float* s_dev) {
-    const unsigned gx = (unsigned)(T < EMB_MAX_GX ? T : EMB_MAX_GX);
-    const dim3 grid(gx, (unsigned)((H + EMB_COLS - 1) / EMB_COLS));
+hipError_t launch_embedding_rows(const int32_t* ids, const uint16_t* dY, uint16_t* W, int64_t T, int64_t H,
+                                 const EmbeddingWs& w, int mode, float s, double* acc, int32_t* flag_out,
+                                 const int32_t* flag_in, hipStream_t st, float lr, float clipv, const float* s_dev) {
+    const dim3 gridA((unsigned)emb_chunk_blocks(T), (unsigned)emb_slabs(H));
+    const int64_t tripsB = (T + 63) / 64;
+    const dim3 gridB((unsigned)(tripsB < EMB_FIX_GX ? tripsB : EMB_FIX_GX), (unsigned)emb_slabs(H));
+    double* partB = w.partials + (int64_t)gridA.x * gridA.y;
+#define LOMO_EMB_LAUNCH(M)                                                                                              \
+    hipLaunchKernelGGL(emb_chunk_kernel<M>, gridA, dim3(ROW_NT), 0, st, ids, dY, W, (int)T, H, w.perm, s, w.chunk_rows, \
+                       w.partials, flag_out, flag_in, lr, clipv, s_dev);                                                \
+    hipLaunchKernelGGL(emb_fixup_kernel<M>, gridB, dim3(EMB_NT), 0, st, w.chunk_rows, W, H, w.unique_ids, w.seg_offsets, \
+                       w.n_unique, s, partB, flag_out, flag_in, lr, clipv, s_dev);
     if (mode == 0) {
-        hipLaunchKernelGGL(emb_rows_kernel<0>, grid, dim3(EMB_NT), 0, st, dY, W, H, w.perm, w.unique_ids, w.seg_offsets,
-                           w.n_unique, s, w.partials, flag_out, flag_in, lr, clipv, s_dev);
-        hipLaunchKernelGGL(emb_finish_sqnorm, dim3(1), dim3(ROW_NT), 0, st, w.partials, (int)(grid.x * grid.y), acc);
+        LOMO_EMB_LAUNCH(0)
+        hipLaunchKernelGGL(emb_finish_sqnorm, dim3(1), dim3(ROW_NT), 0, st, w.partials,
+                           (int)(gridA.x * gridA.y + gridB.x * gridB.y), acc);
     } else if (mode == 1) {
-        hipLaunchKernelGGL(emb_rows_kernel<1>, grid, dim3(EMB_NT), 0, st, dY, W, H, w.perm, w.unique_ids, w.seg_offsets,
-                           w.n_unique, s, w.partials, flag_out, flag_in, lr, clipv, s_dev);
+        LOMO_EMB_LAUNCH(1)
     } else {
-        hipLaunchKernelGGL(emb_rows_kernel<2>, grid, dim3(EMB_NT), 0, st, dY, W, H, w.perm, w.unique_ids, w.seg_offsets,
-                           w.n_unique, s, w.partials, flag_out, flag_in, lr, clipv, s_dev);
+        LOMO_EMB_LAUNCH(2)
     }
+#undef LOMO_EMB_LAUNCH
     return hipGetLastError();
 }
 
