@@ -65,7 +65,11 @@ lomo_status lomo_wgrad_sqnorm(const lomo_half* X, const lomo_half* dY,
 
 /* Same quantity for an embedding table [V x H] whose rows were gathered by ids [T] (device
  * int32): the gradient of row v is the sum of the dY rows at the positions holding id v.
- * ws: device workspace of at least lomo_embedding_workspace_bytes(T, H) bytes. */
+ * The positions are sorted by (id, position); the sorted list is cut into chunks of 16, each chunk's
+ * rows are added in order in fp32, and the partial sums of an id that spans chunks are added in chunk
+ * order: the order of every sum depends on the ids alone, so results are bit-reproducible.
+ * ws: device workspace of at least lomo_embedding_workspace_bytes(T, H) bytes (about T * H / 2 bytes:
+ * fp32 partial rows of ids that cross chunk boundaries). */
 lomo_status lomo_embedding_sqnorm(const int32_t* ids, const lomo_half* dY,
                                   int64_t T, int64_t H, int64_t V,
                                   void* ws, size_t ws_bytes,
