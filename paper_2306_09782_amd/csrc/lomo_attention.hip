@@ -204,7 +204,9 @@ __global__ __launch_bounds__(256, 2) void attention_backward_kernel(attn::Args a
             sDelta[tid] = rd;
         }
         __syncthreads();
+#ifndef LOMO_ATTN_EXP_NO_FETCH     // timing experiment only: the loop re-uses the first moving tiles
         if (blk < last) fetch_moving(blk + 1);     // in flight while this block is multiplied
+#endif
 
         // ---- S^T = K Q^T and dP^T = V dO^T for this wave's 32 keys x 32 queries: the keys are the MFMA rows, so a
         // lane owns one query (one lse, one delta) and four consecutive keys per register group
@@ -242,8 +244,13 @@ __global__ __launch_bounds__(256, 2) void attention_backward_kernel(attn::Args a
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int r = 4 * q4 + e;
+#ifdef LOMO_ATTN_EXP_NO_SOFTMAX   // timing experiment only
+                    float p = accS[r];
+                    float ds = accP[r];
+#else
                     float p = __builtin_amdgcn_exp2f(fmaf(scale_log2e, accS[r], -lq));
                     float ds = scale * p * (accP[r] - dq);
+#endif
                     if (diag && key0 + e > qrow) {
                         p = 0.f;
                         ds = 0.f;
@@ -257,6 +264,7 @@ __global__ __launch_bounds__(256, 2) void attention_backward_kernel(attn::Args a
         }
         __syncthreads();
 
+#ifndef LOMO_ATTN_EXP_NO_ACCUM     // timing experiment only
         if (MODE == 0) {
             // dv^T[dcol][key] += dO^T P,  dk^T[dcol][key] += Q^T dS   (contraction over the 64 queries)
 #pragma unroll
@@ -286,6 +294,7 @@ __global__ __launch_bounds__(256, 2) void attention_backward_kernel(attn::Args a
                 }
             }
         }
+#endif
     }
 
     // ---- results: through LDS as fp32 so that the rotary pairs (c, c + 64) meet and stores are 16 bytes wide
