@@ -294,3 +294,57 @@ def layer_step(dy, saved_attn: Dict, saved_mlp: Dict, p: Dict, cos, sin, s: int,
            for k, g in zip(LAYER_ORDER, grads)}
     return {"params": new, "dh": ca["dh"], "dh_mid": cm["dh"], "mlp": cm, "attn": ca, "flags": flags, "sqnorms": sq,
             "overflow": overflow, "total_sqnorm": total, "norm": norm, "clip_coef": coef}
+
+
+# --------------------------------------------------------------------------- the whole model
+
+
+def model_forward_stored(ids, m: Dict, cos, sin, s: int, n_heads: int, eps: float) -> Dict:
+    """Saved activations of a decoder-only model: embedding rows, the layers, final RMSNorm (the input of the
+    output projection W_lm).  m: {"W_emb", "layers": [layer parameter dicts], "w_f", "W_lm"}."""
+    h = np.array(m["W_emb"][np.asarray(ids)], copy=True)
+    saved = []
+    for p in m["layers"]:
+        sa, sm = layer_forward_stored(h, p, cos, sin, s, n_heads, eps)
+        saved.append((sa, sm))
+        h = O.round_f16(O.as_f64(sa["y"]) + O.as_f64(sm["a"]) @ O.as_f64(p["W_d"]).T)
+    xhat64, r64, _ = M.rmsnorm_forward(h, m["w_f"], eps)
+    xhat = O.round_f16(xhat64)
+    xn = O.round_f16(O.as_f64(xhat) * O.as_f64(m["w_f"])[None, :])
+    return {"layers": saved, "final": {"xhat": xhat, "r": r64.astype(np.float32), "xn": xn}}
+
+
+def model_step(ids, dlogits, saved: Dict, m: Dict, cos, sin, s: int, n_heads: int, lr: float, loss_scale: float,
+               max_norm: float = 1.0, eps_clip: float = 1e-6) -> Dict:
+    """Two-pass LOMO step over the whole model (Algorithm 1 from the output projection down to the embedding):
+    every hand-on gradient is computed from the old parameters, one norm over every tensor sets the clipping
+    coefficient, then every parameter is updated.  Tensor order (= flag order): W_lm, w_f, then for each layer
+    from the last to the first W_d, W_gu, w2, W_o, W_qkv, w1, finally W_emb."""
+    f = saved["final"]
+    names, params, grads, handons = [], [], [], {}
+    dxn = O.input_grad(dlogits, m["W_lm"])
+    names.append("W_lm"); params.append(m["W_lm"]); grads.append(O.linear_grad(f["xn"], dlogits))
+    names.append("w_f"); params.append(m["w_f"]); grads.append(O.vector_grad(f["xhat"], dxn))
+    dy = O.round_f16(M.rmsnorm_backward(dxn, f["xhat"], f["r"], m["w_f"]))
+    handons["dxn_f"], handons["dy_top"] = dxn, dy
+    per_layer = []
+    for li in range(len(m["layers"]) - 1, -1, -1):
+        p = m["layers"][li]
+        sa, sm = saved["layers"][li]
+        cm = M.chain_gradients(dy, sm, p["w2"], p["W_gu"], p["W_d"])
+        ca = chain_gradients(cm["dh"], sa, p["w1"], p["W_qkv"], p["W_o"], cos, sin, s, n_heads)
+        for k, g in zip(LAYER_ORDER, (cm["G_d"], cm["G_gu"], cm["g_w"], ca["G_o"], ca["G_qkv"], ca["g_w"])):
+            names.append(f"layers.{li}.{k}"); params.append(p[k]); grads.append(g)
+        per_layer.append((li, cm, ca))
+        dy = ca["dh"]
+    names.append("W_emb"); params.append(m["W_emb"]); grads.append(O.embedding_grad(ids, dy, m["W_emb"].shape[0]))
+    flags = [O.has_overflow(g) for g in grads]
+    sq = [O.sqnorm(g) for g in grads]
+    overflow = any(flags)
+    total = math.fsum(sq) if not overflow else float("nan")
+    norm = O.grad_norm(total, loss_scale) if not overflow else float("nan")
+    coef = O.clip_coef(norm, max_norm, eps_clip) if not overflow else float("nan")
+    new = {n_: (np.array(p_, copy=True) if overflow else O.sgd_update(p_, g_, lr, coef, loss_scale))
+           for n_, p_, g_ in zip(names, params, grads)}
+    return {"params": new, "names": names, "flags": flags, "sqnorms": sq, "overflow": overflow, "total_sqnorm": total,
+            "norm": norm, "clip_coef": coef, "dh0": dy, "handons": handons, "per_layer": per_layer}

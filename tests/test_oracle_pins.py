@@ -940,3 +940,40 @@ def test_attention_rounding_sensitivity_bounds_a_single_flip():
         bumpP = np.zeros_like(P)
         bumpP[i, j] = P[i, j] * 2.0 ** -11
         assert (np.abs(bumpP.T @ O.as_f64(do)) <= bound[:, 2 * dd:] + 1e-300).all()
+
+
+def test_model_step_is_the_generic_step_on_all_its_tensors():
+    """Two layers, embedding, final norm, output projection: the whole-model oracle equals the generic
+    materialised step applied to its tensors with the hand-on gradients of its own walk."""
+    rng = np.random.default_rng(23)
+    B, s, nh, dd, F, V = 2, 8, 2, 8, 24, 50
+    T, H = B * s, nh * dd
+    f16 = lambda shape, sig: (sig * rng.normal(size=shape)).astype(np.float16)
+    m = {"W_emb": f16((V, H), 1.0), "layers": [_layer_params(rng, H, F, sig=0.3, dtype=np.float16) for _ in range(2)],
+         "w_f": (1.0 + 0.1 * rng.normal(size=H)).astype(np.float16), "W_lm": f16((V, H), 0.3)}
+    ids = rng.integers(0, V, size=T).astype(np.int32)
+    ids[3] = ids[11]                                    # a repeated token: its embedding rows add up
+    dlogits = f16((T, V), 2.0)
+    cos, sin = A.rope_tables(s, dd)
+    saved = A.model_forward_stored(ids, m, cos, sin, s, nh, 1e-5)
+    a = A.model_step(ids, dlogits, saved, m, cos, sin, s, nh, 0.05, 256.0)
+    assert a["names"][0] == "W_lm" and a["names"][-1] == "W_emb" and len(a["names"]) == 2 + 6 * 2 + 1
+    f = saved["final"]
+    recs = [dict(kind="linear", X=f["xn"], dY=dlogits, W=m["W_lm"]), dict(kind="vector", X=f["xhat"], dY=a["handons"]["dxn_f"], W=m["w_f"])]
+    dy = a["handons"]["dy_top"]
+    for li, cm, ca in a["per_layer"]:
+        p = m["layers"][li]
+        sa, sm = saved["layers"][li]
+        recs += [dict(kind="linear", X=sm["a"], dY=dy, W=p["W_d"]), dict(kind="linear", X=sm["xn"], dY=cm["dgu"], W=p["W_gu"]),
+                 dict(kind="vector", X=sm["xhat"], dY=cm["dxn"], W=p["w2"]), dict(kind="linear", X=sa["o"], dY=cm["dh"], W=p["W_o"]),
+                 dict(kind="linear", X=sa["xn"], dY=ca["dqkv"], W=p["W_qkv"]), dict(kind="vector", X=sa["xhat"], dY=ca["dxn"], W=p["w1"])]
+        dy = ca["dh"]
+    recs.append(dict(kind="embedding", ids=ids, dY=dy, W=m["W_emb"]))
+    b = O.step_materialised(recs, 0.05, 256.0)
+    assert a["clip_coef"] == b["clip_coef"] and a["flags"] == b["flags"] and a["clip_coef"] < 1.0
+    for name, want in zip(a["names"], b["W"]):
+        np.testing.assert_array_equal(a["params"][name].view(np.uint16), want.view(np.uint16))
+    # the walk really goes from the top to the bottom: the layer-0 hand-on depends on the top gradient
+    d2 = dlogits.copy()
+    d2[0, 0] = np.float16(float(d2[0, 0]) + 4.0)
+    assert (A.model_step(ids, d2, saved, m, cos, sin, s, nh, 0.05, 256.0)["dh0"].view(np.uint16) != a["dh0"].view(np.uint16)).any()
