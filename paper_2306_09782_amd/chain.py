@@ -23,11 +23,14 @@ from . import binding as B
 class StepState:
     """Accumulator, per-parameter flags (+ the step flag), workspace and scalars of one chained step."""
 
-    def __init__(self, device, n_params: int, T: int, H: int):
+    def __init__(self, device, n_params: int, T: int, H: int, with_embedding: bool = False):
         self.n = n_params
         self.acc = torch.zeros(1, dtype=torch.float64, device=device)
         self.flags = torch.zeros(n_params + 1, dtype=torch.int32, device=device)
-        self.ws = torch.empty(max(B.lomo_vector_workspace_bytes(T, H), 256), dtype=torch.uint8, device=device)
+        nbytes = max(B.lomo_vector_workspace_bytes(T, H), 256)
+        if with_embedding:
+            nbytes = max(nbytes, B.lomo_embedding_workspace_bytes(T, H))
+        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
         self.scalars = torch.zeros(32, dtype=torch.uint8, device=device)
         self._scalars_host = torch.zeros(32, dtype=torch.uint8).pin_memory()
 
@@ -79,12 +82,13 @@ class LomoMlpBlock:
     """Hand-on buffers of the feed-forward block: da [T x F], [dgate|dup] [T x 2F], dxn [T x H].
     `saved`: a [T x F], xn and xhat [T x H], rstd [T] fp32, gate_up [T x 2F]."""
 
-    def __init__(self, device, T: int, H: int, F: int, state: StepState = None, slot0: int = 0):
+    def __init__(self, device, T: int, H: int, F: int, state: StepState = None, slot0: int = 0, share=None):
         self.device = torch.device(device)
         f16 = dict(dtype=torch.float16, device=self.device)
-        self.da = torch.empty(T, F, **f16)
-        self.dgu = torch.empty(T, 2 * F, **f16)
-        self.dxn = torch.empty(T, H, **f16)
+        # hand-on buffers are transient: blocks of different layers may share them (`share` = another block)
+        self.da = share.da if share is not None else torch.empty(T, F, **f16)
+        self.dgu = share.dgu if share is not None else torch.empty(T, 2 * F, **f16)
+        self.dxn = share.dxn if share is not None else torch.empty(T, H, **f16)
         self.state = state if state is not None else StepState(self.device, 3, T, H)
         self.slot0 = slot0
         self._lists = None
@@ -124,15 +128,16 @@ class LomoAttentionBlock:
     """Hand-on buffers of the attention block: do [T x H], [dq|dk|dv] [T x 3H], dxn [T x H], delta [T x heads].
     `saved`: o, xn, xhat [T x H], rstd [T] fp32, qkv [T x 3H] (rotated q and k, v), lse [T x heads] fp32."""
 
-    def __init__(self, device, batch: int, seq: int, H: int, n_heads: int, state: StepState = None, slot0: int = 0):
+    def __init__(self, device, batch: int, seq: int, H: int, n_heads: int, state: StepState = None, slot0: int = 0,
+                 share=None):
         self.device = torch.device(device)
         T = batch * seq
         self.batch, self.seq, self.n_heads = batch, seq, n_heads
         f16 = dict(dtype=torch.float16, device=self.device)
-        self.do = torch.empty(T, H, **f16)
-        self.dqkv = torch.empty(T, 3 * H, **f16)
-        self.dxn = torch.empty(T, H, **f16)
-        self.delta = torch.empty(T * n_heads, dtype=torch.float32, device=self.device)
+        self.do = share.do if share is not None else torch.empty(T, H, **f16)
+        self.dqkv = share.dqkv if share is not None else torch.empty(T, 3 * H, **f16)
+        self.dxn = share.dxn if share is not None else torch.empty(T, H, **f16)
+        self.delta = share.delta if share is not None else torch.empty(T * n_heads, dtype=torch.float32, device=self.device)
         self.state = state if state is not None else StepState(self.device, 3, T, H)
         self.slot0 = slot0
         self._lists = None
@@ -190,6 +195,87 @@ class LomoDecoderLayer:
         self._walk(dy, saved_attn, saved_mlp, p, rope_cos, rope_sin, dh, False, stream)
         self.state.coefficient(lr, loss_scale, max_norm, eps, stream)
         self._walk(dy, saved_attn, saved_mlp, p, rope_cos, rope_sin, dh, True, stream)
+        self.state.finish(stream)
+
+    def result(self) -> Dict:
+        return self.state.result()
+
+
+class LomoModelChain:
+    """Algorithm 1 over a whole decoder-only model: output projection W_lm, final RMSNorm gain, the layers from
+    the last to the first, and the embedding table, under one two-pass step.  Parameter (= flag) order:
+    W_lm, w_f, then per layer (last first) W_d, W_gu, w2, W_o, W_qkv, w1, finally W_emb.
+
+    The hand-on gradients live only until the next stage has read them, so by default all layers share one set
+    of buffers and the gradient between layers alternates between two [T x H] buffers (section 3.2: no gradient
+    outlives its use).  `share_buffers=False` keeps every layer's hand-ons, for inspection."""
+
+    def __init__(self, device, batch: int, seq: int, H: int, F: int, n_heads: int, n_layers: int,
+                 share_buffers: bool = True):
+        self.device = torch.device(device)
+        T = batch * seq
+        self.n_layers = n_layers
+        self.state = StepState(self.device, 2 + 6 * n_layers + 1, T, H, with_embedding=True)
+        self.mlp, self.attn = [], []
+        for k in range(n_layers):                      # k-th layer of the walk = layer n_layers - 1 - k
+            slot = 2 + 6 * k
+            first = k == 0 or not share_buffers
+            self.mlp.append(LomoMlpBlock(self.device, T, H, F, self.state, slot, share=None if first else self.mlp[0]))
+            self.attn.append(LomoAttentionBlock(self.device, batch, seq, H, n_heads, self.state, slot + 3,
+                                                share=None if first else self.attn[0]))
+        f16 = dict(dtype=torch.float16, device=self.device)
+        self.dxn_f = torch.empty(T, H, **f16)
+        n_dy = 2 if share_buffers else n_layers + 1
+        self.dy = [torch.empty(T, H, **f16) for _ in range(n_dy)]          # dy[k % n_dy]: gradient entering walk step k
+        self.dh_mid = [torch.empty(T, H, **f16) for _ in range(1 if share_buffers else n_layers)]
+        self._top = None
+
+    def grad_in(self, k: int):
+        """Buffer holding the gradient that enters the k-th layer of the walk (k = n_layers: the embedding's)."""
+        return self.dy[k % len(self.dy)]
+
+    def grad_mid(self, k: int):
+        return self.dh_mid[k % len(self.dh_mid)]
+
+    def _top_lists(self, dlogits, final, m, ids, dh0):
+        key = tuple(t.data_ptr() for t in (dlogits, final["xn"], final["xhat"], m["W_lm"], m["w_f"], m["W_emb"], ids, dh0))
+        if self._top is None or self._top[0] != key:
+            lm = B.make_tensor_list([{"kind": "linear", "X": final["xn"], "dY": dlogits, "W": m["W_lm"], "dX": self.dxn_f}])
+            gain = B.make_tensor_list([{"kind": "vector", "X": final["xhat"], "dY": self.dxn_f, "W": m["w_f"]}])
+            emb = B.make_tensor_list([{"kind": "embedding", "ids": ids, "dY": dh0, "W": m["W_emb"]}])
+            self._top = (key, lm, gain, emb)
+        return self._top[1:]
+
+    def _walk(self, ids, dlogits, saved, m, rope_cos, rope_sin, update, stream):
+        st = self.state
+        final = saved["final"]
+        L = self.n_layers
+        dh0 = self.grad_in(L)
+        lm, gain, emb = self._top_lists(dlogits, final, m, ids, dh0)
+        _linear(st, 0, final["xn"], dlogits, m["W_lm"], self.dxn_f, lm, update, stream)
+        B.lomo_rmsnorm_backward(self.dxn_f, final["xhat"], final["rstd"], m["w_f"], None, self.grad_in(0), stream)
+        _gain(st, 1, final["xhat"], self.dxn_f, m["w_f"], gain, update, stream)
+        for k in range(L):
+            li = L - 1 - k
+            p = m["layers"][li]
+            sa, sm = saved["layers"][li]
+            dy, mid, dh = self.grad_in(k), self.grad_mid(k), self.grad_in(k + 1)
+            self.mlp[k].walk(dy, sm, p["w2"], p["W_gu"], p["W_d"], mid, update, stream)
+            self.attn[k].walk(mid, sa, p["w1"], p["W_qkv"], p["W_o"], rope_cos, rope_sin, dh, update, stream)
+        slot = st.n - 1
+        if update:
+            B.lomo_step_update_pass_device(emb, st.scalars, st.step_flag, st.ws, stream)
+        else:
+            B.lomo_embedding_sqnorm(ids, dh0, m["W_emb"].shape[0], st.ws, st.acc, st.flags[slot:slot + 1], stream)
+
+    def step(self, ids, dlogits, saved: Dict, m: Dict, rope_cos, rope_sin, lr: float, loss_scale: float,
+             max_norm: float = 1.0, eps: float = 1e-6, stream=None) -> None:
+        """m: {"W_emb", "layers": [{"w1","W_qkv","W_o","w2","W_gu","W_d"}, ...], "w_f", "W_lm"}, updated in place.
+        saved: {"layers": [(attention-block activations, feed-forward-block activations), ...], "final": {...}}."""
+        self.state.begin()
+        self._walk(ids, dlogits, saved, m, rope_cos, rope_sin, False, stream)
+        self.state.coefficient(lr, loss_scale, max_norm, eps, stream)
+        self._walk(ids, dlogits, saved, m, rope_cos, rope_sin, True, stream)
         self.state.finish(stream)
 
     def result(self) -> Dict:

@@ -1,0 +1,181 @@
+"""Algorithm 1 over a whole small decoder-only model on the GPU (output projection, final RMSNorm, decoder layers,
+embedding table) against oracle/attn_chain.py's model_step.
+
+With every layer's hand-on gradients kept (share_buffers=False) each stage is checked on the bits it read, and each
+updated parameter against the oracle's update formed from the device's own hand-on (strict bar: within 1 fp16 ulp on
+>= 99.9 %, none beyond 2) and against the oracle's chain (same bar, with the guard 2^-9 |update| for hand-ons that
+differ in their last bits).  With the buffers shared between the layers, which is how the path runs, the result
+must be bit-identical to the unshared run when clipping is off (the clipping coefficient depends on the order of
+the norm's floating-point atomics in its last bits).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import lomo_oracle as O
+from oracle import mlp_chain as M
+from oracle import attn_chain as A
+from test_gpu_attention import (L, DEV, dev, f16, f64, ulps_ok, dgrad_ok, rms_ok, frob_ok, weights_ok, to_dev_saved,  # noqa: F401
+                                check_attention_hand_ons)
+
+pytestmark = pytest.mark.gpu
+
+
+def make_model(rng, V, H, F, n_layers):
+    gain = lambda: (1.0 + 0.05 * rng.standard_normal(H)).astype(np.float16)
+    layers = [{"w1": gain(), "W_qkv": f16(rng, (3 * H, H), 0.02), "W_o": f16(rng, (H, H), 0.02), "w2": gain(),
+               "W_gu": f16(rng, (2 * F, H), 0.02), "W_d": f16(rng, (H, F), 0.02)} for _ in range(n_layers)]
+    return {"W_emb": f16(rng, (V, H), 1.0), "layers": layers, "w_f": gain(), "W_lm": f16(rng, (V, H), 0.08)}
+
+
+def to_dev_model(m):
+    return {"W_emb": dev(m["W_emb"]), "w_f": dev(m["w_f"]), "W_lm": dev(m["W_lm"]),
+            "layers": [{k: dev(v) for k, v in p.items()} for p in m["layers"]]}
+
+
+def to_dev_model_saved(saved):
+    return {"layers": [(to_dev_saved(sa), to_dev_saved(sm)) for sa, sm in saved["layers"]],
+            "final": to_dev_saved(saved["final"])}
+
+
+def setup(rng, B, s, nh, F, V, n_layers, scale, repeat_ids=True):
+    H, T = nh * 128, B * s
+    m = make_model(rng, V, H, F, n_layers)
+    ids = rng.integers(0, V, size=T).astype(np.int32)
+    if repeat_ids:
+        ids[T // 2:T // 2 + 40] = ids[3]         # one id 41 times: a run that crosses chunk boundaries
+    dlogits = f16(rng, (T, V), 1e-3 * scale)
+    cos, sin = A.rope_tables(s, 128)
+    saved = A.model_forward_stored(ids, m, cos, sin, s, nh, 1e-5)
+    return m, ids, dlogits, cos, sin, saved
+
+
+def visible_lr(ids, dlogits, saved, m, cos, sin, s, nh, scale):
+    probe = A.model_step(ids, dlogits, saved, m, cos, sin, s, nh, 1.0, scale, max_norm=1e30)
+    # the output projection has by far the largest gradient: let it move by about 30 * 2^-16 per element, which
+    # moves the layers' weights (a tenth of that gradient, values near 0.02) by a few ulps
+    typical = math.sqrt(probe["sqnorms"][0] / m["W_lm"].size) / scale
+    return float(np.float32(30 * 2.0 ** -16 / typical))
+
+
+def run_model(B, s, nh, F, V, n_layers, m, ids, dlogits, cos, sin, saved, lr, scale, max_norm, share):
+    from paper_2306_09782_amd.chain import LomoModelChain
+    H = nh * 128
+    chain = LomoModelChain(DEV, B, s, H, F, nh, n_layers, share_buffers=share)
+    dm = to_dev_model(m)
+    chain.step(dev(ids), dev(dlogits), to_dev_model_saved(saved), dm, dev(cos), dev(sin), lr, scale, max_norm)
+    torch.cuda.synchronize()
+    return chain, dm
+
+
+@pytest.mark.parametrize("visible", [True, False], ids=["visible", "clipped"])
+def test_model_step_stage_by_stage(L, visible):
+    rng = np.random.default_rng(41 + visible)
+    B, s, nh, F, V, n_layers, scale = 2, 128, 2, 344, 512, 3, 4096.0
+    m, ids, dlogits, cos, sin, saved = setup(rng, B, s, nh, F, V, n_layers, scale)
+    max_norm = 1e30 if visible else 1.0
+    lr = visible_lr(ids, dlogits, saved, m, cos, sin, s, nh, scale) if visible else 1e-2
+    want = A.model_step(ids, dlogits, saved, m, cos, sin, s, nh, lr, scale, max_norm=max_norm)
+    chain, dm = run_model(B, s, nh, F, V, n_layers, m, ids, dlogits, cos, sin, saved, lr, scale, max_norm, share=False)
+    res = chain.result()
+    assert res["flags"] == want["flags"] == [False] * (3 + 6 * n_layers) and res["overflow"] is False
+    assert abs(res["norm"] / want["norm"] - 1) < 1e-3 and abs(res["clip_coef"] / want["clip_coef"] - 1) < 1e-3
+    hand = dict(lr=lr, coef=res["clip_coef"], S=scale)
+    new = want["params"]
+    final = saved["final"]
+
+    # top of the model: output projection, final norm
+    dxn_f = chain.dxn_f.cpu().numpy()
+    dy_top = chain.grad_in(0).cpu().numpy()
+    ulps_ok(dm["W_lm"].cpu().numpy(), new["W_lm"], "W_lm")
+    dgrad_ok(dxn_f, dlogits, m["W_lm"], "dxn of the final norm")
+    weights_ok(dm["w_f"].cpu().numpy(), new["w_f"], m["w_f"], "w_f", final["xhat"], dxn_f, kind="vector", **hand)
+    ref = M.rmsnorm_backward(dxn_f, final["xhat"], final["r"], m["w_f"])
+    ulps_ok(dy_top, O.round_f16(ref), "gradient entering the last layer",
+            near=np.abs(f64(dy_top) - ref) <= 2.0 ** -18 * np.abs(ref).max(axis=1, keepdims=True))
+    frob_ok(dy_top, want["handons"]["dy_top"], "dy_top")
+
+    # layers, last to first, each on the device's own incoming gradient
+    for k, (li, cm, ca) in enumerate(want["per_layer"]):
+        assert li == n_layers - 1 - k
+        p, (sa, sm) = m["layers"][li], saved["layers"][li]
+        got = {name: t.cpu().numpy() for name, t in dm["layers"][li].items()}
+        mlp, attn = chain.mlp[k], chain.attn[k]
+        dy = chain.grad_in(k).cpu().numpy()
+        da, dgu, dxn = mlp.da.cpu().numpy(), mlp.dgu.cpu().numpy(), mlp.dxn.cpu().numpy()
+        mid = chain.grad_mid(k).cpu().numpy()
+        dh = chain.grad_in(k + 1)
+        pre = f"layers.{li}."
+        weights_ok(got["W_d"], new[pre + "W_d"], p["W_d"], pre + "W_d", sm["a"], dy, **hand)
+        weights_ok(got["W_gu"], new[pre + "W_gu"], p["W_gu"], pre + "W_gu", sm["xn"], dgu, **hand)
+        weights_ok(got["w2"], new[pre + "w2"], p["w2"], pre + "w2", sm["xhat"], dxn, kind="vector", **hand)
+        weights_ok(got["W_o"], new[pre + "W_o"], p["W_o"], pre + "W_o", sa["o"], mid, **hand)
+        weights_ok(got["W_qkv"], new[pre + "W_qkv"], p["W_qkv"], pre + "W_qkv", sa["xn"], attn.dqkv.cpu().numpy(), **hand)
+        weights_ok(got["w1"], new[pre + "w1"], p["w1"], pre + "w1", sa["xhat"], attn.dxn.cpu().numpy(), kind="vector", **hand)
+        dgrad_ok(da, dy, p["W_d"], pre + "da")
+        ulps_ok(dgu, O.round_f16(M.swiglu_backward(da, sm["gate_up"])), pre + "dgu from the device's da")
+        dgrad_ok(dxn, dgu, p["W_gu"], pre + "mlp dxn")
+        rms_ok(mid, dxn, sm, p["w2"], dy, pre + "dh between the blocks")
+        frob_ok(mid, cm["dh"], pre + "dh_mid", tol=2.0 ** -10)
+        check_attention_hand_ons(attn, dh, ca, sa, p["w1"], p["W_qkv"], p["W_o"], mid, cos, sin, s, nh)
+
+    # embedding table: rows of ids that occur move, the others keep their bits
+    dh0 = chain.grad_in(n_layers).cpu().numpy()
+    frob_ok(dh0, want["dh0"], "gradient of the embedding output", tol=2.0 ** -10)
+    got_emb = dm["W_emb"].cpu().numpy()
+    strict = O.sgd_update(m["W_emb"], O.embedding_grad(ids, dh0, V), lr, res["clip_coef"], scale)
+    ulps_ok(got_emb, strict, "W_emb (oracle update from the device's hand-on)")
+    near = np.abs(f64(got_emb) - f64(new["W_emb"])) <= 2.0 ** -9 * np.abs(f64(new["W_emb"]) - f64(m["W_emb"]))
+    ulps_ok(got_emb, new["W_emb"], "W_emb (oracle chain)", near=near)
+    absent = np.setdiff1d(np.arange(V), ids)
+    assert absent.size > 0
+    np.testing.assert_array_equal(got_emb[absent].view(np.uint16), m["W_emb"][absent].view(np.uint16))
+    if visible:
+        for name in ("layers.0.W_qkv", "layers.2.W_gu", "W_lm"):
+            old = m[name] if name in m else m["layers"][int(name.split(".")[1])][name.split(".")[2]]
+            assert (new[name].view(np.uint16) != old.view(np.uint16)).mean() > 0.3, name
+
+
+def test_model_step_with_shared_buffers_is_bit_identical(L):
+    rng = np.random.default_rng(43)
+    B, s, nh, F, V, n_layers, scale = 1, 128, 1, 344, 256, 4, 1024.0
+    m, ids, dlogits, cos, sin, saved = setup(rng, B, s, nh, F, V, n_layers, scale)
+    lr = visible_lr(ids, dlogits, saved, m, cos, sin, s, nh, scale)
+    args = (B, s, nh, F, V, n_layers, m, ids, dlogits, cos, sin, saved, lr, scale, 1e30)
+    c1, d1 = run_model(*args, share=False)
+    c2, d2 = run_model(*args, share=True)
+    r1, r2 = c1.result(), c2.result()
+    assert r1["flags"] == r2["flags"] and r1["clip_coef"] == r2["clip_coef"] == 1.0
+    assert abs(r1["norm"] / r2["norm"] - 1) < 1e-12
+    same = lambda a, b: torch.equal(a.view(torch.int16), b.view(torch.int16))
+    assert same(d1["W_emb"], d2["W_emb"]) and same(d1["W_lm"], d2["W_lm"]) and same(d1["w_f"], d2["w_f"])
+    for p1, p2 in zip(d1["layers"], d2["layers"]):
+        for k in p1:
+            assert same(p1[k], p2[k]), k
+    assert same(c1.grad_in(n_layers), c2.grad_in(n_layers))
+    changed = (d2["layers"][0]["W_qkv"].cpu().numpy().view(np.uint16) != m["layers"][0]["W_qkv"].view(np.uint16)).mean()
+    assert changed > 0.3
+    # a second step with the same objects reuses the cached tensor lists and moves the weights again
+    before = d2["layers"][1]["W_d"].clone()
+    c2.step(dev(ids), dev(dlogits), to_dev_model_saved(saved), d2, dev(cos), dev(sin), lr, scale, 1e30)
+    torch.cuda.synchronize()
+    assert not same(before, d2["layers"][1]["W_d"])
+
+
+def test_model_step_overflow_anywhere_skips_every_tensor(L):
+    rng = np.random.default_rng(44)
+    B, s, nh, F, V, n_layers, scale = 1, 128, 1, 344, 256, 2, 4096.0
+    m, ids, dlogits, cos, sin, saved = setup(rng, B, s, nh, F, V, n_layers, scale)
+    dlogits[50, 7] = np.inf
+    want = A.model_step(ids, dlogits, saved, m, cos, sin, s, nh, 1e-2, scale)
+    chain, dm = run_model(B, s, nh, F, V, n_layers, m, ids, dlogits, cos, sin, saved, 1e-2, scale, 1.0, share=True)
+    res = chain.result()
+    assert want["overflow"] and res["overflow"] is True
+    assert res["flags"] == want["flags"] and res["flags"][0]
+    np.testing.assert_array_equal(dm["W_emb"].cpu().numpy().view(np.uint16), m["W_emb"].view(np.uint16))
+    np.testing.assert_array_equal(dm["W_lm"].cpu().numpy().view(np.uint16), m["W_lm"].view(np.uint16))
+    for p, q in zip(dm["layers"], m["layers"]):
+        for k in q:
+            np.testing.assert_array_equal(p[k].cpu().numpy().view(np.uint16), q[k].view(np.uint16))
