@@ -159,6 +159,66 @@ def chain_bench(L, torch, np, dev, steps, warmup):
                                    "algorithmic_bytes": at_bytes, "gb_per_s": at_bytes / at_ms / 1e6}}
 
 
+def model_chain_bench(L, torch, np, dev, steps, warmup, n_layers=32):
+    """Two-pass step through a whole 7B-shaped decoder-only model (32 layers, H = 4096, 32 heads, F = 11008,
+    vocabulary 32000, 8 x 512 tokens): output projection, final norm, every layer, embedding table, with every
+    hand-on gradient produced by the kernels.  Synthetic saved activations, one set per layer (17 GB), and weight
+    scales chosen so that the gradient neither dies nor overflows on its way down 32 random layers."""
+    from paper_2306_09782_amd.chain import LomoModelChain
+    import lomo_synth as S
+    Bt, s, nh, H, F, V = 8, 512, 32, 4096, 11008, 32000
+    T = Bt * s
+    count = [0]
+
+    def gen(shape, sigma):
+        count[0] += 1
+        return S.normal_f16_torch(S.tensor_key(0, 98, count[0], 0), shape, S.normal_mult(sigma), dev)
+    ones = lambda n, dt: torch.ones(n, dtype=dt, device=dev)
+    pos = torch.arange(s, device=dev, dtype=torch.float32).repeat(Bt)
+    lse = torch.log(1.65 * (pos + 1.0))[:, None].repeat(1, nh).contiguous()     # rows of P sum to about one
+    layers, saved = [], []
+    for _ in range(n_layers):
+        layers.append({"w1": ones(H, torch.float16), "w2": ones(H, torch.float16), "W_qkv": gen((3 * H, H), 0.005),
+                       "W_o": gen((H, H), 0.005), "W_gu": gen((2 * F, H), 0.004), "W_d": gen((H, F), 0.006)})
+        sm = {"a": gen((T, F), 0.3), "xn": gen((T, H), 1.0), "xhat": gen((T, H), 1.0), "gate_up": gen((T, 2 * F), 1.0),
+              "rstd": ones(T, torch.float32)}
+        sa = {"o": gen((T, H), 0.2), "xn": gen((T, H), 1.0), "xhat": gen((T, H), 1.0), "qkv": gen((T, 3 * H), 1.0),
+              "rstd": ones(T, torch.float32), "lse": lse}
+        saved.append((sa, sm))
+    m = {"W_emb": gen((V, H), 1.0), "layers": layers, "w_f": ones(H, torch.float16), "W_lm": gen((V, H), 0.02)}
+    final = {"xn": gen((T, H), 1.0), "xhat": gen((T, H), 1.0), "rstd": ones(T, torch.float32)}
+    ids = torch.from_numpy(S.zipf_ids(98, T, V).astype(np.int32)).to(dev)
+    dlogits = gen((T, V), 1.0)
+    ang = torch.arange(s, device=dev, dtype=torch.float64)[:, None] * (10000.0 ** (-torch.arange(64, device=dev, dtype=torch.float64) / 64.0))[None, :]
+    cos, sin = torch.cos(ang).float().contiguous(), torch.sin(ang).float().contiguous()
+    chain = LomoModelChain(dev, Bt, s, H, F, nh, n_layers)
+    sv = {"layers": saved, "final": final}
+    run = lambda: chain.step(ids, dlogits, sv, m, cos, sin, 1e-3, 1024.0)
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    L.lomo_timing_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    fam = {name: L.lomo_timing_read(i) for i, name in enumerate(L.KERNEL_FAMILIES)}
+    L.lomo_timing_enable(False)
+    res = chain.result()
+    nb = s // 64
+    at_flops = Bt * nh * (nb * (nb + 1) // 2) * 7 * 2 * 64 * 64 * 128
+    n_lin = n_layers * H * (3 * H + H + 2 * F + F) + V * H
+    flops = 4 * 2 * T * n_lin + 2 * n_layers * at_flops
+    n_params = n_lin + V * H + (2 * n_layers + 1) * H
+    return {"workload": f"7B-shaped model, chained ({n_layers} layers, 8 x 512 tokens, H 4096, 32 heads, F 11008, V 32000)",
+            "ms_per_step": ms, "gemms_per_linear": 4, "params": n_params, "tflops": flops / (ms * 1e-3) / 1e12,
+            "tokens_per_s_backward_and_update": T / (ms * 1e-3), "params_per_s": n_params / (ms * 1e-3),
+            "grad_norm": res["norm"], "clip_coef": res["clip_coef"], "overflow": res["overflow"],
+            "device_memory_gb": torch.cuda.max_memory_allocated() / 1e9,
+            "family_ms_per_step": {k: v[0] / steps for k, v in fam.items() if v[1]}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -178,6 +238,8 @@ def main():
                          "metric's flop count describes)")
     ap.add_argument("--no-norm-compare", action="store_true",
                     help="skip the extra timing of pass 1 alone on each route after the timed steps")
+    ap.add_argument("--model-chain", action="store_true",
+                    help="also time the chained two-pass step through a whole 32-layer 7B-shaped model (extra key `model_chain`)")
     ap.add_argument("--chain", action="store_true",
                     help="also time the chained two-pass step through one whole 7B decoder layer (extra key `chain`)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -318,6 +380,10 @@ def main():
         del tensors
         torch.cuda.empty_cache()
         out["chain"] = chain_bench(L, torch, np, dev, max(3, args.steps // 2), 2)
+    if args.model_chain:
+        tensors = None
+        torch.cuda.empty_cache()
+        out["model_chain"] = model_chain_bench(L, torch, np, dev, 3, 1)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))
