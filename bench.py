@@ -159,7 +159,7 @@ def chain_bench(L, torch, np, dev, steps, warmup):
                                    "algorithmic_bytes": at_bytes, "gb_per_s": at_bytes / at_ms / 1e6}}
 
 
-def model_chain_bench(L, torch, np, dev, steps, warmup, n_layers=32):
+def model_chain_bench(L, torch, np, dev, steps, warmup, n_layers=32, keep_handons=False):
     """Two-pass step through a whole 7B-shaped decoder-only model (32 layers, H = 4096, 32 heads, F = 11008,
     vocabulary 32000, 8 x 512 tokens): output projection, final norm, every layer, embedding table, with every
     hand-on gradient produced by the kernels.  Synthetic saved activations, one set per layer (17 GB), and weight
@@ -191,7 +191,7 @@ def model_chain_bench(L, torch, np, dev, steps, warmup, n_layers=32):
     dlogits = gen((T, V), 1.0)
     ang = torch.arange(s, device=dev, dtype=torch.float64)[:, None] * (10000.0 ** (-torch.arange(64, device=dev, dtype=torch.float64) / 64.0))[None, :]
     cos, sin = torch.cos(ang).float().contiguous(), torch.sin(ang).float().contiguous()
-    chain = LomoModelChain(dev, Bt, s, H, F, nh, n_layers)
+    chain = LomoModelChain(dev, Bt, s, H, F, nh, n_layers, keep_handons=keep_handons)
     sv = {"layers": saved, "final": final}
     run = lambda: chain.step(ids, dlogits, sv, m, cos, sin, 1e-3, 1024.0)
     for _ in range(warmup):
@@ -209,10 +209,12 @@ def model_chain_bench(L, torch, np, dev, steps, warmup, n_layers=32):
     nb = s // 64
     at_flops = Bt * nh * (nb * (nb + 1) // 2) * 7 * 2 * 64 * 64 * 128
     n_lin = n_layers * H * (3 * H + H + 2 * F + F) + V * H
-    flops = 4 * 2 * T * n_lin + 2 * n_layers * at_flops
+    gemms = 3 if keep_handons else 4
+    flops = gemms * 2 * T * n_lin + (1 if keep_handons else 2) * n_layers * at_flops
     n_params = n_lin + V * H + (2 * n_layers + 1) * H
     return {"workload": f"7B-shaped model, chained ({n_layers} layers, 8 x 512 tokens, H 4096, 32 heads, F 11008, V 32000)",
-            "ms_per_step": ms, "gemms_per_linear": 4, "params": n_params, "tflops": flops / (ms * 1e-3) / 1e12,
+            "ms_per_step": ms, "gemms_per_linear": gemms, "hand_ons": "kept from pass 1" if keep_handons else "recomputed in pass 2",
+            "params": n_params, "tflops": flops / (ms * 1e-3) / 1e12,
             "tokens_per_s_backward_and_update": T / (ms * 1e-3), "params_per_s": n_params / (ms * 1e-3),
             "grad_norm": res["norm"], "clip_coef": res["clip_coef"], "overflow": res["overflow"],
             "device_memory_gb": torch.cuda.max_memory_allocated() / 1e9,
@@ -384,6 +386,8 @@ def main():
         tensors = None
         torch.cuda.empty_cache()
         out["model_chain"] = model_chain_bench(L, torch, np, dev, 3, 1)
+        torch.cuda.empty_cache()
+        out["model_chain_kept_handons"] = model_chain_bench(L, torch, np, dev, 3, 1, keep_handons=True)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))

@@ -60,10 +60,10 @@ def visible_lr(ids, dlogits, saved, m, cos, sin, s, nh, scale):
     return float(np.float32(30 * 2.0 ** -16 / typical))
 
 
-def run_model(B, s, nh, F, V, n_layers, m, ids, dlogits, cos, sin, saved, lr, scale, max_norm, share):
+def run_model(B, s, nh, F, V, n_layers, m, ids, dlogits, cos, sin, saved, lr, scale, max_norm, share, keep=False):
     from paper_2306_09782_amd.chain import LomoModelChain
     H = nh * 128
-    chain = LomoModelChain(DEV, B, s, H, F, nh, n_layers, share_buffers=share)
+    chain = LomoModelChain(DEV, B, s, H, F, nh, n_layers, share_buffers=share, keep_handons=keep)
     dm = to_dev_model(m)
     chain.step(dev(ids), dev(dlogits), to_dev_model_saved(saved), dm, dev(cos), dev(sin), lr, scale, max_norm)
     torch.cuda.synchronize()
@@ -145,16 +145,18 @@ def test_model_step_with_shared_buffers_is_bit_identical(L):
     lr = visible_lr(ids, dlogits, saved, m, cos, sin, s, nh, scale)
     args = (B, s, nh, F, V, n_layers, m, ids, dlogits, cos, sin, saved, lr, scale, 1e30)
     c1, d1 = run_model(*args, share=False)
-    c2, d2 = run_model(*args, share=True)
-    r1, r2 = c1.result(), c2.result()
-    assert r1["flags"] == r2["flags"] and r1["clip_coef"] == r2["clip_coef"] == 1.0
-    assert abs(r1["norm"] / r2["norm"] - 1) < 1e-12
     same = lambda a, b: torch.equal(a.view(torch.int16), b.view(torch.int16))
-    assert same(d1["W_emb"], d2["W_emb"]) and same(d1["W_lm"], d2["W_lm"]) and same(d1["w_f"], d2["w_f"])
-    for p1, p2 in zip(d1["layers"], d2["layers"]):
-        for k in p1:
-            assert same(p1[k], p2[k]), k
-    assert same(c1.grad_in(n_layers), c2.grad_in(n_layers))
+    r1 = c1.result()
+    for share, keep in ((True, False), (False, True)):       # shared buffers; pass-1 hand-ons kept, pass 2 one launch
+        c2, d2 = run_model(*args, share=share, keep=keep)
+        r2 = c2.result()
+        assert r1["flags"] == r2["flags"] and r1["clip_coef"] == r2["clip_coef"] == 1.0
+        assert abs(r1["norm"] / r2["norm"] - 1) < 1e-12
+        assert same(d1["W_emb"], d2["W_emb"]) and same(d1["W_lm"], d2["W_lm"]) and same(d1["w_f"], d2["w_f"])
+        for p1, p2 in zip(d1["layers"], d2["layers"]):
+            for k in p1:
+                assert same(p1[k], p2[k]), (k, share, keep)
+        assert same(c1.grad_in(n_layers), c2.grad_in(n_layers))
     changed = (d2["layers"][0]["W_qkv"].cpu().numpy().view(np.uint16) != m["layers"][0]["W_qkv"].view(np.uint16)).mean()
     assert changed > 0.3
     # a second step with the same objects reuses the cached tensor lists and moves the weights again
@@ -164,13 +166,15 @@ def test_model_step_with_shared_buffers_is_bit_identical(L):
     assert not same(before, d2["layers"][1]["W_d"])
 
 
-def test_model_step_overflow_anywhere_skips_every_tensor(L):
+@pytest.mark.parametrize("keep", [False, True], ids=["rewalk", "kept-handons"])
+def test_model_step_overflow_anywhere_skips_every_tensor(L, keep):
     rng = np.random.default_rng(44)
     B, s, nh, F, V, n_layers, scale = 1, 128, 1, 344, 256, 2, 4096.0
     m, ids, dlogits, cos, sin, saved = setup(rng, B, s, nh, F, V, n_layers, scale)
     dlogits[50, 7] = np.inf
     want = A.model_step(ids, dlogits, saved, m, cos, sin, s, nh, 1e-2, scale)
-    chain, dm = run_model(B, s, nh, F, V, n_layers, m, ids, dlogits, cos, sin, saved, 1e-2, scale, 1.0, share=True)
+    chain, dm = run_model(B, s, nh, F, V, n_layers, m, ids, dlogits, cos, sin, saved, 1e-2, scale, 1.0, share=True,
+                          keep=keep)
     res = chain.result()
     assert want["overflow"] and res["overflow"] is True
     assert res["flags"] == want["flags"] and res["flags"][0]
