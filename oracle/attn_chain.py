@@ -314,12 +314,10 @@ def model_forward_stored(ids, m: Dict, cos, sin, s: int, n_heads: int, eps: floa
     return {"layers": saved, "final": {"xhat": xhat, "r": r64.astype(np.float32), "xn": xn}}
 
 
-def model_step(ids, dlogits, saved: Dict, m: Dict, cos, sin, s: int, n_heads: int, lr: float, loss_scale: float,
-               max_norm: float = 1.0, eps_clip: float = 1e-6) -> Dict:
-    """Two-pass LOMO step over the whole model (Algorithm 1 from the output projection down to the embedding):
-    every hand-on gradient is computed from the old parameters, one norm over every tensor sets the clipping
-    coefficient, then every parameter is updated.  Tensor order (= flag order): W_lm, w_f, then for each layer
-    from the last to the first W_d, W_gu, w2, W_o, W_qkv, w1, finally W_emb."""
+def model_gradients(ids, dlogits, saved: Dict, m: Dict, cos, sin, s: int, n_heads: int) -> Dict:
+    """One walk of Algorithm 1's loop over the whole model with the current parameters: every tensor's fp64
+    gradient and the stored fp16 hand-ons.  Tensor order: W_lm, w_f, then for each layer from the last to the
+    first W_d, W_gu, w2, W_o, W_qkv, w1, finally W_emb."""
     f = saved["final"]
     names, params, grads, handons = [], [], [], {}
     dxn = O.input_grad(dlogits, m["W_lm"])
@@ -338,6 +336,16 @@ def model_step(ids, dlogits, saved: Dict, m: Dict, cos, sin, s: int, n_heads: in
         per_layer.append((li, cm, ca))
         dy = ca["dh"]
     names.append("W_emb"); params.append(m["W_emb"]); grads.append(O.embedding_grad(ids, dy, m["W_emb"].shape[0]))
+    return {"names": names, "params": params, "grads": grads, "dh0": dy, "handons": handons, "per_layer": per_layer}
+
+
+def model_step(ids, dlogits, saved: Dict, m: Dict, cos, sin, s: int, n_heads: int, lr: float, loss_scale: float,
+               max_norm: float = 1.0, eps_clip: float = 1e-6) -> Dict:
+    """Two-pass LOMO step over the whole model (Algorithm 1 from the output projection down to the embedding):
+    every hand-on gradient is computed from the old parameters, one norm over every tensor sets the clipping
+    coefficient, then every parameter is updated."""
+    w = model_gradients(ids, dlogits, saved, m, cos, sin, s, n_heads)
+    names, params, grads = w["names"], w["params"], w["grads"]
     flags = [O.has_overflow(g) for g in grads]
     sq = [O.sqnorm(g) for g in grads]
     overflow = any(flags)
@@ -347,4 +355,51 @@ def model_step(ids, dlogits, saved: Dict, m: Dict, cos, sin, s: int, n_heads: in
     new = {n_: (np.array(p_, copy=True) if overflow else O.sgd_update(p_, g_, lr, coef, loss_scale))
            for n_, p_, g_ in zip(names, params, grads)}
     return {"params": new, "names": names, "flags": flags, "sqnorms": sq, "overflow": overflow, "total_sqnorm": total,
-            "norm": norm, "clip_coef": coef, "dh0": dy, "handons": handons, "per_layer": per_layer}
+            "norm": norm, "clip_coef": coef, "dh0": w["dh0"], "handons": w["handons"], "per_layer": w["per_layer"]}
+
+
+def model_groups(n_layers: int, layers_per_group: int = 1):
+    """Tensor indices of the parameter groups in walk order: {W_lm, w_f}, then the layers from the last to the
+    first in runs of `layers_per_group` adjacent layers (six tensors each), then {W_emb}."""
+    groups = [[0, 1]]
+    for k0 in range(0, n_layers, layers_per_group):
+        k1 = min(k0 + layers_per_group, n_layers)
+        groups.append(list(range(2 + 6 * k0, 2 + 6 * k1)))
+    groups.append([2 + 6 * n_layers])
+    return groups
+
+
+def model_step_grouped(ids, dlogits, saved: Dict, m: Dict, cos, sin, s: int, n_heads: int, lr: float,
+                       loss_scale: float, max_norm: float = 1.0, eps_clip: float = 1e-6, layers_per_group: int = 1) -> Dict:
+    """Single backward walk with the grouped norm of section 3.3.1's closing paragraph: the norm of a group of
+    parameters (adjacent layers) stands in for the norm of all of them, so a group can be updated as soon as the
+    walk has left it and no second backward pass is needed.  Every group g gets its own coefficient
+    min(1, max_norm / (||g_group|| + eps)) -- a biased stand-in for the global one, never smaller than it.
+
+    Each hand-on gradient is taken from a parameter before that parameter's update and the walk never returns
+    to a group above, so the gradients are those of the two-pass step.  Overflow: a group with a non-finite
+    gradient is not updated, nor is any group after it in the walk; groups above it have been updated already
+    and stay so; the step reports overflow to the loss scaler (section 3.3.2)."""
+    w = model_gradients(ids, dlogits, saved, m, cos, sin, s, n_heads)
+    names, params, grads = w["names"], w["params"], w["grads"]
+    flags = [O.has_overflow(g) for g in grads]
+    sq = [O.sqnorm(g) for g in grads]
+    groups = model_groups(len(m["layers"]), layers_per_group)
+    new, g_norm, g_coef, g_over = {}, [], [], []
+    stopped = False
+    for idx in groups:
+        stopped = stopped or any(flags[i] for i in idx)
+        g_over.append(stopped)
+        if stopped:
+            g_norm.append(float("nan")); g_coef.append(float("nan"))
+            for i in idx:
+                new[names[i]] = np.array(params[i], copy=True)
+            continue
+        norm = O.grad_norm(math.fsum(sq[i] for i in idx), loss_scale)
+        coef = O.clip_coef(norm, max_norm, eps_clip)
+        g_norm.append(norm); g_coef.append(coef)
+        for i in idx:
+            new[names[i]] = O.sgd_update(params[i], grads[i], lr, coef, loss_scale)
+    return {"params": new, "names": names, "flags": flags, "sqnorms": sq, "groups": groups, "group_norms": g_norm,
+            "group_coefs": g_coef, "group_overflow": g_over, "overflow": stopped, "dh0": w["dh0"],
+            "handons": w["handons"], "per_layer": w["per_layer"]}

@@ -942,22 +942,22 @@ def test_attention_rounding_sensitivity_bounds_a_single_flip():
         assert (np.abs(bumpP.T @ O.as_f64(do)) <= bound[:, 2 * dd:] + 1e-300).all()
 
 
-def test_model_step_is_the_generic_step_on_all_its_tensors():
-    """Two layers, embedding, final norm, output projection: the whole-model oracle equals the generic
-    materialised step applied to its tensors with the hand-on gradients of its own walk."""
-    rng = np.random.default_rng(23)
+def _small_model(rng, n_layers=2):
     B, s, nh, dd, F, V = 2, 8, 2, 8, 24, 50
     T, H = B * s, nh * dd
     f16 = lambda shape, sig: (sig * rng.normal(size=shape)).astype(np.float16)
-    m = {"W_emb": f16((V, H), 1.0), "layers": [_layer_params(rng, H, F, sig=0.3, dtype=np.float16) for _ in range(2)],
+    m = {"W_emb": f16((V, H), 1.0), "layers": [_layer_params(rng, H, F, sig=0.3, dtype=np.float16) for _ in range(n_layers)],
          "w_f": (1.0 + 0.1 * rng.normal(size=H)).astype(np.float16), "W_lm": f16((V, H), 0.3)}
     ids = rng.integers(0, V, size=T).astype(np.int32)
     ids[3] = ids[11]                                    # a repeated token: its embedding rows add up
     dlogits = f16((T, V), 2.0)
     cos, sin = A.rope_tables(s, dd)
     saved = A.model_forward_stored(ids, m, cos, sin, s, nh, 1e-5)
-    a = A.model_step(ids, dlogits, saved, m, cos, sin, s, nh, 0.05, 256.0)
-    assert a["names"][0] == "W_lm" and a["names"][-1] == "W_emb" and len(a["names"]) == 2 + 6 * 2 + 1
+    return m, ids, dlogits, cos, sin, saved, s, nh
+
+
+def _model_records(a, saved, m, ids, dlogits):
+    """The model's tensors as records of the generic step, with the hand-on gradients of the walk `a`."""
     f = saved["final"]
     recs = [dict(kind="linear", X=f["xn"], dY=dlogits, W=m["W_lm"]), dict(kind="vector", X=f["xhat"], dY=a["handons"]["dxn_f"], W=m["w_f"])]
     dy = a["handons"]["dy_top"]
@@ -969,7 +969,16 @@ def test_model_step_is_the_generic_step_on_all_its_tensors():
                  dict(kind="linear", X=sa["xn"], dY=ca["dqkv"], W=p["W_qkv"]), dict(kind="vector", X=sa["xhat"], dY=ca["dxn"], W=p["w1"])]
         dy = ca["dh"]
     recs.append(dict(kind="embedding", ids=ids, dY=dy, W=m["W_emb"]))
-    b = O.step_materialised(recs, 0.05, 256.0)
+    return recs
+
+
+def test_model_step_is_the_generic_step_on_all_its_tensors():
+    """Two layers, embedding, final norm, output projection: the whole-model oracle equals the generic
+    materialised step applied to its tensors with the hand-on gradients of its own walk."""
+    m, ids, dlogits, cos, sin, saved, s, nh = _small_model(np.random.default_rng(23))
+    a = A.model_step(ids, dlogits, saved, m, cos, sin, s, nh, 0.05, 256.0)
+    assert a["names"][0] == "W_lm" and a["names"][-1] == "W_emb" and len(a["names"]) == 2 + 6 * 2 + 1
+    b = O.step_materialised(_model_records(a, saved, m, ids, dlogits), 0.05, 256.0)
     assert a["clip_coef"] == b["clip_coef"] and a["flags"] == b["flags"] and a["clip_coef"] < 1.0
     for name, want in zip(a["names"], b["W"]):
         np.testing.assert_array_equal(a["params"][name].view(np.uint16), want.view(np.uint16))
@@ -977,3 +986,48 @@ def test_model_step_is_the_generic_step_on_all_its_tensors():
     d2 = dlogits.copy()
     d2[0, 0] = np.float16(float(d2[0, 0]) + 4.0)
     assert (A.model_step(ids, d2, saved, m, cos, sin, s, nh, 0.05, 256.0)["dh0"].view(np.uint16) != a["dh0"].view(np.uint16)).any()
+
+
+def test_grouped_norm_step_is_the_generic_step_on_each_group():
+    """Section 3.3.1, grouped norm: every group is clipped by its own norm.  Each group's parameters must equal
+    the generic step applied to that group's tensors alone; the group norms add up (in squares) to the global
+    one, so no group's coefficient is below the global coefficient; without clipping nothing differs."""
+    m, ids, dlogits, cos, sin, saved, s, nh = _small_model(np.random.default_rng(24), n_layers=3)
+    lr, S = 0.05, 256.0
+    two = A.model_step(ids, dlogits, saved, m, cos, sin, s, nh, lr, S)
+    recs = _model_records(two, saved, m, ids, dlogits)
+    for per in (1, 2, 3):
+        g = A.model_step_grouped(ids, dlogits, saved, m, cos, sin, s, nh, lr, S, layers_per_group=per)
+        want_groups = {1: [[0, 1], [2, 3, 4, 5, 6, 7], [8, 9, 10, 11, 12, 13], [14, 15, 16, 17, 18, 19], [20]],
+                       2: [[0, 1], list(range(2, 14)), list(range(14, 20)), [20]],
+                       3: [[0, 1], list(range(2, 20)), [20]]}[per]
+        assert g["groups"] == want_groups and g["overflow"] is False
+        assert abs(math.fsum(n * n for n in g["group_norms"]) / two["norm"] ** 2 - 1) < 1e-12
+        assert all(c >= two["clip_coef"] for c in g["group_coefs"]) and len(set(g["group_coefs"])) > 1
+        for idx, coef in zip(g["groups"], g["group_coefs"]):
+            alone = O.step_materialised([recs[i] for i in idx], lr, S)
+            assert alone["clip_coef"] == coef
+            for i, want in zip(idx, alone["W"]):
+                np.testing.assert_array_equal(g["params"][g["names"][i]].view(np.uint16), want.view(np.uint16))
+    free = A.model_step_grouped(ids, dlogits, saved, m, cos, sin, s, nh, lr, S, max_norm=1e30)
+    free2 = A.model_step(ids, dlogits, saved, m, cos, sin, s, nh, lr, S, max_norm=1e30)
+    for name in free["names"]:
+        np.testing.assert_array_equal(free["params"][name].view(np.uint16), free2["params"][name].view(np.uint16))
+
+
+def test_grouped_norm_overflow_stops_the_walk_updates_from_that_group_on():
+    """A non-finite gradient in the middle of the walk: the groups above were updated before it could be known,
+    the group itself and every group below keep their bits, and the step reports overflow."""
+    m, ids, dlogits, cos, sin, saved, s, nh = _small_model(np.random.default_rng(25), n_layers=3)
+    saved["layers"][1][1]["a"][2, 5] = np.inf          # only the gradient of layer 1's W_d sees this activation
+    g = A.model_step_grouped(ids, dlogits, saved, m, cos, sin, s, nh, 0.05, 256.0)
+    k = g["names"].index("layers.1.W_d")
+    assert [i for i, f in enumerate(g["flags"]) if f] == [k]
+    assert g["group_overflow"] == [False, False, True, True, True] and g["overflow"] is True
+    moved = lambda name, old: (g["params"][name].view(np.uint16) != old.view(np.uint16)).any()
+    assert moved("W_lm", m["W_lm"]) and moved("layers.2.W_gu", m["layers"][2]["W_gu"])
+    for li in (1, 0):
+        for key, old in m["layers"][li].items():
+            assert not moved(f"layers.{li}.{key}", old)
+    assert not moved("W_emb", m["W_emb"])
+    assert A.model_step(ids, dlogits, saved, m, cos, sin, s, nh, 0.05, 256.0)["overflow"] is True
