@@ -14,6 +14,7 @@ on a bounded sample of the same workload.
 """
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -159,15 +160,16 @@ def chain_bench(L, torch, np, dev, steps, warmup):
                                    "algorithmic_bytes": at_bytes, "gb_per_s": at_bytes / at_ms / 1e6}}
 
 
-def model_chain_bench(L, torch, np, dev, steps, warmup, n_layers=32, keep_handons=False):
+def model_chain_bench(L, torch, np, dev, steps, warmup, n_layers=32, keep_handons=False, grouped=0):
     """Two-pass step through a whole 7B-shaped decoder-only model (32 layers, H = 4096, 32 heads, F = 11008,
     vocabulary 32000, 8 x 512 tokens): output projection, final norm, every layer, embedding table, with every
     hand-on gradient produced by the kernels.  Synthetic saved activations, one set per layer (17 GB), and weight
     scales chosen so that the gradient neither dies nor overflows on its way down 32 random layers."""
-    from paper_2306_09782_amd.chain import LomoModelChain
+    from paper_2306_09782_amd.chain import LomoModelChain, LomoGroupedNormChain
     import lomo_synth as S
     Bt, s, nh, H, F, V = 8, 512, 32, 4096, 11008, 32000
     T = Bt * s
+    torch.cuda.reset_peak_memory_stats()
     count = [0]
 
     def gen(shape, sigma):
@@ -191,7 +193,10 @@ def model_chain_bench(L, torch, np, dev, steps, warmup, n_layers=32, keep_handon
     dlogits = gen((T, V), 1.0)
     ang = torch.arange(s, device=dev, dtype=torch.float64)[:, None] * (10000.0 ** (-torch.arange(64, device=dev, dtype=torch.float64) / 64.0))[None, :]
     cos, sin = torch.cos(ang).float().contiguous(), torch.sin(ang).float().contiguous()
-    chain = LomoModelChain(dev, Bt, s, H, F, nh, n_layers, keep_handons=keep_handons)
+    if grouped:
+        chain = LomoGroupedNormChain(dev, Bt, s, H, F, nh, n_layers, layers_per_group=grouped)
+    else:
+        chain = LomoModelChain(dev, Bt, s, H, F, nh, n_layers, keep_handons=keep_handons)
     sv = {"layers": saved, "final": final}
     run = lambda: chain.step(ids, dlogits, sv, m, cos, sin, 1e-3, 1024.0)
     for _ in range(warmup):
@@ -209,15 +214,18 @@ def model_chain_bench(L, torch, np, dev, steps, warmup, n_layers=32, keep_handon
     nb = s // 64
     at_flops = Bt * nh * (nb * (nb + 1) // 2) * 7 * 2 * 64 * 64 * 128
     n_lin = n_layers * H * (3 * H + H + 2 * F + F) + V * H
-    gemms = 3 if keep_handons else 4
-    flops = gemms * 2 * T * n_lin + (1 if keep_handons else 2) * n_layers * at_flops
+    once = keep_handons or grouped
+    gemms = 3 if once else 4
+    flops = gemms * 2 * T * n_lin + (1 if once else 2) * n_layers * at_flops
     n_params = n_lin + V * H + (2 * n_layers + 1) * H
     return {"workload": f"7B-shaped model, chained ({n_layers} layers, 8 x 512 tokens, H 4096, 32 heads, F 11008, V 32000)",
-            "ms_per_step": ms, "gemms_per_linear": gemms, "hand_ons": "kept from pass 1" if keep_handons else "recomputed in pass 2",
-            "params": n_params, "tflops": flops / (ms * 1e-3) / 1e12,
+            "ms_per_step": ms, "gemms_per_linear": gemms, "hand_ons": (f"kept within a group of {grouped} layer(s), one walk" if grouped else
+                                                               "kept from pass 1" if keep_handons else "recomputed in pass 2"),
+            "norm": "per group" if grouped else "global", "params": n_params, "tflops": flops / (ms * 1e-3) / 1e12,
             "tokens_per_s_backward_and_update": T / (ms * 1e-3), "params_per_s": n_params / (ms * 1e-3),
-            "grad_norm": res["norm"], "clip_coef": res["clip_coef"], "overflow": res["overflow"],
-            "device_memory_gb": torch.cuda.max_memory_allocated() / 1e9,
+            "grad_norm": res["norm"] if not grouped else math.sqrt(sum(v * v for v in res["group_norms"])),
+            "clip_coef": res["clip_coef"] if not grouped else [min(res["group_coefs"]), max(res["group_coefs"])],
+            "overflow": res["overflow"], "device_memory_gb": torch.cuda.max_memory_allocated() / 1e9,
             "family_ms_per_step": {k: v[0] / steps for k, v in fam.items() if v[1]}}
 
 
@@ -388,6 +396,8 @@ def main():
         out["model_chain"] = model_chain_bench(L, torch, np, dev, 3, 1)
         torch.cuda.empty_cache()
         out["model_chain_kept_handons"] = model_chain_bench(L, torch, np, dev, 3, 1, keep_handons=True)
+        torch.cuda.empty_cache()
+        out["model_chain_grouped_norm"] = model_chain_bench(L, torch, np, dev, 3, 1, grouped=1)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))

@@ -314,3 +314,137 @@ class LomoModelChain:
 
     def result(self) -> Dict:
         return self.state.result()
+
+
+class _GroupState:
+    """What the blocks need of a step state, for one parameter group: its own accumulator cell, tensor flags,
+    step flag and scalars; the workspace is shared (stream order keeps the groups apart)."""
+
+    def __init__(self, acc, flags, step_flag, chain_flags, ws, scalars):
+        self.acc, self.flags, self.step_flag, self.ws, self.scalars = acc, flags, step_flag, ws, scalars
+        self.chain_flags = chain_flags          # [previous group's step flag | this group's tensor flags]
+        self.n = flags.numel()
+
+    def coefficient(self, lr, loss_scale, max_norm, eps, stream):
+        B.lomo_reduce_flags(self.chain_flags, self.step_flag, stream)
+        B.lomo_step_scalars_device(self.acc, self.step_flag, loss_scale, max_norm, eps, lr, self.scalars, stream)
+
+
+class LomoGroupedNormChain:
+    """Single backward walk over the whole model with the grouped norm that section 3.3.1 closes with: the norm of a
+    group of adjacent layers stands in for the norm of all parameters, so each group is updated as soon as the walk
+    has left it and there is no second pass.  Groups in walk order: {W_lm, w_f}, runs of `layers_per_group` layers
+    from the last to the first, {W_emb}.  Within a group the hand-on gradients are kept until its update (one set of
+    buffers per layer of a group, reused by the next group): one dgrad, one norm GEMM and one fused-update GEMM per
+    linear tensor, one attention / SwiGLU / RMSNorm backward.
+
+    Overflow: a group's step flag is the OR of its tensors' flags and of the previous group's step flag, so a group
+    with a non-finite gradient and every group after it keep their bits; groups above have been updated already."""
+
+    def __init__(self, device, batch: int, seq: int, H: int, F: int, n_heads: int, n_layers: int, layers_per_group: int = 1):
+        self.device = torch.device(device)
+        T = batch * seq
+        per = max(1, min(layers_per_group, n_layers))
+        self.n_layers, self.per = n_layers, per
+        self.bounds = [(k0, min(k0 + per, n_layers)) for k0 in range(0, n_layers, per)]
+        sizes = [2] + [6 * (k1 - k0) for k0, k1 in self.bounds] + [1]
+        G = len(sizes)
+        self.acc = torch.zeros(G, dtype=torch.float64, device=self.device)
+        # flag cells: a zero carry, then for every group its tensor flags followed by its step flag
+        self.flags = torch.zeros(1 + sum(sizes) + G, dtype=torch.int32, device=self.device)
+        self.scalars = torch.zeros(G * 32, dtype=torch.uint8, device=self.device)
+        self._scalars_host = torch.zeros(G * 32, dtype=torch.uint8).pin_memory()
+        nbytes = max(B.lomo_vector_workspace_bytes(T, H), B.lomo_embedding_workspace_bytes(T, H), 256)
+        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.groups, self._flag_slices = [], []
+        cell = 1
+        for g, n in enumerate(sizes):
+            self.groups.append(_GroupState(self.acc[g:g + 1], self.flags[cell:cell + n], self.flags[cell + n:cell + n + 1],
+                                           self.flags[cell - 1:cell + n], self.ws, self.scalars[32 * g:32 * g + 32]))
+            self._flag_slices.append((cell, n))
+            cell += n + 1
+        self.mlp, self.attn = [], []
+        for k in range(n_layers):
+            g, j = 1 + k // per, k % per
+            share = j < len(self.mlp) and k >= per          # later groups reuse the first group's buffers
+            self.mlp.append(LomoMlpBlock(self.device, T, H, F, self.groups[g], 6 * j, share=self.mlp[j] if share else None))
+            self.attn.append(LomoAttentionBlock(self.device, batch, seq, H, n_heads, self.groups[g], 6 * j + 3,
+                                                share=self.attn[j] if share else None))
+        f16 = dict(dtype=torch.float16, device=self.device)
+        self.dxn_f = torch.empty(T, H, **f16)
+        self.dy = [torch.empty(T, H, **f16) for _ in range(per + 1)]
+        self.dh_mid = [torch.empty(T, H, **f16) for _ in range(per)]
+        self._lists = None
+
+    def grad_in(self, k: int):
+        return self.dy[k % len(self.dy)]
+
+    def grad_mid(self, k: int):
+        return self.dh_mid[k % len(self.dh_mid)]
+
+    def _tensor_lists(self, ids, dlogits, saved, m):
+        final = saved["final"]
+        key = tuple(t.data_ptr() for t in [ids, dlogits, final["xn"], m["W_lm"], m["W_emb"]] +
+                    [p["W_d"] for p in m["layers"]] + [sm["a"] for _, sm in saved["layers"]])
+        if self._lists is None or self._lists[0] != key:
+            L = self.n_layers
+            lin = lambda X, dY, W: {"kind": "linear", "X": X, "dY": dY, "W": W}
+            vec = lambda X, dY, W: {"kind": "vector", "X": X, "dY": dY, "W": W}
+            lists = [B.make_tensor_list([lin(final["xn"], dlogits, m["W_lm"]), vec(final["xhat"], self.dxn_f, m["w_f"])])]
+            for k0, k1 in self.bounds:
+                recs = []
+                for k in range(k0, k1):
+                    p = m["layers"][L - 1 - k]
+                    sa, sm = saved["layers"][L - 1 - k]
+                    mlp, attn = self.mlp[k], self.attn[k]
+                    recs += [lin(sm["a"], self.grad_in(k), p["W_d"]), lin(sm["xn"], mlp.dgu, p["W_gu"]),
+                             vec(sm["xhat"], mlp.dxn, p["w2"]), lin(sa["o"], self.grad_mid(k), p["W_o"]),
+                             lin(sa["xn"], attn.dqkv, p["W_qkv"]), vec(sa["xhat"], attn.dxn, p["w1"])]
+                lists.append(B.make_tensor_list(recs))
+            lists.append(B.make_tensor_list([{"kind": "embedding", "ids": ids, "dY": self.grad_in(L), "W": m["W_emb"]}]))
+            self._lists = (key, lists)
+        return self._lists[1]
+
+    def step(self, ids, dlogits, saved: Dict, m: Dict, rope_cos, rope_sin, lr: float, loss_scale: float,
+             max_norm: float = 1.0, eps: float = 1e-6, stream=None) -> None:
+        lists = self._tensor_lists(ids, dlogits, saved, m)
+        self.acc.zero_()
+        self.flags.zero_()
+        L = self.n_layers
+        final = saved["final"]
+
+        def close(g):
+            st = self.groups[g]
+            st.coefficient(lr, loss_scale, max_norm, eps, stream)
+            B.lomo_step_update_pass_device(lists[g], st.scalars, st.step_flag, st.ws, stream)
+
+        top = self.groups[0]
+        _linear(top, 0, final["xn"], dlogits, m["W_lm"], self.dxn_f, None, False, stream)
+        B.lomo_rmsnorm_backward(self.dxn_f, final["xhat"], final["rstd"], m["w_f"], None, self.grad_in(0), stream)
+        _gain(top, 1, final["xhat"], self.dxn_f, m["w_f"], None, False, stream)
+        close(0)
+        for g, (k0, k1) in enumerate(self.bounds, start=1):
+            for k in range(k0, k1):
+                p = m["layers"][L - 1 - k]
+                sa, sm = saved["layers"][L - 1 - k]
+                self.mlp[k].walk(self.grad_in(k), sm, p["w2"], p["W_gu"], p["W_d"], self.grad_mid(k), False, stream)
+                self.attn[k].walk(self.grad_mid(k), sa, p["w1"], p["W_qkv"], p["W_o"], rope_cos, rope_sin,
+                                  self.grad_in(k + 1), False, stream)
+            close(g)
+        last = self.groups[-1]
+        B.lomo_embedding_sqnorm(ids, self.grad_in(L), m["W_emb"].shape[0], last.ws, last.acc, last.flags[0:1], stream)
+        close(len(self.groups) - 1)
+        if stream is None:
+            self._scalars_host.copy_(self.scalars, non_blocking=True)
+        else:
+            with torch.cuda.stream(stream):
+                self._scalars_host.copy_(self.scalars, non_blocking=True)
+
+    def result(self) -> Dict:
+        """Per-group scalars and the tensors' flags in walk order (synchronise first)."""
+        per = [B.unpack_step_scalars(self._scalars_host[32 * g:32 * g + 32]) for g in range(len(self.groups))]
+        host = self.flags.cpu().tolist()
+        flags = [bool(v) for cell, n in self._flag_slices for v in host[cell:cell + n]]
+        stops = [bool(host[cell + n]) for cell, n in self._flag_slices]
+        return {"group_norms": [r["norm"] for r in per], "group_coefs": [r["clip_coef"] for r in per],
+                "group_overflow": stops, "overflow": stops[-1], "flags": flags}

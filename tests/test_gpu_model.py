@@ -183,3 +183,100 @@ def test_model_step_overflow_anywhere_skips_every_tensor(L, keep):
     for p, q in zip(dm["layers"], m["layers"]):
         for k in q:
             np.testing.assert_array_equal(p[k].cpu().numpy().view(np.uint16), q[k].view(np.uint16))
+
+
+# --------------------------------------------------------------------------- grouped norm, single walk
+
+
+def run_grouped(B, s, nh, F, n_layers, m, ids, dlogits, cos, sin, saved, lr, scale, max_norm, per):
+    from paper_2306_09782_amd.chain import LomoGroupedNormChain
+    chain = LomoGroupedNormChain(DEV, B, s, nh * 128, F, nh, n_layers, layers_per_group=per)
+    dm = to_dev_model(m)
+    chain.step(dev(ids), dev(dlogits), to_dev_model_saved(saved), dm, dev(cos), dev(sin), lr, scale, max_norm)
+    torch.cuda.synchronize()
+    return chain, dm
+
+
+def model_tensors(dm_or_m, n_layers, names):
+    out = {}
+    for name in names:
+        parts = name.split(".")
+        t = dm_or_m[name] if len(parts) == 1 else dm_or_m["layers"][int(parts[1])][parts[2]]
+        out[name] = t.cpu().numpy() if torch.is_tensor(t) else t
+    return out
+
+
+@pytest.mark.parametrize("per", [1, 2, 3])
+def test_grouped_norm_chain_matches_oracle(L, per):
+    rng = np.random.default_rng(50 + per)
+    B, s, nh, F, V, n_layers, scale = 1, 128, 2, 344, 384, 3, 2048.0
+    m, ids, dlogits, cos, sin, saved = setup(rng, B, s, nh, F, V, n_layers, scale)
+    # a threshold between the groups' norms, well away from each: some groups are clipped and some are not
+    probe = A.model_step_grouped(ids, dlogits, saved, m, cos, sin, s, nh, 1.0, scale, max_norm=1e30, layers_per_group=per)
+    norms = sorted(probe["group_norms"])
+    max_norm = math.sqrt(norms[0] * norms[1])           # the smallest group (the embedding) stays unclipped
+    lr = visible_lr(ids, dlogits, saved, m, cos, sin, s, nh, scale)
+    want = A.model_step_grouped(ids, dlogits, saved, m, cos, sin, s, nh, lr, scale, max_norm=max_norm, layers_per_group=per)
+    assert min(want["group_coefs"]) < 1.0 and max(want["group_coefs"]) == 1.0
+    chain, dm = run_grouped(B, s, nh, F, n_layers, m, ids, dlogits, cos, sin, saved, lr, scale, max_norm, per)
+    res = chain.result()
+    assert res["flags"] == want["flags"] and res["overflow"] is False and res["group_overflow"] == want["group_overflow"]
+    for a, b in zip(res["group_norms"], want["group_norms"]):
+        assert abs(a / b - 1) < 1e-3
+    for a, b in zip(res["group_coefs"], want["group_coefs"]):
+        assert abs(a / b - 1) < 1e-3 and (a == 1.0) == (b == 1.0)
+    got, old = model_tensors(dm, n_layers, want["names"]), model_tensors(m, n_layers, want["names"])
+    for name in want["names"]:
+        w = want["params"][name]
+        near = np.abs(f64(got[name]) - f64(w)) <= 2.0 ** -9 * np.abs(f64(w) - f64(old[name]))
+        ulps_ok(got[name], w, f"{name} (oracle chain, {per} layers per group)", near=near)
+    frob_ok(chain.grad_in(n_layers).cpu().numpy(), want["dh0"], "gradient of the embedding output", tol=2.0 ** -10)
+    # the last layer group's hand-ons are still in the buffers: strict bar on the device's own bits
+    k0, k1 = chain.bounds[-1]
+    coef = res["group_coefs"][-2]
+    for k in range(k0, k1):
+        li = n_layers - 1 - k
+        p, (sa, sm) = m["layers"][li], saved["layers"][li]
+        hand = dict(lr=lr, coef=coef, S=scale)
+        pre = f"layers.{li}."
+        for key, X, dY, kind in (("W_d", sm["a"], chain.grad_in(k), "linear"), ("W_gu", sm["xn"], chain.mlp[k].dgu, "linear"),
+                                 ("w2", sm["xhat"], chain.mlp[k].dxn, "vector"), ("W_o", sa["o"], chain.grad_mid(k), "linear"),
+                                 ("W_qkv", sa["xn"], chain.attn[k].dqkv, "linear"), ("w1", sa["xhat"], chain.attn[k].dxn, "vector")):
+            weights_ok(got[pre + key], want["params"][pre + key], p[key], pre + key, X, dY.cpu().numpy(), kind=kind, **hand)
+    emb = O.sgd_update(m["W_emb"], O.embedding_grad(ids, chain.grad_in(n_layers).cpu().numpy(), V), lr, res["group_coefs"][-1], scale)
+    ulps_ok(got["W_emb"], emb, "W_emb (oracle update from the device's hand-on)")
+
+
+def test_grouped_norm_chain_without_clipping_is_the_two_pass_step_bit_for_bit(L):
+    rng = np.random.default_rng(54)
+    B, s, nh, F, V, n_layers, scale = 1, 128, 1, 344, 256, 4, 1024.0
+    m, ids, dlogits, cos, sin, saved = setup(rng, B, s, nh, F, V, n_layers, scale)
+    lr = visible_lr(ids, dlogits, saved, m, cos, sin, s, nh, scale)
+    _, d1 = run_model(B, s, nh, F, V, n_layers, m, ids, dlogits, cos, sin, saved, lr, scale, 1e30, share=True)
+    same = lambda a, b: torch.equal(a.view(torch.int16), b.view(torch.int16))
+    for per in (1, 3):            # 3: a ragged last group (layers 3, 2, 1 then layer 0)
+        c2, d2 = run_grouped(B, s, nh, F, n_layers, m, ids, dlogits, cos, sin, saved, lr, scale, 1e30, per)
+        assert c2.result()["group_coefs"] == [1.0] * len(c2.groups)
+        assert same(d1["W_emb"], d2["W_emb"]) and same(d1["W_lm"], d2["W_lm"]) and same(d1["w_f"], d2["w_f"])
+        for p1, p2 in zip(d1["layers"], d2["layers"]):
+            for k in p1:
+                assert same(p1[k], p2[k]), (k, per)
+
+
+def test_grouped_norm_chain_overflow_in_mid_walk(L):
+    rng = np.random.default_rng(55)
+    B, s, nh, F, V, n_layers, scale = 1, 128, 1, 344, 256, 3, 4096.0
+    m, ids, dlogits, cos, sin, saved = setup(rng, B, s, nh, F, V, n_layers, scale)
+    saved["layers"][1][1]["a"][2, 5] = np.inf          # only the gradient of layer 1's W_d sees this activation
+    want = A.model_step_grouped(ids, dlogits, saved, m, cos, sin, s, nh, 1e-2, scale)
+    assert want["group_overflow"] == [False, False, True, True, True]
+    chain, dm = run_grouped(B, s, nh, F, n_layers, m, ids, dlogits, cos, sin, saved, 1e-2, scale, 1.0, 1)
+    res = chain.result()
+    assert res["flags"] == want["flags"] and res["group_overflow"] == want["group_overflow"] and res["overflow"] is True
+    got, old = model_tensors(dm, n_layers, want["names"]), model_tensors(m, n_layers, want["names"])
+    for name in want["names"]:
+        if name in ("W_lm", "w_f") or name.startswith("layers.2."):
+            near = np.abs(f64(got[name]) - f64(want["params"][name])) <= 2.0 ** -9 * np.abs(f64(want["params"][name]) - f64(old[name]))
+            ulps_ok(got[name], want["params"][name], name, near=near)
+        else:
+            np.testing.assert_array_equal(got[name].view(np.uint16), old[name].view(np.uint16), err_msg=name)
