@@ -1031,3 +1031,99 @@ def test_grouped_norm_overflow_stops_the_walk_updates_from_that_group_on():
             assert not moved(f"layers.{li}.{key}", old)
     assert not moved("W_emb", m["W_emb"])
     assert A.model_step(ids, dlogits, saved, m, cos, sin, s, nh, 0.05, 256.0)["overflow"] is True
+
+
+# --------------------------------------------------------------------------- loss (oracle/loss.py)
+
+
+def test_cross_entropy_against_finite_differences_and_library():
+    from oracle import loss as LS
+    from scipy.special import log_softmax
+    rng = np.random.default_rng(31)
+    T, V, S = 7, 24, 512.0
+    z = rng.normal(size=(T, V)) * 3.0
+    tg = rng.integers(0, V, size=T)
+    tg[2] = -100                                       # not counted
+    c = LS.cross_entropy(z, tg, S)
+    assert c["n"] == T - 1 and c["token_losses"][2] == 0.0 and not c["dlogits"][2].any()
+    ls = log_softmax(z, axis=1)
+    want = np.array([-ls[t, tg[t]] if tg[t] >= 0 else 0.0 for t in range(T)])
+    np.testing.assert_allclose(c["token_losses"], want, rtol=1e-12, atol=1e-12)
+    assert abs(c["loss"] - want.sum() / (T - 1)) < 1e-12
+    f = lambda zz: S * LS.cross_entropy(zz, tg, S)["loss"]
+    for (t, v) in ((0, int(tg[0])), (3, 5), (6, 0), (2, 1)):
+        d = np.zeros_like(z)
+        d[t, v] = 1e-5
+        fd = (f(z + d) - f(z - d)) / 2e-5
+        assert abs(fd - c["dlogits"][t, v]) < 1e-5 * S, (t, v)
+    np.testing.assert_allclose(c["dlogits"].sum(axis=1), 0.0, atol=1e-9)
+    assert all(c["dlogits"][t, tg[t]] < 0 for t in range(T) if tg[t] >= 0)
+    u = LS.cross_entropy(np.zeros((3, 16)), [1, 2, 3], 1.0)
+    assert abs(u["loss"] - math.log(16)) < 1e-12
+    np.testing.assert_allclose(u["dlogits"][0, 0], 1.0 / 16 / 3)
+    # a planted mistake (sign of the one-hot term) must fail the finite-difference check
+    bad = c["dlogits"].copy()
+    bad[0, tg[0]] += 2 * S / (T - 1)
+    d = np.zeros_like(z); d[0, tg[0]] = 1e-5
+    assert abs((f(z + d) - f(z - d)) / 2e-5 - bad[0, tg[0]]) > 1.0
+
+
+# --------------------------------------------------------------------------- forward passes (recomputation)
+
+
+def test_forward_definitions_against_closed_forms_and_brute_force():
+    """The forward functions are what a recomputing implementation is compared with, so they are pinned on their
+    own: RMSNorm leaves unit mean square (eps = 0); the rotary step makes q . k depend on the distance only;
+    attention against a per-token loop with scipy's logsumexp; silu at 0 and far from 0."""
+    from scipy.special import logsumexp
+    rng = np.random.default_rng(32)
+    h = rng.normal(size=(5, 16)) * 3
+    xhat, r, xn = M.rmsnorm_forward(h, np.full(16, 2.0), 0.0)
+    np.testing.assert_allclose((xhat ** 2).mean(axis=1), 1.0, rtol=1e-12)
+    np.testing.assert_allclose(xn, 2 * xhat)
+    np.testing.assert_allclose(r, 1 / np.sqrt((h ** 2).mean(axis=1)))
+    assert M.silu(np.array([0.0]))[0] == 0.0 and abs(M.silu(np.array([30.0]))[0] - 30.0) < 1e-10
+    assert abs(M.silu(np.array([-30.0]))[0]) < 1e-10 and abs(M.silu(np.array([1.0]))[0] - 1 / (1 + math.exp(-1.0))) < 1e-15
+    # rotary: the same q and k vector placed at positions (2, 5) and (4, 7) give the same product
+    s, d, nh = 8, 8, 1
+    cos, sin = A.rope_tables(s, d)
+    qv, kv = rng.normal(size=d), rng.normal(size=d)
+    q = np.tile(qv, (s, 1)); k = np.tile(kv, (s, 1))
+    qr, kr = A.rope_rotate(q, cos, sin, s, nh), A.rope_rotate(k, cos, sin, s, nh)
+    assert abs(qr[5] @ kr[2] - qr[7] @ kr[4]) < 1e-6 and abs(qr[5] @ kr[2] - qr[5] @ kr[3]) > 1e-3   # fp32 tables
+    np.testing.assert_allclose(qr[0], qv)                       # position 0: no rotation
+    # attention: brute force per token
+    T, nh, d = 12, 2, 4
+    s = 6
+    q, k, v = (rng.normal(size=(T, nh * d)) for _ in range(3))
+    o, lse = A.attention_forward_f64(q, k, v, s, nh)
+    for t in range(T):
+        b, i = divmod(t, s)
+        for n in range(nh):
+            sl = slice(n * d, (n + 1) * d)
+            sc = np.array([q[t, sl] @ k[b * s + j, sl] / math.sqrt(d) for j in range(i + 1)])
+            assert abs(lse[t, n] - logsumexp(sc)) < 1e-12
+            p = np.exp(sc - logsumexp(sc))
+            np.testing.assert_allclose(o[t, sl], sum(p[j] * v[b * s + j, sl] for j in range(i + 1)), atol=1e-12)
+
+
+def test_stored_forward_is_the_definition_up_to_fp16_storage():
+    """What the stored (fp16) forward leaves behind differs from the fp64 definition by storage rounding only."""
+    rng = np.random.default_rng(33)
+    B, s, nh, dd, F = 2, 8, 2, 8, 24
+    T, H = B * s, nh * dd
+    p = _layer_params(rng, H, F, sig=0.3, dtype=np.float16)
+    h = (rng.normal(size=(T, H))).astype(np.float16)
+    cos, sin = A.rope_tables(s, dd)
+    sa, sm = A.layer_forward_stored(h, p, cos, sin, s, nh, 1e-5)
+    y1 = A.block_forward_f64(h, p["w1"], p["W_qkv"], p["W_o"], cos, sin, s, nh, 1e-5)
+    assert np.abs(sa["y"].astype(np.float64) - y1).max() < 2.0 ** -8 * np.abs(y1).max()
+    y2 = M.block_forward_f64(sa["y"], p["w2"], p["W_gu"], p["W_d"], 1e-5)
+    got = sa["y"].astype(np.float64) + sm["a"].astype(np.float64) @ p["W_d"].astype(np.float64).T
+    assert np.abs(got - y2).max() < 2.0 ** -8 * np.abs(y2).max()
+    # saved pieces against their definitions on the stored inputs
+    xhat, r, _ = M.rmsnorm_forward(h, p["w1"], 1e-5)
+    assert (O.ulp_distance_f16(sa["xhat"], O.round_f16(xhat)) == 0).all() and np.allclose(sa["r"], r, rtol=1e-6)
+    o64, lse64 = A.attention_forward_f64(sa["qkv"][:, :H].astype(np.float64), sa["qkv"][:, H:2 * H].astype(np.float64),
+                                         sa["qkv"][:, 2 * H:].astype(np.float64), s, nh)
+    assert np.abs(sa["lse"] - lse64).max() < 1e-5 and np.abs(sa["o"].astype(np.float64) - o64).max() < 2.0 ** -9 * np.abs(o64).max()
