@@ -269,6 +269,45 @@ lomo_status lomo_attention_backward(const lomo_half* qkv, const lomo_half* o, co
                                     const float* rope_cos, const float* rope_sin, float* delta_ws, lomo_half* dqkv,
                                     int64_t B, int64_t s, int64_t n_heads, int64_t head_dim, void* stream);
 
+/* ---------------------------------------------------------------- forward steps: activation recomputation, loss
+ * With activation checkpointing (paper section 2; section 4.1: 45.61 GB -> 1.79 GB of activations at 7B) only each
+ * layer's input is kept, and the activations the backward loop of Algorithm 1 reads are recomputed from it just
+ * before the loop enters the layer.  These are the forward steps of a LLaMA decoder layer in the same storage
+ * convention as the backward steps above (fp16 tensors, fp32 arithmetic, one rounding per stored element). */
+
+/* Y = X W^T (accumulate == 0) or Y <- Y + X W^T rounded once (accumulate != 0: Y holds the residual stream).
+ * X [T x K], W [N x K], Y [T x N]; K % 8 == 0, N % 8 == 0.  Y may not alias X or W. */
+lomo_status lomo_linear_forward(const lomo_half* X, const lomo_half* W, lomo_half* Y,
+                                int64_t T, int64_t K, int64_t N, int accumulate, void* stream);
+
+/* RMSNorm forward: rstd[t] = 1 / sqrt(mean_j h[t][j]^2 + eps) (fp32 [T]), xhat = h * rstd, xn = xhat * gain with
+ * xhat taken as stored.  h, xhat, xn [T x H]; gain [H]; H % 8 == 0.  xhat or xn may not alias h. */
+lomo_status lomo_rmsnorm_forward(const lomo_half* h, const lomo_half* gain, float eps, lomo_half* xhat, float* rstd,
+                                 lomo_half* xn, int64_t T, int64_t H, void* stream);
+
+/* SwiGLU forward: a = gate / (1 + exp(-gate)) * up.  gate_up [T x 2F] rows [gate | up]; a [T x F]; F % 8 == 0. */
+lomo_status lomo_swiglu_forward(const lomo_half* gate_up, lomo_half* a, int64_t T, int64_t F, void* stream);
+
+/* Rotary position step, in place on the q and k parts of qkv [T x 3H] (H = n_heads * 128, token t at position
+ * t % s): pairs (c, c + 64) of each head are rotated by the angle whose cosine / sine is rope_cos / rope_sin
+ * [s x 64] fp32.  head_dim must be 128. */
+lomo_status lomo_rope_forward(lomo_half* qkv, const float* rope_cos, const float* rope_sin,
+                              int64_t T, int64_t s, int64_t n_heads, int64_t head_dim, void* stream);
+
+/* Causal self-attention forward on the rotated qkv [T x 3H]: o [T x H] and lse [T x n_heads] fp32 as
+ * lomo_attention_backward expects them.  Same shape rules (head_dim 128, s % 64 == 0).  Probabilities pass
+ * through fp16 before they multiply v; o is rounded once.  Deterministic. */
+lomo_status lomo_attention_forward(const lomo_half* qkv, lomo_half* o, float* lse,
+                                   int64_t B, int64_t s, int64_t n_heads, int64_t head_dim, void* stream);
+
+/* Token-level cross-entropy and its scaled gradient (section 3.3.2: the loss is multiplied by the scale before
+ * the backward pass).  logits [T x V] fp16, targets [T] int32, loss [T] fp32 out (loss[t] = lse_t - z[t][target]),
+ * dlogits [T x V] out = grad_scale * (softmax(z_t) - onehot(target_t)); pass grad_scale = loss_scale / (number of
+ * counted tokens) for a mean loss.  A target outside [0, V) leaves its token out: loss 0, zero gradient row.
+ * V % 8 == 0.  dlogits may be the logits buffer itself. */
+lomo_status lomo_cross_entropy(const lomo_half* logits, const int32_t* targets, float grad_scale, float* loss,
+                               lomo_half* dlogits, int64_t T, int64_t V, void* stream);
+
 /* How the norm pass (paper section 3.3.1) obtains ||dY^T X||^2 of a linear tensor.
  *   LOMO_NORM_DIRECT  contract the gradient tile by tile and square it (2 T N K flop).  Default.
  *   LOMO_NORM_GRAM    sum over token pairs of (x_t . x_t')(dy_t . dy_t'), lower triangle only
@@ -286,7 +325,7 @@ int lomo_get_norm_algorithm(void);
 /* Kernel families for lomo_timing_read. */
 enum { LOMO_KERNEL_WGRAD_UPDATE = 0, LOMO_KERNEL_WGRAD_SQNORM = 1, LOMO_KERNEL_DGRAD = 2,
        LOMO_KERNEL_EMBEDDING = 3, LOMO_KERNEL_VECTOR = 4, LOMO_KERNEL_GRAM_SQNORM = 5, LOMO_KERNEL_CHAIN = 6,
-       LOMO_KERNEL_ATTENTION = 7, LOMO_KERNEL_FAMILIES = 8 };
+       LOMO_KERNEL_ATTENTION = 7, LOMO_KERNEL_FORWARD = 8, LOMO_KERNEL_FAMILIES = 9 };
 
 /* Per-kernel timing for benchmarks: while enabled, each launch of a kernel family is bracketed
  * by two HIP events recorded on the launch stream (the only host-side state the library keeps;

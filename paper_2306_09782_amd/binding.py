@@ -21,6 +21,8 @@ EXPORTED_SYMBOLS = (
     "lomo_linear_backward_update_clip_value", "lomo_step_update_pass_clip_value",
     "lomo_set_norm_algorithm", "lomo_get_norm_algorithm", "lomo_step_scalars_device", "lomo_step_update_pass_device",
     "lomo_linear_dgrad", "lomo_swiglu_backward", "lomo_rmsnorm_backward", "lomo_attention_backward",
+    "lomo_linear_forward", "lomo_rmsnorm_forward", "lomo_swiglu_forward", "lomo_rope_forward", "lomo_attention_forward",
+    "lomo_cross_entropy",
 )
 
 
@@ -80,6 +82,12 @@ def load_library():
         "lomo_swiglu_backward": (c_int, [P, P, P, I64, I64, P]),
         "lomo_rmsnorm_backward": (c_int, [P, P, P, P, P, P, I64, I64, P]),
         "lomo_attention_backward": (c_int, [P, P, P, P, P, P, P, P, I64, I64, I64, I64, P]),
+        "lomo_linear_forward": (c_int, [P, P, P, I64, I64, I64, c_int, P]),
+        "lomo_rmsnorm_forward": (c_int, [P, P, c_float, P, P, P, I64, I64, P]),
+        "lomo_swiglu_forward": (c_int, [P, P, I64, I64, P]),
+        "lomo_rope_forward": (c_int, [P, P, P, I64, I64, I64, I64, P]),
+        "lomo_attention_forward": (c_int, [P, P, P, I64, I64, I64, I64, P]),
+        "lomo_cross_entropy": (c_int, [P, P, c_float, P, P, I64, I64, P]),
         "lomo_set_norm_algorithm": (c_int, [c_int]),
         "lomo_get_norm_algorithm": (c_int, []),
         "lomo_timing_enable": (c_int, [c_int]),
@@ -190,7 +198,8 @@ def lomo_embedding_grouping(ids, V, ws, unique_ids, seg_offsets, perm, n_unique,
                                                   _ptr(seg_offsets), _ptr(perm), _ptr(n_unique), _stream(stream)))
 
 
-KERNEL_FAMILIES = ("wgrad_update", "wgrad_sqnorm", "dgrad", "embedding", "vector", "gram_sqnorm", "chain", "attention")
+KERNEL_FAMILIES = ("wgrad_update", "wgrad_sqnorm", "dgrad", "embedding", "vector", "gram_sqnorm", "chain", "attention",
+                   "forward")
 NORM_ALGORITHMS = {"direct": 0, "auto": 1, "gram": 2}
 
 
@@ -259,6 +268,45 @@ def lomo_linear_dgrad(dY, W, dX, stream=None):
     K = W.shape[1]
     assert W.shape[0] == N and tuple(dX.shape) == (T, K)
     _check(load_library().lomo_linear_dgrad(_ptr(dY), _ptr(W), _ptr(dX), T, K, N, _stream(stream)))
+
+
+def lomo_linear_forward(X, W, Y, accumulate=False, stream=None):
+    T, K = X.shape
+    N = W.shape[0]
+    assert W.shape[1] == K and tuple(Y.shape) == (T, N)
+    _check(load_library().lomo_linear_forward(_ptr(X), _ptr(W), _ptr(Y), T, K, N, 1 if accumulate else 0, _stream(stream)))
+
+
+def lomo_rmsnorm_forward(h, gain, eps, xhat, rstd, xn, stream=None):
+    T, H = h.shape
+    assert gain.numel() == H and tuple(xhat.shape) == (T, H) and tuple(xn.shape) == (T, H) and rstd.numel() == T
+    _check(load_library().lomo_rmsnorm_forward(_ptr(h), _ptr(gain), eps, _ptr(xhat), _ptr(rstd), _ptr(xn), T, H,
+                                               _stream(stream)))
+
+
+def lomo_swiglu_forward(gate_up, a, stream=None):
+    T, F = a.shape
+    assert tuple(gate_up.shape) == (T, 2 * F)
+    _check(load_library().lomo_swiglu_forward(_ptr(gate_up), _ptr(a), T, F, _stream(stream)))
+
+
+def lomo_rope_forward(qkv, rope_cos, rope_sin, s, n_heads, stream=None):
+    T, H3 = qkv.shape
+    assert H3 == 3 * n_heads * 128 and T % s == 0 and tuple(rope_cos.shape) == (s, 64) and tuple(rope_sin.shape) == (s, 64)
+    _check(load_library().lomo_rope_forward(_ptr(qkv), _ptr(rope_cos), _ptr(rope_sin), T, s, n_heads, 128, _stream(stream)))
+
+
+def lomo_attention_forward(qkv, o, lse, B, s, n_heads, stream=None):
+    T, H = o.shape
+    assert T == B * s and H == n_heads * 128 and tuple(qkv.shape) == (T, 3 * H) and lse.numel() == T * n_heads
+    _check(load_library().lomo_attention_forward(_ptr(qkv), _ptr(o), _ptr(lse), B, s, n_heads, 128, _stream(stream)))
+
+
+def lomo_cross_entropy(logits, targets, grad_scale, loss, dlogits, stream=None):
+    T, V = logits.shape
+    assert targets.numel() == T and loss.numel() == T and tuple(dlogits.shape) == (T, V)
+    _check(load_library().lomo_cross_entropy(_ptr(logits), _ptr(targets), grad_scale, _ptr(loss), _ptr(dlogits), T, V,
+                                             _stream(stream)))
 
 
 def lomo_swiglu_backward(da, gate_up, dgate_up, stream=None):

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_DIR = os.path.join(HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "liblomo.so")
-SOURCES = ["lomo_api.hip", "lomo_gemm.hip", "lomo_gemm_fast.hip", "lomo_gemm_dma.hip", "lomo_gram.hip", "lomo_chain.hip", "lomo_attention.hip", "lomo_rowops.hip", "lomo_timing.hip"]
+SOURCES = ["lomo_api.hip", "lomo_gemm.hip", "lomo_gemm_fast.hip", "lomo_gemm_dma.hip", "lomo_gram.hip", "lomo_chain.hip", "lomo_attention.hip", "lomo_attention_fwd.hip", "lomo_forward.hip", "lomo_rowops.hip", "lomo_timing.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

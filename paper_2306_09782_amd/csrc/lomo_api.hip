@@ -438,6 +438,83 @@ lomo_status lomo_linear_dgrad(const lomo_half* dY, const lomo_half* W, lomo_half
     return from_hip(launch_dgrad(d, static_cast<hipStream_t>(stream)));
 }
 
+lomo_status lomo_linear_forward(const lomo_half* X, const lomo_half* W, lomo_half* Y, int64_t T, int64_t K, int64_t N,
+                                int accumulate, void* stream) {
+    if (T < 0 || K < 0 || N < 0 || (K & 7) || (N & 7)) return LOMO_ERR_SHAPE;
+    if (T == 0 || N == 0) return LOMO_OK;
+    if (!Y) return LOMO_ERR_NULL;
+    if (K > 0 && (!X || !W)) return LOMO_ERR_NULL;
+    if (misaligned(X) || misaligned(W) || misaligned(Y)) return LOMO_ERR_ALIGN;
+    if (K == 0) return LOMO_ERR_SHAPE;   // an empty contraction would leave Y undefined
+    GemmArgs f{};
+    f.A = W; f.B = X; f.Out = Y;
+    f.M = N; f.Nn = T; f.C = K;
+    f.lda = K; f.ldb = K; f.ldo = N;
+    f.s = -1.0f;                         // accumulate: Y <- rne16(Y - s * acc)
+    f.family = LOMO_KERNEL_FORWARD;
+    return from_hip(launch_forward(f, accumulate != 0, static_cast<hipStream_t>(stream)));
+}
+
+lomo_status lomo_rmsnorm_forward(const lomo_half* h, const lomo_half* gain, float eps, lomo_half* xhat, float* rstd,
+                                 lomo_half* xn, int64_t T, int64_t H, void* stream) {
+    if (T < 0 || H < 0 || (H & 7) || T > 0x7fffffff || !(eps >= 0.f)) return LOMO_ERR_SHAPE;
+    if (T == 0 || H == 0) return LOMO_OK;
+    if (!h || !gain || !xhat || !rstd || !xn) return LOMO_ERR_NULL;
+    if (misaligned(h) || misaligned(gain) || misaligned(xhat) || misaligned(xn) || (reinterpret_cast<uintptr_t>(rstd) & 3u))
+        return LOMO_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ScopedTiming timing(LOMO_KERNEL_CHAIN, st);
+    return from_hip(launch_rmsnorm_forward(h, gain, eps, xhat, rstd, xn, T, H, st));
+}
+
+lomo_status lomo_swiglu_forward(const lomo_half* gate_up, lomo_half* a, int64_t T, int64_t F, void* stream) {
+    if (T < 0 || F < 0 || (F & 7)) return LOMO_ERR_SHAPE;
+    if (T == 0 || F == 0) return LOMO_OK;
+    if (!gate_up || !a) return LOMO_ERR_NULL;
+    if (misaligned(gate_up) || misaligned(a)) return LOMO_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ScopedTiming timing(LOMO_KERNEL_CHAIN, st);
+    return from_hip(launch_swiglu_forward(gate_up, a, T, F, st));
+}
+
+lomo_status lomo_rope_forward(lomo_half* qkv, const float* rope_cos, const float* rope_sin, int64_t T, int64_t s,
+                              int64_t n_heads, int64_t head_dim, void* stream) {
+    if (T < 0 || s <= 0 || n_heads <= 0 || head_dim != 128 || s > (1 << 24) || n_heads > (1 << 16)) return LOMO_ERR_SHAPE;
+    if (T == 0) return LOMO_OK;
+    if (!qkv || !rope_cos || !rope_sin) return LOMO_ERR_NULL;
+    if (misaligned(qkv) || (reinterpret_cast<uintptr_t>(rope_cos) & 3u) || (reinterpret_cast<uintptr_t>(rope_sin) & 3u))
+        return LOMO_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ScopedTiming timing(LOMO_KERNEL_CHAIN, st);
+    return from_hip(launch_rope_forward(qkv, rope_cos, rope_sin, T, s, n_heads, st));
+}
+
+lomo_status lomo_cross_entropy(const lomo_half* logits, const int32_t* targets, float grad_scale, float* loss,
+                               lomo_half* dlogits, int64_t T, int64_t V, void* stream) {
+    if (T < 0 || V < 0 || (V & 7) || T > 0x7fffffff || V > 0x7fffffff) return LOMO_ERR_SHAPE;
+    if (T == 0) return LOMO_OK;
+    if (V == 0) return LOMO_ERR_SHAPE;
+    if (!logits || !targets || !loss || !dlogits) return LOMO_ERR_NULL;
+    if (misaligned(logits) || misaligned(dlogits) || (reinterpret_cast<uintptr_t>(targets) & 3u) ||
+        (reinterpret_cast<uintptr_t>(loss) & 3u))
+        return LOMO_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ScopedTiming timing(LOMO_KERNEL_CHAIN, st);
+    return from_hip(launch_cross_entropy(logits, targets, grad_scale, loss, dlogits, T, V, st));
+}
+
+lomo_status lomo_attention_forward(const lomo_half* qkv, lomo_half* o, float* lse, int64_t B, int64_t s, int64_t n_heads,
+                                   int64_t head_dim, void* stream) {
+    if (B < 0 || s < 0 || n_heads <= 0 || head_dim != 128 || (s % 64) != 0) return LOMO_ERR_SHAPE;
+    if (B * s * n_heads > (int64_t)1 << 31 || (s / 64) * n_heads * B > 0x7fffffff) return LOMO_ERR_SHAPE;
+    if (B == 0 || s == 0) return LOMO_OK;
+    if (!qkv || !o || !lse) return LOMO_ERR_NULL;
+    if (misaligned(qkv) || misaligned(o) || (reinterpret_cast<uintptr_t>(lse) & 3u)) return LOMO_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ScopedTiming timing(LOMO_KERNEL_ATTENTION, st);
+    return from_hip(launch_attention_forward(qkv, o, lse, B, s, n_heads, st));
+}
+
 lomo_status lomo_swiglu_backward(const lomo_half* da, const lomo_half* gate_up, lomo_half* dgate_up, int64_t T, int64_t F,
                                  void* stream) {
     if (T < 0 || F < 0 || (F & 7)) return LOMO_ERR_SHAPE;

@@ -95,7 +95,9 @@ __device__ __forceinline__ void store_contig(uint16_t* __restrict__ lds, const u
 
 // ---- the kernel ---------------------------------------------------------------------------
 
-template <int BM, int BN, bool B_STRIDED, int EPI>
+// A_STRIDED = false serves the forward product Y = X W^T (both operands contraction-contiguous: A = W[n][k]
+// supplies the m index, B = X[t][k] the n index), used to recompute activations from a checkpoint.
+template <int BM, int BN, bool B_STRIDED, int EPI, bool A_STRIDED = true>
 __global__ __launch_bounds__(NT) void lomo_contract_kernel(GemmArgs g) {
     constexpr int TM = BM / 64, TN = BN / 64;          // 32x32 MFMA tiles per wave
     constexpr int STAGE = (BM + BN) * LROW;            // halves per LDS stage
@@ -125,12 +127,13 @@ __global__ __launch_bounds__(NT) void lomo_contract_kernel(GemmArgs g) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    const uint16_t* pa = g.A + m0;                                           // (c = 0, m0)
+    const uint16_t* pa = A_STRIDED ? (g.A + m0) : (g.A + m0 * g.lda);        // (c = 0, m0)
     const uint16_t* pb = B_STRIDED ? (g.B + n0) : (g.B + n0 * g.ldb);        // (c = 0, n0)
-    const int64_t a_step = (int64_t)BK * g.lda;
+    const int64_t a_step = A_STRIDED ? (int64_t)BK * g.lda : (int64_t)BK;
     const int64_t b_step = B_STRIDED ? (int64_t)BK * g.ldb : (int64_t)BK;
 
-    uint32_t ra[BM / 128][8];
+    uint32_t ra[A_STRIDED ? BM / 128 : 1][8];
+    u32x4 rac[A_STRIDED ? 1 : BM / 64];
     uint32_t rbs[B_STRIDED ? BN / 128 : 1][8];
     u32x4 rbc[B_STRIDED ? 1 : BN / 64];
 
@@ -142,11 +145,13 @@ __global__ __launch_bounds__(NT) void lomo_contract_kernel(GemmArgs g) {
         const uint16_t* a = pa + (int64_t)kt * a_step;
         const uint16_t* b = pb + (int64_t)kt * b_step;
         if (!guard) {
-            load_strided<BM, false>(a, g.lda, c_rem, m_rem, ra, tid);
+            if constexpr (A_STRIDED) load_strided<BM, false>(a, g.lda, c_rem, m_rem, ra, tid);
+            else load_contig<BM, false>(a, g.lda, c_rem, m_rem, rac, tid);
             if constexpr (B_STRIDED) load_strided<BN, false>(b, g.ldb, c_rem, n_rem, rbs, tid);
             else load_contig<BN, false>(b, g.ldb, c_rem, n_rem, rbc, tid);
         } else {
-            load_strided<BM, true>(a, g.lda, c_rem, m_rem, ra, tid);
+            if constexpr (A_STRIDED) load_strided<BM, true>(a, g.lda, c_rem, m_rem, ra, tid);
+            else load_contig<BM, true>(a, g.lda, c_rem, m_rem, rac, tid);
             if constexpr (B_STRIDED) load_strided<BN, true>(b, g.ldb, c_rem, n_rem, rbs, tid);
             else load_contig<BN, true>(b, g.ldb, c_rem, n_rem, rbc, tid);
         }
@@ -154,7 +159,8 @@ __global__ __launch_bounds__(NT) void lomo_contract_kernel(GemmArgs g) {
     auto stash = [&](int buf) {
         uint16_t* as = smem + buf * STAGE;
         uint16_t* bs = as + BM * LROW;
-        store_strided<BM>(as, ra, tid);
+        if constexpr (A_STRIDED) store_strided<BM>(as, ra, tid);
+        else store_contig<BM>(as, rac, tid);
         if constexpr (B_STRIDED) store_strided<BN>(bs, rbs, tid);
         else store_contig<BN>(bs, rbc, tid);
     };
@@ -194,11 +200,11 @@ __global__ __launch_bounds__(NT) void lomo_contract_kernel(GemmArgs g) {
 
 // ---- host side ----------------------------------------------------------------------------
 
-template <int BM, int BN, bool B_STRIDED, int EPI>
+template <int BM, int BN, bool B_STRIDED, int EPI, bool A_STRIDED = true>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t st) {
     if (a.M <= 0 || a.Nn <= 0) return hipSuccess;
     constexpr size_t lds = 2u * (BM + BN) * LROW * sizeof(uint16_t);
-    auto kern = lomo_contract_kernel<BM, BN, B_STRIDED, EPI>;
+    auto kern = lomo_contract_kernel<BM, BN, B_STRIDED, EPI, A_STRIDED>;
     static bool configured = false;   // benign race: the attribute call is idempotent
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -267,6 +273,19 @@ hipError_t launch_dgrad(const GemmArgs& a, hipStream_t st) {
     if (fast_enabled() && try_launch_fast<false, EPI_STORE>(a, st, &e)) return e;
     return use_big_tiles(a.M, a.Nn) ? launch_one<256, 256, false, EPI_STORE>(a, st)
                                     : launch_one<128, 128, false, EPI_STORE>(a, st);
+}
+
+// Y = X W^T (EPI_STORE) or Y <- Y + X W^T rounded once (EPI_UPDATE with s = -1: the residual connection).
+hipError_t launch_forward(const GemmArgs& a, bool accumulate, hipStream_t st) {
+    hipError_t e;
+    if (accumulate) {
+        if (fast_enabled() && dma_enabled() && try_launch_dma_nt<EPI_UPDATE>(a, st, &e)) return e;
+        return use_big_tiles(a.M, a.Nn) ? launch_one<256, 256, false, EPI_UPDATE, false>(a, st)
+                                        : launch_one<128, 128, false, EPI_UPDATE, false>(a, st);
+    }
+    if (fast_enabled() && dma_enabled() && try_launch_dma_nt<EPI_STORE>(a, st, &e)) return e;
+    return use_big_tiles(a.M, a.Nn) ? launch_one<256, 256, false, EPI_STORE, false>(a, st)
+                                    : launch_one<128, 128, false, EPI_STORE, false>(a, st);
 }
 
 }  // namespace lomo

@@ -68,7 +68,9 @@ __device__ __forceinline__ half8 read_tr8(const uint16_t* p0, const uint16_t* p1
 
 }  // namespace dma
 
-template <bool B_STRIDED, int EPI>
+// A_STRIDED = false: the A operand is contraction-contiguous as well (forward product Y = X W^T with A = W),
+// fetched and read like the contraction-contiguous B.
+template <bool B_STRIDED, int EPI, bool A_STRIDED = true>
 __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga) {
     using namespace dma;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
@@ -102,7 +104,13 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga
     // ---- fragment read offsets (halves): fixed for the whole kernel
     const int g4 = lane >> 4, j16 = lane & 15;
     const int mhalf = g4 & 1, kh = g4 >> 1, rib = j16 >> 2, piece = j16 & 3;
-    const int a_rd = (8 * kh + rib) * BM + (((wm * (BM / 16) + 2 * mhalf + (piece >> 1)) ^ swz_s(rib)) * 8) + (piece & 1) * 4;
+    int a_rd;
+    if constexpr (A_STRIDED) {
+        a_rd = (8 * kh + rib) * BM + (((wm * (BM / 16) + 2 * mhalf + (piece >> 1)) ^ swz_s(rib)) * 8) + (piece & 1) * 4;
+    } else {
+        const int ml = wm * (BM / 2) + (lane & 31), lh = lane >> 5;
+        a_rd = ml * BK + ((lh ^ swz_c(ml)) * 8);
+    }
     int b_rd;
     if constexpr (B_STRIDED) {
         b_rd = (8 * kh + rib) * BN + (((wn * (BN / 16) + 2 * mhalf + (piece >> 1)) ^ swz_s(rib)) * 8) + (piece & 1) * 4;
@@ -138,9 +146,12 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             const int q = wave * 4 + it;
-            {
+            if constexpr (A_STRIDED) {
                 const int r = 2 * q + (lane >> 5), cp = lane & 31;
                 a_voff[it] = (uint32_t)(r * T.lda + ((cp ^ swz_s(r)) * 8)) * 2u;
+            } else {
+                const int n = 16 * q + (lane >> 2), cp = lane & 3;
+                a_voff[it] = (uint32_t)(n * T.lda + ((cp ^ swz_c(n)) * 8)) * 2u;
             }
             if constexpr (B_STRIDED) {
                 const int r = 2 * q + (lane >> 5), cp = lane & 31;
@@ -150,9 +161,9 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga
                 b_voff[it] = (uint32_t)(n * T.ldb + ((cp ^ swz_c(n)) * 8)) * 2u;
             }
         }
-        pa = T.A + m0;
+        pa = A_STRIDED ? (T.A + m0) : (T.A + m0 * (int64_t)T.lda);
         pb = B_STRIDED ? (T.B + n0) : (T.B + n0 * (int64_t)T.ldb);
-        a_step = (int64_t)BK * T.lda;
+        a_step = A_STRIDED ? (int64_t)BK * T.lda : (int64_t)BK;
         b_step = B_STRIDED ? (int64_t)BK * T.ldb : (int64_t)BK;
         KT = T.C / BK;
     };
@@ -187,8 +198,12 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga
         a[i] = *reinterpret_cast<const half8*>(smem + buf * STAGE_HALVES + (lane & 31) * 32 + (lane >> 5) * 8 + kk * 16 + i * 1024);
         return;
 #endif
-        const uint16_t* p = smem + buf * STAGE_HALVES + ((a_rd ^ (i << 5)) + kk * 16 * BM);
-        a[i] = read_tr8(p, p + 4 * BM);
+        if constexpr (A_STRIDED) {
+            const uint16_t* p = smem + buf * STAGE_HALVES + ((a_rd ^ (i << 5)) + kk * 16 * BM);
+            a[i] = read_tr8(p, p + 4 * BM);
+        } else {
+            a[i] = *reinterpret_cast<const half8*>(smem + buf * STAGE_HALVES + ((a_rd ^ (kk << 4)) + i * 32 * BK));
+        }
     };
     auto read_b = [&](half8 (&b)[4], int buf, int kk, int j) {
         const uint16_t* bs = smem + buf * STAGE_HALVES + A_HALVES;
@@ -220,9 +235,9 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga
             if (q == 3) { read_a(a, buf, kk, 2); read_a(a, buf, kk, 3); }
         }
     };
-    constexpr int RB = B_STRIDED ? 2 : 1;                       // LDS read instructions per b fragment
-    constexpr int READS_EARLY[4] = {2 + 2 * RB, 2 * RB + 2, 4, 0};
-    constexpr int READS_EVEN[4] = {2 + RB, 2 * RB, RB + 2, 4};
+    constexpr int RA = A_STRIDED ? 2 : 1, RB = B_STRIDED ? 2 : 1;     // LDS read instructions per fragment
+    constexpr int READS_EARLY[4] = {RA + 2 * RB, 2 * RB + RA, 2 * RA, 0};
+    constexpr int READS_EVEN[4] = {RA + RB, 2 * RB, RB + RA, 2 * RA};
 
     floatx16 acc[4][4];
     auto zero_acc = [&] {
@@ -349,10 +364,10 @@ bool dma_eligible(const GemmArgs& a) {
            (a.M / BM) * (a.Nn / BN) < (1 << 24);
 }
 
-template <bool B_STRIDED, int EPI>
-hipError_t launch_dma_group(const GemmArgs* list, int n, hipStream_t st) {
+template <bool B_STRIDED, int EPI, bool A_STRIDED>
+static hipError_t launch_dma_group_impl(const GemmArgs* list, int n, hipStream_t st) {
     using namespace dma;
-    auto kern = lomo_contract_dma_kernel<B_STRIDED, EPI>;
+    auto kern = lomo_contract_dma_kernel<B_STRIDED, EPI, A_STRIDED>;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -389,6 +404,22 @@ hipError_t launch_dma_group(const GemmArgs* list, int n, hipStream_t st) {
     }
     return hipSuccess;
 }
+
+template <bool B_STRIDED, int EPI>
+hipError_t launch_dma_group(const GemmArgs* list, int n, hipStream_t st) {
+    return launch_dma_group_impl<B_STRIDED, EPI, true>(list, n, st);
+}
+
+// Forward product (A contraction-contiguous): same eligibility, except that A's row stride now multiplies
+// the 256 tile rows instead of the 32 slice rows.
+template <int EPI>
+bool try_launch_dma_nt(const GemmArgs& a, hipStream_t st, hipError_t* err) {
+    if (!dma_eligible(a) || (int64_t)dma::BM * a.lda >= (1 << 30) || (a.M / dma::BM) * (a.Nn / dma::BN) < 192) return false;
+    *err = launch_dma_group_impl<false, EPI, false>(&a, 1, st);
+    return true;
+}
+template bool try_launch_dma_nt<EPI_STORE>(const GemmArgs&, hipStream_t, hipError_t*);
+template bool try_launch_dma_nt<EPI_UPDATE>(const GemmArgs&, hipStream_t, hipError_t*);
 
 // Single tensor: worth it when there are enough tiles to fill most of the chip.
 template <bool B_STRIDED, int EPI>

@@ -19,7 +19,7 @@ enum Epilogue : int {
 };
 
 // One contraction  Out[n][m] (+)= sum_c A(c, m) * B(c, n).
-//   A is always "contraction-strided":   A[c * lda + m]
+//   A is "contraction-strided", A[c * lda + m], except in the forward product (A[m * lda + c]).
 //   B is contraction-strided  (B[c * ldb + n])  or contraction-contiguous (B[n * ldb + c]).
 // wgrad: A = X, B = dY (strided), Out = W;   M = K_in, Nn = N_out, C = T.
 // dgrad: A = W, B = dY (contiguous), Out = dX; M = K_in, Nn = T, C = N_out.
@@ -50,6 +50,9 @@ template <bool B_STRIDED, int EPI>
 bool try_launch_dma(const GemmArgs& a, hipStream_t st, hipError_t* err);
 template <bool B_STRIDED, int EPI>
 hipError_t launch_dma_group(const GemmArgs* list, int n, hipStream_t st);
+// Forward product Y = X W^T: A = W [M x C] and B = X [Nn x C], both contraction-contiguous.
+template <int EPI>
+bool try_launch_dma_nt(const GemmArgs& a, hipStream_t st, hipError_t* err);
 
 // Gram route of the norm pass (lomo_gram.hip): ||dY^T X||^2 from X X^T and dY dY^T.  `a` is a norm-pass
 // contraction (A = X, B = dY, C = T).  Costs are in units of one 256 x 256 x 32 slice on one CU.
@@ -66,6 +69,8 @@ hipError_t launch_wgrad_update(const GemmArgs& a, hipStream_t st);
 hipError_t launch_wgrad_update_clipv(const GemmArgs& a, hipStream_t st);
 hipError_t launch_wgrad_sqnorm(const GemmArgs& a, hipStream_t st);
 hipError_t launch_dgrad(const GemmArgs& a, hipStream_t st);
+// A = W [M = N_out x C = K_in], B = X [Nn = T x C], Out = Y [T x N_out]; accumulate: Y <- rne16(Y + acc).
+hipError_t launch_forward(const GemmArgs& a, bool accumulate, hipStream_t st);
 
 // Row-wise kernels -------------------------------------------------------------------------
 struct EmbeddingWs {          // carved out of the caller's workspace
@@ -128,6 +133,15 @@ hipError_t launch_swiglu_backward(const uint16_t* da, const uint16_t* gate_up, u
                                   hipStream_t st);
 hipError_t launch_rmsnorm_backward(const uint16_t* dxn, const uint16_t* xhat, const float* rstd, const uint16_t* gain,
                                    const uint16_t* dres, uint16_t* dh, int64_t T, int64_t H, hipStream_t st);
+
+// Forward steps for activation recomputation and the loss (lomo_forward.hip, lomo_attention_fwd.hip).
+hipError_t launch_rmsnorm_forward(const uint16_t* h, const uint16_t* gain, float eps, uint16_t* xhat, float* rstd, uint16_t* xn,
+                                  int64_t T, int64_t H, hipStream_t st);
+hipError_t launch_swiglu_forward(const uint16_t* gate_up, uint16_t* a, int64_t T, int64_t F, hipStream_t st);
+hipError_t launch_rope_forward(uint16_t* qkv, const float* cosv, const float* sinv, int64_t T, int64_t s, int64_t nh, hipStream_t st);
+hipError_t launch_cross_entropy(const uint16_t* z, const int32_t* target, float grad_scale, float* loss, uint16_t* dz, int64_t T,
+                                int64_t V, hipStream_t st);
+hipError_t launch_attention_forward(const uint16_t* qkv, uint16_t* o, float* lse, int64_t B, int64_t s, int64_t nh, hipStream_t st);
 
 // Causal attention backward with the rotary step (lomo_attention.hip): head width 128, s % 64 == 0.
 hipError_t launch_attention_backward(const uint16_t* qkv, const uint16_t* o, const uint16_t* dO, const float* lse,
