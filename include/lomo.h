@@ -280,6 +280,11 @@ lomo_status lomo_attention_backward(const lomo_half* qkv, const lomo_half* o, co
 lomo_status lomo_linear_forward(const lomo_half* X, const lomo_half* W, lomo_half* Y,
                                 int64_t T, int64_t K, int64_t N, int accumulate, void* stream);
 
+/* Embedding rows: h[t] = W[ids[t]] (ids [T] int32, W [V x H], h [T x H]); an id outside [0, V) gives a zero row.
+ * H % 8 == 0. */
+lomo_status lomo_embedding_forward(const int32_t* ids, const lomo_half* W, lomo_half* h,
+                                   int64_t T, int64_t H, int64_t V, void* stream);
+
 /* RMSNorm forward: rstd[t] = 1 / sqrt(mean_j h[t][j]^2 + eps) (fp32 [T]), xhat = h * rstd, xn = xhat * gain with
  * xhat taken as stored.  h, xhat, xn [T x H]; gain [H]; H % 8 == 0.  xhat or xn may not alias h. */
 lomo_status lomo_rmsnorm_forward(const lomo_half* h, const lomo_half* gain, float eps, lomo_half* xhat, float* rstd,

@@ -255,7 +255,7 @@ class LomoModelChain:
             self._top = (key, lm, gain, emb)
         return self._top[1:]
 
-    def _walk(self, ids, dlogits, saved, m, rope_cos, rope_sin, update, stream):
+    def _walk(self, ids, dlogits, saved, m, rope_cos, rope_sin, update, stream, before_layer=None):
         st = self.state
         final = saved["final"]
         L = self.n_layers
@@ -268,6 +268,8 @@ class LomoModelChain:
             li = L - 1 - k
             p = m["layers"][li]
             sa, sm = saved["layers"][li]
+            if before_layer is not None:
+                before_layer(li, k)          # e.g. recompute this layer's activations from its checkpoint
             dy, mid, dh = self.grad_in(k), self.grad_mid(k), self.grad_in(k + 1)
             self.mlp[k].walk(dy, sm, p["w2"], p["W_gu"], p["W_d"], mid, update, stream)
             self.attn[k].walk(mid, sa, p["w1"], p["W_qkv"], p["W_o"], rope_cos, rope_sin, dh, update, stream)
@@ -278,17 +280,19 @@ class LomoModelChain:
             B.lomo_embedding_sqnorm(ids, dh0, m["W_emb"].shape[0], st.ws, st.acc, st.flags[slot:slot + 1], stream)
 
     def step(self, ids, dlogits, saved: Dict, m: Dict, rope_cos, rope_sin, lr: float, loss_scale: float,
-             max_norm: float = 1.0, eps: float = 1e-6, stream=None) -> None:
+             max_norm: float = 1.0, eps: float = 1e-6, stream=None, before_layer=None) -> None:
         """m: {"W_emb", "layers": [{"w1","W_qkv","W_o","w2","W_gu","W_d"}, ...], "w_f", "W_lm"}, updated in place.
-        saved: {"layers": [(attention-block activations, feed-forward-block activations), ...], "final": {...}}."""
+        saved: {"layers": [(attention-block activations, feed-forward-block activations), ...], "final": {...}}.
+        before_layer(layer index, walk index) is called before the walk enters a layer, in both passes."""
+        assert before_layer is None or not self.keep_handons, "kept hand-ons need every layer's activations in pass 2"
         self.state.begin()
-        self._walk(ids, dlogits, saved, m, rope_cos, rope_sin, False, stream)
+        self._walk(ids, dlogits, saved, m, rope_cos, rope_sin, False, stream, before_layer)
         self.state.coefficient(lr, loss_scale, max_norm, eps, stream)
         if self.keep_handons:
             st = self.state
             B.lomo_step_update_pass_device(self._all_tensors(ids, dlogits, saved, m), st.scalars, st.step_flag, st.ws, stream)
         else:
-            self._walk(ids, dlogits, saved, m, rope_cos, rope_sin, True, stream)
+            self._walk(ids, dlogits, saved, m, rope_cos, rope_sin, True, stream, before_layer)
         self.state.finish(stream)
 
     def _all_tensors(self, ids, dlogits, saved, m):
@@ -406,7 +410,7 @@ class LomoGroupedNormChain:
         return self._lists[1]
 
     def step(self, ids, dlogits, saved: Dict, m: Dict, rope_cos, rope_sin, lr: float, loss_scale: float,
-             max_norm: float = 1.0, eps: float = 1e-6, stream=None) -> None:
+             max_norm: float = 1.0, eps: float = 1e-6, stream=None, before_layer=None) -> None:
         lists = self._tensor_lists(ids, dlogits, saved, m)
         self.acc.zero_()
         self.flags.zero_()
@@ -427,6 +431,8 @@ class LomoGroupedNormChain:
             for k in range(k0, k1):
                 p = m["layers"][L - 1 - k]
                 sa, sm = saved["layers"][L - 1 - k]
+                if before_layer is not None:
+                    before_layer(L - 1 - k, k)
                 self.mlp[k].walk(self.grad_in(k), sm, p["w2"], p["W_gu"], p["W_d"], self.grad_mid(k), False, stream)
                 self.attn[k].walk(self.grad_mid(k), sa, p["w1"], p["W_qkv"], p["W_o"], rope_cos, rope_sin,
                                   self.grad_in(k + 1), False, stream)
@@ -448,3 +454,116 @@ class LomoGroupedNormChain:
         stops = [bool(host[cell + n]) for cell, n in self._flag_slices]
         return {"group_norms": [r["norm"] for r in per], "group_coefs": [r["clip_coef"] for r in per],
                 "group_overflow": stops, "overflow": stops[-1], "flags": flags}
+
+
+# --------------------------------------------------------------------------- forward, checkpoints, recomputation
+
+
+class LayerActivations:
+    """The activations of one decoder layer that the backward loop reads: attention block {xhat, rstd, xn, qkv
+    (rotated q | rotated k | v), o, lse}, feed-forward block {xhat, rstd, xn, gate_up, a}, and y1, the attention
+    block's output (the feed-forward block's input)."""
+
+    def __init__(self, device, T: int, H: int, F: int, n_heads: int):
+        f16 = dict(dtype=torch.float16, device=device)
+        f32 = dict(dtype=torch.float32, device=device)
+        self.attn = {"xhat": torch.empty(T, H, **f16), "rstd": torch.empty(T, **f32), "xn": torch.empty(T, H, **f16),
+                     "qkv": torch.empty(T, 3 * H, **f16), "o": torch.empty(T, H, **f16), "lse": torch.empty(T, n_heads, **f32)}
+        self.mlp = {"xhat": torch.empty(T, H, **f16), "rstd": torch.empty(T, **f32), "xn": torch.empty(T, H, **f16),
+                    "gate_up": torch.empty(T, 2 * F, **f16), "a": torch.empty(T, F, **f16)}
+        self.y1 = torch.empty(T, H, **f16)
+
+
+def _copy(dst, src, stream):
+    if stream is None:
+        dst.copy_(src)
+    else:
+        with torch.cuda.stream(stream):
+            dst.copy_(src)
+
+
+def layer_forward(h, p: Dict, act: LayerActivations, rope_cos, rope_sin, batch: int, seq: int, n_heads: int, eps: float,
+                  h_next=None, stream=None) -> None:
+    """Forward of one decoder layer from its input h into `act`; with h_next also the layer output
+    h_next = y1 + a W_d^T (a recomputation before the backward walk does not need it)."""
+    sa, sm = act.attn, act.mlp
+    B.lomo_rmsnorm_forward(h, p["w1"], eps, sa["xhat"], sa["rstd"], sa["xn"], stream)
+    B.lomo_linear_forward(sa["xn"], p["W_qkv"], sa["qkv"], False, stream)
+    B.lomo_rope_forward(sa["qkv"], rope_cos, rope_sin, seq, n_heads, stream)
+    B.lomo_attention_forward(sa["qkv"], sa["o"], sa["lse"], batch, seq, n_heads, stream)
+    _copy(act.y1, h, stream)
+    B.lomo_linear_forward(sa["o"], p["W_o"], act.y1, True, stream)                 # y1 = h + o W_o^T, one rounding
+    B.lomo_rmsnorm_forward(act.y1, p["w2"], eps, sm["xhat"], sm["rstd"], sm["xn"], stream)
+    B.lomo_linear_forward(sm["xn"], p["W_gu"], sm["gate_up"], False, stream)
+    B.lomo_swiglu_forward(sm["gate_up"], sm["a"], stream)
+    if h_next is not None:
+        _copy(h_next, act.y1, stream)
+        B.lomo_linear_forward(sm["a"], p["W_d"], h_next, True, stream)
+
+
+class LomoFineTuneStep:
+    """One whole LOMO training step of a decoder-only model from token ids: forward pass keeping only each layer's
+    input (activation checkpointing), token-level cross-entropy with the loss scale folded into its gradient, then
+    Algorithm 1's backward loop with each layer's activations recomputed from its checkpoint just before the walk
+    enters it.  norm="global": two passes (the norm of all parameters), so every layer is recomputed twice;
+    norm="grouped": one walk with per-group norms, one recomputation.  Activation memory: (n_layers + 1) [T x H]
+    checkpoints, one layer's activations (per layer of a group), the logits."""
+
+    def __init__(self, device, batch: int, seq: int, H: int, F: int, n_heads: int, n_layers: int, V: int,
+                 eps: float = 1e-5, norm: str = "global", layers_per_group: int = 1):
+        assert norm in ("global", "grouped")
+        self.device = torch.device(device)
+        T = batch * seq
+        self.batch, self.seq, self.n_heads, self.n_layers, self.eps = batch, seq, n_heads, n_layers, eps
+        f16 = dict(dtype=torch.float16, device=self.device)
+        self.ckpt = [torch.empty(T, H, **f16) for _ in range(n_layers + 1)]
+        per = layers_per_group if norm == "grouped" else 1
+        self.acts = [LayerActivations(self.device, T, H, F, n_heads) for _ in range(max(1, min(per, n_layers)))]
+        self.final = {"xhat": torch.empty(T, H, **f16), "rstd": torch.empty(T, dtype=torch.float32, device=self.device),
+                      "xn": torch.empty(T, H, **f16)}
+        self.logits = torch.empty(T, V, **f16)           # overwritten by its own gradient
+        self.token_loss = torch.empty(T, dtype=torch.float32, device=self.device)
+        if norm == "grouped":
+            self.chain = LomoGroupedNormChain(self.device, batch, seq, H, F, n_heads, n_layers, layers_per_group=per)
+        else:
+            self.chain = LomoModelChain(self.device, batch, seq, H, F, n_heads, n_layers)
+        # walk index k = n_layers - 1 - layer index; the layers of one group use different activation sets
+        self.saved = {"layers": [(self._act(li).attn, self._act(li).mlp) for li in range(n_layers)], "final": self.final}
+
+    def _act(self, li: int) -> LayerActivations:
+        return self.acts[(self.n_layers - 1 - li) % len(self.acts)]
+
+    def forward(self, ids, targets, grad_scale: float, m: Dict, rope_cos, rope_sin, stream=None) -> None:
+        """Checkpoints, final norm, logits, token losses, and the scaled loss gradient in place of the logits."""
+        B.lomo_embedding_forward(ids, m["W_emb"], self.ckpt[0], stream)
+        for li, p in enumerate(m["layers"]):
+            layer_forward(self.ckpt[li], p, self._act(li), rope_cos, rope_sin, self.batch, self.seq, self.n_heads, self.eps,
+                          self.ckpt[li + 1], stream)
+        f = self.final
+        B.lomo_rmsnorm_forward(self.ckpt[self.n_layers], m["w_f"], self.eps, f["xhat"], f["rstd"], f["xn"], stream)
+        B.lomo_linear_forward(f["xn"], m["W_lm"], self.logits, False, stream)
+        B.lomo_cross_entropy(self.logits, targets, grad_scale, self.token_loss, self.logits, stream)
+
+    def step(self, ids, targets, n_counted: int, m: Dict, rope_cos, rope_sin, lr: float, loss_scale: float,
+             max_norm: float = 1.0, eps_clip: float = 1e-6, stream=None) -> None:
+        """m as for LomoModelChain, updated in place.  targets [T] int32 (outside [0, V): not counted); n_counted is
+        the number of counted targets (the mean loss's denominator)."""
+        self.n_counted = n_counted
+        self.forward(ids, targets, loss_scale / n_counted, m, rope_cos, rope_sin, stream)
+        fresh = [self.n_layers - 1]          # the forward pass has just left the last layer's activations in place
+
+        def recompute(li, k):
+            if fresh and fresh[0] == li:
+                fresh.clear()
+                return
+            layer_forward(self.ckpt[li], m["layers"][li], self._act(li), rope_cos, rope_sin, self.batch, self.seq,
+                          self.n_heads, self.eps, None, stream)
+
+        self.chain.step(ids, self.logits, self.saved, m, rope_cos, rope_sin, lr, loss_scale, max_norm, eps_clip, stream,
+                        before_layer=recompute)
+
+    def result(self) -> Dict:
+        """The chain's scalars and flags plus the mean loss over the counted tokens (synchronise first)."""
+        out = self.chain.result()
+        out["loss"] = float(self.token_loss.double().sum().item()) / self.n_counted
+        return out

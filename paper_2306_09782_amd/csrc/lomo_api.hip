@@ -455,6 +455,17 @@ lomo_status lomo_linear_forward(const lomo_half* X, const lomo_half* W, lomo_hal
     return from_hip(launch_forward(f, accumulate != 0, static_cast<hipStream_t>(stream)));
 }
 
+lomo_status lomo_embedding_forward(const int32_t* ids, const lomo_half* W, lomo_half* h, int64_t T, int64_t H, int64_t V,
+                                   void* stream) {
+    if (T < 0 || H < 0 || V < 0 || (H & 7)) return LOMO_ERR_SHAPE;
+    if (T == 0 || H == 0) return LOMO_OK;
+    if (!ids || !h || (V > 0 && !W)) return LOMO_ERR_NULL;
+    if (misaligned(W) || misaligned(h) || (reinterpret_cast<uintptr_t>(ids) & 3u)) return LOMO_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ScopedTiming timing(LOMO_KERNEL_CHAIN, st);
+    return from_hip(launch_embedding_forward(ids, W, h, T, H, V, st));
+}
+
 lomo_status lomo_rmsnorm_forward(const lomo_half* h, const lomo_half* gain, float eps, lomo_half* xhat, float* rstd,
                                  lomo_half* xn, int64_t T, int64_t H, void* stream) {
     if (T < 0 || H < 0 || (H & 7) || T > 0x7fffffff || !(eps >= 0.f)) return LOMO_ERR_SHAPE;

@@ -150,6 +150,26 @@ __global__ __launch_bounds__(FW_NT) void cross_entropy_kernel(const uint16_t* z,
     }
 }
 
+// Embedding rows: h[t] = W[ids[t]]; one thread per 16-byte chunk.  An id outside [0, V) gives a zero row.
+__global__ __launch_bounds__(FW_NT) void embedding_forward_kernel(const int32_t* __restrict__ ids, const uint16_t* __restrict__ W,
+                                                                  uint16_t* __restrict__ h, int64_t T, int64_t H, int64_t V) {
+    const int64_t chunks = H >> 3;
+    const int64_t i = (int64_t)blockIdx.x * FW_NT + threadIdx.x;
+    if (i >= T * chunks) return;
+    const int64_t t = i / chunks, c = (i - t * chunks) << 3;
+    const int64_t id = ids[t];
+    half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (id >= 0 && id < V) v = *reinterpret_cast<const half8*>(W + id * H + c);
+    *reinterpret_cast<half8*>(h + t * H + c) = v;
+}
+
+hipError_t launch_embedding_forward(const int32_t* ids, const uint16_t* W, uint16_t* h, int64_t T, int64_t H, int64_t V,
+                                    hipStream_t st) {
+    const int64_t n = T * (H >> 3);
+    hipLaunchKernelGGL(embedding_forward_kernel, dim3((unsigned)((n + FW_NT - 1) / FW_NT)), dim3(FW_NT), 0, st, ids, W, h, T, H, V);
+    return hipGetLastError();
+}
+
 hipError_t launch_rmsnorm_forward(const uint16_t* h, const uint16_t* gain, float eps, uint16_t* xhat, float* rstd, uint16_t* xn,
                                   int64_t T, int64_t H, hipStream_t st) {
     hipLaunchKernelGGL(rmsnorm_forward_kernel, dim3((unsigned)T), dim3(FW_NT), 0, st, h, gain, eps, xhat, rstd, xn, H);

@@ -141,6 +141,8 @@ hipError_t launch_swiglu_forward(const uint16_t* gate_up, uint16_t* a, int64_t T
 hipError_t launch_rope_forward(uint16_t* qkv, const float* cosv, const float* sinv, int64_t T, int64_t s, int64_t nh, hipStream_t st);
 hipError_t launch_cross_entropy(const uint16_t* z, const int32_t* target, float grad_scale, float* loss, uint16_t* dz, int64_t T,
                                 int64_t V, hipStream_t st);
+hipError_t launch_embedding_forward(const int32_t* ids, const uint16_t* W, uint16_t* h, int64_t T, int64_t H, int64_t V,
+                                    hipStream_t st);
 hipError_t launch_attention_forward(const uint16_t* qkv, uint16_t* o, float* lse, int64_t B, int64_t s, int64_t nh, hipStream_t st);
 
 // Causal attention backward with the rotary step (lomo_attention.hip): head width 128, s % 64 == 0.
