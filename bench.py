@@ -229,6 +229,69 @@ def model_chain_bench(L, torch, np, dev, steps, warmup, n_layers=32, keep_handon
             "family_ms_per_step": {k: v[0] / steps for k, v in fam.items() if v[1]}}
 
 
+def train_step_bench(L, torch, np, dev, steps, warmup, norm, n_layers=32):
+    """One whole fine-tuning step of a 7B-shaped model from token ids (8 x 512 tokens, 32 layers, H 4096, 32 heads,
+    F 11008, V 32000): forward keeping only the layer inputs, cross-entropy, backward loop with every layer
+    recomputed from its checkpoint, fused updates.  Random-init weights (sigma 0.02, gains 1), Zipf token ids;
+    the target of a position is the next token."""
+    from paper_2306_09782_amd.chain import LomoFineTuneStep
+    import lomo_synth as S
+    Bt, s, nh, H, F, V = 8, 512, 32, 4096, 11008, 32000
+    T = Bt * s
+    torch.cuda.reset_peak_memory_stats()
+    count = [0]
+
+    def gen(shape, sigma):
+        count[0] += 1
+        return S.normal_f16_torch(S.tensor_key(0, 97, count[0], 0), shape, S.normal_mult(sigma), dev)
+    ones = lambda n: torch.ones(n, dtype=torch.float16, device=dev)
+    m = {"W_emb": gen((V, H), 1.0), "w_f": ones(H), "W_lm": gen((V, H), 0.02),
+         "layers": [{"w1": ones(H), "w2": ones(H), "W_qkv": gen((3 * H, H), 0.02), "W_o": gen((H, H), 0.02),
+                     "W_gu": gen((2 * F, H), 0.02), "W_d": gen((H, F), 0.02)} for _ in range(n_layers)]}
+    ids_h = S.zipf_ids(97, T, V).astype(np.int32)
+    tg_h = np.roll(ids_h, -1).astype(np.int32)
+    tg_h[s - 1::s] = -100
+    n_counted = int((tg_h >= 0).sum())
+    ids, targets = torch.from_numpy(ids_h).to(dev), torch.from_numpy(tg_h).to(dev)
+    ang = torch.arange(s, device=dev, dtype=torch.float64)[:, None] * (10000.0 ** (-torch.arange(64, device=dev, dtype=torch.float64) / 64.0))[None, :]
+    cos, sin = torch.cos(ang).float().contiguous(), torch.sin(ang).float().contiguous()
+    step = LomoFineTuneStep(dev, Bt, s, H, F, nh, n_layers, V, norm=norm)
+    run = lambda: step.step(ids, targets, n_counted, m, cos, sin, 1e-3, 65536.0)
+    losses = []
+    for _ in range(warmup):
+        run()
+        torch.cuda.synchronize()
+        losses.append(step.result()["loss"])
+    L.lomo_timing_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    fam = {name: L.lomo_timing_read(i) for i, name in enumerate(L.KERNEL_FAMILIES)}
+    L.lomo_timing_enable(False)
+    res = step.result()
+    losses.append(res["loss"])
+    walks = 2 if norm == "global" else 1
+    n_layer_lin = H * (3 * H + H + 2 * F + F)
+    n_lin = n_layers * n_layer_lin + V * H
+    n_params = n_lin + V * H + (2 * n_layers + 1) * H
+    nb = s // 64
+    pairs = Bt * nh * (nb * (nb + 1) // 2)
+    at_fwd, at_bwd = pairs * 2 * 2 * 64 * 64 * 128, pairs * 7 * 2 * 64 * 64 * 128
+    recomputed = n_layers * H * (3 * H + H + 2 * F) * walks - H * (3 * H + H + 2 * F)     # no W_d; last layer once less
+    gemm_flops = 2 * T * (n_lin + recomputed + (walks + 1) * n_lin + walks * (n_lin - 0))   # fwd + recompute + wgrads + dgrads
+    # wgrad: norm pass + update pass = 2 per linear; dgrad: once per walk
+    gemm_flops = 2 * T * (n_lin + recomputed + 2 * n_lin + walks * n_lin)
+    flops = gemm_flops + n_layers * (at_fwd * (1 + walks) - 0) + walks * n_layers * at_bwd
+    return {"workload": f"7B-shaped model from token ids ({n_layers} layers, 8 x 512 tokens, V 32000), checkpointed",
+            "norm": norm, "backward_walks": walks, "ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3), "params": n_params,
+            "executed_tflops": flops / (ms * 1e-3) / 1e12, "model_flops_tflops": 6.0 * n_params * T / (ms * 1e-3) / 1e12,
+            "loss_by_step": losses, "grad_norm": res.get("norm", None) if norm == "global" else math.sqrt(sum(v * v for v in res["group_norms"])),
+            "overflow": res["overflow"], "device_memory_gb": torch.cuda.max_memory_allocated() / 1e9,
+            "family_ms_per_step": {k: v[0] / steps for k, v in fam.items() if v[1]}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -248,6 +311,9 @@ def main():
                          "metric's flop count describes)")
     ap.add_argument("--no-norm-compare", action="store_true",
                     help="skip the extra timing of pass 1 alone on each route after the timed steps")
+    ap.add_argument("--train-step", action="store_true",
+                    help="also time a whole fine-tuning step of a 7B-shaped model from token ids, with activation "
+                         "checkpointing (extra keys `train_step_global_norm`, `train_step_grouped_norm`)")
     ap.add_argument("--model-chain", action="store_true",
                     help="also time the chained two-pass step through a whole 32-layer 7B-shaped model (extra key `model_chain`)")
     ap.add_argument("--chain", action="store_true",
@@ -398,6 +464,12 @@ def main():
         out["model_chain_kept_handons"] = model_chain_bench(L, torch, np, dev, 3, 1, keep_handons=True)
         torch.cuda.empty_cache()
         out["model_chain_grouped_norm"] = model_chain_bench(L, torch, np, dev, 3, 1, grouped=1)
+    if args.train_step:
+        tensors = None
+        torch.cuda.empty_cache()
+        out["train_step_global_norm"] = train_step_bench(L, torch, np, dev, 3, 2, "global")
+        torch.cuda.empty_cache()
+        out["train_step_grouped_norm"] = train_step_bench(L, torch, np, dev, 3, 2, "grouped")
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))
