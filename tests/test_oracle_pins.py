@@ -1127,3 +1127,39 @@ def test_stored_forward_is_the_definition_up_to_fp16_storage():
     o64, lse64 = A.attention_forward_f64(sa["qkv"][:, :H].astype(np.float64), sa["qkv"][:, H:2 * H].astype(np.float64),
                                          sa["qkv"][:, 2 * H:].astype(np.float64), s, nh)
     assert np.abs(sa["lse"] - lse64).max() < 1e-5 and np.abs(sa["o"].astype(np.float64) - o64).max() < 2.0 ** -9 * np.abs(o64).max()
+
+
+def test_training_steps_learn_a_repeated_batch_and_follow_the_scaler_protocol():
+    """Section 3.3.2's protocol around Algorithm 1: overflow -> step dropped, scale halved; growth_interval clean
+    steps -> scale doubled; and the method as a whole trains (the loss on a repeated batch goes down)."""
+    from oracle import training as TR
+    m, ids, dlogits, cos, sin, saved, s, nh = _small_model(np.random.default_rng(35))
+    targets = np.roll(ids, -1).astype(np.int32)
+    targets[s - 1::s] = -100
+    n = int((targets >= 0).sum())
+    S0 = 2.0 ** 20                      # S0 / n > 65504: the target entries of the fp16 loss gradient overflow
+    assert S0 / n > 65504
+    final, log = TR.training_steps(ids, targets, m, cos, sin, s, nh, 1e-5, 12, 0.05, S0, 2)
+    assert log[0]["overflow"] and sum(r["overflow"] for r in log) >= 3 and sum(not r["overflow"] for r in log) >= 6
+    clean = 0
+    for a, b in zip(log, log[1:]):
+        if a["overflow"]:
+            assert b["loss_scale"] == a["loss_scale"] / 2 and b["loss"] == a["loss"]        # dropped: nothing moved
+            clean = 0
+        else:
+            clean += 1
+            assert b["loss"] < a["loss"]                                                     # a step that counts learns
+            assert b["loss_scale"] == (a["loss_scale"] * 2 if clean == 2 else a["loss_scale"])
+            clean %= 2
+    assert log[-1]["loss"] < 0.85 * log[0]["loss"]
+    assert any((final["layers"][0][k].view(np.uint16) != m["layers"][0][k].view(np.uint16)).any() for k in m["layers"][0])
+    # the loss of a step does not depend on the scale: the same run at a safe constant scale gives the same losses
+    # on its clean steps, up to the rounding of differently scaled fp16 gradients
+    _, calm = TR.training_steps(ids, targets, m, cos, sin, s, nh, 1e-5, 4, 0.05, 1024.0, 1000)
+    assert not any(r["overflow"] for r in calm)
+    kept = [r["loss"] for r in log if not r["overflow"]]
+    for a, b in zip(kept, [r["loss"] for r in calm]):
+        assert abs(a - b) < 2e-3 * abs(b)
+    # grouped norm: different step sizes (never smaller than the global one's), still learning
+    _, g = TR.training_steps(ids, targets, m, cos, sin, s, nh, 1e-5, 3, 0.05, 1024.0, 1000, grouped=True)
+    assert g[2]["loss"] < g[1]["loss"] < g[0]["loss"] and g[1]["loss"] <= calm[1]["loss"] + 1e-9
