@@ -567,3 +567,27 @@ class LomoFineTuneStep:
         out = self.chain.result()
         out["loss"] = float(self.token_loss.double().sum().item()) / self.n_counted
         return out
+
+
+class LomoTrainer:
+    """Training steps with the dynamic loss scaler of section 3.3.2 around them: a step that overflowed was dropped
+    on the device (no parameter touched, or from the overflowing group on with the grouped norm) and halves the
+    scale; `growth_interval` clean steps in a row double it.  One host synchronisation per step, to read the
+    step's flag before the next step's scale is known."""
+
+    def __init__(self, step: LomoFineTuneStep, lr: float, loss_scale: float = 65536.0, growth_interval: int = 1000,
+                 max_norm: float = 1.0, eps_clip: float = 1e-6):
+        self.step, self.lr, self.loss_scale, self.growth_interval = step, lr, float(loss_scale), growth_interval
+        self.max_norm, self.eps_clip, self.clean_steps = max_norm, eps_clip, 0
+
+    def train_step(self, ids, targets, n_counted: int, m: Dict, rope_cos, rope_sin, stream=None) -> Dict:
+        used = self.loss_scale
+        self.step.step(ids, targets, n_counted, m, rope_cos, rope_sin, self.lr, used, self.max_norm, self.eps_clip, stream)
+        if stream is None:
+            torch.cuda.synchronize(self.step.device)
+        else:
+            stream.synchronize()
+        res = self.step.result()
+        res["loss_scale"] = used
+        self.loss_scale, self.clean_steps = B.lomo_scaler_step(used, self.clean_steps, self.growth_interval, res["overflow"])
+        return res

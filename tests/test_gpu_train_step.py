@@ -183,3 +183,33 @@ def test_training_step_from_token_ids_against_the_oracle(L, norm):
         assert (d == 0).mean() >= 0.95, (name, (d == 0).mean())
         if w.ndim == 2 and name != "W_emb":
             assert (w.view(np.uint16) != old[name].view(np.uint16)).mean() > 0.5, name
+
+
+@pytest.mark.parametrize("norm", ["global", "grouped"])
+def test_training_run_with_the_dynamic_scaler_follows_the_oracle(L, norm):
+    """Ten steps on a repeated batch: a scale that overflows fp16 in the loss gradient drops the step and halves,
+    three clean steps double it again; the losses follow the oracle's run and go down."""
+    from paper_2306_09782_amd.chain import LomoFineTuneStep, LomoTrainer
+    from oracle import training as TR
+    rng = np.random.default_rng(71)
+    B, s, nh, F, V, n_layers = 2, 64, 1, 344, 256, 2
+    m, ids, targets, cos, sin = problem(rng, B, s, nh, F, V, n_layers)
+    n = int((targets >= 0).sum())
+    S0 = 2.0 ** 24
+    assert S0 / 2 / n > 65504 * 1.01 and S0 / 4 / n < 65504 / 1.9      # inf at S0 and S0 / 2 for certain, far from it at S0 / 4
+    steps, lr = 10, 0.05
+    _, log = TR.training_steps(ids, targets, m, cos, sin, s, nh, 1e-5, steps, lr, S0, 3, grouped=(norm == "grouped"))
+    assert [r["overflow"] for r in log] == [True, True, False, False, False, True, False, False, False, True]
+    trainer = LomoTrainer(LomoFineTuneStep(DEV, B, s, nh * 128, F, nh, n_layers, V, norm=norm), lr, S0, 3)
+    dm = to_dev_model(m)
+    dids, dt, dcos, dsin = dev(ids), dev(targets), dev(cos), dev(sin)
+    before = None
+    for k, want in enumerate(log):
+        if want["overflow"]:
+            before = {name: t.clone() for name, t in dm["layers"][0].items()}
+        res = trainer.train_step(dids, dt, n, dm, dcos, dsin)
+        assert res["overflow"] is want["overflow"] and res["loss_scale"] == want["loss_scale"], k
+        assert abs(res["loss"] / want["loss"] - 1) < 2e-3, (k, res["loss"], want["loss"])
+        if want["overflow"]:      # dropped (the loss gradient itself overflowed, so the first group already): nothing moved
+            assert all(torch.equal(before[name].view(torch.int16), t.view(torch.int16)) for name, t in dm["layers"][0].items())
+    assert log[-1]["loss"] < log[0]["loss"] - 0.01
