@@ -280,6 +280,11 @@ lomo_status lomo_attention_backward(const lomo_half* qkv, const lomo_half* o, co
 lomo_status lomo_linear_forward(const lomo_half* X, const lomo_half* W, lomo_half* Y,
                                 int64_t T, int64_t K, int64_t N, int accumulate, void* stream);
 
+/* Y = rne16(R + X W^T) with the residual stream R [T x N] read from its own buffer (R may be Y itself, which is
+ * lomo_linear_forward with accumulate).  Same shape rules. */
+lomo_status lomo_linear_forward_residual(const lomo_half* X, const lomo_half* W, const lomo_half* R, lomo_half* Y,
+                                         int64_t T, int64_t K, int64_t N, void* stream);
+
 /* Embedding rows: h[t] = W[ids[t]] (ids [T] int32, W [V x H], h [T x H]); an id outside [0, V) gives a zero row.
  * H % 8 == 0. */
 lomo_status lomo_embedding_forward(const int32_t* ids, const lomo_half* W, lomo_half* h,

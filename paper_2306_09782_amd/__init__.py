@@ -15,7 +15,8 @@ from .binding import (LomoError, library_path, load_library, lomo_version, lomo_
                       lomo_step_scalars_device, lomo_step_update_pass_device, unpack_step_scalars, SCALARS_BYTES,
                       lomo_linear_dgrad, lomo_swiglu_backward, lomo_rmsnorm_backward, lomo_attention_backward,
                       lomo_linear_forward, lomo_rmsnorm_forward, lomo_swiglu_forward, lomo_rope_forward,
-                      lomo_attention_forward, lomo_cross_entropy, lomo_embedding_forward, EXPORTED_SYMBOLS)
+                      lomo_attention_forward, lomo_cross_entropy, lomo_embedding_forward, lomo_linear_forward_residual,
+                      EXPORTED_SYMBOLS)
 
 __all__ = [n for n in dir() if n.startswith("lomo_")] + ["LomoError", "library_path", "load_library",
                                                          "EXPORTED_SYMBOLS"]

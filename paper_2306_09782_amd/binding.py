@@ -22,7 +22,7 @@ EXPORTED_SYMBOLS = (
     "lomo_set_norm_algorithm", "lomo_get_norm_algorithm", "lomo_step_scalars_device", "lomo_step_update_pass_device",
     "lomo_linear_dgrad", "lomo_swiglu_backward", "lomo_rmsnorm_backward", "lomo_attention_backward",
     "lomo_linear_forward", "lomo_rmsnorm_forward", "lomo_swiglu_forward", "lomo_rope_forward", "lomo_attention_forward",
-    "lomo_cross_entropy", "lomo_embedding_forward",
+    "lomo_cross_entropy", "lomo_embedding_forward", "lomo_linear_forward_residual",
 )
 
 
@@ -89,6 +89,7 @@ def load_library():
         "lomo_attention_forward": (c_int, [P, P, P, I64, I64, I64, I64, P]),
         "lomo_cross_entropy": (c_int, [P, P, c_float, P, P, I64, I64, P]),
         "lomo_embedding_forward": (c_int, [P, P, P, I64, I64, I64, P]),
+        "lomo_linear_forward_residual": (c_int, [P, P, P, P, I64, I64, I64, P]),
         "lomo_set_norm_algorithm": (c_int, [c_int]),
         "lomo_get_norm_algorithm": (c_int, []),
         "lomo_timing_enable": (c_int, [c_int]),
@@ -276,6 +277,13 @@ def lomo_linear_forward(X, W, Y, accumulate=False, stream=None):
     N = W.shape[0]
     assert W.shape[1] == K and tuple(Y.shape) == (T, N)
     _check(load_library().lomo_linear_forward(_ptr(X), _ptr(W), _ptr(Y), T, K, N, 1 if accumulate else 0, _stream(stream)))
+
+
+def lomo_linear_forward_residual(X, W, R, Y, stream=None):
+    T, K = X.shape
+    N = W.shape[0]
+    assert W.shape[1] == K and tuple(Y.shape) == (T, N) and tuple(R.shape) == (T, N)
+    _check(load_library().lomo_linear_forward_residual(_ptr(X), _ptr(W), _ptr(R), _ptr(Y), T, K, N, _stream(stream)))
 
 
 def lomo_embedding_forward(ids, W, h, stream=None):

@@ -474,14 +474,6 @@ class LayerActivations:
         self.y1 = torch.empty(T, H, **f16)
 
 
-def _copy(dst, src, stream):
-    if stream is None:
-        dst.copy_(src)
-    else:
-        with torch.cuda.stream(stream):
-            dst.copy_(src)
-
-
 def layer_forward(h, p: Dict, act: LayerActivations, rope_cos, rope_sin, batch: int, seq: int, n_heads: int, eps: float,
                   h_next=None, stream=None) -> None:
     """Forward of one decoder layer from its input h into `act`; with h_next also the layer output
@@ -491,14 +483,12 @@ def layer_forward(h, p: Dict, act: LayerActivations, rope_cos, rope_sin, batch: 
     B.lomo_linear_forward(sa["xn"], p["W_qkv"], sa["qkv"], False, stream)
     B.lomo_rope_forward(sa["qkv"], rope_cos, rope_sin, seq, n_heads, stream)
     B.lomo_attention_forward(sa["qkv"], sa["o"], sa["lse"], batch, seq, n_heads, stream)
-    _copy(act.y1, h, stream)
-    B.lomo_linear_forward(sa["o"], p["W_o"], act.y1, True, stream)                 # y1 = h + o W_o^T, one rounding
+    B.lomo_linear_forward_residual(sa["o"], p["W_o"], h, act.y1, stream)           # y1 = h + o W_o^T, one rounding
     B.lomo_rmsnorm_forward(act.y1, p["w2"], eps, sm["xhat"], sm["rstd"], sm["xn"], stream)
     B.lomo_linear_forward(sm["xn"], p["W_gu"], sm["gate_up"], False, stream)
     B.lomo_swiglu_forward(sm["gate_up"], sm["a"], stream)
     if h_next is not None:
-        _copy(h_next, act.y1, stream)
-        B.lomo_linear_forward(sm["a"], p["W_d"], h_next, True, stream)
+        B.lomo_linear_forward_residual(sm["a"], p["W_d"], act.y1, h_next, stream)
 
 
 class LomoFineTuneStep:

@@ -455,6 +455,23 @@ lomo_status lomo_linear_forward(const lomo_half* X, const lomo_half* W, lomo_hal
     return from_hip(launch_forward(f, accumulate != 0, static_cast<hipStream_t>(stream)));
 }
 
+lomo_status lomo_linear_forward_residual(const lomo_half* X, const lomo_half* W, const lomo_half* R, lomo_half* Y, int64_t T,
+                                         int64_t K, int64_t N, void* stream) {
+    if (T < 0 || K < 0 || N < 0 || (K & 7) || (N & 7)) return LOMO_ERR_SHAPE;
+    if (T == 0 || N == 0) return LOMO_OK;
+    if (!Y || !R) return LOMO_ERR_NULL;
+    if (K > 0 && (!X || !W)) return LOMO_ERR_NULL;
+    if (misaligned(X) || misaligned(W) || misaligned(Y) || misaligned(R)) return LOMO_ERR_ALIGN;
+    if (K == 0) return LOMO_ERR_SHAPE;
+    GemmArgs f{};
+    f.A = W; f.B = X; f.Out = Y; f.Res = R;
+    f.M = N; f.Nn = T; f.C = K;
+    f.lda = K; f.ldb = K; f.ldo = N;
+    f.s = -1.0f;
+    f.family = LOMO_KERNEL_FORWARD;
+    return from_hip(launch_forward(f, true, static_cast<hipStream_t>(stream)));
+}
+
 lomo_status lomo_embedding_forward(const int32_t* ids, const lomo_half* W, lomo_half* h, int64_t T, int64_t H, int64_t V,
                                    void* stream) {
     if (T < 0 || H < 0 || V < 0 || (H & 7)) return LOMO_ERR_SHAPE;

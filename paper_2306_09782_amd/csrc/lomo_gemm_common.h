@@ -75,8 +75,10 @@ __device__ __forceinline__ void epilogue(floatx16 (&acc)[BM / 64][BN / 64], cons
         };
         auto mloc = [&](int i, int a) { return wm * (BM / 2) + 32 * i + 16 * a + 8 * lh; };
         half8 wbuf[2][TM][2];
+        const uint16_t* old_base = (EPI == EPI_UPDATE && g.Res != nullptr) ? g.Res : g.Out;
         auto load_stripe = [&](int j, half8 (&w)[TM][2]) {
-            uint16_t* row = row_ptr(j);
+            const int nl_ = wn * (BN / 2) + 32 * j + l32;
+            const uint16_t* row = (nl_ < n_rem) ? old_base + (n0 + nl_) * g.ldo + m0 : nullptr;
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll

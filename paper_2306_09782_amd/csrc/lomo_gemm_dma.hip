@@ -36,6 +36,7 @@ struct GroupTensor {
     const uint16_t* A;
     const uint16_t* B;
     uint16_t* Out;
+    const uint16_t* Res;
     int32_t* flag_out;
     int M, Nn, C, lda, ldb, ldo;
     int tiles_m, tiles_n, tile_begin;
@@ -321,6 +322,7 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga
         // epilogue arguments of the tile just finished
         GemmArgs g;
         g.Out = ga.t[tensor].Out;
+        g.Res = ga.t[tensor].Res;
         g.ldo = ga.t[tensor].ldo;
         g.s = ga.s;
         g.s_dev = ga.s_dev;
@@ -390,7 +392,7 @@ static hipError_t launch_dma_group_impl(const GemmArgs* list, int n, hipStream_t
         for (int i = 0; i < cnt; ++i) {
             const GemmArgs& a = list[first + i];
             GroupTensor& t = ga.t[i];
-            t.A = a.A; t.B = a.B; t.Out = a.Out; t.flag_out = a.flag_out;
+            t.A = a.A; t.B = a.B; t.Out = a.Out; t.Res = a.Res; t.flag_out = a.flag_out;
             t.M = (int)a.M; t.Nn = (int)a.Nn; t.C = (int)a.C;
             t.lda = (int)a.lda; t.ldb = (int)a.ldb; t.ldo = (int)a.ldo;
             t.tiles_m = (int)(a.M / BM); t.tiles_n = (int)(a.Nn / BN);

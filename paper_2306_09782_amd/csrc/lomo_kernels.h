@@ -28,6 +28,7 @@ struct GemmArgs {
     const uint16_t* A;
     const uint16_t* B;
     uint16_t* Out;
+    const uint16_t* Res;     // EPI_UPDATE only: read the old value from here instead of Out (same layout); null = Out
     int64_t M, Nn, C;
     int64_t lda, ldb, ldo;
     float s;                 // update step (EPI_UPDATE)

@@ -36,6 +36,21 @@ def test_linear_forward(L, T, K, N, acc):
     ulps_ok(got, O.round_f16(ref), f"Y {T}x{K}x{N}", near=np.abs(f64(got) - ref) <= 2.0 ** -20 * mag)
 
 
+@pytest.mark.parametrize("T,K,N", [(64, 344, 256), (4096, 128, 3072)])
+def test_linear_forward_residual_from_its_own_buffer(L, T, K, N):
+    rng = np.random.default_rng(T + K + N + 1)
+    X, W, R = f16(rng, (T, K), 1.0), f16(rng, (N, K), 0.05), f16(rng, (T, N), 1.0)
+    dR = dev(R)
+    Y = torch.full((T, N), 7.0, dtype=torch.float16, device=DEV)
+    L.lomo_linear_forward_residual(dev(X), dev(W), dR, Y)
+    Y2 = dev(R)
+    L.lomo_linear_forward(dev(X), dev(W), Y2, accumulate=True)
+    assert torch.equal(Y.view(torch.int16), Y2.view(torch.int16)) and torch.equal(dR.view(torch.int16), dev(R).view(torch.int16))
+    ref = f64(X) @ f64(W).T + f64(R)
+    got = Y.cpu().numpy()
+    ulps_ok(got, O.round_f16(ref), "Y", near=np.abs(f64(got) - ref) <= 2.0 ** -20 * (np.abs(f64(X)) @ np.abs(f64(W)).T + np.abs(f64(R))))
+
+
 def test_linear_forward_rejects_bad_arguments(L):
     import ctypes
     lib = L.load_library()
