@@ -229,14 +229,14 @@ def model_chain_bench(L, torch, np, dev, steps, warmup, n_layers=32, keep_handon
             "family_ms_per_step": {k: v[0] / steps for k, v in fam.items() if v[1]}}
 
 
-def train_step_bench(L, torch, np, dev, steps, warmup, norm, n_layers=32):
+def train_step_bench(L, torch, np, dev, steps, warmup, norm, n_layers=32, batch=8, seq=512):
     """One whole fine-tuning step of a 7B-shaped model from token ids (8 x 512 tokens, 32 layers, H 4096, 32 heads,
     F 11008, V 32000): forward keeping only the layer inputs, cross-entropy, backward loop with every layer
     recomputed from its checkpoint, fused updates.  Random-init weights (sigma 0.02, gains 1), Zipf token ids;
     the target of a position is the next token."""
     from paper_2306_09782_amd.chain import LomoFineTuneStep
     import lomo_synth as S
-    Bt, s, nh, H, F, V = 8, 512, 32, 4096, 11008, 32000
+    Bt, s, nh, H, F, V = batch, seq, 32, 4096, 11008, 32000
     T = Bt * s
     torch.cuda.reset_peak_memory_stats()
     count = [0]
@@ -284,7 +284,7 @@ def train_step_bench(L, torch, np, dev, steps, warmup, norm, n_layers=32):
     # wgrad: norm pass + update pass = 2 per linear; dgrad: once per walk
     gemm_flops = 2 * T * (n_lin + recomputed + 2 * n_lin + walks * n_lin)
     flops = gemm_flops + n_layers * (at_fwd * (1 + walks) - 0) + walks * n_layers * at_bwd
-    return {"workload": f"7B-shaped model from token ids ({n_layers} layers, 8 x 512 tokens, V 32000), checkpointed",
+    return {"workload": f"7B-shaped model from token ids ({n_layers} layers, {Bt} x {s} tokens, V 32000), checkpointed",
             "norm": norm, "backward_walks": walks, "ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3), "params": n_params,
             "executed_tflops": flops / (ms * 1e-3) / 1e12, "model_flops_tflops": 6.0 * n_params * T / (ms * 1e-3) / 1e12,
             "loss_by_step": losses, "grad_norm": res.get("norm", None) if norm == "global" else math.sqrt(sum(v * v for v in res["group_norms"])),
@@ -311,6 +311,7 @@ def main():
                          "metric's flop count describes)")
     ap.add_argument("--no-norm-compare", action="store_true",
                     help="skip the extra timing of pass 1 alone on each route after the timed steps")
+    ap.add_argument("--train-shape", default="8x512", help="batch x sequence length of --train-step (default 8x512)")
     ap.add_argument("--train-step", action="store_true",
                     help="also time a whole fine-tuning step of a 7B-shaped model from token ids, with activation "
                          "checkpointing (extra keys `train_step_global_norm`, `train_step_grouped_norm`)")
@@ -467,9 +468,10 @@ def main():
     if args.train_step:
         tensors = None
         torch.cuda.empty_cache()
-        out["train_step_global_norm"] = train_step_bench(L, torch, np, dev, 3, 2, "global")
+        tb, ts = (int(v) for v in args.train_shape.split("x"))
+        out["train_step_global_norm"] = train_step_bench(L, torch, np, dev, 3, 2, "global", batch=tb, seq=ts)
         torch.cuda.empty_cache()
-        out["train_step_grouped_norm"] = train_step_bench(L, torch, np, dev, 3, 2, "grouped")
+        out["train_step_grouped_norm"] = train_step_bench(L, torch, np, dev, 3, 2, "grouped", batch=tb, seq=ts)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))
