@@ -229,7 +229,7 @@ def model_chain_bench(L, torch, np, dev, steps, warmup, n_layers=32, keep_handon
             "family_ms_per_step": {k: v[0] / steps for k, v in fam.items() if v[1]}}
 
 
-def train_step_bench(L, torch, np, dev, steps, warmup, norm, n_layers=32, batch=8, seq=512):
+def train_step_bench(L, torch, np, dev, steps, warmup, norm, n_layers=32, batch=8, seq=512, checkpoint=True, keep_handons=False):
     """One whole fine-tuning step of a 7B-shaped model from token ids (8 x 512 tokens, 32 layers, H 4096, 32 heads,
     F 11008, V 32000): forward keeping only the layer inputs, cross-entropy, backward loop with every layer
     recomputed from its checkpoint, fused updates.  Random-init weights (sigma 0.02, gains 1), Zipf token ids;
@@ -255,7 +255,7 @@ def train_step_bench(L, torch, np, dev, steps, warmup, norm, n_layers=32, batch=
     ids, targets = torch.from_numpy(ids_h).to(dev), torch.from_numpy(tg_h).to(dev)
     ang = torch.arange(s, device=dev, dtype=torch.float64)[:, None] * (10000.0 ** (-torch.arange(64, device=dev, dtype=torch.float64) / 64.0))[None, :]
     cos, sin = torch.cos(ang).float().contiguous(), torch.sin(ang).float().contiguous()
-    step = LomoFineTuneStep(dev, Bt, s, H, F, nh, n_layers, V, norm=norm)
+    step = LomoFineTuneStep(dev, Bt, s, H, F, nh, n_layers, V, norm=norm, checkpoint=checkpoint, keep_handons=keep_handons)
     run = lambda: step.step(ids, targets, n_counted, m, cos, sin, 1e-3, 65536.0)
     losses = []
     for _ in range(warmup):
@@ -272,7 +272,7 @@ def train_step_bench(L, torch, np, dev, steps, warmup, norm, n_layers=32, batch=
     L.lomo_timing_enable(False)
     res = step.result()
     losses.append(res["loss"])
-    walks = 2 if norm == "global" else 1
+    walks = 2 if (norm == "global" and not keep_handons) else 1
     n_layer_lin = H * (3 * H + H + 2 * F + F)
     n_lin = n_layers * n_layer_lin + V * H
     n_params = n_lin + V * H + (2 * n_layers + 1) * H
@@ -280,11 +280,15 @@ def train_step_bench(L, torch, np, dev, steps, warmup, norm, n_layers=32, batch=
     pairs = Bt * nh * (nb * (nb + 1) // 2)
     at_fwd, at_bwd = pairs * 2 * 2 * 64 * 64 * 128, pairs * 7 * 2 * 64 * 64 * 128
     recomputed = n_layers * H * (3 * H + H + 2 * F) * walks - H * (3 * H + H + 2 * F)     # no W_d; last layer once less
+    if not checkpoint:
+        recomputed = 0
     gemm_flops = 2 * T * (n_lin + recomputed + (walks + 1) * n_lin + walks * (n_lin - 0))   # fwd + recompute + wgrads + dgrads
     # wgrad: norm pass + update pass = 2 per linear; dgrad: once per walk
     gemm_flops = 2 * T * (n_lin + recomputed + 2 * n_lin + walks * n_lin)
-    flops = gemm_flops + n_layers * (at_fwd * (1 + walks) - 0) + walks * n_layers * at_bwd
-    return {"workload": f"7B-shaped model from token ids ({n_layers} layers, {Bt} x {s} tokens, V 32000), checkpointed",
+    flops = gemm_flops + n_layers * at_fwd * (1 + (walks if checkpoint else 0)) + walks * n_layers * at_bwd
+    return {"workload": f"7B-shaped model from token ids ({n_layers} layers, {Bt} x {s} tokens, V 32000)",
+            "activations": "checkpointed and recomputed" if checkpoint else "kept",
+            "hand_ons": "kept from pass 1" if keep_handons else "not kept",
             "norm": norm, "backward_walks": walks, "ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3), "params": n_params,
             "executed_tflops": flops / (ms * 1e-3) / 1e12, "model_flops_tflops": 6.0 * n_params * T / (ms * 1e-3) / 1e12,
             "loss_by_step": losses, "grad_norm": res.get("norm", None) if norm == "global" else math.sqrt(sum(v * v for v in res["group_norms"])),
@@ -472,6 +476,15 @@ def main():
         out["train_step_global_norm"] = train_step_bench(L, torch, np, dev, 3, 2, "global", batch=tb, seq=ts)
         torch.cuda.empty_cache()
         out["train_step_grouped_norm"] = train_step_bench(L, torch, np, dev, 3, 2, "grouped", batch=tb, seq=ts)
+        torch.cuda.empty_cache()
+        out["train_step_global_norm_kept_activations"] = train_step_bench(L, torch, np, dev, 3, 2, "global", batch=tb, seq=ts,
+                                                                          checkpoint=False)
+        torch.cuda.empty_cache()
+        out["train_step_global_norm_kept_activations_and_handons"] = train_step_bench(
+            L, torch, np, dev, 3, 2, "global", batch=tb, seq=ts, checkpoint=False, keep_handons=True)
+        torch.cuda.empty_cache()
+        out["train_step_grouped_norm_kept_activations"] = train_step_bench(L, torch, np, dev, 3, 2, "grouped", batch=tb, seq=ts,
+                                                                           checkpoint=False)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))

@@ -497,18 +497,27 @@ class LomoFineTuneStep:
     Algorithm 1's backward loop with each layer's activations recomputed from its checkpoint just before the walk
     enters it.  norm="global": two passes (the norm of all parameters), so every layer is recomputed twice;
     norm="grouped": one walk with per-group norms, one recomputation.  Activation memory: (n_layers + 1) [T x H]
-    checkpoints, one layer's activations (per layer of a group), the logits."""
+    checkpoints, one layer's activations (per layer of a group), the logits.
+
+    Two switches trade memory for arithmetic where the memory is there (at 7B and 4096 tokens each costs 17 GB):
+    checkpoint=False keeps every layer's activations from the forward pass, so nothing is recomputed;
+    keep_handons=True (global norm, needs checkpoint=False) also keeps pass 1's hand-on gradients, so pass 2 is
+    one grouped fused-update launch over the whole model.  Neither changes a bit of the result."""
 
     def __init__(self, device, batch: int, seq: int, H: int, F: int, n_heads: int, n_layers: int, V: int,
-                 eps: float = 1e-5, norm: str = "global", layers_per_group: int = 1):
+                 eps: float = 1e-5, norm: str = "global", layers_per_group: int = 1, checkpoint: bool = True,
+                 keep_handons: bool = False):
         assert norm in ("global", "grouped")
+        assert not keep_handons or (norm == "global" and not checkpoint), "kept hand-ons: global norm, no checkpointing"
         self.device = torch.device(device)
         T = batch * seq
         self.batch, self.seq, self.n_heads, self.n_layers, self.eps = batch, seq, n_heads, n_layers, eps
+        self.checkpoint = checkpoint
         f16 = dict(dtype=torch.float16, device=self.device)
         self.ckpt = [torch.empty(T, H, **f16) for _ in range(n_layers + 1)]
         per = layers_per_group if norm == "grouped" else 1
-        self.acts = [LayerActivations(self.device, T, H, F, n_heads) for _ in range(max(1, min(per, n_layers)))]
+        n_sets = max(1, min(per, n_layers)) if checkpoint else n_layers
+        self.acts = [LayerActivations(self.device, T, H, F, n_heads) for _ in range(n_sets)]
         self.final = {"xhat": torch.empty(T, H, **f16), "rstd": torch.empty(T, dtype=torch.float32, device=self.device),
                       "xn": torch.empty(T, H, **f16)}
         self.logits = torch.empty(T, V, **f16)           # overwritten by its own gradient
@@ -516,7 +525,7 @@ class LomoFineTuneStep:
         if norm == "grouped":
             self.chain = LomoGroupedNormChain(self.device, batch, seq, H, F, n_heads, n_layers, layers_per_group=per)
         else:
-            self.chain = LomoModelChain(self.device, batch, seq, H, F, n_heads, n_layers)
+            self.chain = LomoModelChain(self.device, batch, seq, H, F, n_heads, n_layers, keep_handons=keep_handons)
         # walk index k = n_layers - 1 - layer index; the layers of one group use different activation sets
         self.saved = {"layers": [(self._act(li).attn, self._act(li).mlp) for li in range(n_layers)], "final": self.final}
 
@@ -550,7 +559,7 @@ class LomoFineTuneStep:
                           self.n_heads, self.eps, None, stream)
 
         self.chain.step(ids, self.logits, self.saved, m, rope_cos, rope_sin, lr, loss_scale, max_norm, eps_clip, stream,
-                        before_layer=recompute)
+                        before_layer=recompute if self.checkpoint else None)
 
     def result(self) -> Dict:
         """The chain's scalars and flags plus the mean loss over the counted tokens (synchronise first)."""

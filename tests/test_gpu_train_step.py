@@ -117,6 +117,31 @@ def kept_activation_step(B, s, nh, F, V, n_layers, m, ids, targets, n_counted, c
     return dm, chain, raw_logits.cpu().numpy(), loss.cpu().numpy()
 
 
+@pytest.mark.parametrize("norm,kw", [("global", dict(checkpoint=False)), ("global", dict(checkpoint=False, keep_handons=True)),
+                                     ("grouped", dict(checkpoint=False))])
+def test_memory_policies_do_not_change_a_bit(L, norm, kw):
+    """Keeping the activations (and the hand-ons) instead of recomputing them gives the checkpointed step's bits."""
+    from paper_2306_09782_amd.chain import LomoFineTuneStep
+    rng = np.random.default_rng(64)
+    B, s, nh, F, V, n_layers, scale = 2, 64, 1, 344, 256, 3, 1024.0
+    m, ids, targets, cos, sin = problem(rng, B, s, nh, F, V, n_layers)
+    n_counted = int((targets >= 0).sum())
+    out = []
+    for extra in (dict(), kw):
+        step = LomoFineTuneStep(DEV, B, s, nh * 128, F, nh, n_layers, V, norm=norm, **extra)
+        dm = to_dev_model(m)
+        step.step(dev(ids), dev(targets), n_counted, dm, dev(cos), dev(sin), 0.05, scale, 1e30)
+        torch.cuda.synchronize()
+        out.append((dm, step.result()))
+    (d1, r1), (d2, r2) = out
+    assert r1["loss"] == r2["loss"] and r1["overflow"] is False and r2["overflow"] is False
+    same = lambda a, b: torch.equal(a.view(torch.int16), b.view(torch.int16))
+    assert same(d1["W_emb"], d2["W_emb"]) and same(d1["W_lm"], d2["W_lm"]) and same(d1["w_f"], d2["w_f"])
+    for p1, p2 in zip(d1["layers"], d2["layers"]):
+        for k in p1:
+            assert same(p1[k], p2[k]), k
+
+
 @pytest.mark.parametrize("norm,per", [("global", 1), ("grouped", 1), ("grouped", 2)])
 def test_checkpointed_step_equals_kept_activation_step_bit_for_bit(L, norm, per):
     from paper_2306_09782_amd.chain import LomoFineTuneStep
