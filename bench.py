@@ -229,7 +229,8 @@ def model_chain_bench(L, torch, np, dev, steps, warmup, n_layers=32, keep_handon
             "family_ms_per_step": {k: v[0] / steps for k, v in fam.items() if v[1]}}
 
 
-def train_step_bench(L, torch, np, dev, steps, warmup, norm, n_layers=32, batch=8, seq=512, checkpoint=True, keep_handons=False):
+def train_step_bench(L, torch, np, dev, steps, warmup, norm, n_layers=32, batch=8, seq=512, checkpoint=True, keep_handons=False,
+                     overlap=False):
     """One whole fine-tuning step of a 7B-shaped model from token ids (8 x 512 tokens, 32 layers, H 4096, 32 heads,
     F 11008, V 32000): forward keeping only the layer inputs, cross-entropy, backward loop with every layer
     recomputed from its checkpoint, fused updates.  Random-init weights (sigma 0.02, gains 1), Zipf token ids;
@@ -255,7 +256,8 @@ def train_step_bench(L, torch, np, dev, steps, warmup, norm, n_layers=32, batch=
     ids, targets = torch.from_numpy(ids_h).to(dev), torch.from_numpy(tg_h).to(dev)
     ang = torch.arange(s, device=dev, dtype=torch.float64)[:, None] * (10000.0 ** (-torch.arange(64, device=dev, dtype=torch.float64) / 64.0))[None, :]
     cos, sin = torch.cos(ang).float().contiguous(), torch.sin(ang).float().contiguous()
-    step = LomoFineTuneStep(dev, Bt, s, H, F, nh, n_layers, V, norm=norm, checkpoint=checkpoint, keep_handons=keep_handons)
+    step = LomoFineTuneStep(dev, Bt, s, H, F, nh, n_layers, V, norm=norm, checkpoint=checkpoint, keep_handons=keep_handons,
+                            overlap_norm_pass=overlap)
     run = lambda: step.step(ids, targets, n_counted, m, cos, sin, 1e-3, 65536.0)
     losses = []
     for _ in range(warmup):
@@ -288,7 +290,7 @@ def train_step_bench(L, torch, np, dev, steps, warmup, norm, n_layers=32, batch=
     flops = gemm_flops + n_layers * at_fwd * (1 + (walks if checkpoint else 0)) + walks * n_layers * at_bwd
     return {"workload": f"7B-shaped model from token ids ({n_layers} layers, {Bt} x {s} tokens, V 32000)",
             "activations": "checkpointed and recomputed" if checkpoint else "kept",
-            "hand_ons": "kept from pass 1" if keep_handons else "not kept",
+            "hand_ons": "kept from pass 1" if keep_handons else "not kept", "norm_pass_on_second_stream": overlap,
             "norm": norm, "backward_walks": walks, "ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3), "params": n_params,
             "executed_tflops": flops / (ms * 1e-3) / 1e12, "model_flops_tflops": 6.0 * n_params * T / (ms * 1e-3) / 1e12,
             "loss_by_step": losses, "grad_norm": res.get("norm", None) if norm == "global" else math.sqrt(sum(v * v for v in res["group_norms"])),
@@ -482,6 +484,9 @@ def main():
         torch.cuda.empty_cache()
         out["train_step_global_norm_kept_activations_and_handons"] = train_step_bench(
             L, torch, np, dev, 3, 2, "global", batch=tb, seq=ts, checkpoint=False, keep_handons=True)
+        torch.cuda.empty_cache()
+        out["train_step_global_norm_kept_activations_and_handons_two_streams"] = train_step_bench(
+            L, torch, np, dev, 3, 2, "global", batch=tb, seq=ts, checkpoint=False, keep_handons=True, overlap=True)
         torch.cuda.empty_cache()
         out["train_step_grouped_norm_kept_activations"] = train_step_bench(L, torch, np, dev, 3, 2, "grouped", batch=tb, seq=ts,
                                                                            checkpoint=False)

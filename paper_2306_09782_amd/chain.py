@@ -33,6 +33,33 @@ class StepState:
         self.ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
         self.scalars = torch.zeros(32, dtype=torch.uint8, device=device)
         self._scalars_host = torch.zeros(32, dtype=torch.uint8).pin_memory()
+        self.device = torch.device(device)
+        self.side = None          # second stream for the norm-pass GEMMs (see use_side_stream)
+
+    def use_side_stream(self):
+        """Pass 1's norm contractions do not feed the walk: with a second stream (default priority) they run beside
+        the dgrad / element-wise / attention kernels that do, and fill each other's partial last rounds.  Only safe
+        when no hand-on buffer is reused within a pass (every layer has its own)."""
+        self.side = torch.cuda.Stream(self.device)
+
+    def fork(self, stream):
+        """Stream for work that depends only on what is already queued on `stream`: the side stream, made to wait
+        for that; or `stream` itself when there is no side stream."""
+        if self.side is None:
+            return stream
+        main = stream if stream is not None else torch.cuda.current_stream(self.device)
+        ev = torch.cuda.Event()
+        ev.record(main)
+        self.side.wait_event(ev)
+        return self.side
+
+    def join(self, stream):
+        if self.side is None:
+            return
+        main = stream if stream is not None else torch.cuda.current_stream(self.device)
+        ev = torch.cuda.Event()
+        ev.record(self.side)
+        main.wait_event(ev)
 
     @property
     def step_flag(self):
@@ -43,6 +70,7 @@ class StepState:
         self.flags.zero_()
 
     def coefficient(self, lr, loss_scale, max_norm, eps, stream):
+        self.join(stream)
         B.lomo_reduce_flags(self.flags[:self.n], self.step_flag, stream)
         B.lomo_step_scalars_device(self.acc, self.step_flag, loss_scale, max_norm, eps, lr, self.scalars, stream)
 
@@ -62,20 +90,25 @@ class StepState:
         return out
 
 
+def _fork(state, stream):
+    return state.fork(stream) if getattr(state, "side", None) is not None else stream
+
+
 def _linear(state: StepState, slot: int, X, dY, W, dX, tensor_list, update: bool, stream):
     """One linear tensor of the walk: hand-on gradient from the old W, then norm (pass 1) or fused update (pass 2)."""
     if update:
         B.lomo_step_update_pass_device(tensor_list, state.scalars, state.step_flag, state.ws, stream)
     else:
+        side = _fork(state, stream)          # the norm contraction reads X and dY only: it may run beside the dgrad
         B.lomo_linear_dgrad(dY, W, dX, stream)
-        B.lomo_wgrad_sqnorm(X, dY, state.acc, state.flags[slot:slot + 1], stream)
+        B.lomo_wgrad_sqnorm(X, dY, state.acc, state.flags[slot:slot + 1], side)
 
 
 def _gain(state: StepState, slot: int, xhat, dxn, w, tensor_list, update: bool, stream):
     if update:
         B.lomo_step_update_pass_device(tensor_list, state.scalars, state.step_flag, state.ws, stream)
     else:
-        B.lomo_vector_sqnorm(xhat, dxn, state.ws, state.acc, state.flags[slot:slot + 1], stream)
+        B.lomo_vector_sqnorm(xhat, dxn, state.ws, state.acc, state.flags[slot:slot + 1], _fork(state, stream))
 
 
 class LomoMlpBlock:
@@ -217,14 +250,17 @@ class LomoModelChain:
     out bit-identical to the re-walked step, since the hand-ons of both passes are the same bits."""
 
     def __init__(self, device, batch: int, seq: int, H: int, F: int, n_heads: int, n_layers: int,
-                 share_buffers: bool = True, keep_handons: bool = False):
+                 share_buffers: bool = True, keep_handons: bool = False, overlap_norm_pass: bool = False):
         self.device = torch.device(device)
         T = batch * seq
         self.n_layers = n_layers
         self.keep_handons = keep_handons
         share_buffers = share_buffers and not keep_handons
+        assert not overlap_norm_pass or not share_buffers, "a side stream needs hand-on buffers that are not reused"
         self._all = None
         self.state = StepState(self.device, 2 + 6 * n_layers + 1, T, H, with_embedding=True)
+        if overlap_norm_pass:
+            self.state.use_side_stream()
         self.mlp, self.attn = [], []
         for k in range(n_layers):                      # k-th layer of the walk = layer n_layers - 1 - k
             slot = 2 + 6 * k
@@ -277,7 +313,7 @@ class LomoModelChain:
         if update:
             B.lomo_step_update_pass_device(emb, st.scalars, st.step_flag, st.ws, stream)
         else:
-            B.lomo_embedding_sqnorm(ids, dh0, m["W_emb"].shape[0], st.ws, st.acc, st.flags[slot:slot + 1], stream)
+            B.lomo_embedding_sqnorm(ids, dh0, m["W_emb"].shape[0], st.ws, st.acc, st.flags[slot:slot + 1], _fork(st, stream))
 
     def step(self, ids, dlogits, saved: Dict, m: Dict, rope_cos, rope_sin, lr: float, loss_scale: float,
              max_norm: float = 1.0, eps: float = 1e-6, stream=None, before_layer=None) -> None:
@@ -502,11 +538,12 @@ class LomoFineTuneStep:
     Two switches trade memory for arithmetic where the memory is there (at 7B and 4096 tokens each costs 17 GB):
     checkpoint=False keeps every layer's activations from the forward pass, so nothing is recomputed;
     keep_handons=True (global norm, needs checkpoint=False) also keeps pass 1's hand-on gradients, so pass 2 is
-    one grouped fused-update launch over the whole model.  Neither changes a bit of the result."""
+    one grouped fused-update launch over the whole model.  Neither changes a bit of the result.
+    overlap_norm_pass=True (with keep_handons) runs pass 1's norm contractions on a second stream beside the walk."""
 
     def __init__(self, device, batch: int, seq: int, H: int, F: int, n_heads: int, n_layers: int, V: int,
                  eps: float = 1e-5, norm: str = "global", layers_per_group: int = 1, checkpoint: bool = True,
-                 keep_handons: bool = False):
+                 keep_handons: bool = False, overlap_norm_pass: bool = False):
         assert norm in ("global", "grouped")
         assert not keep_handons or (norm == "global" and not checkpoint), "kept hand-ons: global norm, no checkpointing"
         self.device = torch.device(device)
@@ -525,7 +562,8 @@ class LomoFineTuneStep:
         if norm == "grouped":
             self.chain = LomoGroupedNormChain(self.device, batch, seq, H, F, n_heads, n_layers, layers_per_group=per)
         else:
-            self.chain = LomoModelChain(self.device, batch, seq, H, F, n_heads, n_layers, keep_handons=keep_handons)
+            self.chain = LomoModelChain(self.device, batch, seq, H, F, n_heads, n_layers, keep_handons=keep_handons,
+                                        overlap_norm_pass=overlap_norm_pass)
         # walk index k = n_layers - 1 - layer index; the layers of one group use different activation sets
         self.saved = {"layers": [(self._act(li).attn, self._act(li).mlp) for li in range(n_layers)], "final": self.final}
 

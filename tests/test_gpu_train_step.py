@@ -118,6 +118,7 @@ def kept_activation_step(B, s, nh, F, V, n_layers, m, ids, targets, n_counted, c
 
 
 @pytest.mark.parametrize("norm,kw", [("global", dict(checkpoint=False)), ("global", dict(checkpoint=False, keep_handons=True)),
+                                     ("global", dict(checkpoint=False, keep_handons=True, overlap_norm_pass=True)),
                                      ("grouped", dict(checkpoint=False))])
 def test_memory_policies_do_not_change_a_bit(L, norm, kw):
     """Keeping the activations (and the hand-ons) instead of recomputing them gives the checkpointed step's bits."""
@@ -135,6 +136,8 @@ def test_memory_policies_do_not_change_a_bit(L, norm, kw):
         out.append((dm, step.result()))
     (d1, r1), (d2, r2) = out
     assert r1["loss"] == r2["loss"] and r1["overflow"] is False and r2["overflow"] is False
+    if norm == "global":
+        assert abs(r1["norm"] / r2["norm"] - 1) < 1e-12 and r1["flags"] == r2["flags"]
     same = lambda a, b: torch.equal(a.view(torch.int16), b.view(torch.int16))
     assert same(d1["W_emb"], d2["W_emb"]) and same(d1["W_lm"], d2["W_lm"]) and same(d1["w_f"], d2["w_f"])
     for p1, p2 in zip(d1["layers"], d2["layers"]):
