@@ -34,10 +34,11 @@ def mixed_ok(got, ref64, what, mag=None, frac=0.999):
     assert ((d <= 1) | (np.abs(f64(got) - ref64) <= 2.0 ** -12 * rms)).mean() >= frac, what
 
 
-def test_layer_forward_stage_by_stage(L):
+@pytest.mark.parametrize("B,s,nh,F", [(2, 128, 2, 344), (3, 192, 3, 1032),
+                                      pytest.param(8, 512, 32, 11008, marks=pytest.mark.timeout(900), id="llama7b_layer")])
+def test_layer_forward_stage_by_stage(L, B, s, nh, F):
     from paper_2306_09782_amd.chain import LayerActivations, layer_forward
     rng = np.random.default_rng(61)
-    B, s, nh, F = 2, 128, 2, 344
     H, T = nh * 128, B * s
     p = make_model(rng, 8, H, F, 1)["layers"][0]
     h = f16(rng, (T, H), 1.0)
@@ -57,7 +58,13 @@ def test_layer_forward_stage_by_stage(L):
     raw = O.round_f16(f64(sa["xn"]) @ f64(p["W_qkv"]).T)
     rot = np.concatenate((A.rope_rotate(raw[:, :H], cos, sin, s, nh), A.rope_rotate(raw[:, H:2 * H], cos, sin, s, nh),
                           f64(raw[:, 2 * H:])), axis=1)
-    mixed_ok(sa["qkv"], rot, "rotated qkv")
+    # an input of the rotation may sit one ulp off the oracle's (the contraction's last bit), which moves the output by up
+    # to that ulp times |cos| + |sin|; where the contraction's terms cancel, its fp32 accumulation error (2^-20 of the sum
+    # of their magnitudes, as for every contraction here) passes through the rotation as well
+    terms = np.abs(f64(sa["xn"])) @ np.abs(f64(p["W_qkv"])).T
+    pair = (np.abs(f64(raw)) + 2.0 ** -10 * terms).reshape(T, 3 * nh, 2, 64)
+    pair = np.broadcast_to(pair.sum(axis=2, keepdims=True), pair.shape).reshape(T, 3 * H)
+    mixed_ok(sa["qkv"], rot, "rotated qkv", mag=pair)
     o64, lse64, mag = attention_reference(sa["qkv"], s, nh)
     np.testing.assert_allclose(sa["lse"], lse64, rtol=1e-5, atol=1e-5)
     mixed_ok(sa["o"], o64, "o", mag=2.0 * mag, frac=0.99)
@@ -72,9 +79,10 @@ def test_layer_forward_stage_by_stage(L):
     ref = f64(y1) + f64(sm["a"]) @ f64(p["W_d"]).T
     ulps_ok(hn, O.round_f16(ref), "layer output", near=np.abs(f64(hn) - ref) <= 2.0 ** -20 * (np.abs(f64(y1)) + np.abs(f64(sm["a"])) @ np.abs(f64(p["W_d"])).T))
     # the whole layer against the oracle's stored forward
-    osa, osm = A.layer_forward_stored(h, p, cos, sin, s, nh, 1e-5)
-    want = O.round_f16(f64(osa["y"]) + f64(osm["a"]) @ f64(p["W_d"]).T)
-    assert np.linalg.norm(f64(hn) - f64(want)) / np.linalg.norm(f64(want)) < 2.0 ** -10
+    if T * H <= 1 << 20:
+        osa, osm = A.layer_forward_stored(h, p, cos, sin, s, nh, 1e-5)
+        want = O.round_f16(f64(osa["y"]) + f64(osm["a"]) @ f64(p["W_d"]).T)
+        assert np.linalg.norm(f64(hn) - f64(want)) / np.linalg.norm(f64(want)) < 2.0 ** -10
 
 
 def problem(rng, B, s, nh, F, V, n_layers):
@@ -170,11 +178,13 @@ def test_checkpointed_step_equals_kept_activation_step_bit_for_bit(L, norm, per)
     assert moved > 0.05, moved
 
 
-@pytest.mark.parametrize("norm", ["global", "grouped"])
-def test_training_step_from_token_ids_against_the_oracle(L, norm):
+@pytest.mark.parametrize("norm,shape", [("global", (2, 128, 2, 344, 512, 2)), ("grouped", (2, 128, 2, 344, 512, 2)),
+                                        ("global", (3, 192, 3, 1032, 1000, 1))])
+def test_training_step_from_token_ids_against_the_oracle(L, norm, shape):
     from paper_2306_09782_amd.chain import LomoFineTuneStep
     rng = np.random.default_rng(63)
-    B, s, nh, F, V, n_layers, scale = 2, 128, 2, 344, 512, 2, 4096.0
+    B, s, nh, F, V, n_layers = shape
+    scale = 4096.0
     m, ids, targets, cos, sin = problem(rng, B, s, nh, F, V, n_layers)
     n_counted = int((targets >= 0).sum())
     saved = A.model_forward_stored(ids, m, cos, sin, s, nh, 1e-5)
