@@ -29,10 +29,10 @@ namespace dma {
 
 constexpr int BM = 256, BN = 256, BK = 32, NS = 4;
 constexpr int A_HALVES = BK * BM, B_HALVES = BK * BN, STAGE_HALVES = A_HALVES + B_HALVES;
-constexpr int EPI_UNIT_HALVES = 32 * 64;                 // staging unit of the row epilogue: 32 rows x 64 columns (4 KiB)
-// four stages + a reduction scratch + one staging unit per wave (the other unit of each wave's pair lives in the
-// B part of stage 3, which is idle between the last slice of a tile and the first half-slice of the next)
-constexpr int LDS_BYTES = NS * STAGE_HALVES * 2 + 256 + 4 * EPI_UNIT_HALVES * 2;
+constexpr int EPI_UNIT_HALVES = 32 * 64;                 // staging block of the row epilogue: 32 rows x 64 columns (4 KiB)
+// four stages + 32 KiB behind them: two staging blocks per wave for the row epilogue (update, store), whose first
+// 256 bytes serve as the reduction scratch of the norm epilogue.  160 KiB in all, the whole LDS of a CU.
+constexpr int LDS_BYTES = NS * STAGE_HALVES * 2 + 8 * EPI_UNIT_HALVES * 2;
 constexpr int MAX_GROUP = 40;
 
 struct GroupTensor {
@@ -75,110 +75,120 @@ __device__ __forceinline__ half8 read_tr8(const uint16_t* p0, const uint16_t* p1
 // memory would touch 32 rows x 32 bytes.  Here each wave stages 32 x 64 blocks of its 128 x 128 sub-tile in
 // LDS: the old W block arrives row-contiguous by direct-to-LDS loads (8 rows x 128 bytes per instruction),
 // lanes pick their 16-byte pieces out of it, update, put the results back in the same places, and the block
-// leaves row-contiguous again.  Two blocks per wave alternate, the load of the block after next is issued as
-// soon as a block's results are in registers.  16-byte chunk c of row r sits at chunk position c ^ ((r >> 1) & 7),
-// which makes both access patterns conflict-free.
+// leaves row-contiguous again.  Three blocks per wave rotate; the first three loads are issued right after
+// the tile's last slice, ahead of the next tile's first slices, and block u + 3 is requested as soon as block u
+// is in registers.  16-byte chunk c of row r sits at chunk position c ^ ((r >> 1) & 7), which makes both access
+// patterns conflict-free.
 __device__ __forceinline__ int swz_e(int r) { return (r >> 1) & 7; }
 
-template <int EPI>
-__device__ __forceinline__ void epilogue_rows(floatx16 (&acc)[4][4], const GemmArgs& g, uint16_t* smem, int wave, int64_t m0,
-                                              int64_t n0) {
-    static_assert(EPI == EPI_UPDATE || EPI == EPI_STORE, "row epilogue: update or store");
-    typedef uint32_t u32x2v __attribute__((ext_vector_type(2)));
-    const int lane = threadIdx.x & 63;
-    const int wm = wave & 1, wn = wave >> 1;
-    const int l32 = lane & 31, lh = lane >> 5;
-    uint16_t* const buf0 = smem + 3 * STAGE_HALVES + A_HALVES + wave * EPI_UNIT_HALVES;
-    uint16_t* const buf1 = smem + NS * STAGE_HALVES + 128 + wave * EPI_UNIT_HALVES;
-    const float s = g.s_dev != nullptr ? *g.s_dev : g.s;
-    const uint16_t* old_base = (g.Res != nullptr) ? g.Res : g.Out;
-    const int64_t ldo = g.ldo;
-
-    // row-contiguous mapping inside a block: instruction q covers rows 8 q .. 8 q + 7, eight lanes per row
-    const int rr = lane >> 3, slot = lane & 7;
+struct RowEpilogue {
+    uint16_t* buf[3];
     uint32_t voff[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int r = 8 * q + rr;
-        voff[q] = (uint32_t)(r * ldo + ((slot ^ swz_e(r)) * 8)) * 2u;
-    }
-    // accumulator-layout mapping: this lane's piece (il, a) of row l32
-    int poff[2][2];
-#pragma unroll
-    for (int il = 0; il < 2; ++il)
-#pragma unroll
-        for (int a = 0; a < 2; ++a) poff[il][a] = l32 * 64 + (((4 * il + 2 * a + lh) ^ swz_e(l32)) * 8);
+    const uint16_t* old_base;
+    uint16_t* out_base;
+    int64_t ldo, origin;      // origin: halves from the tensor base to this wave's 128 x 128 sub-tile
 
-    auto unit_off = [&](int u) -> int64_t {     // halves from the tensor base to block u = (j, ih) of this wave
-        return (n0 + wn * (BN / 2) + 32 * (u >> 1)) * ldo + m0 + wm * (BM / 2) + 64 * (u & 1);
-    };
-    auto fill = [&](int u) {
-        const uint16_t* base = old_base + unit_off(u);
-        const uint32_t l = (uint32_t)(uintptr_t)((u & 1) ? buf1 : buf0);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) dma16(voff[q], base, l + (uint32_t)q * 1024u);
-    };
-
-    if constexpr (EPI == EPI_UPDATE) {
-        fill(0);
-        fill(1);
-    }
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-        const int j = u >> 1, ih = u & 1;
-        uint16_t* b = (u & 1) ? buf1 : buf0;
-        half8 w[2][2];
-        if constexpr (EPI == EPI_UPDATE) {
-            // Vector-memory operations complete in issue order.  Younger than this block's four loads are: the loads
-            // of the next block (issued one block ago, except at the end) and the stores of the last two blocks.
-            if (u == 0) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-            else if (u == 1 || u == 7) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
-#pragma unroll
-            for (int il = 0; il < 2; ++il)
-#pragma unroll
-                for (int a = 0; a < 2; ++a) w[il][a] = *reinterpret_cast<const half8*>(b + poff[il][a]);
-        }
-#pragma unroll
-        for (int il = 0; il < 2; ++il)
-#pragma unroll
-            for (int a = 0; a < 2; ++a) {
-                const int i = 2 * ih + il;
-                float v[8];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const u32x2v sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[i][j][8 * a + e]),
-                                                                       __float_as_uint(acc[i][j][8 * a + 4 + e]), false, false);
-                    v[e] = __uint_as_float(sw[0]);
-                    v[4 + e] = __uint_as_float(sw[1]);
-                }
-                half8 out;
-                if constexpr (EPI == EPI_UPDATE) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) out[e] = (_Float16)fmaf(-s, v[e], (float)w[il][a][e]);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) out[e] = (_Float16)v[e];
-                }
-                *reinterpret_cast<half8*>(b + poff[il][a]) = out;
-            }
-        half8 rows[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) rows[q] = *reinterpret_cast<const half8*>(b + q * 512 + lane * 8);
-        if constexpr (EPI == EPI_UPDATE) {
-            if (u + 2 < 8) {
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // the block is in registers: its buffer is free
-                fill(u + 2);
-            }
-        }
-        uint16_t* dst = g.Out + unit_off(u);
+    __device__ __forceinline__ RowEpilogue(const GemmArgs& g, uint16_t* smem, int wave, int64_t m0, int64_t n0) {
+        const int lane = threadIdx.x & 63;
+        const int wm = wave & 1, wn = wave >> 1;
+        // two blocks per wave behind the stages, the third in the B part of stage 3, which is idle between the last
+        // slice of a tile and the first half-slice of the next
+        buf[0] = smem + NS * STAGE_HALVES + wave * EPI_UNIT_HALVES;
+        buf[1] = buf[0] + 4 * EPI_UNIT_HALVES;
+        buf[2] = smem + 3 * STAGE_HALVES + A_HALVES + wave * EPI_UNIT_HALVES;
+        ldo = g.ldo;
+        old_base = (g.Res != nullptr) ? g.Res : g.Out;
+        out_base = g.Out;
+        origin = (n0 + wn * (BN / 2)) * ldo + m0 + wm * (BM / 2);
+        // row-contiguous mapping inside a block: instruction q covers rows 8 q .. 8 q + 7, eight lanes per row
+        const int rr = lane >> 3, slot = lane & 7;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int r = 8 * q + rr;
-            *reinterpret_cast<half8*>(dst + r * ldo + ((slot ^ swz_e(r)) * 8)) = rows[q];
+            voff[q] = (uint32_t)(r * ldo + ((slot ^ swz_e(r)) * 8)) * 2u;
         }
     }
-}
+    __device__ __forceinline__ int64_t unit_off(int u) const { return origin + 32 * (u >> 1) * ldo + 64 * (u & 1); }
+    __device__ __forceinline__ void fill(int u) const {
+        const uint16_t* base = old_base + unit_off(u);
+        const uint32_t l = (uint32_t)(uintptr_t)buf[u % 3];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) dma16(voff[q], base, l + (uint32_t)q * 1024u);
+    }
+
+    // `ahead`: vector-memory operations issued between the first three fills and this call (the next tile's first slices)
+    template <int EPI>
+    __device__ __forceinline__ void run(floatx16 (&acc)[4][4], float s, bool ahead) const {
+        typedef uint32_t u32x2v __attribute__((ext_vector_type(2)));
+        const int lane = threadIdx.x & 63;
+        const int l32 = lane & 31, lh = lane >> 5;
+        int poff[2][2];     // accumulator-layout mapping: this lane's piece (il, a) of row l32
+#pragma unroll
+        for (int il = 0; il < 2; ++il)
+#pragma unroll
+            for (int a = 0; a < 2; ++a) poff[il][a] = l32 * 64 + (((4 * il + 2 * a + lh) ^ swz_e(l32)) * 8);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int j = u >> 1, ih = u & 1;
+            uint16_t* b = buf[u % 3];
+            half8 w[2][2];
+            if constexpr (EPI == EPI_UPDATE) {
+                // Vector-memory operations complete in issue order.  Issued after this block's four loads: blocks 0-2,
+                // the 28 loads of the next tile's first slices (if any), then per block u its stores and the loads of
+                // block u + 3.  Wait until only those may still be outstanding.
+                if (u == 0) { if (ahead) asm volatile("s_waitcnt vmcnt(36)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); }
+                else if (u == 1) { if (ahead) asm volatile("s_waitcnt vmcnt(40)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); }
+                else if (u == 2) { if (ahead) asm volatile("s_waitcnt vmcnt(44)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); }
+                else if (u <= 5) asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
+                else if (u == 6) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+#pragma unroll
+                for (int il = 0; il < 2; ++il)
+#pragma unroll
+                    for (int a = 0; a < 2; ++a) w[il][a] = *reinterpret_cast<const half8*>(b + poff[il][a]);
+            }
+#pragma unroll
+            for (int il = 0; il < 2; ++il)
+#pragma unroll
+                for (int a = 0; a < 2; ++a) {
+                    const int i = 2 * ih + il;
+                    float v[8];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const u32x2v sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[i][j][8 * a + e]),
+                                                                           __float_as_uint(acc[i][j][8 * a + 4 + e]), false, false);
+                        v[e] = __uint_as_float(sw[0]);
+                        v[4 + e] = __uint_as_float(sw[1]);
+                    }
+                    half8 out;
+                    if constexpr (EPI == EPI_UPDATE) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) out[e] = (_Float16)fmaf(-s, v[e], (float)w[il][a][e]);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) out[e] = (_Float16)v[e];
+                    }
+                    *reinterpret_cast<half8*>(b + poff[il][a]) = out;
+                }
+            half8 rows[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) rows[q] = *reinterpret_cast<const half8*>(b + q * 512 + lane * 8);
+            if constexpr (EPI == EPI_UPDATE) {
+                if (u + 3 < 8) {
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // the block is in registers: its buffer is free
+                    fill(u + 3);
+                }
+            }
+            uint16_t* dst = out_base + unit_off(u);
+            const int rr = lane >> 3, slot = lane & 7;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int r = 8 * q + rr;
+                *reinterpret_cast<half8*>(dst + r * ldo + ((slot ^ swz_e(r)) * 8)) = rows[q];
+            }
+        }
+    }
+};
 
 }  // namespace dma
 
@@ -446,15 +456,28 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga
         g.flag_out = ga.t[tensor].flag_out;
         const int64_t em0 = m0, en0 = n0;
 
-        // request the first slices of the next tile, then finish this one
+        // request the first blocks of W (update), then the first slices of the next tile, then finish this one
         w += G;
         const bool more = w < ga.total_tiles;
-        if (more) {
-            setup(w, tensor, m0, n0);
-            issue_prologue();
+        if constexpr (EPI == EPI_UPDATE || EPI == EPI_STORE) {
+            const RowEpilogue re(g, smem, wave, em0, en0);
+            if constexpr (EPI == EPI_UPDATE) {
+                re.fill(0);
+                re.fill(1);
+                re.fill(2);
+            }
+            if (more) {
+                setup(w, tensor, m0, n0);
+                issue_prologue();
+            }
+            re.template run<EPI>(acc, g.s_dev != nullptr ? *g.s_dev : g.s, more);
+        } else {
+            if (more) {
+                setup(w, tensor, m0, n0);
+                issue_prologue();
+            }
+            epilogue<BM, BN, EPI>(acc, g, red_scratch, em0, en0, BM, BN);
         }
-        if constexpr (EPI == EPI_UPDATE || EPI == EPI_STORE) epilogue_rows<EPI>(acc, g, smem, wave, em0, en0);
-        else epilogue<BM, BN, EPI>(acc, g, red_scratch, em0, en0, BM, BN);
         if (!more) break;
         zero_acc();
     }
