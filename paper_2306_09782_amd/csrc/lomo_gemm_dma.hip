@@ -77,9 +77,10 @@ __device__ __forceinline__ half8 read_tr8(const uint16_t* p0, const uint16_t* p1
 // lanes pick their 16-byte pieces out of it, update, put the results back in the same places, and the block
 // leaves row-contiguous again.  Three blocks per wave rotate; the first three loads are issued right after
 // the tile's last slice, ahead of the next tile's first slices, and block u + 3 is requested as soon as block u
-// is in registers.  16-byte chunk c of row r sits at chunk position c ^ ((r >> 1) & 7), which makes both access
-// patterns conflict-free.
-__device__ __forceinline__ int swz_e(int r) { return (r >> 1) & 7; }
+// is in registers.  16-byte chunk c of row r sits at chunk position c ^ (r & 7): the LDS serves eight lanes of a
+// 16-byte access per clock (128 bytes), and eight consecutive lanes are either eight consecutive rows at one
+// chunk (pieces) or the eight chunks of one row (rows), so both patterns are conflict-free.
+__device__ __forceinline__ int swz_e(int r) { return r & 7; }
 
 struct RowEpilogue {
     uint16_t* buf[3];
