@@ -177,3 +177,47 @@ def test_cross_entropy(L, T, V):
     zz = dev(z)
     L.lomo_cross_entropy(zz, dev(tg), S / want["n"], loss, zz)
     np.testing.assert_array_equal(zz.cpu().numpy().view(np.uint16), got.view(np.uint16))
+
+
+def test_forward_entry_points_check_their_arguments(L):
+    """Empty problems succeed without touching memory; wrong shapes and null pointers are refused before any launch."""
+    import ctypes
+    lib = L.load_library()
+    z = ctypes.c_void_p(0)
+    f = ctypes.c_float
+    assert lib.lomo_rmsnorm_forward(z, z, f(1e-5), z, z, z, 0, 256, z) == 0
+    assert lib.lomo_rmsnorm_forward(z, z, f(1e-5), z, z, z, 4, 12, z) == 2            # H % 8
+    assert lib.lomo_rmsnorm_forward(z, z, f(-1.0), z, z, z, 4, 16, z) == 2            # negative eps
+    assert lib.lomo_rmsnorm_forward(z, z, f(1e-5), z, z, z, 4, 16, z) == 1            # null
+    assert lib.lomo_swiglu_forward(z, z, 0, 64, z) == 0 and lib.lomo_swiglu_forward(z, z, 4, 12, z) == 2
+    assert lib.lomo_swiglu_forward(z, z, 4, 16, z) == 1
+    assert lib.lomo_rope_forward(z, z, z, 0, 64, 2, 128, z) == 0
+    assert lib.lomo_rope_forward(z, z, z, 64, 64, 2, 64, z) == 2                      # head width
+    assert lib.lomo_rope_forward(z, z, z, 64, 64, 2, 128, z) == 1
+    assert lib.lomo_attention_forward(z, z, z, 0, 64, 2, 128, z) == 0
+    assert lib.lomo_attention_forward(z, z, z, 1, 100, 2, 128, z) == 2                # s % 64
+    assert lib.lomo_attention_forward(z, z, z, 1, 64, 2, 64, z) == 2
+    assert lib.lomo_attention_forward(z, z, z, 1, 64, 2, 128, z) == 1
+    assert lib.lomo_cross_entropy(z, z, f(1.0), z, z, 0, 512, z) == 0
+    assert lib.lomo_cross_entropy(z, z, f(1.0), z, z, 4, 12, z) == 2 and lib.lomo_cross_entropy(z, z, f(1.0), z, z, 4, 0, z) == 2
+    assert lib.lomo_cross_entropy(z, z, f(1.0), z, z, 4, 16, z) == 1
+    assert lib.lomo_embedding_forward(z, z, z, 0, 64, 100, z) == 0 and lib.lomo_embedding_forward(z, z, z, 4, 12, 100, z) == 2
+    assert lib.lomo_embedding_forward(z, z, z, 4, 16, 100, z) == 1
+    assert lib.lomo_linear_forward_residual(z, z, z, z, 4, 16, 16, z) == 1 and lib.lomo_linear_forward_residual(z, z, z, z, 4, 12, 16, z) == 2
+    # misaligned pointers
+    buf = torch.zeros(4096, dtype=torch.float16, device=DEV)
+    p, q = ctypes.c_void_p(buf.data_ptr()), ctypes.c_void_p(buf.data_ptr() + 2)
+    assert lib.lomo_swiglu_forward(q, p, 4, 16, z) == 3
+    assert lib.lomo_linear_forward(p, p, q, 4, 16, 16, 0, z) == 3
+
+
+def test_embedding_forward(L):
+    rng = np.random.default_rng(9)
+    T, H, V = 70, 136, 50
+    W = f16(rng, (V, H), 1.0)
+    ids = rng.integers(0, V, size=T).astype(np.int32)
+    ids[5], ids[6] = -1, V                      # out of range: zero rows
+    h = torch.full((T, H), 3.0, dtype=torch.float16, device=DEV)
+    L.lomo_embedding_forward(dev(ids), dev(W), h)
+    want = np.where(((ids >= 0) & (ids < V))[:, None], W[np.clip(ids, 0, V - 1)], np.float16(0))
+    np.testing.assert_array_equal(h.cpu().numpy().view(np.uint16), want.view(np.uint16))
