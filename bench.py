@@ -229,26 +229,40 @@ def model_chain_bench(L, torch, np, dev, steps, warmup, n_layers=32, keep_handon
             "family_ms_per_step": {k: v[0] / steps for k, v in fam.items() if v[1]}}
 
 
-def train_step_bench(L, torch, np, dev, steps, warmup, norm, n_layers=32, batch=8, seq=512, checkpoint=True, keep_handons=False,
-                     overlap=False):
-    """One whole fine-tuning step of a 7B-shaped model from token ids (8 x 512 tokens, 32 layers, H 4096, 32 heads,
-    F 11008, V 32000): forward keeping only the layer inputs, cross-entropy, backward loop with every layer
-    recomputed from its checkpoint, fused updates.  Random-init weights (sigma 0.02, gains 1), Zipf token ids;
-    the target of a position is the next token."""
-    from paper_2306_09782_amd.chain import LomoFineTuneStep
+# layers, hidden width, heads (of width 128), feed-forward width of the LLaMA sizes the paper trains (section 4.2)
+TRAIN_MODELS = {"7b": (32, 4096, 32, 11008), "13b": (40, 5120, 40, 13824), "30b": (60, 6656, 52, 17920),
+                "65b": (80, 8192, 64, 22016)}
+
+
+def train_model(torch, dev, name):
+    """Random-init weights of a LLaMA-shaped model: sigma 0.02 at H = 4096, scaled with 1 / sqrt(H); gains 1."""
     import lomo_synth as S
-    Bt, s, nh, H, F, V = batch, seq, 32, 4096, 11008, 32000
-    T = Bt * s
-    torch.cuda.reset_peak_memory_stats()
+    n_layers, H, nh, F = TRAIN_MODELS[name]
+    V = 32000
+    sig = 0.02 * math.sqrt(4096.0 / H)
     count = [0]
 
     def gen(shape, sigma):
         count[0] += 1
         return S.normal_f16_torch(S.tensor_key(0, 97, count[0], 0), shape, S.normal_mult(sigma), dev)
     ones = lambda n: torch.ones(n, dtype=torch.float16, device=dev)
-    m = {"W_emb": gen((V, H), 1.0), "w_f": ones(H), "W_lm": gen((V, H), 0.02),
-         "layers": [{"w1": ones(H), "w2": ones(H), "W_qkv": gen((3 * H, H), 0.02), "W_o": gen((H, H), 0.02),
-                     "W_gu": gen((2 * F, H), 0.02), "W_d": gen((H, F), 0.02)} for _ in range(n_layers)]}
+    return {"W_emb": gen((V, H), 1.0), "w_f": ones(H), "W_lm": gen((V, H), sig),
+            "layers": [{"w1": ones(H), "w2": ones(H), "W_qkv": gen((3 * H, H), sig), "W_o": gen((H, H), sig),
+                        "W_gu": gen((2 * F, H), sig), "W_d": gen((H, F), sig)} for _ in range(n_layers)]}
+
+
+def train_step_bench(L, torch, np, dev, steps, warmup, norm, m, model="7b", batch=8, seq=512, checkpoint=True, keep_handons=False,
+                     overlap=False):
+    """One whole fine-tuning step of a LLaMA-shaped model from token ids (default 7B: 32 layers, H 4096, 32 heads,
+    F 11008, V 32000; 8 x 512 tokens): forward keeping only the layer inputs, cross-entropy, backward loop with every
+    layer recomputed from its checkpoint, fused updates.  Random-init weights `m` (updated in place), Zipf token ids;
+    the target of a position is the next token."""
+    from paper_2306_09782_amd.chain import LomoFineTuneStep
+    import lomo_synth as S
+    n_layers, H, nh, F = TRAIN_MODELS[model]
+    Bt, s, V = batch, seq, 32000
+    T = Bt * s
+    torch.cuda.reset_peak_memory_stats()
     ids_h = S.zipf_ids(97, T, V).astype(np.int32)
     tg_h = np.roll(ids_h, -1).astype(np.int32)
     tg_h[s - 1::s] = -100
@@ -284,11 +298,11 @@ def train_step_bench(L, torch, np, dev, steps, warmup, norm, n_layers=32, batch=
     recomputed = n_layers * H * (3 * H + H + 2 * F) * walks - H * (3 * H + H + 2 * F)     # no W_d; last layer once less
     if not checkpoint:
         recomputed = 0
-    gemm_flops = 2 * T * (n_lin + recomputed + (walks + 1) * n_lin + walks * (n_lin - 0))   # fwd + recompute + wgrads + dgrads
-    # wgrad: norm pass + update pass = 2 per linear; dgrad: once per walk
+    # forward + recomputation + wgrad (norm pass and update pass: 2 per linear) + dgrad (once per walk)
     gemm_flops = 2 * T * (n_lin + recomputed + 2 * n_lin + walks * n_lin)
     flops = gemm_flops + n_layers * at_fwd * (1 + (walks if checkpoint else 0)) + walks * n_layers * at_bwd
-    return {"workload": f"7B-shaped model from token ids ({n_layers} layers, {Bt} x {s} tokens, V 32000)",
+    return {"workload": f"{model.upper()}-shaped model from token ids ({n_layers} layers, H {H}, {nh} heads, F {F}, V 32000; "
+                        f"{Bt} x {s} tokens)",
             "activations": "checkpointed and recomputed" if checkpoint else "kept",
             "hand_ons": "kept from pass 1" if keep_handons else "not kept", "norm_pass_on_second_stream": overlap,
             "norm": norm, "backward_walks": walks, "ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3), "params": n_params,
@@ -318,6 +332,9 @@ def main():
     ap.add_argument("--no-norm-compare", action="store_true",
                     help="skip the extra timing of pass 1 alone on each route after the timed steps")
     ap.add_argument("--train-shape", default="8x512", help="batch x sequence length of --train-step (default 8x512)")
+    ap.add_argument("--train-model", default="7b", choices=sorted(TRAIN_MODELS), help="model size of --train-step (default 7b)")
+    ap.add_argument("--train-policies", default="all", choices=["all", "checkpointed"],
+                    help="--train-step: every memory policy, or only the two checkpointed ones (for the largest models)")
     ap.add_argument("--train-step", action="store_true",
                     help="also time a whole fine-tuning step of a 7B-shaped model from token ids, with activation "
                          "checkpointing (extra keys `train_step_global_norm`, `train_step_grouped_norm`)")
@@ -475,21 +492,25 @@ def main():
         tensors = None
         torch.cuda.empty_cache()
         tb, ts = (int(v) for v in args.train_shape.split("x"))
-        out["train_step_global_norm"] = train_step_bench(L, torch, np, dev, 3, 2, "global", batch=tb, seq=ts)
+        tm = train_model(torch, dev, args.train_model)
+        kw = dict(model=args.train_model, batch=tb, seq=ts)
+        nst, nwu = (3, 2) if args.train_model == "7b" else (2, 1)
+        out["train_step_global_norm"] = train_step_bench(L, torch, np, dev, nst, nwu, "global", tm, **kw)
         torch.cuda.empty_cache()
-        out["train_step_grouped_norm"] = train_step_bench(L, torch, np, dev, 3, 2, "grouped", batch=tb, seq=ts)
-        torch.cuda.empty_cache()
-        out["train_step_global_norm_kept_activations"] = train_step_bench(L, torch, np, dev, 3, 2, "global", batch=tb, seq=ts,
-                                                                          checkpoint=False)
-        torch.cuda.empty_cache()
-        out["train_step_global_norm_kept_activations_and_handons"] = train_step_bench(
-            L, torch, np, dev, 3, 2, "global", batch=tb, seq=ts, checkpoint=False, keep_handons=True)
-        torch.cuda.empty_cache()
-        out["train_step_global_norm_kept_activations_and_handons_two_streams"] = train_step_bench(
-            L, torch, np, dev, 3, 2, "global", batch=tb, seq=ts, checkpoint=False, keep_handons=True, overlap=True)
-        torch.cuda.empty_cache()
-        out["train_step_grouped_norm_kept_activations"] = train_step_bench(L, torch, np, dev, 3, 2, "grouped", batch=tb, seq=ts,
-                                                                           checkpoint=False)
+        out["train_step_grouped_norm"] = train_step_bench(L, torch, np, dev, nst, nwu, "grouped", tm, **kw)
+        if args.train_policies == "all":
+            torch.cuda.empty_cache()
+            out["train_step_global_norm_kept_activations"] = train_step_bench(L, torch, np, dev, nst, nwu, "global", tm, checkpoint=False, **kw)
+            torch.cuda.empty_cache()
+            out["train_step_global_norm_kept_activations_and_handons"] = train_step_bench(
+                L, torch, np, dev, nst, nwu, "global", tm, checkpoint=False, keep_handons=True, **kw)
+            torch.cuda.empty_cache()
+            out["train_step_global_norm_kept_activations_and_handons_two_streams"] = train_step_bench(
+                L, torch, np, dev, nst, nwu, "global", tm, checkpoint=False, keep_handons=True, overlap=True, **kw)
+            torch.cuda.empty_cache()
+            out["train_step_grouped_norm_kept_activations"] = train_step_bench(L, torch, np, dev, nst, nwu, "grouped", tm,
+                                                                               checkpoint=False, **kw)
+        del tm
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))
