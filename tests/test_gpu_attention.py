@@ -329,3 +329,14 @@ def test_decoder_layer_llama7b_shape(L):
     rng = np.random.default_rng(34)
     out = run_layer(L, rng, 8, 512, 32, 11008, 65536.0, 1e-2)
     check_layer(*out, 512, 32)
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("B,s,nh,F", [(1, 512, 40, 13824), (1, 256, 64, 22016)], ids=["llama13b_width", "llama65b_width"])
+def test_decoder_layer_at_the_larger_widths(L, B, s, nh, F):
+    """One decoder layer at the 13B (H = 5120, 40 heads, F = 13824) and 65B (H = 8192, 64 heads, F = 22016) widths on a
+    short batch, so that the full oracle stays affordable: the contraction kernels run their many-tile paths and the
+    attention kernels their widest head counts."""
+    rng = np.random.default_rng(35 + nh)
+    out = run_layer(L, rng, B, s, nh, F, 65536.0, 1e-2)
+    check_layer(*out, s, nh)
