@@ -333,8 +333,9 @@ def main():
                     help="skip the extra timing of pass 1 alone on each route after the timed steps")
     ap.add_argument("--train-shape", default="8x512", help="batch x sequence length of --train-step (default 8x512)")
     ap.add_argument("--train-model", default="7b", choices=sorted(TRAIN_MODELS), help="model size of --train-step (default 7b)")
-    ap.add_argument("--train-policies", default="all", choices=["all", "checkpointed"],
-                    help="--train-step: every memory policy, or only the two checkpointed ones (for the largest models)")
+    ap.add_argument("--train-policies", default="all", choices=["all", "checkpointed", "kept-activations"],
+                    help="--train-step: every memory policy, only the two checkpointed ones, or only the two that keep the "
+                         "activations but not the hand-ons (the largest models do not fit the others)")
     ap.add_argument("--train-step", action="store_true",
                     help="also time a whole fine-tuning step of a 7B-shaped model from token ids, with activation "
                          "checkpointing (extra keys `train_step_global_norm`, `train_step_grouped_norm`)")
@@ -495,9 +496,15 @@ def main():
         tm = train_model(torch, dev, args.train_model)
         kw = dict(model=args.train_model, batch=tb, seq=ts)
         nst, nwu = (3, 2) if args.train_model == "7b" else (2, 1)
-        out["train_step_global_norm"] = train_step_bench(L, torch, np, dev, nst, nwu, "global", tm, **kw)
-        torch.cuda.empty_cache()
-        out["train_step_grouped_norm"] = train_step_bench(L, torch, np, dev, nst, nwu, "grouped", tm, **kw)
+        if args.train_policies != "kept-activations":
+            out["train_step_global_norm"] = train_step_bench(L, torch, np, dev, nst, nwu, "global", tm, **kw)
+            torch.cuda.empty_cache()
+            out["train_step_grouped_norm"] = train_step_bench(L, torch, np, dev, nst, nwu, "grouped", tm, **kw)
+        else:
+            out["train_step_global_norm_kept_activations"] = train_step_bench(L, torch, np, dev, nst, nwu, "global", tm, checkpoint=False, **kw)
+            torch.cuda.empty_cache()
+            out["train_step_grouped_norm_kept_activations"] = train_step_bench(L, torch, np, dev, nst, nwu, "grouped", tm,
+                                                                               checkpoint=False, **kw)
         if args.train_policies == "all":
             torch.cuda.empty_cache()
             out["train_step_global_norm_kept_activations"] = train_step_bench(L, torch, np, dev, nst, nwu, "global", tm, checkpoint=False, **kw)
