@@ -17,13 +17,18 @@
  *   - linear tensor: W [N x K] (N out-features, K in-features), X [T x K], dY [T x N],
  *     dX [T x K]; forward was Y = X W^T; scaled gradient G = dY^T X; dX = dY W.
  *     dY carries the loss scale; inv_loss_scale = 1 / loss_scale removes it.
- *   - the caller owns every buffer; the library allocates nothing, keeps no state between
- *     calls, launches on `stream` (a hipStream_t, NULL = default stream) and never
- *     synchronises.  `acc` and `overflow_flag` are zeroed by the caller before pass 1.
+ *   - the caller owns every buffer; the library allocates no device memory and keeps no state that
+ *     changes a result between calls (what it does keep: the event pool of lomo_timing_*, one-time
+ *     kernel attributes).  Every choice that changes how a result is computed is an argument.  Calls
+ *     launch on `stream` (a hipStream_t, NULL = default stream) and never synchronise.  `acc` and
+ *     `overflow_flag` are zeroed by the caller before pass 1.
  *   - pointers must be 16-byte aligned; K, N and H must be multiples of 8; T >= 0 is free.
  *     X / dY must not alias W / dX.  Token ids must lie in [0, V).
- *   - errors are return codes; a call that does not return LOMO_OK has launched nothing.
- *     Sizes equal to zero are accepted and do nothing.
+ *   - errors are return codes.  Every argument check is made before the first launch, so a call that
+ *     returns LOMO_ERR_NULL / SHAPE / ALIGN / WORKSPACE has launched nothing.  LOMO_ERR_LAUNCH means the
+ *     HIP runtime refused a launch: a per-tensor call has then queued at most its dgrad, a whole-pass
+ *     call (lomo_step_*) may have queued the launches that came before the refused one, and the caller
+ *     should treat the step's outputs as undefined.  Sizes equal to zero are accepted and do nothing.
  */
 #ifndef LOMO_H
 #define LOMO_H
@@ -62,6 +67,23 @@ const char* lomo_status_str(lomo_status s);
 lomo_status lomo_wgrad_sqnorm(const lomo_half* X, const lomo_half* dY,
                               int64_t T, int64_t K, int64_t N,
                               double* acc, int32_t* overflow_flag, void* stream);
+
+/* How a norm-pass call obtains ||dY^T X||^2 of a linear tensor (section 3.3.1 asks only for the norm).
+ *   LOMO_NORM_DIRECT  contract the gradient tile by tile and square it (2 T N K flop).  What
+ *                     lomo_wgrad_sqnorm does.
+ *   LOMO_NORM_GRAM    sum over token pairs of (x_t . x_t')(dy_t . dy_t'), lower triangle only
+ *                     (T^2 (K + N) flop); needs T % 256 == 0, K % 128 == 0, N % 128 == 0 and dense
+ *                     rows, other tensors take the direct route.  Same value up to rounding, same
+ *                     overflow flag; its rounding error is relative to sum_t |x_t|^2 |dy_t|^2 instead
+ *                     of ||G||^2, so it loses accuracy when per-token gradients cancel in the sum.
+ *   LOMO_NORM_AUTO    per tensor, whichever the cost model says is faster.
+ * The route is an argument of the call that uses it; the library holds no setting. */
+enum { LOMO_NORM_DIRECT = 0, LOMO_NORM_AUTO = 1, LOMO_NORM_GRAM = 2 };
+
+/* lomo_wgrad_sqnorm with the route given.  LOMO_ERR_SHAPE for an unknown norm_algorithm. */
+lomo_status lomo_wgrad_sqnorm_route(const lomo_half* X, const lomo_half* dY,
+                                    int64_t T, int64_t K, int64_t N,
+                                    double* acc, int32_t* overflow_flag, int norm_algorithm, void* stream);
 
 /* Same quantity for an embedding table [V x H] whose rows were gathered by ids [T] (device
  * int32): the gradient of row v is the sum of the dY rows at the positions holding id v.
@@ -151,21 +173,37 @@ typedef struct {
                               vector: K = H, N = 1                                                  */
 } lomo_tensor;
 
-/* Device workspace needed by the row kernels of the listed tensors (host function). */
+/* Choices of a whole-pass call, owned by the caller; a NULL pointer means all zeros (the defaults). */
+typedef struct lomo_step_options {
+    int32_t norm_algorithm;   /* lomo_step_norm_pass: LOMO_NORM_* route of the linear tensors (0 = direct)       */
+    int32_t reuse_grouping;   /* update passes: non-zero promises that `ws` still holds what lomo_step_norm_pass
+                                 left there for the SAME tensor list (nothing else wrote to it since), so the
+                                 embedding's token grouping is not computed a second time.  Only used when the
+                                 list holds exactly one embedding tensor.                                          */
+} lomo_step_options;
+
+/* Device workspace needed by the row kernels of the listed tensors (host function).  Layout: the embedding's
+ * token grouping first (kept between the passes of a step), then one area shared by the embedding's partial
+ * rows and the gain vectors' partial column sums.  All gain vectors of equal shape run in one launch per stage
+ * as far as that area holds their partial sums (it is sized for 64 MiB of them at most: 64 vectors at the 7B
+ * shape); a smaller workspace is accepted as long as it holds one vector's. */
 size_t lomo_step_workspace_bytes(const lomo_tensor* tensors, int64_t n);
+/* The least `ws_bytes` the whole-pass calls accept for the list (one gain vector per launch). */
+size_t lomo_step_workspace_min_bytes(const lomo_tensor* tensors, int64_t n);
 
 /* Pass 1 over tensors[0..n) (host array of descriptors, device buffers inside): acc[0] += the squared
  * norm of every scaled gradient; flags[i] |= 1 if tensor i's gradient holds inf/NaN; finally
  * flags[n] = any(flags[0..n)).  acc (device double) and flags (device int32[n + 1]) are zeroed by the
  * caller.  W and dX members are ignored. */
 lomo_status lomo_step_norm_pass(const lomo_tensor* tensors, int64_t n, double* acc, int32_t* flags,
-                                void* ws, size_t ws_bytes, void* stream);
+                                void* ws, size_t ws_bytes, const lomo_step_options* options, void* stream);
 
 /* Pass 2 over the same list: dX (where given) and the fused gradient + SGD update of every tensor,
  * W <- round_fp16(W - lr * clip_coef * inv_loss_scale * G), skipped entirely if step_flag[0] != 0. */
 lomo_status lomo_step_update_pass(const lomo_tensor* tensors, int64_t n,
                                   float lr, float inv_loss_scale, float clip_coef,
-                                  const int32_t* step_flag, void* ws, size_t ws_bytes, void* stream);
+                                  const int32_t* step_flag, void* ws, size_t ws_bytes,
+                                  const lomo_step_options* options, void* stream);
 
 /* The coefficient of a step without a host round trip (sections 3.3.1 and 3.3.2, appendix A): a one-thread
  * kernel reads the scaled squared norm acc[0] and the step flag that pass 1 left on the device and
@@ -187,7 +225,8 @@ typedef struct lomo_step_scalars {
 lomo_status lomo_step_scalars_device(const double* acc, const int32_t* step_flag, double loss_scale, double max_norm,
                                      double eps, double lr, lomo_step_scalars* scalars, void* stream);
 lomo_status lomo_step_update_pass_device(const lomo_tensor* tensors, int64_t n, const lomo_step_scalars* scalars,
-                                         const int32_t* step_flag, void* ws, size_t ws_bytes, void* stream);
+                                         const int32_t* step_flag, void* ws, size_t ws_bytes,
+                                         const lomo_step_options* options, void* stream);
 
 /* ---------------------------------------------------------------- clip by value (section 3.3.1, first
  * alternative): one pass, no norm.  Each element of the unscaled gradient g = G / loss_scale is clamped
@@ -318,24 +357,17 @@ lomo_status lomo_attention_forward(const lomo_half* qkv, lomo_half* o, float* ls
 lomo_status lomo_cross_entropy(const lomo_half* logits, const int32_t* targets, float grad_scale, float* loss,
                                lomo_half* dlogits, int64_t T, int64_t V, void* stream);
 
-/* How the norm pass (paper section 3.3.1) obtains ||dY^T X||^2 of a linear tensor.
- *   LOMO_NORM_DIRECT  contract the gradient tile by tile and square it (2 T N K flop).  Default.
- *   LOMO_NORM_GRAM    sum over token pairs of (x_t . x_t')(dy_t . dy_t'), lower triangle only
- *                     (T^2 (K + N) flop); needs T % 256 == 0, K % 128 == 0, N % 128 == 0 and dense
- *                     rows, other tensors take the direct route.  Same value up to rounding, same
- *                     overflow flag; its rounding error is relative to sum_t |x_t|^2 |dy_t|^2 instead
- *                     of ||G||^2, so it loses accuracy when per-token gradients cancel in the sum.
- *   LOMO_NORM_AUTO    per tensor, whichever the cost model says is faster.
- * Applies to lomo_wgrad_sqnorm and lomo_step_norm_pass; process-wide host-side setting, not
- * thread-safe against concurrent launches.  Returns LOMO_ERR_SHAPE for an unknown value. */
-enum { LOMO_NORM_DIRECT = 0, LOMO_NORM_AUTO = 1, LOMO_NORM_GRAM = 2 };
-lomo_status lomo_set_norm_algorithm(int algorithm);
-int lomo_get_norm_algorithm(void);
+/* The mean loss of a batch in one call: counts the targets inside [0, V) on the device (n), runs lomo_cross_entropy
+ * with grad_scale = (float)(loss_scale / n) (formed in double from the device count), and writes
+ * stats[0] = sum_t loss[t] / n (fp64, fixed summation order) and stats[1] = n to device memory (double[3], 8-byte
+ * aligned, caller-owned; stats[2] is scratch).  n == 0 gives grad_scale 0, a zero gradient and stats = {0, 0}. */
+lomo_status lomo_cross_entropy_mean(const lomo_half* logits, const int32_t* targets, double loss_scale, float* loss,
+                                    lomo_half* dlogits, double* stats, int64_t T, int64_t V, void* stream);
 
 /* Kernel families for lomo_timing_read. */
 enum { LOMO_KERNEL_WGRAD_UPDATE = 0, LOMO_KERNEL_WGRAD_SQNORM = 1, LOMO_KERNEL_DGRAD = 2,
        LOMO_KERNEL_EMBEDDING = 3, LOMO_KERNEL_VECTOR = 4, LOMO_KERNEL_GRAM_SQNORM = 5, LOMO_KERNEL_CHAIN = 6,
-       LOMO_KERNEL_ATTENTION = 7, LOMO_KERNEL_FORWARD = 8, LOMO_KERNEL_FAMILIES = 9 };
+       LOMO_KERNEL_ATTENTION = 7, LOMO_KERNEL_FORWARD = 8, LOMO_KERNEL_PROBE = 9, LOMO_KERNEL_FAMILIES = 10 };
 
 /* Per-kernel timing for benchmarks: while enabled, each launch of a kernel family is bracketed
  * by two HIP events recorded on the launch stream (the only host-side state the library keeps;
@@ -344,6 +376,26 @@ enum { LOMO_KERNEL_WGRAD_UPDATE = 0, LOMO_KERNEL_WGRAD_SQNORM = 1, LOMO_KERNEL_D
  * time in milliseconds and the number of timed launches (host pointers). */
 lomo_status lomo_timing_enable(int on);
 lomo_status lomo_timing_read(int family, double* total_ms, int64_t* launches);
+
+/* ---------------------------------------------------------------- measured ceilings (benchmark aids)
+ * The denominators a roofline needs next to the published peaks: what this chip sustains on the matrix cores with
+ * nothing else going on, and on a plain streaming copy.  Neither is part of the method. */
+
+/* Matrix-core loop without memory traffic.  One workgroup per CU, waves_per_simd (1 or 2) waves on each of its four
+ * SIMDs; every wave loads sixteen 32 x 16 fp16 operand fragments once from `operands` (device, at least
+ * LOMO_PROBE_OPERAND_BYTES bytes: all zeros, or N(0,1) values, or anything else the caller wants to measure with)
+ * and then issues iters x 32 v_mfma_f32_32x32x16_f16 in the 4 x 4 register blocking of the contraction kernels
+ * (iters x 16 in a 4 x 2 blocking with two waves per SIMD, which have half the registers each), alternating
+ * between two operand sets.  The accumulators are summed into sink[workgroup] (device float[n_cu]) so
+ * the work cannot be dropped.  flops_out (host, may be NULL) receives the flop count of the launch.  Timed as
+ * family LOMO_KERNEL_PROBE when timing is on. */
+#define LOMO_PROBE_OPERAND_BYTES (16 * 64 * 16)
+lomo_status lomo_probe_mfma(const lomo_half* operands, int64_t iters, int waves_per_simd, float* sink, int64_t sink_len,
+                            double* flops_out, void* stream);
+
+/* dst[0 .. bytes) = src[0 .. bytes) with 16-byte loads and stores, grid-stride (bytes % 16 == 0, 16-byte aligned
+ * pointers): 2 x bytes of HBM traffic.  Timed as family LOMO_KERNEL_PROBE when timing is on. */
+lomo_status lomo_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

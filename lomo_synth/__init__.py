@@ -10,8 +10,8 @@ device twin (torch integer ops, used as plumbing) yields the same bits.
 from .generators import (tensor_key, normal_f16_np, normal_f16_torch, normal_mult,
                          zipf_ids, splitmix64_np)
 from .configs import (TensorSpec, Workload, workload, llama_tensor_list, WORKLOAD_NAMES,
-                      count_params)
+                      count_params, StreamedStack)
 
 __all__ = ["tensor_key", "normal_f16_np", "normal_f16_torch", "normal_mult", "zipf_ids",
            "splitmix64_np", "TensorSpec", "Workload", "workload", "llama_tensor_list",
-           "WORKLOAD_NAMES", "count_params"]
+           "WORKLOAD_NAMES", "count_params", "StreamedStack"]

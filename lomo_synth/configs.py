@@ -190,3 +190,56 @@ def workload(name: str) -> Workload:
         inj_layer = min(17, n_layers - 1)
         w.inject_inf = (f"layers.{inj_layer}.down_proj", 0, 0)
     return w
+
+
+class StreamedStack:
+    """A stack workload whose activations do not stay resident: every parameter tensor is generated once and kept,
+    while X / dY (and the dX outputs) live in ONE set of buffers per tensor position of a decoder layer, shared by
+    all layers and refilled from the seed whenever a layer's turn comes ("activations regenerated per layer").
+
+    groups[g] is a list of records {kind, name, spec, X | ids, dY, W, dX?} as the step sequencing expects them:
+    group 0 = lm_head, groups 1..L = decoder layers from the last to the first, group L + 1 = the embedding.
+    prepare(g) refills the shared buffers with group g's inputs (same bits as Workload.X_np / dY_np give on the CPU)."""
+
+    def __init__(self, wl: Workload, device):
+        import torch
+        self.wl, self.device = wl, device
+        f16 = dict(dtype=torch.float16, device=device)
+        shared = {}
+
+        def buffers(spec: TensorSpec, slot):
+            key = (slot, spec.kind, spec.T, spec.N, spec.K)
+            if key not in shared:
+                b = {"dY": torch.empty(spec.dy_shape, **f16)}
+                if spec.kind != "embedding":
+                    b["X"] = torch.empty(spec.x_shape, **f16)
+                if spec.kind == "linear":
+                    b["dX"] = torch.empty(spec.T, spec.K, **f16)
+                shared[key] = b
+            return shared[key]
+
+        self.groups, self.specs = [], []
+        order = []          # (group key, spec) in list order
+        for spec in wl.tensors:
+            gkey = spec.layer if spec.layer >= 0 else spec.name
+            if not order or order[-1][0] != gkey:
+                order.append((gkey, []))
+            order[-1][1].append(spec)
+        for gkey, specs in order:
+            recs = []
+            for spec in specs:
+                slot = spec.index if spec.layer >= 0 else spec.name
+                rec = {"kind": spec.kind, "name": spec.name, "spec": spec, "W": wl.W_torch(spec, device)}
+                rec.update(buffers(spec, slot))
+                if spec.kind == "embedding":
+                    rec["ids"] = torch.from_numpy(wl.ids_np(spec)).to(device)
+                recs.append(rec)
+            self.groups.append(recs)
+        self.shared_bytes = sum(t.numel() * 2 for b in shared.values() for t in b.values())
+
+    def prepare(self, g: int) -> None:
+        for rec in self.groups[g]:
+            spec = rec["spec"]
+            self.wl.dY_torch(spec, self.device, out=rec["dY"])
+            if spec.kind != "embedding":
+                self.wl.X_torch(spec, self.device, out=rec["X"])

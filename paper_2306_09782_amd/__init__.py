@@ -11,11 +11,12 @@ from .binding import (LomoError, library_path, load_library, lomo_version, lomo_
                       lomo_embedding_grouping, lomo_timing_enable, lomo_timing_read, KERNEL_FAMILIES,
                       lomo_step_workspace_bytes, lomo_step_norm_pass, lomo_step_update_pass, make_tensor_list,
                       lomo_linear_backward_update_clip_value, lomo_step_update_pass_clip_value,
-                      lomo_set_norm_algorithm, lomo_get_norm_algorithm, NORM_ALGORITHMS, LomoTensor,
+                      lomo_wgrad_sqnorm_route, lomo_step_workspace_min_bytes, NORM_ALGORITHMS, LomoTensor, LomoStepOptions,
                       lomo_step_scalars_device, lomo_step_update_pass_device, unpack_step_scalars, SCALARS_BYTES,
                       lomo_linear_dgrad, lomo_swiglu_backward, lomo_rmsnorm_backward, lomo_attention_backward,
                       lomo_linear_forward, lomo_rmsnorm_forward, lomo_swiglu_forward, lomo_rope_forward,
                       lomo_attention_forward, lomo_cross_entropy, lomo_embedding_forward, lomo_linear_forward_residual,
+                      lomo_cross_entropy_mean, lomo_probe_mfma, lomo_probe_copy, PROBE_OPERAND_BYTES, on_stream,
                       EXPORTED_SYMBOLS)
 
 __all__ = [n for n in dir() if n.startswith("lomo_")] + ["LomoError", "library_path", "load_library",

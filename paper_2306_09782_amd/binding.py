@@ -19,10 +19,11 @@ EXPORTED_SYMBOLS = (
     "lomo_vector_workspace_bytes", "lomo_embedding_grouping", "lomo_timing_enable", "lomo_timing_read",
     "lomo_step_workspace_bytes", "lomo_step_norm_pass", "lomo_step_update_pass",
     "lomo_linear_backward_update_clip_value", "lomo_step_update_pass_clip_value",
-    "lomo_set_norm_algorithm", "lomo_get_norm_algorithm", "lomo_step_scalars_device", "lomo_step_update_pass_device",
+    "lomo_wgrad_sqnorm_route", "lomo_step_workspace_min_bytes", "lomo_step_scalars_device", "lomo_step_update_pass_device",
     "lomo_linear_dgrad", "lomo_swiglu_backward", "lomo_rmsnorm_backward", "lomo_attention_backward",
     "lomo_linear_forward", "lomo_rmsnorm_forward", "lomo_swiglu_forward", "lomo_rope_forward", "lomo_attention_forward",
-    "lomo_cross_entropy", "lomo_embedding_forward", "lomo_linear_forward_residual",
+    "lomo_cross_entropy", "lomo_embedding_forward", "lomo_linear_forward_residual", "lomo_cross_entropy_mean",
+    "lomo_probe_mfma", "lomo_probe_copy",
 )
 
 
@@ -30,6 +31,11 @@ class LomoTensor(ctypes.Structure):
     """Mirror of the C struct lomo_tensor."""
     _fields_ = [("kind", c_int32), ("X", c_void_p), ("dY", c_void_p), ("W", c_void_p), ("dX", c_void_p),
                 ("ids", c_void_p), ("T", c_int64), ("K", c_int64), ("N", c_int64)]
+
+
+class LomoStepOptions(ctypes.Structure):
+    """Mirror of the C struct lomo_step_options."""
+    _fields_ = [("norm_algorithm", c_int32), ("reuse_grouping", c_int32)]
 
 
 KIND_CODES = {"linear": 0, "embedding": 1, "vector": 2}
@@ -59,6 +65,7 @@ def load_library():
         "lomo_version": (c_int, []),
         "lomo_status_str": (c_char_p, [c_int]),
         "lomo_wgrad_sqnorm": (c_int, [P, P, I64, I64, I64, P, P, P]),
+        "lomo_wgrad_sqnorm_route": (c_int, [P, P, I64, I64, I64, P, P, c_int, P]),
         "lomo_embedding_sqnorm": (c_int, [P, P, I64, I64, I64, P, c_size_t, P, P, P]),
         "lomo_vector_sqnorm": (c_int, [P, P, I64, I64, P, c_size_t, P, P, P]),
         "lomo_clip_coef": (c_double, [c_double, c_double, c_double, c_double]),
@@ -71,13 +78,15 @@ def load_library():
         "lomo_vector_workspace_bytes": (c_size_t, [I64, I64]),
         "lomo_embedding_grouping": (c_int, [P, I64, I64, P, c_size_t, P, P, P, P, P]),
         "lomo_step_workspace_bytes": (c_size_t, [POINTER(LomoTensor), I64]),
-        "lomo_step_norm_pass": (c_int, [POINTER(LomoTensor), I64, P, P, P, c_size_t, P]),
-        "lomo_step_update_pass": (c_int, [POINTER(LomoTensor), I64, c_float, c_float, c_float, P, P, c_size_t, P]),
+        "lomo_step_workspace_min_bytes": (c_size_t, [POINTER(LomoTensor), I64]),
+        "lomo_step_norm_pass": (c_int, [POINTER(LomoTensor), I64, P, P, P, c_size_t, POINTER(LomoStepOptions), P]),
+        "lomo_step_update_pass": (c_int, [POINTER(LomoTensor), I64, c_float, c_float, c_float, P, P, c_size_t,
+                                          POINTER(LomoStepOptions), P]),
         "lomo_linear_backward_update_clip_value": (c_int, [P, P, P, P, I64, I64, I64, c_float, c_float, c_float, P, P]),
         "lomo_step_update_pass_clip_value": (c_int, [POINTER(LomoTensor), I64, c_float, c_float, c_float, P, P,
                                                      c_size_t, P]),
         "lomo_step_scalars_device": (c_int, [P, P, c_double, c_double, c_double, c_double, P, P]),
-        "lomo_step_update_pass_device": (c_int, [POINTER(LomoTensor), I64, P, P, P, c_size_t, P]),
+        "lomo_step_update_pass_device": (c_int, [POINTER(LomoTensor), I64, P, P, P, c_size_t, POINTER(LomoStepOptions), P]),
         "lomo_linear_dgrad": (c_int, [P, P, P, I64, I64, I64, P]),
         "lomo_swiglu_backward": (c_int, [P, P, P, I64, I64, P]),
         "lomo_rmsnorm_backward": (c_int, [P, P, P, P, P, P, I64, I64, P]),
@@ -90,8 +99,9 @@ def load_library():
         "lomo_cross_entropy": (c_int, [P, P, c_float, P, P, I64, I64, P]),
         "lomo_embedding_forward": (c_int, [P, P, P, I64, I64, I64, P]),
         "lomo_linear_forward_residual": (c_int, [P, P, P, P, I64, I64, I64, P]),
-        "lomo_set_norm_algorithm": (c_int, [c_int]),
-        "lomo_get_norm_algorithm": (c_int, []),
+        "lomo_cross_entropy_mean": (c_int, [P, P, c_double, P, P, P, I64, I64, P]),
+        "lomo_probe_mfma": (c_int, [P, I64, c_int, P, I64, POINTER(c_double), P]),
+        "lomo_probe_copy": (c_int, [P, P, c_size_t, P]),
         "lomo_timing_enable": (c_int, [c_int]),
         "lomo_timing_read": (c_int, [c_int, POINTER(c_double), POINTER(c_int64)]),
     }
@@ -130,11 +140,35 @@ def lomo_status_str(code: int) -> str:
     return load_library().lomo_status_str(code).decode()
 
 
+def on_stream(stream):
+    """Context in which torch's own operations (fills, copies) are queued on `stream` (None: the current one)."""
+    import contextlib
+    import torch
+    return contextlib.nullcontext() if stream is None else torch.cuda.stream(stream)
+
+
+def _route(norm_algorithm) -> int:
+    return NORM_ALGORITHMS[norm_algorithm] if isinstance(norm_algorithm, str) else int(norm_algorithm)
+
+
+def _options(norm_algorithm="direct", reuse_grouping=False):
+    return ctypes.byref(LomoStepOptions(_route(norm_algorithm), 1 if reuse_grouping else 0))
+
+
 def lomo_wgrad_sqnorm(X, dY, acc, overflow_flag=None, stream=None):
     T, K = X.shape
     N = dY.shape[1]
     assert dY.shape[0] == T
     _check(load_library().lomo_wgrad_sqnorm(_ptr(X), _ptr(dY), T, K, N, _ptr(acc), _ptr(overflow_flag), _stream(stream)))
+
+
+def lomo_wgrad_sqnorm_route(X, dY, acc, overflow_flag=None, norm_algorithm="direct", stream=None):
+    """lomo_wgrad_sqnorm on the route named ('direct', 'auto', 'gram' or the integer code)."""
+    T, K = X.shape
+    N = dY.shape[1]
+    assert dY.shape[0] == T
+    _check(load_library().lomo_wgrad_sqnorm_route(_ptr(X), _ptr(dY), T, K, N, _ptr(acc), _ptr(overflow_flag),
+                                                  _route(norm_algorithm), _stream(stream)))
 
 
 def lomo_embedding_sqnorm(ids, dY, V, ws, acc, overflow_flag=None, stream=None):
@@ -201,18 +235,8 @@ def lomo_embedding_grouping(ids, V, ws, unique_ids, seg_offsets, perm, n_unique,
 
 
 KERNEL_FAMILIES = ("wgrad_update", "wgrad_sqnorm", "dgrad", "embedding", "vector", "gram_sqnorm", "chain", "attention",
-                   "forward")
+                   "forward", "probe")
 NORM_ALGORITHMS = {"direct": 0, "auto": 1, "gram": 2}
-
-
-def lomo_set_norm_algorithm(algorithm):
-    """'direct' (default), 'auto' or 'gram' (or the integer code): route of the norm pass for linear tensors."""
-    code = NORM_ALGORITHMS[algorithm] if isinstance(algorithm, str) else int(algorithm)
-    _check(load_library().lomo_set_norm_algorithm(code))
-
-
-def lomo_get_norm_algorithm() -> int:
-    return load_library().lomo_get_norm_algorithm()
 
 
 def lomo_timing_enable(on: bool):
@@ -254,15 +278,21 @@ def lomo_step_workspace_bytes(tensor_list) -> int:
     return load_library().lomo_step_workspace_bytes(tensor_list, len(tensor_list))
 
 
-def lomo_step_norm_pass(tensor_list, acc, flags, ws, stream=None):
+def lomo_step_workspace_min_bytes(tensor_list) -> int:
+    return load_library().lomo_step_workspace_min_bytes(tensor_list, len(tensor_list))
+
+
+def lomo_step_norm_pass(tensor_list, acc, flags, ws, stream=None, norm_algorithm="direct"):
     assert flags.numel() >= len(tensor_list) + 1
     _check(load_library().lomo_step_norm_pass(tensor_list, len(tensor_list), _ptr(acc), _ptr(flags), _ptr(ws),
-                                              _nbytes(ws), _stream(stream)))
+                                              _nbytes(ws), _options(norm_algorithm), _stream(stream)))
 
 
-def lomo_step_update_pass(tensor_list, lr, inv_loss_scale, clip_coef, step_flag, ws, stream=None):
+def lomo_step_update_pass(tensor_list, lr, inv_loss_scale, clip_coef, step_flag, ws, stream=None, reuse_grouping=False):
+    """reuse_grouping: `ws` still holds what lomo_step_norm_pass left there for the same list."""
     _check(load_library().lomo_step_update_pass(tensor_list, len(tensor_list), lr, inv_loss_scale, clip_coef,
-                                                _ptr(step_flag), _ptr(ws), _nbytes(ws), _stream(stream)))
+                                                _ptr(step_flag), _ptr(ws), _nbytes(ws),
+                                                _options(reuse_grouping=reuse_grouping), _stream(stream)))
 
 
 def lomo_linear_dgrad(dY, W, dX, stream=None):
@@ -324,6 +354,31 @@ def lomo_cross_entropy(logits, targets, grad_scale, loss, dlogits, stream=None):
                                              _stream(stream)))
 
 
+def lomo_cross_entropy_mean(logits, targets, loss_scale, loss, dlogits, stats, stream=None):
+    """stats: device float64[3]; receives (mean loss over the counted targets, their number, scratch)."""
+    T, V = logits.shape
+    assert targets.numel() == T and loss.numel() == T and tuple(dlogits.shape) == (T, V) and _nbytes(stats) >= 24
+    _check(load_library().lomo_cross_entropy_mean(_ptr(logits), _ptr(targets), loss_scale, _ptr(loss), _ptr(dlogits),
+                                                  _ptr(stats), T, V, _stream(stream)))
+
+
+PROBE_OPERAND_BYTES = 16 * 64 * 16
+
+
+def lomo_probe_mfma(operands, iters, waves_per_simd, sink, stream=None) -> float:
+    """Launches the matrix-core loop; returns the flop count of the launch."""
+    assert _nbytes(operands) >= PROBE_OPERAND_BYTES
+    flops = c_double(0.0)
+    _check(load_library().lomo_probe_mfma(_ptr(operands), iters, waves_per_simd, _ptr(sink), sink.numel(),
+                                          ctypes.byref(flops), _stream(stream)))
+    return flops.value
+
+
+def lomo_probe_copy(src, dst, stream=None):
+    assert _nbytes(src) == _nbytes(dst)
+    _check(load_library().lomo_probe_copy(_ptr(src), _ptr(dst), _nbytes(src), _stream(stream)))
+
+
 def lomo_swiglu_backward(da, gate_up, dgate_up, stream=None):
     T, F = da.shape
     assert tuple(gate_up.shape) == (T, 2 * F) and tuple(dgate_up.shape) == (T, 2 * F)
@@ -356,9 +411,10 @@ def lomo_step_scalars_device(acc, step_flag, loss_scale, max_norm, eps, lr, scal
                                                    _ptr(scalars), _stream(stream)))
 
 
-def lomo_step_update_pass_device(tensor_list, scalars, step_flag, ws, stream=None):
+def lomo_step_update_pass_device(tensor_list, scalars, step_flag, ws, stream=None, reuse_grouping=False):
     _check(load_library().lomo_step_update_pass_device(tensor_list, len(tensor_list), _ptr(scalars), _ptr(step_flag),
-                                                       _ptr(ws), _nbytes(ws), _stream(stream)))
+                                                       _ptr(ws), _nbytes(ws), _options(reuse_grouping=reuse_grouping),
+                                                       _stream(stream)))
 
 
 def unpack_step_scalars(host_bytes):

@@ -65,9 +65,10 @@ class StepState:
     def step_flag(self):
         return self.flags[self.n:self.n + 1]
 
-    def begin(self):
-        self.acc.zero_()
-        self.flags.zero_()
+    def begin(self, stream=None):
+        with B.on_stream(stream):      # the fills are queued on the step's stream, ahead of pass 1's atomics
+            self.acc.zero_()
+            self.flags.zero_()
 
     def coefficient(self, lr, loss_scale, max_norm, eps, stream):
         self.join(stream)
@@ -75,11 +76,8 @@ class StepState:
         B.lomo_step_scalars_device(self.acc, self.step_flag, loss_scale, max_norm, eps, lr, self.scalars, stream)
 
     def finish(self, stream):
-        if stream is None:
+        with B.on_stream(stream):
             self._scalars_host.copy_(self.scalars, non_blocking=True)
-        else:
-            with torch.cuda.stream(stream):
-                self._scalars_host.copy_(self.scalars, non_blocking=True)
 
     def result(self) -> Dict:
         """Scalars and flags of the last step (synchronise first)."""
@@ -147,7 +145,7 @@ class LomoMlpBlock:
     def step(self, dy, saved: Dict, w, W_gu, W_d, dh, lr: float, loss_scale: float, max_norm: float = 1.0,
              eps: float = 1e-6, stream=None) -> None:
         """Queues the whole two-pass step of this block alone; dh receives the gradient of the block input."""
-        self.state.begin()
+        self.state.begin(stream)
         self.walk(dy, saved, w, W_gu, W_d, dh, False, stream)
         self.state.coefficient(lr, loss_scale, max_norm, eps, stream)
         self.walk(dy, saved, w, W_gu, W_d, dh, True, stream)
@@ -196,7 +194,7 @@ class LomoAttentionBlock:
 
     def step(self, dy, saved: Dict, w, W_qkv, W_o, rope_cos, rope_sin, dh, lr: float, loss_scale: float,
              max_norm: float = 1.0, eps: float = 1e-6, stream=None) -> None:
-        self.state.begin()
+        self.state.begin(stream)
         self.walk(dy, saved, w, W_qkv, W_o, rope_cos, rope_sin, dh, False, stream)
         self.state.coefficient(lr, loss_scale, max_norm, eps, stream)
         self.walk(dy, saved, w, W_qkv, W_o, rope_cos, rope_sin, dh, True, stream)
@@ -224,7 +222,7 @@ class LomoDecoderLayer:
     def step(self, dy, saved_attn: Dict, saved_mlp: Dict, p: Dict, rope_cos, rope_sin, dh, lr: float, loss_scale: float,
              max_norm: float = 1.0, eps: float = 1e-6, stream=None) -> None:
         """p: {"w1", "W_qkv", "W_o", "w2", "W_gu", "W_d"} device tensors, updated in place; dh: gradient of the layer input."""
-        self.state.begin()
+        self.state.begin(stream)
         self._walk(dy, saved_attn, saved_mlp, p, rope_cos, rope_sin, dh, False, stream)
         self.state.coefficient(lr, loss_scale, max_norm, eps, stream)
         self._walk(dy, saved_attn, saved_mlp, p, rope_cos, rope_sin, dh, True, stream)
@@ -321,7 +319,7 @@ class LomoModelChain:
         saved: {"layers": [(attention-block activations, feed-forward-block activations), ...], "final": {...}}.
         before_layer(layer index, walk index) is called before the walk enters a layer, in both passes."""
         assert before_layer is None or not self.keep_handons, "kept hand-ons need every layer's activations in pass 2"
-        self.state.begin()
+        self.state.begin(stream)
         self._walk(ids, dlogits, saved, m, rope_cos, rope_sin, False, stream, before_layer)
         self.state.coefficient(lr, loss_scale, max_norm, eps, stream)
         if self.keep_handons:
@@ -448,8 +446,9 @@ class LomoGroupedNormChain:
     def step(self, ids, dlogits, saved: Dict, m: Dict, rope_cos, rope_sin, lr: float, loss_scale: float,
              max_norm: float = 1.0, eps: float = 1e-6, stream=None, before_layer=None) -> None:
         lists = self._tensor_lists(ids, dlogits, saved, m)
-        self.acc.zero_()
-        self.flags.zero_()
+        with B.on_stream(stream):
+            self.acc.zero_()
+            self.flags.zero_()
         L = self.n_layers
         final = saved["final"]
 
@@ -559,6 +558,7 @@ class LomoFineTuneStep:
                       "xn": torch.empty(T, H, **f16)}
         self.logits = torch.empty(T, V, **f16)           # overwritten by its own gradient
         self.token_loss = torch.empty(T, dtype=torch.float32, device=self.device)
+        self.loss_stats = torch.zeros(3, dtype=torch.float64, device=self.device)     # mean loss, counted targets, scratch
         if norm == "grouped":
             self.chain = LomoGroupedNormChain(self.device, batch, seq, H, F, n_heads, n_layers, layers_per_group=per)
         else:
@@ -570,7 +570,7 @@ class LomoFineTuneStep:
     def _act(self, li: int) -> LayerActivations:
         return self.acts[(self.n_layers - 1 - li) % len(self.acts)]
 
-    def forward(self, ids, targets, grad_scale: float, m: Dict, rope_cos, rope_sin, stream=None) -> None:
+    def forward(self, ids, targets, loss_scale: float, m: Dict, rope_cos, rope_sin, stream=None) -> None:
         """Checkpoints, final norm, logits, token losses, and the scaled loss gradient in place of the logits."""
         B.lomo_embedding_forward(ids, m["W_emb"], self.ckpt[0], stream)
         for li, p in enumerate(m["layers"]):
@@ -579,14 +579,13 @@ class LomoFineTuneStep:
         f = self.final
         B.lomo_rmsnorm_forward(self.ckpt[self.n_layers], m["w_f"], self.eps, f["xhat"], f["rstd"], f["xn"], stream)
         B.lomo_linear_forward(f["xn"], m["W_lm"], self.logits, False, stream)
-        B.lomo_cross_entropy(self.logits, targets, grad_scale, self.token_loss, self.logits, stream)
+        B.lomo_cross_entropy_mean(self.logits, targets, loss_scale, self.token_loss, self.logits, self.loss_stats, stream)
 
-    def step(self, ids, targets, n_counted: int, m: Dict, rope_cos, rope_sin, lr: float, loss_scale: float,
+    def step(self, ids, targets, m: Dict, rope_cos, rope_sin, lr: float, loss_scale: float,
              max_norm: float = 1.0, eps_clip: float = 1e-6, stream=None) -> None:
-        """m as for LomoModelChain, updated in place.  targets [T] int32 (outside [0, V): not counted); n_counted is
-        the number of counted targets (the mean loss's denominator)."""
-        self.n_counted = n_counted
-        self.forward(ids, targets, loss_scale / n_counted, m, rope_cos, rope_sin, stream)
+        """m as for LomoModelChain, updated in place.  targets [T] int32 (outside [0, V): not counted); the mean loss's
+        denominator, the number of counted targets, is taken on the device."""
+        self.forward(ids, targets, loss_scale, m, rope_cos, rope_sin, stream)
         fresh = [self.n_layers - 1]          # the forward pass has just left the last layer's activations in place
 
         def recompute(li, k):
@@ -602,7 +601,7 @@ class LomoFineTuneStep:
     def result(self) -> Dict:
         """The chain's scalars and flags plus the mean loss over the counted tokens (synchronise first)."""
         out = self.chain.result()
-        out["loss"] = float(self.token_loss.double().sum().item()) / self.n_counted
+        out["loss"] = float(self.loss_stats[0].item())
         return out
 
 
@@ -617,9 +616,9 @@ class LomoTrainer:
         self.step, self.lr, self.loss_scale, self.growth_interval = step, lr, float(loss_scale), growth_interval
         self.max_norm, self.eps_clip, self.clean_steps = max_norm, eps_clip, 0
 
-    def train_step(self, ids, targets, n_counted: int, m: Dict, rope_cos, rope_sin, stream=None) -> Dict:
+    def train_step(self, ids, targets, m: Dict, rope_cos, rope_sin, stream=None) -> Dict:
         used = self.loss_scale
-        self.step.step(ids, targets, n_counted, m, rope_cos, rope_sin, self.lr, used, self.max_norm, self.eps_clip, stream)
+        self.step.step(ids, targets, m, rope_cos, rope_sin, self.lr, used, self.max_norm, self.eps_clip, stream)
         if stream is None:
             torch.cuda.synchronize(self.step.device)
         else:

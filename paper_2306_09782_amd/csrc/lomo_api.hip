@@ -37,6 +37,13 @@ const char* lomo_status_str(lomo_status s) {
 
 lomo_status lomo_wgrad_sqnorm(const lomo_half* X, const lomo_half* dY, int64_t T, int64_t K, int64_t N, double* acc,
                               int32_t* overflow_flag, void* stream) {
+    return lomo_wgrad_sqnorm_route(X, dY, T, K, N, acc, overflow_flag, LOMO_NORM_DIRECT, stream);
+}
+
+lomo_status lomo_wgrad_sqnorm_route(const lomo_half* X, const lomo_half* dY, int64_t T, int64_t K, int64_t N, double* acc,
+                                    int32_t* overflow_flag, int norm_algorithm, void* stream) {
+    if (norm_algorithm != LOMO_NORM_DIRECT && norm_algorithm != LOMO_NORM_AUTO && norm_algorithm != LOMO_NORM_GRAM)
+        return LOMO_ERR_SHAPE;
     if (T < 0 || K < 0 || N < 0 || (K & 7) || (N & 7)) return LOMO_ERR_SHAPE;
     if (!acc) return LOMO_ERR_NULL;
     if (T == 0 || K == 0 || N == 0) return LOMO_OK;
@@ -48,7 +55,7 @@ lomo_status lomo_wgrad_sqnorm(const lomo_half* X, const lomo_half* dY, int64_t T
     a.lda = K; a.ldb = N; a.ldo = K;
     a.acc = acc; a.flag_out = overflow_flag;
     a.family = LOMO_KERNEL_WGRAD_SQNORM;
-    return from_hip(launch_wgrad_sqnorm(a, static_cast<hipStream_t>(stream)));
+    return from_hip(launch_wgrad_sqnorm(a, norm_algorithm, static_cast<hipStream_t>(stream)));
 }
 
 lomo_status lomo_linear_backward_update(const lomo_half* X, const lomo_half* dY, lomo_half* W, lomo_half* dX, int64_t T,
@@ -185,21 +192,60 @@ static lomo_status check_linear(const lomo_tensor& t, bool need_w) {
     return LOMO_OK;
 }
 
-size_t lomo_step_workspace_bytes(const lomo_tensor* tensors, int64_t n) {
-    size_t need = 0;
-    if (!tensors) return 0;
+// Workspace layout of a whole-pass call: [ embedding grouping | shared area ].  The shared area serves the
+// embedding's partial rows and the gain vectors' partial column sums in turn (everything runs on one stream).
+struct StepWs {
+    size_t grouping = 0;     // bytes of the head (largest embedding batch of the list)
+    size_t emb_rest = 0;     // bytes the embedding needs behind its grouping
+    size_t vec_one = 0;      // largest single gain vector's partial sums
+    size_t vec_all = 0;      // the same for every gain vector of the most demanding shape at once (capped)
+    int n_embedding = 0;
+};
+constexpr size_t kVecBatchBytes = (size_t)64 << 20;     // partial sums worth batching per launch
+
+static StepWs plan_step_ws(const lomo_tensor* tensors, int64_t n) {
+    StepWs p;
+    if (!tensors) return p;
     for (int64_t i = 0; i < n; ++i) {
-        size_t b = 0;
-        if (tensors[i].kind == LOMO_TENSOR_EMBEDDING) b = embedding_ws_bytes(tensors[i].T, tensors[i].K);
-        if (tensors[i].kind == LOMO_TENSOR_VECTOR) b = vector_ws_bytes(tensors[i].T, tensors[i].K);
-        if (b > need) need = b;
+        const lomo_tensor& t = tensors[i];
+        if (t.T <= 0 || t.K <= 0) continue;
+        if (t.kind == LOMO_TENSOR_EMBEDDING) {
+            const size_t g = embedding_grouping_bytes(t.T);
+            const size_t all = embedding_ws_bytes(t.T, t.K);
+            if (g > p.grouping) p.grouping = g;
+            if (all - g > p.emb_rest) p.emb_rest = all - g;
+            p.n_embedding++;
+        } else if (t.kind == LOMO_TENSOR_VECTOR) {
+            const size_t one = vector_ws_bytes(t.T, t.K);
+            size_t same = 0;
+            for (int64_t j = 0; j < n; ++j)
+                if (tensors[j].kind == LOMO_TENSOR_VECTOR && tensors[j].T == t.T && tensors[j].K == t.K) ++same;
+            if (same > (size_t)VEC_BATCH) same = VEC_BATCH;
+            size_t all = one * same;
+            if (all > kVecBatchBytes) all = (kVecBatchBytes / one > 0 ? kVecBatchBytes / one : 1) * one;
+            if (one > p.vec_one) p.vec_one = one;
+            if (all > p.vec_all) p.vec_all = all;
+        }
     }
-    return need;
+    return p;
+}
+
+size_t lomo_step_workspace_bytes(const lomo_tensor* tensors, int64_t n) {
+    const StepWs p = plan_step_ws(tensors, n);
+    return p.grouping + (p.emb_rest > p.vec_all ? p.emb_rest : p.vec_all);
+}
+
+size_t lomo_step_workspace_min_bytes(const lomo_tensor* tensors, int64_t n) {
+    const StepWs p = plan_step_ws(tensors, n);
+    return p.grouping + (p.emb_rest > p.vec_one ? p.emb_rest : p.vec_one);
 }
 
 static lomo_status check_step(const lomo_tensor* tensors, int64_t n, bool update, void* ws, size_t ws_bytes) {
     if (n < 0) return LOMO_ERR_SHAPE;
     if (n > 0 && !tensors) return LOMO_ERR_NULL;
+    const size_t need = lomo_step_workspace_min_bytes(tensors, n);
+    if (need > 0 && (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 255u))) return LOMO_ERR_WORKSPACE;
+    // the per-kind checks below see a workspace that is known to be large enough for each tensor on its own
     for (int64_t i = 0; i < n; ++i) {
         const lomo_tensor& t = tensors[i];
         lomo_status s;
@@ -219,8 +265,53 @@ static lomo_status check_step(const lomo_tensor* tensors, int64_t n, bool update
     return LOMO_OK;
 }
 
+// The row kernels of a pass: every gain vector (one launch per stage and shape, as far as the shared area holds
+// their partial sums), then the embedding.  mode as in launch_vector / launch_embedding_rows; flags: per-tensor
+// flags to raise (modes 0 and 2) or null.
+static lomo_status run_row_kernels(const lomo_tensor* tensors, int64_t n, void* ws, size_t ws_bytes, int mode, float s,
+                                   const float* s_dev, double* acc, int32_t* flags, const int32_t* step_flag, float lr,
+                                   float clipv, bool reuse_grouping, hipStream_t st) {
+    const StepWs plan = plan_step_ws(tensors, n);
+    char* shared = static_cast<char*>(ws) + plan.grouping;
+    const size_t shared_bytes = ws_bytes - plan.grouping;
+    std::vector<char> done((size_t)n, 0);
+    for (int64_t i = 0; i < n; ++i) {
+        const lomo_tensor& t = tensors[i];
+        if (t.kind != LOMO_TENSOR_VECTOR || done[i] || t.T == 0 || t.K == 0) continue;
+        std::vector<VecItem> items;
+        for (int64_t j = i; j < n; ++j) {
+            const lomo_tensor& u = tensors[j];
+            if (u.kind != LOMO_TENSOR_VECTOR || u.T != t.T || u.K != t.K) continue;
+            done[j] = 1;
+            items.push_back(VecItem{u.X, u.dY, mode == 0 ? nullptr : u.W, flags ? flags + j : nullptr});
+        }
+        ScopedTiming timing(LOMO_KERNEL_VECTOR, st);
+        if (launch_vector_batch(items.data(), (int)items.size(), t.T, t.K, shared, shared_bytes, mode, s, acc, step_flag, st,
+                                lr, clipv, s_dev) != hipSuccess)
+            return LOMO_ERR_LAUNCH;
+    }
+    for (int64_t i = 0; i < n; ++i) {
+        const lomo_tensor& t = tensors[i];
+        if (t.kind != LOMO_TENSOR_EMBEDDING || t.T == 0 || t.K == 0 || t.N == 0) continue;
+        EmbeddingWs w = carve_embedding_ws(ws, t.T, t.K);
+        // partial sums go behind the grouping of the LARGEST embedding batch, where the shared area starts
+        const ptrdiff_t shift = shared - reinterpret_cast<char*>(w.partials);
+        w.partials = reinterpret_cast<double*>(reinterpret_cast<char*>(w.partials) + shift);
+        w.chunk_rows = reinterpret_cast<float*>(reinterpret_cast<char*>(w.chunk_rows) + shift);
+        ScopedTiming timing(LOMO_KERNEL_EMBEDDING, st);
+        if (!(reuse_grouping && plan.n_embedding == 1) && launch_embedding_grouping(t.ids, t.T, t.N, w, st) != hipSuccess)
+            return LOMO_ERR_LAUNCH;
+        if (launch_embedding_rows(t.ids, t.dY, mode == 0 ? nullptr : t.W, t.T, t.K, w, mode, s, acc, flags ? flags + i : nullptr,
+                                  step_flag, st, lr, clipv, s_dev) != hipSuccess)
+            return LOMO_ERR_LAUNCH;
+    }
+    return LOMO_OK;
+}
+
 lomo_status lomo_step_norm_pass(const lomo_tensor* tensors, int64_t n, double* acc, int32_t* flags, void* ws,
-                                size_t ws_bytes, void* stream) {
+                                size_t ws_bytes, const lomo_step_options* options, void* stream) {
+    const int route = options ? options->norm_algorithm : LOMO_NORM_DIRECT;
+    if (route != LOMO_NORM_DIRECT && route != LOMO_NORM_AUTO && route != LOMO_NORM_GRAM) return LOMO_ERR_SHAPE;
     lomo_status cs = check_step(tensors, n, false, ws, ws_bytes);
     if (cs != LOMO_OK) return cs;
     if (!acc || !flags) return LOMO_ERR_NULL;
@@ -229,39 +320,30 @@ lomo_status lomo_step_norm_pass(const lomo_tensor* tensors, int64_t n, double* a
     std::vector<GemmArgs> grouped;
     for (int64_t i = 0; i < n; ++i) {
         const lomo_tensor& t = tensors[i];
-        if (t.T == 0 || t.K == 0 || t.N == 0) continue;
-        if (t.kind == LOMO_TENSOR_LINEAR) {
-            GemmArgs a{};
-            a.A = t.X; a.B = t.dY; a.Out = nullptr;
-            a.M = t.K; a.Nn = t.N; a.C = t.T;
-            a.lda = t.K; a.ldb = t.N; a.ldo = t.K;
-            a.acc = acc; a.flag_out = flags + i;
-            a.family = LOMO_KERNEL_WGRAD_SQNORM;
-            if (dma_eligible(a)) grouped.push_back(a);
-            else if (launch_wgrad_sqnorm(a, st) != hipSuccess) return LOMO_ERR_LAUNCH;
-        } else if (t.kind == LOMO_TENSOR_EMBEDDING) {
-            EmbeddingWs w = carve_embedding_ws(ws, t.T, t.K);
-            ScopedTiming timing(LOMO_KERNEL_EMBEDDING, st);
-            if (launch_embedding_grouping(t.ids, t.T, t.N, w, st) != hipSuccess) return LOMO_ERR_LAUNCH;
-            if (launch_embedding_rows(t.ids, t.dY, nullptr, t.T, t.K, w, 0, 0.f, acc, flags + i, nullptr, st) != hipSuccess)
-                return LOMO_ERR_LAUNCH;
-        } else {
-            ScopedTiming timing(LOMO_KERNEL_VECTOR, st);
-            if (launch_vector(t.X, t.dY, nullptr, t.T, t.K, ws, 0, 0.f, acc, flags + i, nullptr, st) != hipSuccess)
-                return LOMO_ERR_LAUNCH;
-        }
+        if (t.kind != LOMO_TENSOR_LINEAR || t.T == 0 || t.K == 0 || t.N == 0) continue;
+        GemmArgs a{};
+        a.A = t.X; a.B = t.dY; a.Out = nullptr;
+        a.M = t.K; a.Nn = t.N; a.C = t.T;
+        a.lda = t.K; a.ldb = t.N; a.ldo = t.K;
+        a.acc = acc; a.flag_out = flags + i;
+        a.family = LOMO_KERNEL_WGRAD_SQNORM;
+        if (dma_eligible(a)) grouped.push_back(a);
+        else if (launch_wgrad_sqnorm(a, route, st) != hipSuccess) return LOMO_ERR_LAUNCH;
     }
     std::vector<GemmArgs> gram, direct;
-    choose_norm_route(grouped, gram, direct);
+    choose_norm_route(route, grouped, gram, direct);
     if (!gram.empty() && launch_gram_group(gram.data(), (int)gram.size(), st) != hipSuccess) return LOMO_ERR_LAUNCH;
     if (!direct.empty() && launch_dma_group<true, EPI_SQNORM>(direct.data(), (int)direct.size(), st) != hipSuccess)
         return LOMO_ERR_LAUNCH;
+    cs = run_row_kernels(tensors, n, ws, ws_bytes, 0, 0.f, nullptr, acc, flags, nullptr, 0.f, 0.f, false, st);
+    if (cs != LOMO_OK) return cs;
     return from_hip(launch_reduce_flags(flags, n, flags + n, st));
 }
 
 // Pass 2 with the step size given by value (s_dev == nullptr) or read by the kernels from device memory.
 static lomo_status update_pass(const lomo_tensor* tensors, int64_t n, float s, const float* s_dev,
-                               const int32_t* step_flag, void* ws, size_t ws_bytes, void* stream) {
+                               const int32_t* step_flag, void* ws, size_t ws_bytes, const lomo_step_options* options,
+                               void* stream) {
     lomo_status cs = check_step(tensors, n, true, ws, ws_bytes);
     if (cs != LOMO_OK) return cs;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -294,29 +376,14 @@ static lomo_status update_pass(const lomo_tensor* tensors, int64_t n, float s, c
         return LOMO_ERR_LAUNCH;
     for (const GemmArgs& a : updates_plain)
         if (launch_wgrad_update(a, st) != hipSuccess) return LOMO_ERR_LAUNCH;
-    for (int64_t i = 0; i < n; ++i) {
-        const lomo_tensor& t = tensors[i];
-        if (t.T == 0 || t.K == 0 || t.N == 0) continue;
-        if (t.kind == LOMO_TENSOR_EMBEDDING) {
-            EmbeddingWs w = carve_embedding_ws(ws, t.T, t.K);
-            ScopedTiming timing(LOMO_KERNEL_EMBEDDING, st);
-            if (launch_embedding_grouping(t.ids, t.T, t.N, w, st) != hipSuccess) return LOMO_ERR_LAUNCH;
-            if (launch_embedding_rows(t.ids, t.dY, t.W, t.T, t.K, w, 1, s, nullptr, nullptr, step_flag, st, 0.f, 0.f, s_dev) !=
-                hipSuccess)
-                return LOMO_ERR_LAUNCH;
-        } else if (t.kind == LOMO_TENSOR_VECTOR) {
-            ScopedTiming timing(LOMO_KERNEL_VECTOR, st);
-            if (launch_vector(t.X, t.dY, t.W, t.T, t.K, ws, 1, s, nullptr, nullptr, step_flag, st, 0.f, 0.f, s_dev) !=
-                hipSuccess)
-                return LOMO_ERR_LAUNCH;
-        }
-    }
-    return LOMO_OK;
+    return run_row_kernels(tensors, n, ws, ws_bytes, 1, s, s_dev, nullptr, nullptr, step_flag, 0.f, 0.f,
+                           options != nullptr && options->reuse_grouping != 0, st);
 }
 
 lomo_status lomo_step_update_pass(const lomo_tensor* tensors, int64_t n, float lr, float inv_loss_scale,
-                                  float clip_coef, const int32_t* step_flag, void* ws, size_t ws_bytes, void* stream) {
-    return update_pass(tensors, n, step_size(lr, inv_loss_scale, clip_coef), nullptr, step_flag, ws, ws_bytes, stream);
+                                  float clip_coef, const int32_t* step_flag, void* ws, size_t ws_bytes,
+                                  const lomo_step_options* options, void* stream) {
+    return update_pass(tensors, n, step_size(lr, inv_loss_scale, clip_coef), nullptr, step_flag, ws, ws_bytes, options, stream);
 }
 
 lomo_status lomo_step_scalars_device(const double* acc, const int32_t* step_flag, double loss_scale, double max_norm,
@@ -329,10 +396,11 @@ lomo_status lomo_step_scalars_device(const double* acc, const int32_t* step_flag
 }
 
 lomo_status lomo_step_update_pass_device(const lomo_tensor* tensors, int64_t n, const lomo_step_scalars* scalars,
-                                         const int32_t* step_flag, void* ws, size_t ws_bytes, void* stream) {
+                                         const int32_t* step_flag, void* ws, size_t ws_bytes,
+                                         const lomo_step_options* options, void* stream) {
     if (!scalars) return LOMO_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(scalars) & 7u) return LOMO_ERR_ALIGN;
-    return update_pass(tensors, n, 0.f, &scalars->step, step_flag, ws, ws_bytes, stream);
+    return update_pass(tensors, n, 0.f, &scalars->step, step_flag, ws, ws_bytes, options, stream);
 }
 
 // ---- clip by value (single pass) -----------------------------------------------------------
@@ -402,23 +470,8 @@ lomo_status lomo_step_update_pass_clip_value(const lomo_tensor* tensors, int64_t
         return LOMO_ERR_LAUNCH;
     for (const GemmArgs& a : updates_plain)
         if (launch_wgrad_update_clipv(a, st) != hipSuccess) return LOMO_ERR_LAUNCH;
-    for (int64_t i = 0; i < n; ++i) {
-        const lomo_tensor& t = tensors[i];
-        if (t.T == 0 || t.K == 0 || t.N == 0) continue;
-        if (t.kind == LOMO_TENSOR_EMBEDDING) {
-            EmbeddingWs w = carve_embedding_ws(ws, t.T, t.K);
-            ScopedTiming timing(LOMO_KERNEL_EMBEDDING, st);
-            if (launch_embedding_grouping(t.ids, t.T, t.N, w, st) != hipSuccess) return LOMO_ERR_LAUNCH;
-            if (launch_embedding_rows(t.ids, t.dY, t.W, t.T, t.K, w, 2, inv_loss_scale, nullptr, flags + i, nullptr, st, lr,
-                                      clip_value) != hipSuccess)
-                return LOMO_ERR_LAUNCH;
-        } else if (t.kind == LOMO_TENSOR_VECTOR) {
-            ScopedTiming timing(LOMO_KERNEL_VECTOR, st);
-            if (launch_vector(t.X, t.dY, t.W, t.T, t.K, ws, 2, inv_loss_scale, nullptr, flags + i, nullptr, st, lr,
-                              clip_value) != hipSuccess)
-                return LOMO_ERR_LAUNCH;
-        }
-    }
+    cs = run_row_kernels(tensors, n, ws, ws_bytes, 2, inv_loss_scale, nullptr, nullptr, flags, nullptr, lr, clip_value, false, st);
+    if (cs != LOMO_OK) return cs;
     return from_hip(launch_reduce_flags(flags, n, flags + n, st));
 }
 
@@ -531,6 +584,21 @@ lomo_status lomo_cross_entropy(const lomo_half* logits, const int32_t* targets, 
     return from_hip(launch_cross_entropy(logits, targets, grad_scale, loss, dlogits, T, V, st));
 }
 
+lomo_status lomo_cross_entropy_mean(const lomo_half* logits, const int32_t* targets, double loss_scale, float* loss,
+                                    lomo_half* dlogits, double* stats, int64_t T, int64_t V, void* stream) {
+    if (T < 0 || V < 0 || (V & 7) || T > 0x7fffffff || V > 0x7fffffff || !(loss_scale > 0.0)) return LOMO_ERR_SHAPE;
+    if (!stats) return LOMO_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(stats) & 7u) return LOMO_ERR_ALIGN;
+    if (T > 0 && V == 0) return LOMO_ERR_SHAPE;
+    if (T > 0 && (!logits || !targets || !loss || !dlogits)) return LOMO_ERR_NULL;
+    if (misaligned(logits) || misaligned(dlogits) || (reinterpret_cast<uintptr_t>(targets) & 3u) ||
+        (reinterpret_cast<uintptr_t>(loss) & 3u))
+        return LOMO_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ScopedTiming timing(LOMO_KERNEL_CHAIN, st);
+    return from_hip(launch_cross_entropy_mean(logits, targets, loss_scale, loss, dlogits, stats, T, V, st));
+}
+
 lomo_status lomo_attention_forward(const lomo_half* qkv, lomo_half* o, float* lse, int64_t B, int64_t s, int64_t n_heads,
                                    int64_t head_dim, void* stream) {
     if (B < 0 || s < 0 || n_heads <= 0 || head_dim != 128 || (s % 64) != 0) return LOMO_ERR_SHAPE;
@@ -584,13 +652,6 @@ lomo_status lomo_attention_backward(const lomo_half* qkv, const lomo_half* o, co
     ScopedTiming timing(LOMO_KERNEL_ATTENTION, st);
     return from_hip(launch_attention_backward(qkv, o, dO, lse, rope_cos, rope_sin, delta_ws, dqkv, B, s, n_heads, st));
 }
-
-lomo_status lomo_set_norm_algorithm(int algorithm) {
-    if (algorithm != LOMO_NORM_DIRECT && algorithm != LOMO_NORM_AUTO && algorithm != LOMO_NORM_GRAM) return LOMO_ERR_SHAPE;
-    set_norm_algorithm(algorithm);
-    return LOMO_OK;
-}
-int lomo_get_norm_algorithm(void) { return norm_algorithm(); }
 
 lomo_status lomo_reduce_flags(const int32_t* flags, int64_t n, int32_t* out, void* stream) {
     if (n < 0) return LOMO_ERR_SHAPE;

@@ -164,9 +164,7 @@ __global__ __launch_bounds__(256, 2) void attention_backward_kernel(attn::Args a
             sDelta[tid] = rd;
         }
         __syncthreads();
-#ifndef LOMO_ATTN_EXP_NO_FETCH     // timing experiment only: the loop re-uses the first moving tiles
         if (blk < last) fetch_moving(blk + 1);     // in flight while this block is multiplied
-#endif
 
         // ---- S^T = K Q^T and dP^T = V dO^T for this wave's 32 keys x 32 queries: the keys are the MFMA rows, so a
         // lane owns one query (one lse, one delta) and four consecutive keys per register group
@@ -204,13 +202,8 @@ __global__ __launch_bounds__(256, 2) void attention_backward_kernel(attn::Args a
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int r = 4 * q4 + e;
-#ifdef LOMO_ATTN_EXP_NO_SOFTMAX   // timing experiment only
-                    float p = accS[r];
-                    float ds = accP[r];
-#else
                     float p = __builtin_amdgcn_exp2f(fmaf(scale_log2e, accS[r], -lq));
                     float ds = scale * p * (accP[r] - dq);
-#endif
                     if (diag && key0 + e > qrow) {
                         p = 0.f;
                         ds = 0.f;
@@ -224,7 +217,6 @@ __global__ __launch_bounds__(256, 2) void attention_backward_kernel(attn::Args a
         }
         __syncthreads();
 
-#ifndef LOMO_ATTN_EXP_NO_ACCUM     // timing experiment only
         if (MODE == 0) {
             // dv^T[dcol][key] += dO^T P,  dk^T[dcol][key] += Q^T dS   (contraction over the 64 queries)
 #pragma unroll
@@ -254,7 +246,6 @@ __global__ __launch_bounds__(256, 2) void attention_backward_kernel(attn::Args a
                 }
             }
         }
-#endif
     }
 
     // ---- results: through LDS as fp32 so that the rotary pairs (c, c + 64) meet and stores are 16 bytes wide
@@ -320,16 +311,11 @@ hipError_t launch_attention_backward(const uint16_t* qkv, const uint16_t* o, con
                                      const float* cosv, const float* sinv, float* delta, uint16_t* dqkv, int64_t B, int64_t s,
                                      int64_t nh, hipStream_t st) {
     using namespace attn;
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attention_backward_kernel<0>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(attention_backward_kernel<1>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    // thread-safe one-time set-up (initialisation of a function-local static)
+    static const hipError_t cfg0 = allow_dynamic_lds(attention_backward_kernel<0>, LDS_BYTES);
+    if (cfg0 != hipSuccess) return cfg0;
+    static const hipError_t cfg1 = allow_dynamic_lds(attention_backward_kernel<1>, LDS_BYTES);
+    if (cfg1 != hipSuccess) return cfg1;
     const int64_t rows = B * s * nh;
     hipLaunchKernelGGL(attention_delta_kernel, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, o, dO, delta, rows);
     Args a;

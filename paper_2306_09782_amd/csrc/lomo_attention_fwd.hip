@@ -207,13 +207,9 @@ __global__ __launch_bounds__(256, 2) void attention_forward_kernel(attn::FwdArgs
 hipError_t launch_attention_forward(const uint16_t* qkv, uint16_t* o, float* lse, int64_t B, int64_t s, int64_t nh,
                                     hipStream_t st) {
     using namespace attn;
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attention_forward_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, FWD_LDS_BYTES);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    // thread-safe one-time set-up (initialisation of a function-local static)
+    static const hipError_t cfg0 = allow_dynamic_lds(attention_forward_kernel, FWD_LDS_BYTES);
+    if (cfg0 != hipSuccess) return cfg0;
     FwdArgs a;
     a.qkv = qkv; a.o = o; a.lse = lse;
     a.s = (int)s; a.nh = (int)nh; a.H = (int)(nh * D);

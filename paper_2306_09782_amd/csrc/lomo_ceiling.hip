@@ -1,0 +1,120 @@
+// Measured ceilings for the roofline denominators (benchmark aids, not part of the method): what the chip
+// sustains on its matrix cores when nothing else runs, and on a plain streaming copy.  The contraction
+// kernels' TFLOP/s are reported next to these, because the rate the matrix cores hold depends on the operand
+// data (power management): zeros and normally distributed values give very different figures.
+#include "lomo.h"
+#include "lomo_kernels.h"
+
+namespace lomo {
+
+typedef _Float16 probe_half8 __attribute__((ext_vector_type(8)));
+typedef float probe_floatx16 __attribute__((ext_vector_type(16)));
+
+// Every wave: 2 sets x (4 A + 4 B) fragments in registers, NI x NJ accumulators of 32 x 32; per iteration
+// 2 x NI x NJ MFMAs in the order of the contraction kernels' half-slices (A fragment outer, B fragment inner).
+// No LDS, no global memory inside the loop.  4 x 4 with one wave per SIMD is the contraction kernels' blocking
+// (256 accumulator registers); two waves per SIMD have 256 registers each, hence 4 x 2.
+template <int NI, int NJ, int THREADS>
+__global__ __launch_bounds__(THREADS) void probe_mfma_kernel(const uint16_t* __restrict__ operands, int64_t iters,
+                                                             float* __restrict__ sink) {
+    const int lane = threadIdx.x & 63;
+    probe_half8 a[2][4], b[2][4];
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            a[s][i] = *reinterpret_cast<const probe_half8*>(operands + ((s * 8 + i) * 64 + lane) * 8);
+            b[s][i] = *reinterpret_cast<const probe_half8*>(operands + ((s * 8 + 4 + i) * 64 + lane) * 8);
+        }
+    probe_floatx16 acc[NI][NJ];
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    for (int64_t it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[s][i], b[s][j], acc[i][j], 0, 0, 0);
+    }
+    float v = 0.f;
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) v += acc[i][j][r];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    if (lane == 0) atomicAdd(sink + blockIdx.x, v);
+}
+
+__global__ __launch_bounds__(256) void probe_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t n16) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {      // four independent 16-byte loads in flight per thread
+        const uint4 v0 = src[i], v1 = src[i + stride], v2 = src[i + 2 * stride], v3 = src[i + 3 * stride];
+        dst[i] = v0;
+        dst[i + stride] = v1;
+        dst[i + 2 * stride] = v2;
+        dst[i + 3 * stride] = v3;
+    }
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+static int probe_cu_count() {
+    static const int n = [] {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 256;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) return 256;
+        return v;
+    }();
+    return n;
+}
+
+}  // namespace lomo
+
+using namespace lomo;
+
+extern "C" {
+
+lomo_status lomo_probe_mfma(const lomo_half* operands, int64_t iters, int waves_per_simd, float* sink, int64_t sink_len,
+                            double* flops_out, void* stream) {
+    if (iters < 0 || (waves_per_simd != 1 && waves_per_simd != 2)) return LOMO_ERR_SHAPE;
+    if (!operands || !sink) return LOMO_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(operands) & 15u) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return LOMO_ERR_ALIGN;
+    const int cus = probe_cu_count();
+    if (sink_len < cus) return LOMO_ERR_WORKSPACE;
+    const int threads = 256 * waves_per_simd;
+    const double mfmas_per_iter = waves_per_simd == 1 ? 32.0 : 16.0;
+    if (flops_out) *flops_out = (double)cus * (threads / 64) * (double)iters * mfmas_per_iter * (2.0 * 32 * 32 * 16);
+    if (iters == 0) return LOMO_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const hipError_t e = waves_per_simd == 1
+        ? launch_timed(LOMO_KERNEL_PROBE, probe_mfma_kernel<4, 4, 256>, dim3((unsigned)cus), dim3(256), 0, st, operands, iters, sink)
+        : launch_timed(LOMO_KERNEL_PROBE, probe_mfma_kernel<4, 2, 512>, dim3((unsigned)cus), dim3(512), 0, st, operands, iters, sink);
+    return e == hipSuccess ? LOMO_OK : LOMO_ERR_LAUNCH;
+}
+
+lomo_status lomo_probe_copy(const void* src, void* dst, size_t bytes, void* stream) {
+    if (bytes & 15u) return LOMO_ERR_SHAPE;
+    if (bytes == 0) return LOMO_OK;
+    if (!src || !dst) return LOMO_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(src) & 15u) || (reinterpret_cast<uintptr_t>(dst) & 15u)) return LOMO_ERR_ALIGN;
+    const int64_t n16 = (int64_t)(bytes >> 4);
+    int64_t blocks = (n16 + 4 * 256 - 1) / (4 * 256);
+    const int64_t cap = (int64_t)probe_cu_count() * 16;
+    if (blocks > cap) blocks = cap;
+    return launch_timed(LOMO_KERNEL_PROBE, probe_copy_kernel, dim3((unsigned)blocks), dim3(256), 0,
+                        static_cast<hipStream_t>(stream), static_cast<const uint4*>(src), static_cast<uint4*>(dst), n16) ==
+                   hipSuccess
+               ? LOMO_OK
+               : LOMO_ERR_LAUNCH;
+}
+
+}  // extern "C"

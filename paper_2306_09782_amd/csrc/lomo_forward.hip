@@ -112,10 +112,12 @@ __global__ __launch_bounds__(FW_NT) void rope_forward_kernel(uint16_t* __restric
 }
 
 // One workgroup per token: max, sum of exponentials, then the scaled gradient.  z and dz may be the same buffer.
+// grad_scale_dev (when not null) holds the scale in device memory, written earlier on the stream.
 __global__ __launch_bounds__(FW_NT) void cross_entropy_kernel(const uint16_t* z, const int32_t* __restrict__ target,
-                                                              float grad_scale, float* __restrict__ loss, uint16_t* dz,
-                                                              int64_t V) {
+                                                              float grad_scale, const float* __restrict__ grad_scale_dev,
+                                                              float* __restrict__ loss, uint16_t* dz, int64_t V) {
     __shared__ float red[FW_NT / 64];
+    if (grad_scale_dev != nullptr) grad_scale = grad_scale_dev[0];
     const int64_t t = blockIdx.x;
     const uint16_t* row = z + t * V;
     const int tgt = target[t];
@@ -192,7 +194,52 @@ hipError_t launch_rope_forward(uint16_t* qkv, const float* cosv, const float* si
 
 hipError_t launch_cross_entropy(const uint16_t* z, const int32_t* target, float grad_scale, float* loss, uint16_t* dz, int64_t T,
                                 int64_t V, hipStream_t st) {
-    hipLaunchKernelGGL(cross_entropy_kernel, dim3((unsigned)T), dim3(FW_NT), 0, st, z, target, grad_scale, loss, dz, V);
+    hipLaunchKernelGGL(cross_entropy_kernel, dim3((unsigned)T), dim3(FW_NT), 0, st, z, target, grad_scale,
+                       static_cast<const float*>(nullptr), loss, dz, V);
+    return hipGetLastError();
+}
+
+// stats[1] = n = number of targets inside [0, V); stats[2] (as float) = (float)(loss_scale / n), 0 when n == 0.
+__global__ __launch_bounds__(FW_NT) void count_targets_kernel(const int32_t* __restrict__ target, int64_t T, int64_t V,
+                                                              double loss_scale, double* __restrict__ stats) {
+    __shared__ int red[FW_NT];
+    int c = 0;
+    for (int64_t t = threadIdx.x; t < T; t += FW_NT) c += (target[t] >= 0 && target[t] < V) ? 1 : 0;
+    red[threadIdx.x] = c;
+    __syncthreads();
+    for (int off = FW_NT / 2; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const int n = red[0];
+        stats[1] = (double)n;
+        *reinterpret_cast<float*>(stats + 2) = n > 0 ? (float)(loss_scale / (double)n) : 0.f;
+    }
+}
+
+// stats[0] = sum_t loss[t] / n in fp64: threads take strided shares in ascending order, then a fixed tree.
+__global__ __launch_bounds__(FW_NT) void mean_loss_kernel(const float* __restrict__ loss, int64_t T, double* __restrict__ stats) {
+    __shared__ double red[FW_NT];
+    double v = 0.0;
+    for (int64_t t = threadIdx.x; t < T; t += FW_NT) v += (double)loss[t];
+    red[threadIdx.x] = v;
+    __syncthreads();
+    for (int off = FW_NT / 2; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) stats[0] = stats[1] > 0.0 ? red[0] / stats[1] : 0.0;
+}
+
+// stats: device double[3]; [0] mean loss, [1] counted targets, [2] scratch (the gradient scale as a float).
+hipError_t launch_cross_entropy_mean(const uint16_t* z, const int32_t* target, double loss_scale, float* loss, uint16_t* dz,
+                                     double* stats, int64_t T, int64_t V, hipStream_t st) {
+    hipLaunchKernelGGL(count_targets_kernel, dim3(1), dim3(FW_NT), 0, st, target, T, V, loss_scale, stats);
+    if (T > 0)
+        hipLaunchKernelGGL(cross_entropy_kernel, dim3((unsigned)T), dim3(FW_NT), 0, st, z, target, 0.f,
+                           reinterpret_cast<const float*>(stats + 2), loss, dz, V);
+    hipLaunchKernelGGL(mean_loss_kernel, dim3(1), dim3(FW_NT), 0, st, loss, T, stats);
     return hipGetLastError();
 }
 

@@ -205,13 +205,9 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t st) {
     if (a.M <= 0 || a.Nn <= 0) return hipSuccess;
     constexpr size_t lds = 2u * (BM + BN) * LROW * sizeof(uint16_t);
     auto kern = lomo_contract_kernel<BM, BN, B_STRIDED, EPI, A_STRIDED>;
-    static bool configured = false;   // benign race: the attribute call is idempotent
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    // thread-safe one-time set-up (initialisation of a function-local static)
+    static const hipError_t cfg0 = allow_dynamic_lds(kern, (int)lds);
+    if (cfg0 != hipSuccess) return cfg0;
     const int64_t tiles = ((a.M + BM - 1) / BM) * ((a.Nn + BN - 1) / BN);
     if (tiles > 0x7fffffff) return hipErrorInvalidValue;
     return launch_timed(a.family, kern, dim3((unsigned)tiles), dim3(NT), lds, st, a);
@@ -255,11 +251,11 @@ hipError_t launch_wgrad_update_clipv(const GemmArgs& a, hipStream_t st) {
     return use_big_tiles(a.M, a.Nn) ? launch_one<256, 256, true, EPI_CLIPV>(a, st)
                                     : launch_one<128, 128, true, EPI_CLIPV>(a, st);
 }
-hipError_t launch_wgrad_sqnorm(const GemmArgs& a, hipStream_t st) {
+hipError_t launch_wgrad_sqnorm(const GemmArgs& a, int norm_route, hipStream_t st) {
     hipError_t e;
-    if (norm_algorithm() != LOMO_NORM_DIRECT && fast_enabled() && dma_enabled()) {
+    if (norm_route != LOMO_NORM_DIRECT && fast_enabled() && dma_enabled()) {
         std::vector<GemmArgs> one(1, a), gram, direct;
-        choose_norm_route(one, gram, direct);
+        choose_norm_route(norm_route, one, gram, direct);
         if (!gram.empty()) return launch_gram_group(gram.data(), 1, st);
     }
     if (fast_enabled() && dma_enabled() && try_launch_dma<true, EPI_SQNORM>(a, st, &e)) return e;

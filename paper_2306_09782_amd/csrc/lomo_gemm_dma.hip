@@ -215,11 +215,7 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga
     {
         const int x = (int)(blockIdx.x & 7), local = (int)(blockIdx.x >> 3);
         const int q = G >> 3, r = G & 7;
-#ifdef LOMO_EXP_PLAIN_ORDER   // timing experiment: tiles in launch order
-        pos = (int)blockIdx.x + 0 * (x + local + q + r);
-#else
         pos = x * q + (x < r ? x : r) + local;
-#endif
     }
 
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
@@ -295,9 +291,6 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga
 
     // One DMA instruction: part 0 = A tile, part 1 = B tile; `it` selects this wave's KiB slot.
     auto issue1 = [&](int stage, int buf, int part, int it) {
-#ifdef LOMO_EXP_NO_DMA   // timing experiment only: results are meaningless
-        return;
-#endif
         const int s = stage < KT ? stage : KT - 1;   // past the end: harmless re-read, keeps the counter regular
         const uint32_t l = lds_wave + (uint32_t)buf * (STAGE_HALVES * 2u) + (uint32_t)part * (A_HALVES * 2u) +
                            (uint32_t)it * 1024u;
@@ -319,10 +312,6 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga
 
     // ---- fragment reads, in the order the MFMAs consume them: a0, b0..b3, a1..a3
     auto read_a = [&](half8 (&a)[4], int buf, int kk, int i) {
-#ifdef LOMO_EXP_B128_READS   // timing experiment only: plain 16-byte reads, results are meaningless
-        a[i] = *reinterpret_cast<const half8*>(smem + buf * STAGE_HALVES + (lane & 31) * 32 + (lane >> 5) * 8 + kk * 16 + i * 1024);
-        return;
-#endif
         if constexpr (A_STRIDED) {
             const uint16_t* p = smem + buf * STAGE_HALVES + ((a_rd ^ (i << 5)) + kk * 16 * BM);
             a[i] = read_tr8(p, p + 4 * BM);
@@ -333,10 +322,6 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga
     auto read_b = [&](half8 (&b)[4], int buf, int kk, int j) {
         const uint16_t* bs = smem + buf * STAGE_HALVES + A_HALVES;
         if constexpr (B_STRIDED) {
-#ifdef LOMO_EXP_B128_READS
-            b[j] = *reinterpret_cast<const half8*>(bs + (lane & 31) * 32 + (lane >> 5) * 8 + kk * 16 + j * 1024);
-            return;
-#endif
             const uint16_t* p = bs + ((b_rd ^ (j << 5)) + kk * 16 * BN);
             b[j] = read_tr8(p, p + 4 * BN);
         } else {
@@ -346,9 +331,6 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga
     // Fragment groups.  EARLY packs the eight fragments into the first three groups, so that every
     // read has completed when the half-slice ends at a barrier.
     auto read_group = [&](half8 (&a)[4], half8 (&b)[4], int buf, int kk, int q, bool early) {
-#ifdef LOMO_EXP_NO_LDSREAD   // timing experiment only
-        if (buf >= 0) return;
-#endif
         if (early) {
             if (q == 0) { read_a(a, buf, kk, 0); read_b(b, buf, kk, 0); read_b(b, buf, kk, 1); }
             if (q == 1) { read_b(b, buf, kk, 2); read_b(b, buf, kk, 3); read_a(a, buf, kk, 1); }
@@ -385,7 +367,6 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 acc[q][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ua[q], ub[j], acc[q][j], 0, 0, 0);
-#ifndef LOMO_EXP_NO_LDSREAD
             {   // spread this group's reads in front of its four MFMAs
                 int left = early ? READS_EARLY[q] : READS_EVEN[q];
 #pragma unroll
@@ -398,7 +379,6 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga
                     left -= now;
                 }
             }
-#endif
             __builtin_amdgcn_sched_barrier(0);
             issue1(dstage, dbuf, dpart, q);
             __builtin_amdgcn_sched_barrier(0);
@@ -429,11 +409,7 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga
                 // first half of slice kt+u; reads its second half's fragments; loads the B part of slice kt+u+3
                 half_slice(fa0, fb0, fa1, fb1, u, 1, true, kt + u + 3, (u + 3) & 3, 1);
                 // own loads of slice kt+u+1 landed (two younger slices may still fly); own LDS reads done
-#ifdef LOMO_EXP_NO_BARRIER   // timing experiment only: waves drift apart, results are meaningless
-                asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
-#else
                 asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-#endif
                 __builtin_amdgcn_sched_barrier(0);
                 // second half; reads the first fragments of the next slice; loads the A part of slice
                 // kt+u+4 into the buffer of slice kt+u, which nobody reads any more
@@ -508,13 +484,9 @@ template <bool B_STRIDED, int EPI, bool A_STRIDED>
 static hipError_t launch_dma_group_impl(const GemmArgs* list, int n, hipStream_t st) {
     using namespace dma;
     auto kern = lomo_contract_dma_kernel<B_STRIDED, EPI, A_STRIDED>;
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    // thread-safe one-time set-up (initialisation of a function-local static)
+    static const hipError_t cfg0 = allow_dynamic_lds(kern, LDS_BYTES);
+    if (cfg0 != hipSuccess) return cfg0;
     for (int first = 0; first < n; first += MAX_GROUP) {
         const int cnt = (n - first < MAX_GROUP) ? (n - first) : MAX_GROUP;
         GroupArgs ga{};

@@ -193,13 +193,9 @@ template <int BM, int BN, bool B_STRIDED, int EPI>
 static hipError_t launch_fast_one(const GemmArgs& a, hipStream_t st) {
     constexpr size_t lds = 2u * FBK * (BM + BN) * sizeof(uint16_t);
     auto kern = lomo_contract_fast_kernel<BM, BN, B_STRIDED, EPI>;
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    // thread-safe one-time set-up (initialisation of a function-local static)
+    static const hipError_t cfg0 = allow_dynamic_lds(kern, (int)lds);
+    if (cfg0 != hipSuccess) return cfg0;
     const int tiles_m = (int)(a.M / BM), tiles_n = (int)(a.Nn / BN);
     return launch_timed(a.family, kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(NT), lds, st, a, tiles_m, tiles_n);
 }

@@ -351,12 +351,7 @@ double direct_cost(const GemmArgs& a) {
     return (double)((a.M + 255) / 256) * (double)((a.Nn + 255) / 256) * (double)a.C / 32.0;
 }
 
-static int g_norm_algorithm = LOMO_NORM_DIRECT;
-int norm_algorithm() { return g_norm_algorithm; }
-void set_norm_algorithm(int v) { g_norm_algorithm = v; }
-
-void choose_norm_route(const std::vector<GemmArgs>& all, std::vector<GemmArgs>& gram, std::vector<GemmArgs>& direct) {
-    const int mode = g_norm_algorithm;
+void choose_norm_route(int mode, const std::vector<GemmArgs>& all, std::vector<GemmArgs>& gram, std::vector<GemmArgs>& direct) {
     for (const GemmArgs& a : all) {
         const bool g = mode != LOMO_NORM_DIRECT && gram_eligible(a) && (mode == LOMO_NORM_GRAM || gram_cost(a) < direct_cost(a));
         (g ? gram : direct).push_back(a);
@@ -382,13 +377,9 @@ void choose_norm_route(const std::vector<GemmArgs>& all, std::vector<GemmArgs>& 
 hipError_t launch_gram_group(const GemmArgs* list, int n, hipStream_t st) {
     using namespace gram;
     auto kern = lomo_gram_sqnorm_kernel;
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    // thread-safe one-time set-up (initialisation of a function-local static)
+    static const hipError_t cfg0 = allow_dynamic_lds(kern, LDS_BYTES);
+    if (cfg0 != hipSuccess) return cfg0;
     // Longest tiles first: the static round-robin then ends on the short ones.
     std::vector<GemmArgs> order(list, list + n);
     std::stable_sort(order.begin(), order.end(),

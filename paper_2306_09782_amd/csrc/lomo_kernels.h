@@ -61,14 +61,12 @@ bool gram_eligible(const GemmArgs& a);
 double gram_cost(const GemmArgs& a);
 double direct_cost(const GemmArgs& a);
 hipError_t launch_gram_group(const GemmArgs* list, int n, hipStream_t st);
-int norm_algorithm();
-void set_norm_algorithm(int v);
-// Splits the eligible tensors of `all` between the two routes according to the current setting.
-void choose_norm_route(const std::vector<GemmArgs>& all, std::vector<GemmArgs>& gram, std::vector<GemmArgs>& direct);
+// Splits the eligible tensors of `all` between the two routes according to `mode` (LOMO_NORM_*).
+void choose_norm_route(int mode, const std::vector<GemmArgs>& all, std::vector<GemmArgs>& gram, std::vector<GemmArgs>& direct);
 
 hipError_t launch_wgrad_update(const GemmArgs& a, hipStream_t st);
 hipError_t launch_wgrad_update_clipv(const GemmArgs& a, hipStream_t st);
-hipError_t launch_wgrad_sqnorm(const GemmArgs& a, hipStream_t st);
+hipError_t launch_wgrad_sqnorm(const GemmArgs& a, int norm_route, hipStream_t st);
 hipError_t launch_dgrad(const GemmArgs& a, hipStream_t st);
 // A = W [M = N_out x C = K_in], B = X [Nn = T x C], Out = Y [T x N_out]; accumulate: Y <- rne16(Y + acc).
 hipError_t launch_forward(const GemmArgs& a, bool accumulate, hipStream_t st);
@@ -84,6 +82,7 @@ struct EmbeddingWs {          // carved out of the caller's workspace
     float* chunk_rows;        // [2 * ceil(T / 16)][H] fp32 partial sums of runs that cross chunk boundaries
 };
 size_t embedding_ws_bytes(int64_t T, int64_t H);
+size_t embedding_grouping_bytes(int64_t T);     // head of the workspace: what launch_embedding_grouping fills
 EmbeddingWs carve_embedding_ws(void* ws, int64_t T, int64_t H);
 hipError_t launch_embedding_grouping(const int32_t* ids, int64_t T, int64_t V, const EmbeddingWs& w, hipStream_t st);
 // mode 0: squared norm into acc (+ flag_out); mode 1: in-place row update honouring flag_in;
@@ -98,6 +97,25 @@ hipError_t launch_vector(const uint16_t* Xhat, const uint16_t* dY, uint16_t* w, 
                          void* ws, int mode, float s, double* acc, int32_t* flag_out, const int32_t* flag_in,
                          hipStream_t st, float lr = 0.f, float clipv = 0.f, const float* s_dev = nullptr);
 // mode 1 with s_dev: the step is read from device memory (written by launch_step_scalars earlier on the stream).
+
+// Gain vectors of one shape [T x H] in one launch per stage (kernel arguments carry the pointers).
+constexpr int VEC_BATCH = 64;
+struct VecItem {
+    const uint16_t* Xhat;
+    const uint16_t* dY;
+    uint16_t* w;            // null in mode 0
+    int32_t* flag_out;      // modes 0 and 2, may be null
+};
+struct VecBatch {
+    const uint16_t* Xh[VEC_BATCH];
+    const uint16_t* dY[VEC_BATCH];
+    uint16_t* w[VEC_BATCH];
+    int32_t* flag_out[VEC_BATCH];
+};
+// ws_bytes decides how many vectors share a launch: floor(ws_bytes / vector_ws_bytes(T, H)), at least 1 required.
+hipError_t launch_vector_batch(const VecItem* items, int n, int64_t T, int64_t H, void* ws, size_t ws_bytes, int mode,
+                               float s, double* acc, const int32_t* flag_in, hipStream_t st, float lr = 0.f,
+                               float clipv = 0.f, const float* s_dev = nullptr);
 
 // Device-side form of the host coefficient: reads the scaled squared norm and the step flag, writes
 // {clip, norm, step = lr * clip / S, overflow} to `out`.
@@ -119,6 +137,13 @@ struct ScopedTiming {
         if (on) timing_end(family, st);
     }
 };
+
+// Raises a kernel's dynamic-LDS limit; callers keep the result in a function-local static, whose initialisation is
+// thread-safe, so concurrent first launches make the runtime call once per kernel.
+template <typename Kern>
+inline hipError_t allow_dynamic_lds(Kern kern, int bytes) {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
 
 // Launch with the family's timing events attached when timing is on.
 template <typename Kern, typename... Args>
@@ -142,6 +167,8 @@ hipError_t launch_swiglu_forward(const uint16_t* gate_up, uint16_t* a, int64_t T
 hipError_t launch_rope_forward(uint16_t* qkv, const float* cosv, const float* sinv, int64_t T, int64_t s, int64_t nh, hipStream_t st);
 hipError_t launch_cross_entropy(const uint16_t* z, const int32_t* target, float grad_scale, float* loss, uint16_t* dz, int64_t T,
                                 int64_t V, hipStream_t st);
+hipError_t launch_cross_entropy_mean(const uint16_t* z, const int32_t* target, double loss_scale, float* loss, uint16_t* dz,
+                                     double* stats, int64_t T, int64_t V, hipStream_t st);
 hipError_t launch_embedding_forward(const int32_t* ids, const uint16_t* W, uint16_t* h, int64_t T, int64_t H, int64_t V,
                                     hipStream_t st);
 hipError_t launch_attention_forward(const uint16_t* qkv, uint16_t* o, float* lse, int64_t B, int64_t s, int64_t nh, hipStream_t st);

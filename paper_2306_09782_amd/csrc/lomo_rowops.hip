@@ -268,6 +268,13 @@ size_t embedding_ws_bytes(int64_t T, int64_t H) {
     return b;
 }
 
+// Bytes of the grouping part (keys, perm, unique ids, offsets, count): the head of the embedding workspace, which a
+// step keeps from its norm pass to its update pass.
+size_t embedding_grouping_bytes(int64_t T) {
+    if (T <= 0) return 0;
+    return align_up((size_t)next_pow2(T) * 8, 256) + align_up((size_t)T * 4, 256) * 2 + align_up((size_t)(T + 1) * 4, 256) + 256;
+}
+
 EmbeddingWs carve_embedding_ws(void* ws, int64_t T, int64_t H) {
     EmbeddingWs w;
     char* p = static_cast<char*>(ws);
@@ -381,7 +388,8 @@ __global__ __launch_bounds__(ROW_NT) void emb_chunk_kernel(const int32_t* __rest
                                                            const int32_t* __restrict__ perm, float s,
                                                            float* __restrict__ chunk_rows, double* __restrict__ partials,
                                                            int32_t* __restrict__ flag_out, const int32_t* __restrict__ flag_in,
-                                                           float lr, float clipv, const float* __restrict__ s_dev) {
+                                                           float lr, float clipv, const float* __restrict__ s_dev,
+                                                           int32_t* __restrict__ ticket) {
     if (MODE == 1 && flag_in != nullptr && flag_in[0] != 0) return;
     if (MODE == 1 && s_dev != nullptr) s = s_dev[0];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -444,6 +452,7 @@ __global__ __launch_bounds__(ROW_NT) void emb_chunk_kernel(const int32_t* __rest
         __shared__ float red[4];
         const float total = block_sum_256(sq, red);
         if (threadIdx.x == 0) partials[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = (double)total;
+        if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0) ticket[0] = 0;   // for the fix-up kernel that follows
     }
     if (MODE != 1 && flag_out != nullptr && __any(bad) && lane == 0) atomicOr(flag_out, 1);
 }
@@ -458,7 +467,8 @@ __global__ __launch_bounds__(EMB_NT) void emb_fixup_kernel(const float* __restri
                                                            const int32_t* __restrict__ n_unique, float s,
                                                            double* __restrict__ partials, int32_t* __restrict__ flag_out,
                                                            const int32_t* __restrict__ flag_in, float lr, float clipv,
-                                                           const float* __restrict__ s_dev) {
+                                                           const float* __restrict__ s_dev, int32_t* __restrict__ ticket,
+                                                           int n_shares_a, double* __restrict__ acc) {
     __shared__ float part[EMB_W - 1][64][9];
     if (MODE == 1 && flag_in != nullptr && flag_in[0] != 0) return;
     if (MODE == 1 && s_dev != nullptr) s = s_dev[0];
@@ -525,28 +535,36 @@ __global__ __launch_bounds__(EMB_NT) void emb_fixup_kernel(const float* __restri
         __syncthreads();
       }
     }
-    if (wave != 0) return;
+    if (MODE != 1 && wave == 0 && flag_out != nullptr && __any(bad) && lane == 0) atomicOr(flag_out, 1);
     if (MODE == 0) {
+        // This workgroup's share goes behind the n_shares_a shares of the chunk kernel.  The workgroup that arrives
+        // last adds all shares in index order (threads strided, then a fixed tree), so the embedding's squared norm
+        // does not depend on the order in which workgroups finish.
+        __shared__ int last_s;
+        __shared__ double dred[EMB_NT];
+        if (wave == 0) {
 #pragma unroll
-        for (int off = 32; off > 0; off >>= 1) sq += __shfl_xor(sq, off, 64);
-        if (lane == 0) partials[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = (double)sq;
-    }
-    if (MODE != 1 && flag_out != nullptr && __any(bad) && lane == 0) atomicOr(flag_out, 1);
-}
-
-// Adds the per-workgroup shares in index order: the embedding's squared norm is bit-reproducible.
-__global__ __launch_bounds__(ROW_NT) void emb_finish_sqnorm(const double* __restrict__ partials, int n,
-                                                            double* __restrict__ acc) {
-    __shared__ double red[ROW_NT];
-    double v = 0.0;
-    for (int i = threadIdx.x; i < n; i += ROW_NT) v += partials[i];
-    red[threadIdx.x] = v;
-    __syncthreads();
-    for (int off = ROW_NT / 2; off > 0; off >>= 1) {
-        if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+            for (int off = 32; off > 0; off >>= 1) sq += __shfl_xor(sq, off, 64);
+            if (lane == 0) {
+                partials[n_shares_a + (int64_t)blockIdx.y * gridDim.x + blockIdx.x] = (double)sq;
+                __threadfence();
+                last_s = atomicAdd(ticket, 1) == (int)(gridDim.x * gridDim.y) - 1;
+            }
+        }
         __syncthreads();
+        if (!last_s) return;
+        __threadfence();
+        const int n = n_shares_a + (int)(gridDim.x * gridDim.y);
+        double v = 0.0;
+        for (int i = threadIdx.x; i < n; i += EMB_NT) v += __hip_atomic_load(partials + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        dred[threadIdx.x] = v;
+        __syncthreads();
+        for (int off = EMB_NT / 2; off > 0; off >>= 1) {
+            if ((int)threadIdx.x < off) dred[threadIdx.x] += dred[threadIdx.x + off];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) atomicAdd(acc, dred[0]);
     }
-    if (threadIdx.x == 0) atomicAdd(acc, red[0]);
 }
 
 hipError_t launch_embedding_rows(const int32_t* ids, const uint16_t* dY, uint16_t* W, int64_t T, int64_t H,
@@ -555,16 +573,15 @@ hipError_t launch_embedding_rows(const int32_t* ids, const uint16_t* dY, uint16_
     const dim3 gridA((unsigned)emb_chunk_blocks(T), (unsigned)emb_slabs(H));
     const int64_t tripsB = (T + 63) / 64;
     const dim3 gridB((unsigned)(tripsB < EMB_FIX_GX ? tripsB : EMB_FIX_GX), (unsigned)emb_slabs(H));
-    double* partB = w.partials + (int64_t)gridA.x * gridA.y;
+    int32_t* ticket = w.n_unique + 1;     // the count's 256-byte slot has room for the arrival counter
+    const int sharesA = (int)(gridA.x * gridA.y);
 #define LOMO_EMB_LAUNCH(M)                                                                                              \
     hipLaunchKernelGGL(emb_chunk_kernel<M>, gridA, dim3(ROW_NT), 0, st, ids, dY, W, (int)T, H, w.perm, s, w.chunk_rows, \
-                       w.partials, flag_out, flag_in, lr, clipv, s_dev);                                                \
+                       w.partials, flag_out, flag_in, lr, clipv, s_dev, ticket);                                        \
     hipLaunchKernelGGL(emb_fixup_kernel<M>, gridB, dim3(EMB_NT), 0, st, w.chunk_rows, W, H, w.unique_ids, w.seg_offsets, \
-                       w.n_unique, s, partB, flag_out, flag_in, lr, clipv, s_dev);
+                       w.n_unique, s, w.partials, flag_out, flag_in, lr, clipv, s_dev, ticket, sharesA, acc);
     if (mode == 0) {
         LOMO_EMB_LAUNCH(0)
-        hipLaunchKernelGGL(emb_finish_sqnorm, dim3(1), dim3(ROW_NT), 0, st, w.partials,
-                           (int)(gridA.x * gridA.y + gridB.x * gridB.y), acc);
     } else if (mode == 1) {
         LOMO_EMB_LAUNCH(1)
     } else {
@@ -602,10 +619,13 @@ size_t vector_ws_bytes(int64_t T, int64_t H) {
 // takes eight consecutive rows and issues all sixteen loads before using any, so a CU keeps about
 // 256 KiB in flight; a wave adds its rows in ascending order, the eight waves are then added in a
 // fixed tree: the result depends on T and H only, not on scheduling.
-__global__ __launch_bounds__(VEC_NT) void vec_partial_kernel(const uint16_t* __restrict__ Xh,
-                                                             const uint16_t* __restrict__ dY, int64_t T, int64_t H,
+// blockIdx.z selects the gain vector of the batch; its partial sums follow those of the vectors before it.
+__global__ __launch_bounds__(VEC_NT) void vec_partial_kernel(VecBatch batch, int64_t T, int64_t H,
                                                              int splits, float* __restrict__ partial) {
     __shared__ float part[VEC_W - 1][64][9];
+    const uint16_t* __restrict__ Xh = batch.Xh[blockIdx.z];
+    const uint16_t* __restrict__ dY = batch.dY[blockIdx.z];
+    partial += (int64_t)blockIdx.z * splits * H;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t col = (int64_t)blockIdx.x * VEC_COLS + lane * 8;
     const bool active = col < H;
@@ -665,9 +685,8 @@ constexpr int FIN_COLS = 128;
 constexpr int FIN_GROUPS = ROW_NT / 32;
 
 template <int MODE>
-__global__ __launch_bounds__(ROW_NT) void vec_finish_kernel(const float* __restrict__ partial, int64_t H, int splits,
-                                                            uint16_t* __restrict__ w, float s, double* __restrict__ acc,
-                                                            int32_t* __restrict__ flag_out,
+__global__ __launch_bounds__(ROW_NT) void vec_finish_kernel(VecBatch batch, const float* __restrict__ partial, int64_t H,
+                                                            int splits, float s, double* __restrict__ acc,
                                                             const int32_t* __restrict__ flag_in, float lr, float clipv,
                                                             const float* __restrict__ s_dev) {
     __shared__ float4 part[FIN_GROUPS - 1][32];
@@ -675,6 +694,9 @@ __global__ __launch_bounds__(ROW_NT) void vec_finish_kernel(const float* __restr
     __shared__ int redflag[4];
     if (MODE == 1 && flag_in != nullptr && flag_in[0] != 0) return;
     if (MODE == 1 && s_dev != nullptr) s = s_dev[0];
+    uint16_t* __restrict__ w = batch.w[blockIdx.y];
+    int32_t* __restrict__ flag_out = batch.flag_out[blockIdx.y];
+    partial += (int64_t)blockIdx.y * splits * H;
     const int c4 = threadIdx.x & 31, grp = threadIdx.x >> 5;
     const int64_t j = (int64_t)blockIdx.x * FIN_COLS + c4 * 4;
     const bool active = j < H;                     // H is a multiple of 8: four whole columns or none
@@ -744,24 +766,48 @@ __global__ __launch_bounds__(ROW_NT) void vec_finish_kernel(const float* __restr
     }
 }
 
+// Vectors of one shape, as many per launch pair as the workspace holds partial sums for (at most VEC_BATCH).
+hipError_t launch_vector_batch(const VecItem* items, int n, int64_t T, int64_t H, void* ws, size_t ws_bytes, int mode,
+                               float s, double* acc, const int32_t* flag_in, hipStream_t st, float lr, float clipv,
+                               const float* s_dev) {
+    const int splits = vector_splits(T);
+    const size_t per = vector_ws_bytes(T, H);
+    int64_t cap = per > 0 ? (int64_t)(ws_bytes / per) : 0;
+    if (cap < 1) return hipErrorInvalidValue;
+    if (cap > VEC_BATCH) cap = VEC_BATCH;
+    float* partial = static_cast<float*>(ws);
+    for (int first = 0; first < n; first += (int)cap) {
+        const int cnt = (n - first < (int)cap) ? (n - first) : (int)cap;
+        VecBatch b{};
+        for (int i = 0; i < cnt; ++i) {
+            b.Xh[i] = items[first + i].Xhat;
+            b.dY[i] = items[first + i].dY;
+            b.w[i] = items[first + i].w;
+            b.flag_out[i] = items[first + i].flag_out;
+        }
+        hipLaunchKernelGGL(vec_partial_kernel, dim3((unsigned)((H + VEC_COLS - 1) / VEC_COLS), (unsigned)splits, (unsigned)cnt),
+                           dim3(VEC_NT), 0, st, b, T, H, splits, partial);
+        const dim3 grid((unsigned)((H + FIN_COLS - 1) / FIN_COLS), (unsigned)cnt);
+        if (mode == 0)
+            hipLaunchKernelGGL(vec_finish_kernel<0>, grid, dim3(ROW_NT), 0, st, b, partial, H, splits, s, acc, flag_in, lr,
+                               clipv, s_dev);
+        else if (mode == 1)
+            hipLaunchKernelGGL(vec_finish_kernel<1>, grid, dim3(ROW_NT), 0, st, b, partial, H, splits, s, acc, flag_in, lr,
+                               clipv, s_dev);
+        else
+            hipLaunchKernelGGL(vec_finish_kernel<2>, grid, dim3(ROW_NT), 0, st, b, partial, H, splits, s, acc, flag_in, lr,
+                               clipv, s_dev);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 hipError_t launch_vector(const uint16_t* Xhat, const uint16_t* dY, uint16_t* w, int64_t T, int64_t H, void* ws, int mode,
                          float s, double* acc, int32_t* flag_out, const int32_t* flag_in, hipStream_t st, float lr,
                          float clipv, const float* s_dev) {
-    const int splits = vector_splits(T);
-    float* partial = static_cast<float*>(ws);
-    hipLaunchKernelGGL(vec_partial_kernel, dim3((unsigned)((H + VEC_COLS - 1) / VEC_COLS), (unsigned)splits),
-                       dim3(VEC_NT), 0, st, Xhat, dY, T, H, splits, partial);
-    const dim3 grid((unsigned)((H + FIN_COLS - 1) / FIN_COLS));
-    if (mode == 0)
-        hipLaunchKernelGGL(vec_finish_kernel<0>, grid, dim3(ROW_NT), 0, st, partial, H, splits, w, s, acc, flag_out,
-                           flag_in, lr, clipv, s_dev);
-    else if (mode == 1)
-        hipLaunchKernelGGL(vec_finish_kernel<1>, grid, dim3(ROW_NT), 0, st, partial, H, splits, w, s, acc, flag_out,
-                           flag_in, lr, clipv, s_dev);
-    else
-        hipLaunchKernelGGL(vec_finish_kernel<2>, grid, dim3(ROW_NT), 0, st, partial, H, splits, w, s, acc, flag_out,
-                           flag_in, lr, clipv, s_dev);
-    return hipGetLastError();
+    const VecItem one{Xhat, dY, w, flag_out};
+    return launch_vector_batch(&one, 1, T, H, ws, vector_ws_bytes(T, H), mode, s, acc, flag_in, st, lr, clipv, s_dev);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -69,13 +69,24 @@ def test_shape_errors_are_reported_before_any_launch(lib):
     assert lib.lomo_embedding_update(P, P, P, 4, 12, 10, 0.1, 1.0, 1.0, P, P, 0, P) == 2
     assert lib.lomo_vector_update(P, P, P, 4, 8, 0.1, 1.0, 1.0, P, P, 0, P) == 1
     assert lib.lomo_vector_sqnorm(P, P, 0, 8, P, 0, P, P, P) == 1     # acc still required
-    assert lib.lomo_step_norm_pass(None, 3, P, P, P, 0, P) == 1          # descriptor list missing
-    assert lib.lomo_step_norm_pass(None, -1, P, P, P, 0, P) == 2
+    assert lib.lomo_step_norm_pass(None, 3, P, P, P, 0, None, P) == 1          # descriptor list missing
+    assert lib.lomo_step_norm_pass(None, -1, P, P, P, 0, None, P) == 2
     bad = (binding.LomoTensor * 1)()
     bad[0].kind, bad[0].T, bad[0].K, bad[0].N = 0, 4, 12, 8
-    assert lib.lomo_step_norm_pass(bad, 1, P, P, P, 0, P) == 2           # K not a multiple of 8
+    assert lib.lomo_step_norm_pass(bad, 1, P, P, P, 0, None, P) == 2           # K not a multiple of 8
     bad[0].kind = 7
-    assert lib.lomo_step_update_pass(bad, 1, 0.1, 1.0, 1.0, P, P, 0, P) == 2
+    assert lib.lomo_step_update_pass(bad, 1, 0.1, 1.0, 1.0, P, P, 0, None, P) == 2
+    import ctypes
+    opt = binding.LomoStepOptions(9, 0)
+    assert lib.lomo_step_norm_pass(None, 0, P, P, P, 0, ctypes.byref(opt), P) == 2      # unknown norm route
+    assert lib.lomo_wgrad_sqnorm_route(P, P, 4, 8, 8, P, P, 9, P) == 2
+    assert lib.lomo_probe_mfma(P, 1, 3, P, 0, None, P) == 2 and lib.lomo_probe_copy(P, P, 24, P) == 2
+    assert lib.lomo_cross_entropy_mean(P, P, 1.0, P, P, P, 4, 8, P) == 1                # stats missing
+    vec = (binding.LomoTensor * 2)()
+    for v in vec:
+        v.kind, v.T, v.K, v.N = 2, 4096, 4096, 1
+    one = lib.lomo_vector_workspace_bytes(4096, 4096)
+    assert lib.lomo_step_workspace_min_bytes(vec, 2) == one and lib.lomo_step_workspace_bytes(vec, 2) == 2 * one
     assert lib.lomo_step_workspace_bytes(bad, 0) == 0
     assert lib.lomo_embedding_workspace_bytes(0, 4096) == 0
     assert lib.lomo_embedding_workspace_bytes(4096, 4096) >= 4096 * 8 + 3 * 4096 * 4

@@ -31,9 +31,7 @@ def L():
 
 @pytest.fixture()
 def gram(L):
-    L.lomo_set_norm_algorithm("gram")
-    yield L
-    L.lomo_set_norm_algorithm("direct")
+    return L
 
 
 def dev(a):
@@ -51,10 +49,10 @@ def correlated(seed, T, C, sigma, role):
     return (base + noise).astype(np.float16)
 
 
-def device_sqnorm(L, X, dY):
+def device_sqnorm(L, X, dY, route="gram"):
     acc = torch.zeros(1, dtype=torch.float64, device=DEV)
     flag = torch.zeros(1, dtype=torch.int32, device=DEV)
-    L.lomo_wgrad_sqnorm(dev(X), dev(dY), acc, flag)
+    L.lomo_wgrad_sqnorm_route(dev(X), dev(dY), acc, flag, route)
     torch.cuda.synchronize()
     return float(acc.item()), int(flag.item())
 
@@ -84,8 +82,7 @@ def test_gram_norm_matches_oracle(gram, T, K, N, kind):
     assert abs(got / want - 1) < 1e-3, (got, want)
     assert abs(got / want - 1) < 2e-5, (got, want)       # what fp32 accumulation actually delivers
     # the direct route on the same bits
-    L.lomo_set_norm_algorithm("direct")
-    direct, _ = device_sqnorm(L, X, dY)
+    direct, _ = device_sqnorm(L, X, dY, "direct")
     assert abs(direct / want - 1) < 2e-5
     if kind == "correlated":
         # the diagonal pairs alone are a small part of the sum here: the triangle weights matter
@@ -144,31 +141,35 @@ def test_norm_pass_routes(L, mode):
         ts.append({"kind": "linear", "X": dev(X), "dY": dev(dY), "W": dev(W)})
         if i != 1:
             want += O.sqnorm(O.linear_grad(X, dY))
-    L.lomo_set_norm_algorithm(mode)
-    try:
-        stepper = LomoStep(DEV, max_T=512, max_H=4096, max_tensors=len(ts))
-        stepper.norm_pass(ts)
-        res = stepper.read_back(len(ts))
-        assert res["flags"] == [False, True, False, False, False] and res["overflow"] is True
-        ts[1]["dY"][511, 127] = 0.0
-        stepper.norm_pass(ts)
-        res = stepper.read_back(len(ts))
-        hX, hdY = ts[1]["X"].cpu().numpy(), ts[1]["dY"].cpu().numpy()
-        total = want + O.sqnorm(O.linear_grad(hX, hdY))
-        assert not any(res["flags"]) and res["overflow"] is False
-        assert abs(res["total_sqnorm"] / total - 1) < 2e-5
-    finally:
-        L.lomo_set_norm_algorithm("direct")
+    stepper = LomoStep(DEV, max_T=512, max_H=4096, max_tensors=len(ts), norm_algorithm=mode)
+    stepper.norm_pass(ts)
+    res = stepper.read_back(len(ts))
+    assert res["flags"] == [False, True, False, False, False] and res["overflow"] is True
+    ts[1]["dY"][511, 127] = 0.0
+    stepper.norm_pass(ts)
+    res = stepper.read_back(len(ts))
+    hX, hdY = ts[1]["X"].cpu().numpy(), ts[1]["dY"].cpu().numpy()
+    total = want + O.sqnorm(O.linear_grad(hX, hdY))
+    assert not any(res["flags"]) and res["overflow"] is False
+    assert abs(res["total_sqnorm"] / total - 1) < 2e-5
 
 
-def test_norm_algorithm_setting(L):
-    assert L.lomo_get_norm_algorithm() == L.NORM_ALGORITHMS["direct"]
-    for name, code in L.NORM_ALGORITHMS.items():
-        L.lomo_set_norm_algorithm(name)
-        assert L.lomo_get_norm_algorithm() == code
-    L.lomo_set_norm_algorithm("direct")
+def test_norm_route_is_an_argument(L):
+    """The route is chosen per call: the plain call stays on the direct kernels whatever an earlier call used, and
+    an unknown code is refused before anything is launched."""
+    L.lomo_timing_enable(True)
+    fam = L.KERNEL_FAMILIES.index("gram_sqnorm")
+    X, dY = gen(7, (512, 256), 1.0, 0), gen(8, (512, 384), 1.0, 1)
+    device_sqnorm(L, X, dY, "gram")
+    assert L.lomo_timing_read(fam)[1] == 1
+    acc = torch.zeros(1, dtype=torch.float64, device=DEV)
+    L.lomo_wgrad_sqnorm(dev(X), dev(dY), acc)
+    assert L.lomo_timing_read(fam)[1] == 1
+    L.lomo_timing_enable(False)
     with pytest.raises(L.LomoError):
-        L.lomo_set_norm_algorithm(7)
+        L.lomo_wgrad_sqnorm_route(dev(X), dev(dY), acc, None, 7)
+    with pytest.raises(L.LomoError):
+        L.lomo_step_norm_pass(L.make_tensor_list([]), acc, torch.zeros(1, dtype=torch.int32, device=DEV), None, None, 7)
 
 
 @pytest.mark.parametrize("K,N", [(8192, 8192), (8192, 22016), (22016, 8192)])
@@ -182,10 +183,9 @@ def test_gram_llama65b_tensor_shapes(gram, K, N):
     acc = torch.zeros(2, dtype=torch.float64, device=DEV)
     flag = torch.zeros(1, dtype=torch.int32, device=DEV)
     L.lomo_timing_enable(True)
-    L.lomo_wgrad_sqnorm(X, dY, acc[0:1], flag)
+    L.lomo_wgrad_sqnorm_route(X, dY, acc[0:1], flag, "gram")
     used = L.lomo_timing_read(L.KERNEL_FAMILIES.index("gram_sqnorm"))[1]
     L.lomo_timing_enable(False)
-    L.lomo_set_norm_algorithm("direct")
     L.lomo_wgrad_sqnorm(X, dY, acc[1:2], flag)
     torch.cuda.synchronize()
     want = O.sqnorm(O.linear_grad(X.cpu().numpy(), dY.cpu().numpy()))

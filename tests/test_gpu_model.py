@@ -280,3 +280,39 @@ def test_grouped_norm_chain_overflow_in_mid_walk(L):
             ulps_ok(got[name], want["params"][name], name, near=near)
         else:
             np.testing.assert_array_equal(got[name].view(np.uint16), old[name].view(np.uint16), err_msg=name)
+
+
+def test_model_step_on_a_stream_that_is_not_current(L):
+    """The chained step on a stream of its own, with the current stream kept busy and stale values in the
+    accumulator and the flags: bit-identical parameters, same norm, same flags as the step on the current stream
+    (which test_model_step_stage_by_stage holds against the oracle)."""
+    from paper_2306_09782_amd.chain import LomoModelChain
+    rng = np.random.default_rng(47)
+    B, s, nh, F, V, n_layers, scale = 1, 128, 1, 344, 256, 2, 1024.0
+    m, ids, dlogits, cos, sin, saved = setup(rng, B, s, nh, F, V, n_layers, scale)
+    lr = visible_lr(ids, dlogits, saved, m, cos, sin, s, nh, scale)
+    c1, d1 = run_model(B, s, nh, F, V, n_layers, m, ids, dlogits, cos, sin, saved, lr, scale, 1e30, share=True)
+    r1 = c1.result()
+    ref = A.model_step(ids, dlogits, saved, m, cos, sin, s, nh, lr, scale, max_norm=1e30)
+    assert abs(r1["norm"] / ref["norm"] - 1) < 1e-3 and r1["overflow"] is False
+
+    c2 = LomoModelChain(DEV, B, s, nh * 128, F, nh, n_layers, share_buffers=True)
+    d2 = to_dev_model(m)
+    c2.state.acc.fill_(1e30)
+    c2.state.flags.fill_(1)
+    args = (dev(ids), dev(dlogits), to_dev_model_saved(saved), d2, dev(cos), dev(sin))
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream(DEV)
+    busy = torch.randn(4096, 4096, device=DEV)
+    for _ in range(20):
+        busy = busy @ busy * 1e-3
+    c2.step(*args, lr, scale, 1e30, 1e-6, side)
+    side.synchronize()
+    r2 = c2.result()
+    torch.cuda.synchronize()
+    same = lambda a, b: torch.equal(a.view(torch.int16), b.view(torch.int16))
+    assert r2["overflow"] is False and r2["flags"] == r1["flags"] and abs(r2["norm"] / r1["norm"] - 1) < 1e-12
+    assert same(d1["W_emb"], d2["W_emb"]) and same(d1["W_lm"], d2["W_lm"]) and same(d1["w_f"], d2["w_f"])
+    for p1, p2 in zip(d1["layers"], d2["layers"]):
+        for k in p1:
+            assert same(p1[k], p2[k]), k

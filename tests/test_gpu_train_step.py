@@ -139,7 +139,7 @@ def test_memory_policies_do_not_change_a_bit(L, norm, kw):
     for extra in (dict(), kw):
         step = LomoFineTuneStep(DEV, B, s, nh * 128, F, nh, n_layers, V, norm=norm, **extra)
         dm = to_dev_model(m)
-        step.step(dev(ids), dev(targets), n_counted, dm, dev(cos), dev(sin), 0.05, scale, 1e30)
+        step.step(dev(ids), dev(targets), dm, dev(cos), dev(sin), 0.05, scale, 1e30)
         torch.cuda.synchronize()
         out.append((dm, step.result()))
     (d1, r1), (d2, r2) = out
@@ -165,7 +165,7 @@ def test_checkpointed_step_equals_kept_activation_step_bit_for_bit(L, norm, per)
                                                        1e30, per if norm == "grouped" else 0)
     step = LomoFineTuneStep(DEV, B, s, nh * 128, F, nh, n_layers, V, norm=norm, layers_per_group=per)
     dm = to_dev_model(m)
-    step.step(dev(ids), dev(targets), n_counted, dm, dev(cos), dev(sin), lr, scale, 1e30)
+    step.step(dev(ids), dev(targets), dm, dev(cos), dev(sin), lr, scale, 1e30)
     torch.cuda.synchronize()
     res = step.result()
     assert res["overflow"] is False and abs(res["loss"] - ref_loss.astype(np.float64).sum() / n_counted) < 1e-9
@@ -200,7 +200,7 @@ def test_training_step_from_token_ids_against_the_oracle(L, norm, shape):
     want = stepper(ids, ce["dlogits_f16"], saved, m, cos, sin, s, nh, lr, scale, max_norm=max_norm)
     step = LomoFineTuneStep(DEV, B, s, nh * 128, F, nh, n_layers, V, norm=norm)
     dm = to_dev_model(m)
-    step.step(dev(ids), dev(targets), n_counted, dm, dev(cos), dev(sin), lr, scale, max_norm)
+    step.step(dev(ids), dev(targets), dm, dev(cos), dev(sin), lr, scale, max_norm)
     torch.cuda.synchronize()
     res = step.result()
     assert res["overflow"] is False and res["flags"] == want["flags"]
@@ -245,7 +245,7 @@ def test_training_run_with_the_dynamic_scaler_follows_the_oracle(L, norm):
     for k, want in enumerate(log):
         if want["overflow"]:
             before = {name: t.clone() for name, t in dm["layers"][0].items()}
-        res = trainer.train_step(dids, dt, n, dm, dcos, dsin)
+        res = trainer.train_step(dids, dt, dm, dcos, dsin)
         assert res["overflow"] is want["overflow"] and res["loss_scale"] == want["loss_scale"], k
         assert abs(res["loss"] / want["loss"] - 1) < 2e-3, (k, res["loss"], want["loss"])
         if want["overflow"]:      # dropped (the loss gradient itself overflowed, so the first group already): nothing moved

@@ -152,3 +152,46 @@ def test_device_coefficient_step_matches_oracle(L, name):
     assert res["overflow"] is True and res["clip_coef"] == 0.0 and res["step"] == 0.0
     for g, b in zip(gpu, before):
         assert torch.equal(g["W"].view(torch.int16), b.view(torch.int16))
+
+
+@pytest.mark.parametrize("mode", ["host_coefficient", "device_coefficient"])
+def test_step_on_a_stream_that_is_not_current(L, mode):
+    """Every part of the step -- zeroing the accumulator and the flags, the kernels, the read-back -- goes to the
+    stream that is passed in.  The current stream is kept busy meanwhile and the accumulator starts dirty, so a
+    fill or a read-back that went to the current stream would come too late (wrong norm) or too early."""
+    from paper_2306_09782_amd.step import LomoStep
+    T, V, H, N = 320, 700, 264, 392
+    Sc = 1024.0
+    mk = lambda i, shape, sig, sc=1.0: S.normal_f16_np(S.tensor_key(3, 0, i, 0), shape, S.normal_mult(sig, sc))
+    cpu = [
+        dict(kind="linear", X=mk(0, (T, H), 1.0), dY=mk(1, (T, N), 0.01, Sc), W=mk(2, (N, H), 0.02)),
+        dict(kind="vector", X=mk(3, (T, H), 1.0), dY=mk(4, (T, H), 0.01, Sc), W=np.ones(H, np.float16)),
+        dict(kind="embedding", ids=S.zipf_ids(3, T, V), dY=mk(5, (T, H), 0.01, Sc), W=mk(6, (V, H), 0.02)),
+    ]
+    gpu = [{k: (torch.from_numpy(v).to(DEV) if isinstance(v, np.ndarray) else v) for k, v in t.items()} for t in cpu]
+    gpu[0]["dX"] = torch.empty(T, H, dtype=torch.float16, device=DEV)
+    ref = O.step_materialised(cpu, 4.0, Sc)
+    stepper = LomoStep(DEV, max_T=T, max_H=H)
+    stepper.acc.fill_(1e30)                       # stale contents from "a previous step"
+    stepper.flags.fill_(1)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream(DEV)                 # default priority
+    busy_a = torch.randn(4096, 4096, device=DEV)
+    for _ in range(20):                           # tens of milliseconds of work queued on the current stream
+        busy_a = busy_a @ busy_a * 1e-3
+    if mode == "host_coefficient":
+        res = stepper.run(gpu, 4.0, Sc, stream=side)
+    else:
+        stepper.run_async(gpu, 4.0, Sc, stream=side)
+        side.synchronize()
+        res = stepper.result()
+        res["flags"] = stepper.read_back(len(gpu), side)["flags"]
+    side.synchronize()
+    assert res["overflow"] is False and res["flags"] == ref["flags"]
+    assert abs(res["norm"] / ref["norm"] - 1) < 1e-5
+    for g, t, w in zip(gpu, cpu, ref["W"]):
+        got = g["W"].cpu().numpy()
+        _check_ulps(got, w, t["kind"])
+        assert (got.view(np.uint16) != t["W"].view(np.uint16)).any()
+    _check_dx(gpu[0]["dX"].cpu().numpy(), cpu[0]["dY"], cpu[0]["W"], "dX")
+    torch.cuda.synchronize()
