@@ -19,7 +19,8 @@
  *     dY carries the loss scale; inv_loss_scale = 1 / loss_scale removes it.
  *   - the caller owns every buffer; the library allocates no device memory and keeps no state that
  *     changes a result between calls (what it does keep: the event pool of lomo_timing_*, one-time
- *     kernel attributes).  Every choice that changes how a result is computed is an argument.  Calls
+ *     kernel attributes, and the fixed scratch array of lomo_vector_update_static, described with
+ *     that call).  Every choice that changes how a result is computed is an argument.  Calls
  *     launch on `stream` (a hipStream_t, NULL = default stream) and never synchronise.  `acc` and
  *     `overflow_flag` are zeroed by the caller before pass 1.
  *   - pointers must be 16-byte aligned; K, N and H must be multiples of 8; T >= 0 is free.
@@ -46,7 +47,8 @@ typedef enum {
     LOMO_ERR_SHAPE = 2,      /* negative size, or K/N/H not a multiple of 8      */
     LOMO_ERR_ALIGN = 3,      /* a pointer is not 16-byte aligned                 */
     LOMO_ERR_WORKSPACE = 4,  /* workspace NULL or smaller than *_workspace_bytes */
-    LOMO_ERR_LAUNCH = 5      /* the HIP runtime refused a launch                 */
+    LOMO_ERR_LAUNCH = 5,     /* the HIP runtime refused a launch                 */
+    LOMO_ERR_TOO_LARGE = 6   /* beyond the fixed scratch of lomo_vector_update_static */
 } lomo_status;
 
 typedef uint16_t lomo_half;
@@ -150,6 +152,21 @@ lomo_status lomo_vector_update(const lomo_half* Xhat, const lomo_half* dY, lomo_
                                float lr, float inv_loss_scale, float clip_coef,
                                const int32_t* overflow_flag,
                                void* ws, size_t ws_bytes, void* stream);
+
+/* lomo_vector_update for callers that cannot allocate device memory or carry a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arithmetic, same kernels, same result bit
+ * for bit; the partial column sums go to a fixed array of LOMO_VECTOR_STATIC_BYTES (4 MiB) of device memory inside
+ * the library instead of a caller workspace.  Each GPU the library runs on holds that array until the process ends.
+ * The call allocates nothing (no hipMalloc / hipFree, no event, no stream), records no timing, and returns
+ * LOMO_ERR_TOO_LARGE when lomo_vector_workspace_bytes(T, H) exceeds the array (H up to 8192 fits for any T).
+ * Every call on one GPU uses the same array: calls that overlap in time on one GPU (different streams, different
+ * threads) race with each other; calls on one stream are ordered and safe.  Nothing in the array has to start at
+ * zero (every partial sum is written before it is read). */
+#define LOMO_VECTOR_STATIC_BYTES (4u << 20)
+lomo_status lomo_vector_update_static(const lomo_half* Xhat, const lomo_half* dY, lomo_half* w,
+                                      int64_t T, int64_t H,
+                                      float lr, float inv_loss_scale, float clip_coef,
+                                      const int32_t* overflow_flag, void* stream);
 
 /* ---------------------------------------------------------------- whole passes over a list of tensors
  *

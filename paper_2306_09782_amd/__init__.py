@@ -16,7 +16,7 @@ from .binding import (LomoError, library_path, load_library, lomo_version, lomo_
                       lomo_linear_dgrad, lomo_swiglu_backward, lomo_rmsnorm_backward, lomo_attention_backward,
                       lomo_linear_forward, lomo_rmsnorm_forward, lomo_swiglu_forward, lomo_rope_forward,
                       lomo_attention_forward, lomo_cross_entropy, lomo_embedding_forward, lomo_linear_forward_residual,
-                      lomo_cross_entropy_mean, lomo_probe_mfma, lomo_probe_copy, PROBE_OPERAND_BYTES, on_stream,
+                      lomo_cross_entropy_mean, lomo_vector_update_static, VECTOR_STATIC_BYTES, lomo_probe_mfma, lomo_probe_copy, PROBE_OPERAND_BYTES, on_stream,
                       EXPORTED_SYMBOLS)
 
 __all__ = [n for n in dir() if n.startswith("lomo_")] + ["LomoError", "library_path", "load_library",

@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = (
     "lomo_linear_dgrad", "lomo_swiglu_backward", "lomo_rmsnorm_backward", "lomo_attention_backward",
     "lomo_linear_forward", "lomo_rmsnorm_forward", "lomo_swiglu_forward", "lomo_rope_forward", "lomo_attention_forward",
     "lomo_cross_entropy", "lomo_embedding_forward", "lomo_linear_forward_residual", "lomo_cross_entropy_mean",
-    "lomo_probe_mfma", "lomo_probe_copy",
+    "lomo_probe_mfma", "lomo_probe_copy", "lomo_vector_update_static",
 )
 
 
@@ -74,6 +74,7 @@ def load_library():
         "lomo_linear_backward_update": (c_int, [P, P, P, P, I64, I64, I64, c_float, c_float, c_float, P, P]),
         "lomo_embedding_update": (c_int, [P, P, P, I64, I64, I64, c_float, c_float, c_float, P, P, c_size_t, P]),
         "lomo_vector_update": (c_int, [P, P, P, I64, I64, c_float, c_float, c_float, P, P, c_size_t, P]),
+        "lomo_vector_update_static": (c_int, [P, P, P, I64, I64, c_float, c_float, c_float, P, P]),
         "lomo_embedding_workspace_bytes": (c_size_t, [I64, I64]),
         "lomo_vector_workspace_bytes": (c_size_t, [I64, I64]),
         "lomo_embedding_grouping": (c_int, [P, I64, I64, P, c_size_t, P, P, P, P, P]),
@@ -218,6 +219,17 @@ def lomo_vector_update(Xhat, dY, w, lr, inv_loss_scale, clip_coef, ws, overflow_
     assert w.numel() == H
     _check(load_library().lomo_vector_update(_ptr(Xhat), _ptr(dY), _ptr(w), T, H, lr, inv_loss_scale, clip_coef,
                                              _ptr(overflow_flag), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+VECTOR_STATIC_BYTES = 4 << 20
+
+
+def lomo_vector_update_static(Xhat, dY, w, lr, inv_loss_scale, clip_coef, overflow_flag=None, stream=None):
+    """lomo_vector_update without a workspace argument: the library's fixed scratch array takes its place."""
+    T, H = dY.shape
+    assert w.numel() == H
+    _check(load_library().lomo_vector_update_static(_ptr(Xhat), _ptr(dY), _ptr(w), T, H, lr, inv_loss_scale, clip_coef,
+                                                    _ptr(overflow_flag), _stream(stream)))
 
 
 def lomo_embedding_workspace_bytes(T: int, H: int) -> int:

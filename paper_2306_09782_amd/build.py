@@ -22,7 +22,7 @@ LIB_PATH = os.path.join(LIB_DIR, "liblomo.so")
 OBJ_DIR = os.path.join(ROOT, "_build", "lomo")
 SOURCES = ["lomo_api.hip", "lomo_gemm.hip", "lomo_gemm_fast.hip", "lomo_gemm_dma.hip", "lomo_gram.hip", "lomo_chain.hip",
            "lomo_attention.hip", "lomo_attention_fwd.hip", "lomo_forward.hip", "lomo_rowops.hip", "lomo_timing.hip",
-           "lomo_ceiling.hip"]
+           "lomo_ceiling.hip", "lomo_static.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # Packed fp32 VALU arithmetic is kept off on the test machines.  -Xclang reaches both passes of a HIP

@@ -31,6 +31,7 @@ const char* lomo_status_str(lomo_status s) {
         case LOMO_ERR_ALIGN: return "pointer not 16-byte aligned";
         case LOMO_ERR_WORKSPACE: return "workspace missing or too small";
         case LOMO_ERR_LAUNCH: return "HIP launch failed";
+        case LOMO_ERR_TOO_LARGE: return "size beyond the fixed scratch of the allocation-free entry point";
     }
     return "unknown status";
 }
