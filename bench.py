@@ -288,20 +288,29 @@ def measured_ceilings(L, torch, np, S, dev):
     ops = {"zeros": torch.zeros(L.PROBE_OPERAND_BYTES // 2, dtype=torch.float16, device=dev),
            "normal": S.normal_f16_torch(S.tensor_key(0, 90, 0, 0), (L.PROBE_OPERAND_BYTES // 2,), S.normal_mult(1.0), dev)}
     fam = L.KERNEL_FAMILIES.index("probe")
+
+    def rate(buf, waves, idle=0, lds=False, iters=20000):
+        for _ in range(2):
+            L.lomo_probe_mfma(buf, iters, waves, sink, idle, lds)          # warm: clocks and power settle under load
+        torch.cuda.synchronize()
+        L.lomo_timing_enable(True)
+        flops = 0.0
+        for _ in range(3):
+            flops += L.lomo_probe_mfma(buf, iters, waves, sink, idle, lds)
+        torch.cuda.synchronize()
+        ms, _n = L.lomo_timing_read(fam)
+        L.lomo_timing_enable(False)
+        return flops / (ms * 1e-3) / 1e12
+
     for waves in (1, 2):
         for kind, buf in ops.items():
-            iters = 20000
-            for _ in range(2):
-                L.lomo_probe_mfma(buf, iters, waves, sink)          # warm: clocks and power settle under load
-            torch.cuda.synchronize()
-            L.lomo_timing_enable(True)
-            flops = 0.0
-            for _ in range(3):
-                flops += L.lomo_probe_mfma(buf, iters, waves, sink)
-            torch.cuda.synchronize()
-            ms, n = L.lomo_timing_read(fam)
-            L.lomo_timing_enable(False)
-            out[f"mfma_only_{kind}_{waves}wave_per_simd_tflops"] = flops / (ms * 1e-3) / 1e12
+            out[f"mfma_only_{kind}_{waves}wave_per_simd_tflops"] = rate(buf, waves)
+    # duty cycle below one (one wave per SIMD; an iteration is 32 MFMAs = 1024 clocks, a sleep 64): if the rate were set
+    # by a fixed clock these would be 0.76 and 0.50 of the figure above; power management pays idle time back
+    for kind, buf in ops.items():
+        out[f"mfma_only_{kind}_duty76_tflops"] = rate(buf, 1, idle=5)
+        out[f"mfma_only_{kind}_duty50_tflops"] = rate(buf, 1, idle=16)
+        out[f"mfma_with_lds_reads_{kind}_tflops"] = rate(buf, 1, lds=True)
     n = 1 << 30
     src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(3)
     dst = torch.empty(n, dtype=torch.uint8, device=dev)

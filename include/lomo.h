@@ -403,12 +403,15 @@ lomo_status lomo_timing_read(int family, double* total_ms, int64_t* launches);
  * LOMO_PROBE_OPERAND_BYTES bytes: all zeros, or N(0,1) values, or anything else the caller wants to measure with)
  * and then issues iters x 32 v_mfma_f32_32x32x16_f16 in the 4 x 4 register blocking of the contraction kernels
  * (iters x 16 in a 4 x 2 blocking with two waves per SIMD, which have half the registers each), alternating
- * between two operand sets.  The accumulators are summed into sink[workgroup] (device float[n_cu]) so
- * the work cannot be dropped.  flops_out (host, may be NULL) receives the flop count of the launch.  Timed as
- * family LOMO_KERNEL_PROBE when timing is on. */
+ * between two operand sets.  idle_sleeps (0 .. 4096): each wave sleeps that many times 64 clocks after every
+ * iteration, which lowers the duty cycle of the matrix pipes (is the sustained rate set by power, so that idle time is
+ * paid back by a higher clock, or by a fixed clock?).  lds_reads != 0: each operand set is re-read from LDS before
+ * use (the contraction kernels' LDS read traffic per MFMA, no global loads).  The accumulators are summed into
+ * sink[workgroup] (device float[n_cu]) so the work cannot be dropped.  flops_out (host, may be NULL) receives the flop
+ * count of the launch.  Timed as family LOMO_KERNEL_PROBE when timing is on. */
 #define LOMO_PROBE_OPERAND_BYTES (16 * 64 * 16)
-lomo_status lomo_probe_mfma(const lomo_half* operands, int64_t iters, int waves_per_simd, float* sink, int64_t sink_len,
-                            double* flops_out, void* stream);
+lomo_status lomo_probe_mfma(const lomo_half* operands, int64_t iters, int waves_per_simd, int idle_sleeps, int lds_reads,
+                            float* sink, int64_t sink_len, double* flops_out, void* stream);
 
 /* dst[0 .. bytes) = src[0 .. bytes) with 16-byte loads and stores, grid-stride (bytes % 16 == 0, 16-byte aligned
  * pointers): 2 x bytes of HBM traffic.  Timed as family LOMO_KERNEL_PROBE when timing is on. */

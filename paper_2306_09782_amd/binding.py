@@ -101,7 +101,7 @@ def load_library():
         "lomo_embedding_forward": (c_int, [P, P, P, I64, I64, I64, P]),
         "lomo_linear_forward_residual": (c_int, [P, P, P, P, I64, I64, I64, P]),
         "lomo_cross_entropy_mean": (c_int, [P, P, c_double, P, P, P, I64, I64, P]),
-        "lomo_probe_mfma": (c_int, [P, I64, c_int, P, I64, POINTER(c_double), P]),
+        "lomo_probe_mfma": (c_int, [P, I64, c_int, c_int, c_int, P, I64, POINTER(c_double), P]),
         "lomo_probe_copy": (c_int, [P, P, c_size_t, P]),
         "lomo_timing_enable": (c_int, [c_int]),
         "lomo_timing_read": (c_int, [c_int, POINTER(c_double), POINTER(c_int64)]),
@@ -377,12 +377,12 @@ def lomo_cross_entropy_mean(logits, targets, loss_scale, loss, dlogits, stats, s
 PROBE_OPERAND_BYTES = 16 * 64 * 16
 
 
-def lomo_probe_mfma(operands, iters, waves_per_simd, sink, stream=None) -> float:
+def lomo_probe_mfma(operands, iters, waves_per_simd, sink, idle_sleeps=0, lds_reads=False, stream=None) -> float:
     """Launches the matrix-core loop; returns the flop count of the launch."""
     assert _nbytes(operands) >= PROBE_OPERAND_BYTES
     flops = c_double(0.0)
-    _check(load_library().lomo_probe_mfma(_ptr(operands), iters, waves_per_simd, _ptr(sink), sink.numel(),
-                                          ctypes.byref(flops), _stream(stream)))
+    _check(load_library().lomo_probe_mfma(_ptr(operands), iters, waves_per_simd, idle_sleeps, 1 if lds_reads else 0,
+                                          _ptr(sink), sink.numel(), ctypes.byref(flops), _stream(stream)))
     return flops.value
 
 

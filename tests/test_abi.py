@@ -80,7 +80,7 @@ def test_shape_errors_are_reported_before_any_launch(lib):
     opt = binding.LomoStepOptions(9, 0)
     assert lib.lomo_step_norm_pass(None, 0, P, P, P, 0, ctypes.byref(opt), P) == 2      # unknown norm route
     assert lib.lomo_wgrad_sqnorm_route(P, P, 4, 8, 8, P, P, 9, P) == 2
-    assert lib.lomo_probe_mfma(P, 1, 3, P, 0, None, P) == 2 and lib.lomo_probe_copy(P, P, 24, P) == 2
+    assert lib.lomo_probe_mfma(P, 1, 3, 0, 0, P, 0, None, P) == 2 and lib.lomo_probe_copy(P, P, 24, P) == 2
     assert lib.lomo_cross_entropy_mean(P, P, 1.0, P, P, P, 4, 8, P) == 1                # stats missing
     vec = (binding.LomoTensor * 2)()
     for v in vec:
