@@ -248,8 +248,9 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga
     int KT = 0;
 
     // Locate tile number w of the concatenated list; set up the load state; return its coordinates.
+    // A workgroup's tile numbers only grow, so the search for the tile's tensor resumes at the previous tile's.
     auto setup = [&](int w, int& tensor, int64_t& m0, int64_t& n0) {
-        int k = 0;
+        int k = tensor;
         while (k + 1 < ga.n && w >= ga.t[k + 1].tile_begin) ++k;
         const GroupTensor& T = ga.t[k];
         const int t = w - T.tile_begin;
@@ -388,7 +389,7 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga
     // ---- walk the tile list: tile w = round * G + pos; every workgroup leaves through `break`
     int w = pos;
     if (w >= ga.total_tiles) return;   // cannot happen with grid <= total_tiles; nothing was issued yet
-    int tensor;
+    int tensor = 0;
     int64_t m0, n0;
     setup(w, tensor, m0, n0);
     issue_prologue();

@@ -349,9 +349,10 @@ __device__ __forceinline__ float block_sum_256(float v, float* red) {
 
 // What happens to a finished segment sum g (8 columns of this lane): MODE 0 squared norm + overflow test,
 // MODE 1 row update W <- rne16(W - s g), MODE 2 clip-by-value update (s = 1 / loss scale).
+// `w`: the row's old 8 columns, loaded by the caller (update modes).
 template <int MODE>
 __device__ __forceinline__ void emb_finish_row(const float (&g)[8], uint16_t* __restrict__ W, int64_t row_off, bool active,
-                                               float s, float lr, float clipv, float& sq, bool& bad) {
+                                               float s, float lr, float clipv, float& sq, bool& bad, const half8& w) {
     if (MODE == 0) {
         uint32_t worst = 0u;
 #pragma unroll
@@ -363,7 +364,6 @@ __device__ __forceinline__ void emb_finish_row(const float (&g)[8], uint16_t* __
         bad |= worst >= 0x7f800000u;
     } else if (active) {
         half8* p = reinterpret_cast<half8*>(W + row_off);
-        const half8 w = *p;
         half8 o;
         if (MODE == 1) {
 #pragma unroll
@@ -388,8 +388,7 @@ __global__ __launch_bounds__(ROW_NT) void emb_chunk_kernel(const int32_t* __rest
                                                            const int32_t* __restrict__ perm, float s,
                                                            float* __restrict__ chunk_rows, double* __restrict__ partials,
                                                            int32_t* __restrict__ flag_out, const int32_t* __restrict__ flag_in,
-                                                           float lr, float clipv, const float* __restrict__ s_dev,
-                                                           int32_t* __restrict__ ticket) {
+                                                           float lr, float clipv, const float* __restrict__ s_dev) {
     if (MODE == 1 && flag_in != nullptr && flag_in[0] != 0) return;
     if (MODE == 1 && s_dev != nullptr) s = s_dev[0];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -411,13 +410,37 @@ __global__ __launch_bounds__(ROW_NT) void emb_chunk_kernel(const int32_t* __rest
                 myid = ids[myp];
             }
         }
+        // Which positions end a run that lies wholly inside the chunk (uniform): those runs are finished here, and in the
+        // update modes their old rows are requested now, together with the dY rows, instead of one by one later.
+        const int id_prev = __builtin_amdgcn_readlane(myid, 0);
+        bool whole[EMB_CHUNK];
+        {
+            bool seen_end = false;
+#pragma unroll
+            for (int u = 0; u < EMB_CHUNK; ++u) {
+                const int id_u = __builtin_amdgcn_readlane(myid, u + 1);
+                const int id_n = __builtin_amdgcn_readlane(myid, u + 2);      // -1 past the end of the batch
+                const bool end = u < n && (u == n - 1 || id_n != id_u);
+                const bool from_prev = !seen_end && id_prev == id_u;
+                const bool to_next = u == n - 1 && id_n == id_u;
+                whole[u] = end && !from_prev && !to_next;
+                seen_end |= end;
+            }
+        }
         half8 v[EMB_CHUNK];
 #pragma unroll
         for (int u = 0; u < EMB_CHUNK; ++u) {
             const int p = __builtin_amdgcn_readlane(myp, u + 1);
             if (u < n && active) v[u] = *reinterpret_cast<const half8*>(dY + (int64_t)p * H + col);
         }
-        const int id_prev = __builtin_amdgcn_readlane(myid, 0);
+        half8 wold[EMB_CHUNK];
+        if (MODE != 0) {
+#pragma unroll
+            for (int u = 0; u < EMB_CHUNK; ++u) {
+                const int id_u = __builtin_amdgcn_readlane(myid, u + 1);
+                if (whole[u] && active) wold[u] = *reinterpret_cast<const half8*>(W + (int64_t)id_u * H + col);
+            }
+        }
         float g[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) g[e] = 0.f;
@@ -430,12 +453,11 @@ __global__ __launch_bounds__(ROW_NT) void emb_chunk_kernel(const int32_t* __rest
                     for (int e = 0; e < 8; ++e) g[e] += (float)v[u][e];
                 }
                 const int id_u = __builtin_amdgcn_readlane(myid, u + 1);
-                const int id_n = __builtin_amdgcn_readlane(myid, u + 2);      // -1 past the end of the batch
+                const int id_n = __builtin_amdgcn_readlane(myid, u + 2);
                 if (u == n - 1 || id_n != id_u) {                             // the run ends here
                     const bool from_prev = first && id_prev == id_u;
-                    const bool to_next = u == n - 1 && id_n == id_u;
-                    if (!from_prev && !to_next) {
-                        emb_finish_row<MODE>(g, W, (int64_t)id_u * H + col, active, s, lr, clipv, sq, bad);
+                    if (whole[u]) {
+                        emb_finish_row<MODE>(g, W, (int64_t)id_u * H + col, active, s, lr, clipv, sq, bad, wold[u]);
                     } else if (active) {
                         float4* dst = reinterpret_cast<float4*>(chunk_rows + ((int64_t)chunk * 2 + (from_prev ? 0 : 1)) * H + col);
                         dst[0] = make_float4(g[0], g[1], g[2], g[3]);
@@ -452,7 +474,6 @@ __global__ __launch_bounds__(ROW_NT) void emb_chunk_kernel(const int32_t* __rest
         __shared__ float red[4];
         const float total = block_sum_256(sq, red);
         if (threadIdx.x == 0) partials[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = (double)total;
-        if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0) ticket[0] = 0;   // for the fix-up kernel that follows
     }
     if (MODE != 1 && flag_out != nullptr && __any(bad) && lane == 0) atomicOr(flag_out, 1);
 }
@@ -467,9 +488,7 @@ __global__ __launch_bounds__(EMB_NT) void emb_fixup_kernel(const float* __restri
                                                            const int32_t* __restrict__ n_unique, float s,
                                                            double* __restrict__ partials, int32_t* __restrict__ flag_out,
                                                            const int32_t* __restrict__ flag_in, float lr, float clipv,
-                                                           const float* __restrict__ s_dev, int32_t* __restrict__ ticket,
-                                                           int n_shares_a, double* __restrict__ acc) {
-    __shared__ float part[EMB_W - 1][64][9];
+                                                           const float* __restrict__ s_dev) {
     if (MODE == 1 && flag_in != nullptr && flag_in[0] != 0) return;
     if (MODE == 1 && s_dev != nullptr) s = s_dev[0];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -478,93 +497,99 @@ __global__ __launch_bounds__(EMB_NT) void emb_fixup_kernel(const float* __restri
     const int nseg = n_unique[0];
     float sq = 0.f;
     bool bad = false;
-    // 64 segments per trip: every lane looks at one segment's offsets, a ballot names the few that span chunks
+    // 64 segments per trip: every lane looks at one segment's offsets, a ballot names those that span chunks, and the
+    // spanning segments of the trip go to the eight waves in turn.  A wave adds its segment's partial rows in chunk order,
+    // eight loads in flight, then finishes the row: no exchange between waves, and the order of every sum depends on the
+    // ids alone.
     for (int base = blockIdx.x * 64; base < nseg; base += gridDim.x * 64) {
-      int lbeg = 0, lend = 1;
-      if (base + lane < nseg) {
-          lbeg = seg_offsets[base + lane];
-          lend = seg_offsets[base + lane + 1];
-      }
-      unsigned long long spanning = __ballot(lbeg / EMB_CHUNK != (lend - 1) / EMB_CHUNK);
-      while (spanning != 0ull) {        // uniform across the workgroup: every wave computed the same mask
-        const int bit = __builtin_ctzll(spanning);
-        spanning &= spanning - 1ull;
-        const int seg = base + bit;
-        const int beg = __shfl(lbeg, bit, 64), end = __shfl(lend, bit, 64);
-        const int cf = beg / EMB_CHUNK, cl = (end - 1) / EMB_CHUNK;
-        float g[8];
+        int lbeg = 0, lend = 1;
+        if (base + lane < nseg) {
+            lbeg = seg_offsets[base + lane];
+            lend = seg_offsets[base + lane + 1];
+        }
+        unsigned long long spanning = __ballot(lbeg / EMB_CHUNK != (lend - 1) / EMB_CHUNK);
+        int turn = 0;
+        while (spanning != 0ull) {        // uniform: every wave computed the same mask
+            const int bit = __builtin_ctzll(spanning);
+            spanning &= spanning - 1ull;
+            if ((turn++ & (EMB_W - 1)) != wave) continue;
+            const int seg = base + bit;
+            const int beg = __shfl(lbeg, bit, 64), end = __shfl(lend, bit, 64);
+            const int cf = beg / EMB_CHUNK, cl = (end - 1) / EMB_CHUNK;
+            const int64_t row_off = (int64_t)unique_ids[seg] * H + col;
+            half8 wold;
+            if (MODE != 0 && active) wold = *reinterpret_cast<const half8*>(W + row_off);
+            float g[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) g[e] = 0.f;
-        if (active) {
-            // the first chunk holds the segment's run in slot 1 (it goes on), every later chunk in slot 0
-            auto row = [&](int c) { return chunk_rows + ((int64_t)c * 2 + (c == cf ? 1 : 0)) * H + col; };
-            int c = cf + wave;
-            for (; c + 3 * EMB_W <= cl; c += 4 * EMB_W) {
-                float4 a[4][2];
+            for (int e = 0; e < 8; ++e) g[e] = 0.f;
+            if (active) {
+                // the first chunk holds the segment's run in slot 1 (it goes on), every later chunk in slot 0
+                auto row = [&](int c) { return chunk_rows + ((int64_t)c * 2 + (c == cf ? 1 : 0)) * H + col; };
+                int c = cf;
+                for (; c + 7 <= cl; c += 8) {
+                    float4 a[8][2];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const float4* src = reinterpret_cast<const float4*>(row(c + u * EMB_W));
-                    a[u][0] = src[0];
-                    a[u][1] = src[1];
+                    for (int u = 0; u < 8; ++u) {
+                        const float4* src = reinterpret_cast<const float4*>(row(c + u));
+                        a[u][0] = src[0];
+                        a[u][1] = src[1];
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        g[0] += a[u][0].x; g[1] += a[u][0].y; g[2] += a[u][0].z; g[3] += a[u][0].w;
+                        g[4] += a[u][1].x; g[5] += a[u][1].y; g[6] += a[u][1].z; g[7] += a[u][1].w;
+                    }
+                }
+                float4 t[7][2];
+                const int left = cl - c + 1;        // 0 .. 7 (uniform)
+#pragma unroll
+                for (int u = 0; u < 7; ++u) {
+                    if (u < left) {
+                        const float4* src = reinterpret_cast<const float4*>(row(c + u));
+                        t[u][0] = src[0];
+                        t[u][1] = src[1];
+                    }
                 }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    g[0] += a[u][0].x; g[1] += a[u][0].y; g[2] += a[u][0].z; g[3] += a[u][0].w;
-                    g[4] += a[u][1].x; g[5] += a[u][1].y; g[6] += a[u][1].z; g[7] += a[u][1].w;
+                for (int u = 0; u < 7; ++u) {
+                    if (u < left) {
+                        g[0] += t[u][0].x; g[1] += t[u][0].y; g[2] += t[u][0].z; g[3] += t[u][0].w;
+                        g[4] += t[u][1].x; g[5] += t[u][1].y; g[6] += t[u][1].z; g[7] += t[u][1].w;
+                    }
                 }
             }
-            for (; c <= cl; c += EMB_W) {
-                const float4* src = reinterpret_cast<const float4*>(row(c));
-                const float4 a0 = src[0], a1 = src[1];
-                g[0] += a0.x; g[1] += a0.y; g[2] += a0.z; g[3] += a0.w;
-                g[4] += a1.x; g[5] += a1.y; g[6] += a1.z; g[7] += a1.w;
-            }
+            emb_finish_row<MODE>(g, W, row_off, active, s, lr, clipv, sq, bad, wold);
         }
-        if (wave > 0) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) part[wave - 1][lane][e] = g[e];
-        }
-        __syncthreads();
-        if (wave == 0) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                g[e] = ((g[e] + part[0][lane][e]) + (part[1][lane][e] + part[2][lane][e])) +
-                       ((part[3][lane][e] + part[4][lane][e]) + (part[5][lane][e] + part[6][lane][e]));
-            emb_finish_row<MODE>(g, W, (int64_t)unique_ids[seg] * H + col, active, s, lr, clipv, sq, bad);
-        }
-        __syncthreads();
-      }
     }
-    if (MODE != 1 && wave == 0 && flag_out != nullptr && __any(bad) && lane == 0) atomicOr(flag_out, 1);
-    if (MODE == 0) {
-        // This workgroup's share goes behind the n_shares_a shares of the chunk kernel.  The workgroup that arrives
-        // last adds all shares in index order (threads strided, then a fixed tree), so the embedding's squared norm
-        // does not depend on the order in which workgroups finish.
-        __shared__ int last_s;
-        __shared__ double dred[EMB_NT];
-        if (wave == 0) {
+    if (MODE != 1 && flag_out != nullptr && __any(bad) && lane == 0) atomicOr(flag_out, 1);
+    if (MODE == 0) {      // one share per workgroup: its eight waves added in a fixed tree
+        __shared__ float wsq[EMB_W];
 #pragma unroll
-            for (int off = 32; off > 0; off >>= 1) sq += __shfl_xor(sq, off, 64);
-            if (lane == 0) {
-                partials[n_shares_a + (int64_t)blockIdx.y * gridDim.x + blockIdx.x] = (double)sq;
-                __threadfence();
-                last_s = atomicAdd(ticket, 1) == (int)(gridDim.x * gridDim.y) - 1;
-            }
-        }
+        for (int off = 32; off > 0; off >>= 1) sq += __shfl_xor(sq, off, 64);
+        if (lane == 0) wsq[wave] = sq;
         __syncthreads();
-        if (!last_s) return;
-        __threadfence();
-        const int n = n_shares_a + (int)(gridDim.x * gridDim.y);
-        double v = 0.0;
-        for (int i = threadIdx.x; i < n; i += EMB_NT) v += __hip_atomic_load(partials + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        dred[threadIdx.x] = v;
-        __syncthreads();
-        for (int off = EMB_NT / 2; off > 0; off >>= 1) {
-            if ((int)threadIdx.x < off) dred[threadIdx.x] += dred[threadIdx.x + off];
-            __syncthreads();
+        if (threadIdx.x == 0) {
+            const float total = ((wsq[0] + wsq[1]) + (wsq[2] + wsq[3])) + ((wsq[4] + wsq[5]) + (wsq[6] + wsq[7]));
+            partials[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = (double)total;
         }
-        if (threadIdx.x == 0) atomicAdd(acc, dred[0]);
     }
+}
+
+// Adds the per-workgroup shares of both kernels in index order: the embedding's squared norm is bit-reproducible.  (A
+// last-workgroup-to-arrive reduction inside the fix-up kernel was slower: hundreds of workgroups taking a ticket from one
+// address serialise in the L2's atomic unit.)
+__global__ __launch_bounds__(ROW_NT) void emb_finish_sqnorm(const double* __restrict__ partials, int n,
+                                                            double* __restrict__ acc) {
+    __shared__ double red[ROW_NT];
+    double v = 0.0;
+    for (int i = threadIdx.x; i < n; i += ROW_NT) v += partials[i];
+    red[threadIdx.x] = v;
+    __syncthreads();
+    for (int off = ROW_NT / 2; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) atomicAdd(acc, red[0]);
 }
 
 hipError_t launch_embedding_rows(const int32_t* ids, const uint16_t* dY, uint16_t* W, int64_t T, int64_t H,
@@ -573,15 +598,16 @@ hipError_t launch_embedding_rows(const int32_t* ids, const uint16_t* dY, uint16_
     const dim3 gridA((unsigned)emb_chunk_blocks(T), (unsigned)emb_slabs(H));
     const int64_t tripsB = (T + 63) / 64;
     const dim3 gridB((unsigned)(tripsB < EMB_FIX_GX ? tripsB : EMB_FIX_GX), (unsigned)emb_slabs(H));
-    int32_t* ticket = w.n_unique + 1;     // the count's 256-byte slot has room for the arrival counter
-    const int sharesA = (int)(gridA.x * gridA.y);
+    double* partB = w.partials + (int64_t)gridA.x * gridA.y;
 #define LOMO_EMB_LAUNCH(M)                                                                                              \
     hipLaunchKernelGGL(emb_chunk_kernel<M>, gridA, dim3(ROW_NT), 0, st, ids, dY, W, (int)T, H, w.perm, s, w.chunk_rows, \
-                       w.partials, flag_out, flag_in, lr, clipv, s_dev, ticket);                                        \
+                       w.partials, flag_out, flag_in, lr, clipv, s_dev);                                                \
     hipLaunchKernelGGL(emb_fixup_kernel<M>, gridB, dim3(EMB_NT), 0, st, w.chunk_rows, W, H, w.unique_ids, w.seg_offsets, \
-                       w.n_unique, s, w.partials, flag_out, flag_in, lr, clipv, s_dev, ticket, sharesA, acc);
+                       w.n_unique, s, partB, flag_out, flag_in, lr, clipv, s_dev);
     if (mode == 0) {
         LOMO_EMB_LAUNCH(0)
+        hipLaunchKernelGGL(emb_finish_sqnorm, dim3(1), dim3(ROW_NT), 0, st, w.partials,
+                           (int)(gridA.x * gridA.y + gridB.x * gridB.y), acc);
     } else if (mode == 1) {
         LOMO_EMB_LAUNCH(1)
     } else {
