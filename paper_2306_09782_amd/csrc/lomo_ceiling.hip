@@ -81,15 +81,20 @@ __global__ __launch_bounds__(THREADS) void probe_mfma_kernel(const uint16_t* __r
     if (lane == 0) atomicAdd(sink + blockIdx.x, v);
 }
 
-__global__ __launch_bounds__(256) void probe_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t n16) {
+// Streaming copy: every thread keeps eight independent 16-byte loads in flight; loads and stores carry the
+// non-temporal hint (the data is touched once).
+typedef uint32_t probe_u32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void probe_copy_kernel(const probe_u32x4* __restrict__ src, probe_u32x4* __restrict__ dst, int64_t n16) {
+    constexpr int U = 8;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    for (; i + 3 * stride < n16; i += 4 * stride) {      // four independent 16-byte loads in flight per thread
-        const uint4 v0 = src[i], v1 = src[i + stride], v2 = src[i + 2 * stride], v3 = src[i + 3 * stride];
-        dst[i] = v0;
-        dst[i + stride] = v1;
-        dst[i + 2 * stride] = v2;
-        dst[i + 3 * stride] = v3;
+    for (; i + (U - 1) * stride < n16; i += U * stride) {
+        probe_u32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < U; ++u) __builtin_nontemporal_store(v[u], dst + i + u * stride);
     }
     for (; i < n16; i += stride) dst[i] = src[i];
 }
@@ -141,11 +146,11 @@ lomo_status lomo_probe_copy(const void* src, void* dst, size_t bytes, void* stre
     if (!src || !dst) return LOMO_ERR_NULL;
     if ((reinterpret_cast<uintptr_t>(src) & 15u) || (reinterpret_cast<uintptr_t>(dst) & 15u)) return LOMO_ERR_ALIGN;
     const int64_t n16 = (int64_t)(bytes >> 4);
-    int64_t blocks = (n16 + 4 * 256 - 1) / (4 * 256);
-    const int64_t cap = (int64_t)probe_cu_count() * 16;
+    int64_t blocks = (n16 + 8 * 256 - 1) / (8 * 256);
+    const int64_t cap = (int64_t)probe_cu_count() * 32;
     if (blocks > cap) blocks = cap;
     return launch_timed(LOMO_KERNEL_PROBE, probe_copy_kernel, dim3((unsigned)blocks), dim3(256), 0,
-                        static_cast<hipStream_t>(stream), static_cast<const uint4*>(src), static_cast<uint4*>(dst), n16) ==
+                        static_cast<hipStream_t>(stream), static_cast<const probe_u32x4*>(src), static_cast<probe_u32x4*>(dst), n16) ==
                    hipSuccess
                ? LOMO_OK
                : LOMO_ERR_LAUNCH;

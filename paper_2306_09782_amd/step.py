@@ -142,8 +142,9 @@ class LomoStreamedStep:
     groups, so norm, coefficient and the skip on overflow are those of the whole step; nothing waits on the host.
     Sequencing only: every computation is a C-ABI call."""
 
-    def __init__(self, device="cuda:0", max_tensors: int = 4096):
+    def __init__(self, device="cuda:0", max_tensors: int = 4096, norm_algorithm: str = "direct"):
         self.device = torch.device(device)
+        self.norm_algorithm = norm_algorithm
         self.acc = torch.zeros(1, dtype=torch.float64, device=self.device)
         self.flags = torch.zeros(max_tensors + 1, dtype=torch.int32, device=self.device)
         self.ws = torch.empty(256, dtype=torch.uint8, device=self.device)
@@ -175,7 +176,7 @@ class LomoStreamedStep:
             self.flags.zero_()
         for g, (arr, b) in enumerate(zip(lists, bases)):
             prepare(g)
-            B.lomo_step_norm_pass(arr, self.acc, self.flags[b:b + len(arr) + 1], self.ws, stream)
+            B.lomo_step_norm_pass(arr, self.acc, self.flags[b:b + len(arr) + 1], self.ws, stream, self.norm_algorithm)
         B.lomo_reduce_flags(self.flags[:nf], step_flag, stream)
         B.lomo_step_scalars_device(self.acc, step_flag, loss_scale, max_norm, eps, lr, self.scalars, stream)
         for g, arr in enumerate(lists):

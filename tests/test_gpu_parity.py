@@ -372,3 +372,96 @@ def test_generators_agree_on_device():
         np.testing.assert_array_equal(a.view(np.uint16), b.view(np.uint16))
         c = S.normal_f16_torch(key, (300, 520), mult, DEV, force_torch_ops=True).cpu().numpy()
         np.testing.assert_array_equal(a.view(np.uint16), c.view(np.uint16))
+
+
+def _mixed_step_tensors(seed=0):
+    """70 gain vectors of one shape (more than one launch holds), 3 of another, 2 of a third with T = 1, an embedding
+    and a small linear tensor, against the oracle's materialised step."""
+    Sc = 256.0
+    recs = []
+    k = [0]
+
+    def g(shape, sig, sc=1.0):
+        k[0] += 1
+        return S.normal_f16_np(S.tensor_key(seed, 31, k[0], 0), shape, S.normal_mult(sig, sc))
+    for (T, H, n) in ((96, 264, 70), (200, 1032, 3), (1, 72, 2)):
+        for _ in range(n):
+            recs.append(dict(kind="vector", X=g((T, H), 1.0), dY=g((T, H), 0.02, Sc), W=g((H,), 1.0)))
+    recs.insert(5, dict(kind="embedding", ids=S.zipf_ids(seed, 300, 400), dY=g((300, 264), 0.02, Sc), W=g((400, 264), 0.05)))
+    recs.insert(40, dict(kind="linear", X=g((96, 264), 1.0), dY=g((96, 136), 0.02, Sc), W=g((136, 264), 0.05)))
+    return recs, Sc
+
+
+@pytest.mark.parametrize("workspace", ["recommended", "minimum"])
+def test_step_with_many_gain_vectors_of_mixed_shapes(L, workspace):
+    """Gain vectors are batched per shape as far as the workspace holds their partial sums: with the recommended size
+    64 of the 70 share a launch, with the minimum every vector gets its own; the results are the per-tensor calls' bit
+    for bit, and the oracle's to the usual bar."""
+    from paper_2306_09782_amd.step import LomoStep
+    cpu, Sc = _mixed_step_tensors()
+    lr = 0.5
+    ref = O.step_materialised(cpu, lr, Sc)
+    assert not ref["overflow"]
+    results = []
+    for grouped in (True, False):
+        gpu = [{k: (dev(v) if isinstance(v, np.ndarray) else v) for k, v in t.items()} for t in cpu]
+        gpu[40]["dX"] = torch.empty(96, 264, dtype=torch.float16, device=DEV)
+        stepper = LomoStep(DEV, max_T=300, max_H=1032, max_tensors=len(gpu), grouped=grouped)
+        if grouped:
+            arr = L.make_tensor_list(gpu)
+            need, least = L.lomo_step_workspace_bytes(arr), L.lomo_step_workspace_min_bytes(arr)
+            one = L.lomo_vector_workspace_bytes(96, 264)
+            assert least < need and need >= 64 * one
+            stepper._list(gpu)                       # binds the list and sizes the workspace
+            if workspace == "minimum":
+                stepper.ws = torch.empty(least, dtype=torch.uint8, device=DEV)
+                with pytest.raises(L.LomoError, match="workspace"):
+                    L.lomo_step_norm_pass(arr, stepper.acc, stepper.flags, stepper.ws[:least - 256])
+        res = stepper.run(gpu, lr, Sc)
+        torch.cuda.synchronize()
+        assert res["flags"] == ref["flags"] and res["overflow"] is False
+        assert abs(res["norm"] / ref["norm"] - 1) < 1e-5
+        results.append([host(t["W"]) for t in gpu])
+    moved = 0
+    for a, b, t, w in zip(results[0], results[1], cpu, ref["W"]):
+        assert np.array_equal(a.view(np.uint16), b.view(np.uint16)), t["kind"]
+        assert_weights_close(a, w, t["kind"])
+        moved += int((a.view(np.uint16) != t["W"].view(np.uint16)).sum())
+    assert moved > 1000
+
+
+def test_update_pass_reuses_the_grouping_of_the_norm_pass(L):
+    """reuse_grouping = the workspace still holds pass 1's token grouping: same bits as grouping again; a stale
+    workspace must not be trusted without the promise; two embeddings in one list never reuse."""
+    cpu, Sc = _mixed_step_tensors(seed=3)
+    cpu = cpu[:12]                                   # 11 gain vectors + the embedding at position 5
+    lr, coef = 0.5, 0.25
+    outs = []
+    for reuse in (False, True):
+        gpu = [{k: (dev(v) if isinstance(v, np.ndarray) else v) for k, v in t.items()} for t in cpu]
+        arr = L.make_tensor_list(gpu)
+        ws = torch.empty(L.lomo_step_workspace_bytes(arr), dtype=torch.uint8, device=DEV)
+        acc = torch.zeros(1, dtype=torch.float64, device=DEV)
+        flags = torch.zeros(len(gpu) + 1, dtype=torch.int32, device=DEV)
+        L.lomo_step_norm_pass(arr, acc, flags, ws)
+        if not reuse:
+            ws[:4096].fill_(0xAB)                    # the head of the workspace is the grouping: spoil it, then regroup
+        L.lomo_step_update_pass(arr, lr, 1.0 / Sc, coef, flags[len(gpu):], ws, reuse_grouping=reuse)
+        torch.cuda.synchronize()
+        outs.append([host(t["W"]) for t in gpu])
+    for a, b, t in zip(outs[0], outs[1], cpu):
+        assert np.array_equal(a.view(np.uint16), b.view(np.uint16)), t["kind"]
+        G = O.tensor_grad(t)
+        assert_weights_close(a, O.sgd_update(t["W"], G, lr, coef, Sc), t["kind"])
+    # two embedding tensors share the one grouping slot: the flag is ignored and both are grouped again
+    two = [cpu[5], dict(cpu[5], ids=S.zipf_ids(9, 300, 400))]
+    gpu = [{k: (dev(v) if isinstance(v, np.ndarray) else v) for k, v in t.items()} for t in two]
+    arr = L.make_tensor_list(gpu)
+    ws = torch.empty(L.lomo_step_workspace_bytes(arr), dtype=torch.uint8, device=DEV)
+    acc = torch.zeros(1, dtype=torch.float64, device=DEV)
+    flags = torch.zeros(3, dtype=torch.int32, device=DEV)
+    L.lomo_step_norm_pass(arr, acc, flags, ws)
+    L.lomo_step_update_pass(arr, lr, 1.0 / Sc, coef, flags[2:], ws, reuse_grouping=True)
+    torch.cuda.synchronize()
+    for g_, t in zip(gpu, two):
+        assert_weights_close(host(g_["W"]), O.sgd_update(t["W"], O.tensor_grad(t), lr, coef, Sc), "embedding pair")
