@@ -193,3 +193,31 @@ class LomoStreamedStep:
         host = self.flags[:self._n_flags].cpu().tolist()
         out["flags"] = [[bool(v) for v in host[b:b + len(arr)]] for arr, b in zip(self._lists, self._bases)]
         return out
+
+
+class CapturedStep:
+    """One whole step (LomoStep.run_async: fills, pass 1, coefficient kernel, pass 2, copy of the scalars to pinned
+    memory) recorded once as a HIP graph and replayed with a single launch.  For steps whose kernels are short
+    against their launch overhead (a single small layer); the tensors' pointers and shapes, lr and the loss scale are
+    part of the recording.  Every node of the graph is a kernel launch or a device-to-host copy (the fills are torch's
+    fill kernels, no memset nodes).  The library's timing must be off while recording."""
+
+    def __init__(self, stepper: LomoStep, tensors: List[Dict], lr: float, loss_scale: float, max_norm: float = 1.0,
+                 eps: float = 1e-6):
+        assert stepper.grouped
+        self.stepper = stepper
+        side = torch.cuda.Stream(stepper.device)                 # default priority
+        side.wait_stream(torch.cuda.current_stream(stepper.device))
+        with torch.cuda.stream(side):                             # warm-up outside the recording: workspace, kernel attributes
+            stepper.run_async(tensors, lr, loss_scale, max_norm, eps)
+        torch.cuda.current_stream(stepper.device).wait_stream(side)
+        torch.cuda.synchronize(stepper.device)
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            stepper.run_async(tensors, lr, loss_scale, max_norm, eps)
+
+    def replay(self) -> None:
+        self.graph.replay()
+
+    def result(self) -> Dict:
+        return self.stepper.result()

@@ -195,3 +195,57 @@ def test_step_on_a_stream_that_is_not_current(L, mode):
         assert (got.view(np.uint16) != t["W"].view(np.uint16)).any()
     _check_dx(gpu[0]["dX"].cpu().numpy(), cpu[0]["dY"], cpu[0]["W"], "dX")
     torch.cuda.synchronize()
+
+
+def test_captured_step_replays_like_the_eager_step(L):
+    """The whole step recorded as a HIP graph: every replay (three of them, with eager steps and synchronisations in
+    between) must leave the weights the eager step leaves from the same start, and report the same scalars."""
+    from paper_2306_09782_amd.step import LomoStep, CapturedStep
+    T, V, H, N = 320, 700, 264, 392
+    Sc = 1024.0
+    mk = lambda i, shape, sig, sc=1.0: S.normal_f16_np(S.tensor_key(4, 0, i, 0), shape, S.normal_mult(sig, sc))
+    cpu = [
+        dict(kind="linear", X=mk(0, (T, H), 1.0), dY=mk(1, (T, N), 0.01, Sc), W=mk(2, (N, H), 0.02)),
+        dict(kind="linear", X=mk(7, (512, 1024), 1.0), dY=mk(8, (512, 1024), 0.01, Sc), W=mk(9, (1024, 1024), 0.02)),
+        dict(kind="vector", X=mk(3, (T, H), 1.0), dY=mk(4, (T, H), 0.01, Sc), W=np.ones(H, np.float16)),
+        dict(kind="embedding", ids=S.zipf_ids(4, T, V), dY=mk(5, (T, H), 0.01, Sc), W=mk(6, (V, H), 0.02)),
+    ]
+    lr = 4.0
+    ref = O.step_materialised(cpu, lr, Sc)
+    gpu = [{k: (torch.from_numpy(v).to(DEV) if isinstance(v, np.ndarray) else v) for k, v in t.items()} for t in cpu]
+    gpu[0]["dX"] = torch.empty(T, H, dtype=torch.float16, device=DEV)
+    gpu[1]["dX"] = torch.empty(512, 1024, dtype=torch.float16, device=DEV)
+    start = [t["W"].clone() for t in gpu]
+
+    def reset():
+        for t, w in zip(gpu, start):
+            t["W"].copy_(w)
+
+    stepper = LomoStep(DEV, max_T=512, max_H=1024)
+    captured = CapturedStep(stepper, gpu, lr, Sc)          # its warm-up and its recording do not count as steps here ...
+    reset()                                                # ... but the warm-up has moved the weights
+    stepper.run_async(gpu, lr, Sc)
+    torch.cuda.synchronize()
+    eager = [t["W"].clone() for t in gpu]
+    eager_res = stepper.result()
+    eager_dx = gpu[0]["dX"].clone()
+    for rep in range(3):
+        reset()
+        gpu[0]["dX"].zero_()
+        captured.replay()
+        torch.cuda.synchronize()
+        res = captured.result()
+        assert res["overflow"] is False and abs(res["norm"] / eager_res["norm"] - 1) < 1e-9, rep
+        assert abs(res["norm"] / ref["norm"] - 1) < 1e-5
+        for t, e, w, c in zip(gpu, eager, ref["W"], cpu):
+            got = t["W"]
+            same = (got.view(torch.int16) == e.view(torch.int16)).float().mean().item()
+            assert same > 0.9999, (rep, c["kind"], same)      # the step size may differ in its last bit (atomic order)
+            _check_ulps(got.cpu().numpy(), w, f"replay {rep} {c['kind']}")
+        assert torch.equal(gpu[0]["dX"].view(torch.int16), eager_dx.view(torch.int16))
+        # the program's own eager work between replays
+        reset()
+        stepper.run_async(gpu, lr, Sc)
+        torch.cuda.synchronize()
+        for t, e in zip(gpu, eager):
+            assert (t["W"].view(torch.int16) == e.view(torch.int16)).float().mean().item() > 0.9999
