@@ -127,58 +127,98 @@ __global__ __launch_bounds__(SORT_NT) void emb_segments(const uint64_t* __restri
 
 // ------------------------------------------------------------------------------------------
 // Small batches (at most 8192 positions, id * 8192 below 2^32): keys, sort and segments in ONE workgroup.
-// 32-bit keys id << shift | position; every thread keeps 8 consecutive elements in registers.  The sort is a
-// least-significant-bit-first radix sort over the id bits, one stable split per bit: elements whose bit is 0
-// keep their order and move to the front, the others follow in order (a workgroup-wide exclusive scan of the
-// per-thread zero counts gives every element its new index; the exchange goes through LDS).  Positions start
-// in ascending order and every split is stable, so equal ids end up in ascending position order.
+// 32-bit keys id << shift | position; every thread keeps 8 elements in registers.  The sort is a
+// least-significant-digit-first radix sort over the id bits, four bits per pass, every pass stable: positions
+// start in ascending order, so equal ids end up in ascending position order.
+// One pass: wave w owns the 512 consecutive elements w * 512 + r * 64 + lane (r = 0..7).  For each r the lanes
+// that hold the same digit find each other with four ballots; the lowest of them adds the group's size to the
+// wave's counter of that digit in LDS and hands the counter's old value to the group, so an element's rank
+// among the wave's elements of its digit is (old value) + (lanes of the group below it): rounds r are issued in
+// order and LDS executes a wave's operations in order.  After one barrier every wave scans the 16 x waves
+// counters (digit-major, wave-minor) for itself and knows where its elements of each digit start; the exchange
+// goes through LDS.  Two barriers per pass.
 // ------------------------------------------------------------------------------------------
 
 constexpr int GS_KPT = 8;
 constexpr int GS_MAX = 8192;
+constexpr int GS_DIGIT_BITS = 4, GS_DIGITS = 1 << GS_DIGIT_BITS;
 
 __global__ __launch_bounds__(1024) void emb_group_small(const int32_t* __restrict__ ids, int T, int N, int shift,
                                                         int id_bits, int32_t* __restrict__ perm,
                                                         int32_t* __restrict__ unique_ids, int32_t* __restrict__ seg_offsets,
                                                         int32_t* __restrict__ n_unique) {
-    __shared__ uint32_t sk[GS_MAX];
+    __shared__ __attribute__((aligned(16))) uint32_t sk[GS_MAX];
+    __shared__ __attribute__((aligned(16))) int32_t hist[GS_DIGITS * 16];     // [digit][wave]
+    __shared__ int32_t wbase[16 * GS_DIGITS];                               // [wave][digit]
     __shared__ int32_t wsum[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int nw = (int)(blockDim.x >> 6);
-    const int e0 = tid * GS_KPT;
+    const int nw = (int)(blockDim.x >> 6);                                  // 1, 2, 4, 8 or 16
+    const int s0 = wave * (64 * GS_KPT) + lane;                             // this lane's element of round r: s0 + 64 r
+    const uint64_t below = (1ull << lane) - 1ull;
     uint32_t key[GS_KPT];
 #pragma unroll
     for (int r = 0; r < GS_KPT; ++r) {
-        const int e = e0 + r;
+        const int e = s0 + 64 * r;
         key[r] = (e < T) ? (((uint32_t)ids[e] << shift) | (uint32_t)e) : 0xffffffffu;   // padding: every bit set
     }
-    for (int bit = shift; bit < shift + id_bits; ++bit) {
-        int zeros = 0;
-#pragma unroll
-        for (int r = 0; r < GS_KPT; ++r) zeros += ((key[r] >> bit) & 1u) ? 0 : 1;
-        int v = zeros;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const int o = __shfl_up(v, off, 64);
-            if (lane >= off) v += o;
-        }
-        if (lane == 63) wsum[wave] = v;
-        __syncthreads();     // also: everybody has read its keys of the previous split out of sk
-        int zbase = v - zeros, total_zeros = 0;
-        for (int w = 0; w < nw; ++w) {
-            zbase += w < wave ? wsum[w] : 0;
-            total_zeros += wsum[w];
-        }
-        int z = zbase;       // zeros before the current element
+    for (int bit = shift; bit < shift + id_bits; bit += GS_DIGIT_BITS) {
+        if (lane < GS_DIGITS) hist[lane * nw + wave] = 0;
+        int rank[GS_KPT], digit[GS_KPT];
 #pragma unroll
         for (int r = 0; r < GS_KPT; ++r) {
-            const bool one = (key[r] >> bit) & 1u;
-            sk[one ? total_zeros + (e0 + r - z) : z] = key[r];
-            z += one ? 0 : 1;
+            const int d = (int)((key[r] >> bit) & (uint32_t)(GS_DIGITS - 1));
+            uint64_t same = ~0ull;
+#pragma unroll
+            for (int b = 0; b < GS_DIGIT_BITS; ++b) {
+                const bool set = (d >> b) & 1;
+                const uint64_t vote = __ballot(set);
+                same &= set ? vote : ~vote;
+            }
+            const int lower = __popcll(same & below);
+            int old = 0;
+            if (lower == 0) old = atomicAdd(&hist[d * nw + wave], __popcll(same));
+            rank[r] = __shfl(old, __ffsll((unsigned long long)same) - 1, 64) + lower;
+            digit[r] = d;
         }
+        __syncthreads();     // all counters are final; everybody has read its keys of the previous pass out of sk
+        {
+            // entries 4 lane .. 4 lane + 3 of the digit-major list of 16 * nw counters
+            int v[4] = {0, 0, 0, 0};
+            const bool live = 4 * lane < GS_DIGITS * nw;
+            if (live) {
+                const int4 q = *reinterpret_cast<const int4*>(hist + 4 * lane);
+                v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+            }
+            const int mine = (v[0] + v[1]) + (v[2] + v[3]);
+            int incl = mine;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int o = __shfl_up(incl, off, 64);
+                if (lane >= off) incl += o;
+            }
+            int start = incl - mine;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int i = 4 * lane + k;
+                if (live && (i & (nw - 1)) == wave) wbase[wave * GS_DIGITS + i / nw] = start;
+                start += v[k];
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int r = 0; r < GS_KPT; ++r) sk[wbase[wave * GS_DIGITS + digit[r]] + rank[r]] = key[r];
         __syncthreads();
 #pragma unroll
-        for (int r = 0; r < GS_KPT; ++r) key[r] = sk[e0 + r];
+        for (int r = 0; r < GS_KPT; ++r) key[r] = sk[s0 + 64 * r];
+    }
+    // ---- sk holds the sorted keys (at least one pass has run): eight consecutive ones per thread from here on
+    const int e0 = tid * GS_KPT;
+    {
+        const uint4 q0 = *reinterpret_cast<const uint4*>(sk + e0), q1 = *reinterpret_cast<const uint4*>(sk + e0 + 4);
+        key[0] = q0.x; key[1] = q0.y; key[2] = q0.z; key[3] = q0.w;
+        key[4] = q1.x; key[5] = q1.y; key[6] = q1.z; key[7] = q1.w;
     }
     __syncthreads();
     // ---- segments: head flags, exclusive scan, outputs
