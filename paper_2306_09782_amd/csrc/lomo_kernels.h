@@ -74,6 +74,7 @@ hipError_t launch_forward(const GemmArgs& a, bool accumulate, hipStream_t st);
 // Row-wise kernels -------------------------------------------------------------------------
 struct EmbeddingWs {          // carved out of the caller's workspace
     uint64_t* keys;           // [Tpad] (id << 32 | position), padded with all-ones
+    uint64_t* keys2;          // [Tpad] second key buffer of the merge rounds (batches above 8192 positions; else null)
     int32_t* perm;            // [T]
     int32_t* unique_ids;      // [T]
     int32_t* seg_offsets;     // [T + 1]

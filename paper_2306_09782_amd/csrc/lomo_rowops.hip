@@ -143,24 +143,15 @@ constexpr int GS_KPT = 8;
 constexpr int GS_MAX = 8192;
 constexpr int GS_DIGIT_BITS = 4, GS_DIGITS = 1 << GS_DIGIT_BITS;
 
-__global__ __launch_bounds__(1024) void emb_group_small(const int32_t* __restrict__ ids, int T, int N, int shift,
-                                                        int id_bits, int32_t* __restrict__ perm,
-                                                        int32_t* __restrict__ unique_ids, int32_t* __restrict__ seg_offsets,
-                                                        int32_t* __restrict__ n_unique) {
-    __shared__ __attribute__((aligned(16))) uint32_t sk[GS_MAX];
-    __shared__ __attribute__((aligned(16))) int32_t hist[GS_DIGITS * 16];     // [digit][wave]
-    __shared__ int32_t wbase[16 * GS_DIGITS];                               // [wave][digit]
-    __shared__ int32_t wsum[16];
+// The passes.  In: key[r] = element wave * 512 + r * 64 + lane of the workgroup's blockDim.x * 8 keys; the bits
+// [shift, shift + id_bits) are sorted on.  Out: the sorted keys in sk (a barrier has been passed; at least one
+// pass runs).  hist: 16 x waves counters, digit-major; wbase: waves x 16.
+__device__ __forceinline__ void radix_sort_in_lds(uint32_t (&key)[GS_KPT], uint32_t* __restrict__ sk, int32_t* __restrict__ hist,
+                                                  int32_t* __restrict__ wbase, int shift, int id_bits) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nw = (int)(blockDim.x >> 6);                                  // 1, 2, 4, 8 or 16
-    const int s0 = wave * (64 * GS_KPT) + lane;                             // this lane's element of round r: s0 + 64 r
+    const int s0 = wave * (64 * GS_KPT) + lane;
     const uint64_t below = (1ull << lane) - 1ull;
-    uint32_t key[GS_KPT];
-#pragma unroll
-    for (int r = 0; r < GS_KPT; ++r) {
-        const int e = s0 + 64 * r;
-        key[r] = (e < T) ? (((uint32_t)ids[e] << shift) | (uint32_t)e) : 0xffffffffu;   // padding: every bit set
-    }
     for (int bit = shift; bit < shift + id_bits; bit += GS_DIGIT_BITS) {
         if (lane < GS_DIGITS) hist[lane * nw + wave] = 0;
         int rank[GS_KPT], digit[GS_KPT];
@@ -213,6 +204,26 @@ __global__ __launch_bounds__(1024) void emb_group_small(const int32_t* __restric
 #pragma unroll
         for (int r = 0; r < GS_KPT; ++r) key[r] = sk[s0 + 64 * r];
     }
+}
+
+__global__ __launch_bounds__(1024) void emb_group_small(const int32_t* __restrict__ ids, int T, int N, int shift,
+                                                        int id_bits, int32_t* __restrict__ perm,
+                                                        int32_t* __restrict__ unique_ids, int32_t* __restrict__ seg_offsets,
+                                                        int32_t* __restrict__ n_unique) {
+    __shared__ __attribute__((aligned(16))) uint32_t sk[GS_MAX];
+    __shared__ __attribute__((aligned(16))) int32_t hist[GS_DIGITS * 16];     // [digit][wave]
+    __shared__ int32_t wbase[16 * GS_DIGITS];                               // [wave][digit]
+    __shared__ int32_t wsum[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nw = (int)(blockDim.x >> 6);
+    const int s0 = wave * (64 * GS_KPT) + lane;                             // this lane's element of round r: s0 + 64 r
+    uint32_t key[GS_KPT];
+#pragma unroll
+    for (int r = 0; r < GS_KPT; ++r) {
+        const int e = s0 + 64 * r;
+        key[r] = (e < T) ? (((uint32_t)ids[e] << shift) | (uint32_t)e) : 0xffffffffu;   // padding: every bit set
+    }
+    radix_sort_in_lds(key, sk, hist, wbase, shift, id_bits);
     // ---- sk holds the sorted keys (at least one pass has run): eight consecutive ones per thread from here on
     const int e0 = tid * GS_KPT;
     {
@@ -283,6 +294,173 @@ static inline bool group_small_plan(int64_t T, int64_t V, int* N, int* shift, in
     return true;
 }
 
+// ------------------------------------------------------------------------------------------
+// Larger batches (ids below 2^19): every 8192 consecutive positions are sorted by one workgroup with the radix
+// sort above (keys id << 13 | position inside the chunk) and written as 64-bit keys id << 32 | position; the
+// sorted runs are merged pairwise, doubling per round, between two key buffers (merge path: a workgroup owns
+// 2048 consecutive outputs, finds where they start in both runs by bisection, stages its inputs in LDS and every
+// thread merges eight outputs).  Keys are unique, so the merge needs no tie rule.  Segments: heads are counted
+// per 2048 keys, then every workgroup adds up the counts before it and writes its part.
+// ------------------------------------------------------------------------------------------
+
+constexpr int GS_CHUNK_SHIFT = 13;     // log2(GS_MAX)
+constexpr int MG_NT = 256, MG_KPT = 8, MG_TILE = MG_NT * MG_KPT;
+
+static inline bool group_chunks_plan(int64_t T, int64_t V, int* id_bits) {
+    if (T <= GS_MAX || V <= 0) return false;
+    if ((V - 1) >> (32 - GS_CHUNK_SHIFT) != 0) return false;
+    if ((((V - 1) << GS_CHUNK_SHIFT) | (GS_MAX - 1)) >= 0xffffffffll) return false;
+    int ib = 1;
+    while ((1ll << ib) < V) ++ib;
+    *id_bits = ib;
+    return true;
+}
+
+__global__ __launch_bounds__(1024) void emb_sort_chunks(const int32_t* __restrict__ ids, int64_t T, int id_bits,
+                                                        uint64_t* __restrict__ out) {
+    __shared__ __attribute__((aligned(16))) uint32_t sk[GS_MAX];
+    __shared__ __attribute__((aligned(16))) int32_t hist[GS_DIGITS * 16];
+    __shared__ int32_t wbase[16 * GS_DIGITS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t base = (int64_t)blockIdx.x * GS_MAX;
+    const int n = (int)((T - base) < GS_MAX ? (T - base) : GS_MAX);
+    const int s0 = wave * (64 * GS_KPT) + lane;
+    uint32_t key[GS_KPT];
+#pragma unroll
+    for (int r = 0; r < GS_KPT; ++r) {
+        const int e = s0 + 64 * r;
+        key[r] = (e < n) ? (((uint32_t)ids[base + e] << GS_CHUNK_SHIFT) | (uint32_t)e) : 0xffffffffu;
+    }
+    radix_sort_in_lds(key, sk, hist, wbase, GS_CHUNK_SHIFT, id_bits);
+    for (int e = tid; e < n; e += (int)blockDim.x) {
+        const uint32_t k = sk[e];
+        out[base + e] = ((uint64_t)(k >> GS_CHUNK_SHIFT) << 32) | (uint64_t)(base + (int64_t)(k & (uint32_t)(GS_MAX - 1)));
+    }
+}
+
+// How many of the first d merged outputs of the sorted runs A (nA keys) and B (nB keys) come from A.
+template <typename Index>
+__device__ __forceinline__ Index merge_split(const uint64_t* A, Index nA, const uint64_t* B, Index nB, Index d) {
+    Index lo = d > nB ? d - nB : 0, hi = d < nA ? d : nA;
+    while (lo < hi) {
+        const Index mid = (lo + hi) >> 1;
+        if (A[mid] < B[d - 1 - mid]) lo = mid + 1;
+        else hi = mid;
+    }
+    return lo;
+}
+
+// One round: runs of `run` keys (the last one may be shorter or have no partner) become runs of 2 * run keys.
+// MG_TILE divides 2 * run, so a workgroup's outputs belong to one pair of runs.
+__global__ __launch_bounds__(MG_NT) void emb_merge_round(const uint64_t* __restrict__ src, uint64_t* __restrict__ dst, int64_t T,
+                                                         int64_t run) {
+    __shared__ uint64_t s[MG_TILE];
+    __shared__ int64_t split[2];
+    const int tid = threadIdx.x;
+    const int64_t out0 = (int64_t)blockIdx.x * MG_TILE;
+    const int64_t a0 = out0 / (2 * run) * (2 * run);
+    const int64_t a1 = a0 + run < T ? a0 + run : T, b1 = a0 + 2 * run < T ? a0 + 2 * run : T;
+    const uint64_t* A = src + a0;
+    const uint64_t* B = src + a1;
+    const int64_t nA = a1 - a0, nB = b1 - a1;
+    const int64_t d0 = out0 - a0, d1 = d0 + MG_TILE < nA + nB ? d0 + MG_TILE : nA + nB;
+    if (tid < 2) split[tid] = merge_split<int64_t>(A, nA, B, nB, tid ? d1 : d0);
+    __syncthreads();
+    const int64_t i0 = split[0], j0 = d0 - i0;
+    const int na = (int)(split[1] - i0), n = (int)(d1 - d0), nb = n - na;
+    for (int i = tid; i < n; i += MG_NT) s[i] = i < na ? A[i0 + i] : B[j0 + (i - na)];
+    __syncthreads();
+    const int k0 = tid * MG_KPT < n ? tid * MG_KPT : n;
+    int i = merge_split<int>(s, na, s + na, nb, k0), j = k0 - i;
+#pragma unroll
+    for (int r = 0; r < MG_KPT; ++r) {
+        if (k0 + r < n) {
+            const bool from_a = j >= nb || (i < na && s[i] < s[na + j]);
+            dst[out0 + k0 + r] = from_a ? s[i] : s[na + j];
+            i += from_a ? 1 : 0;
+            j += from_a ? 0 : 1;
+        }
+    }
+}
+
+// Heads (first position of every id) among the sorted keys [blockIdx.x * MG_TILE, + MG_TILE): their number.
+__device__ __forceinline__ int tile_heads(const uint64_t* __restrict__ keys, int64_t T, int64_t e0, uint32_t (&id)[MG_KPT],
+                                          uint32_t (&pos)[MG_KPT], bool (&head)[MG_KPT]) {
+    uint32_t before = e0 > 0 && e0 <= T ? (uint32_t)(keys[e0 - 1] >> 32) : 0u;
+    int heads = 0;
+#pragma unroll
+    for (int r = 0; r < MG_KPT; ++r) {
+        const int64_t e = e0 + r;
+        const uint64_t k = e < T ? keys[e] : 0ull;
+        id[r] = (uint32_t)(k >> 32);
+        pos[r] = (uint32_t)k;
+        head[r] = e < T && (e == 0 || before != id[r]);
+        heads += head[r] ? 1 : 0;
+        before = id[r];
+    }
+    return heads;
+}
+
+__device__ __forceinline__ int block_sum_int_256(int v, int32_t* red) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+__global__ __launch_bounds__(MG_NT) void emb_count_heads(const uint64_t* __restrict__ keys, int64_t T, int32_t* __restrict__ counts) {
+    __shared__ int32_t red[4];
+    uint32_t id[MG_KPT], pos[MG_KPT];
+    bool head[MG_KPT];
+    const int heads = tile_heads(keys, T, (int64_t)blockIdx.x * MG_TILE + (int64_t)threadIdx.x * MG_KPT, id, pos, head);
+    const int total = block_sum_int_256(heads, red);
+    if (threadIdx.x == 0) counts[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(MG_NT) void emb_segments_tiled(const uint64_t* __restrict__ keys, int64_t T,
+                                                            const int32_t* __restrict__ counts, int32_t* __restrict__ perm,
+                                                            int32_t* __restrict__ unique_ids, int32_t* __restrict__ seg_offsets,
+                                                            int32_t* __restrict__ n_unique) {
+    __shared__ int32_t red[4], wsum[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int before_me = 0;
+    for (int b = tid; b < (int)blockIdx.x; b += MG_NT) before_me += counts[b];
+    const int base = block_sum_int_256(before_me, red);
+    uint32_t id[MG_KPT], pos[MG_KPT];
+    bool head[MG_KPT];
+    const int64_t e0 = (int64_t)blockIdx.x * MG_TILE + (int64_t)tid * MG_KPT;
+    const int heads = tile_heads(keys, T, e0, id, pos, head);
+    int v = heads;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(v, off, 64);
+        if (lane >= off) v += o;
+    }
+    if (lane == 63) wsum[wave] = v;
+    __syncthreads();
+    int waves_before = 0, total = 0;
+    for (int w = 0; w < 4; ++w) {
+        waves_before += w < wave ? wsum[w] : 0;
+        total += wsum[w];
+    }
+    int idx = base + waves_before + v - heads;
+#pragma unroll
+    for (int r = 0; r < MG_KPT; ++r) {
+        const int64_t e = e0 + r;
+        if (e < T) perm[e] = (int32_t)pos[r];
+        if (head[r]) {
+            unique_ids[idx] = (int32_t)id[r];
+            seg_offsets[idx] = (int32_t)e;
+            ++idx;
+        }
+    }
+    if (blockIdx.x == gridDim.x - 1 && tid == 0) {
+        n_unique[0] = base + total;
+        seg_offsets[base + total] = (int32_t)T;
+    }
+}
+
 // Rows are summed in chunks of EMB_CHUNK sorted positions (one wave per chunk and 512-column slab).
 constexpr int EMB_CHUNK = 16;
 constexpr int EMB_COLS = 512;      // 64 lanes x 8 halves
@@ -299,7 +477,7 @@ static inline size_t emb_partials_bytes(int64_t T, int64_t H) {
 size_t embedding_ws_bytes(int64_t T, int64_t H) {
     if (T <= 0) return 0;
     const int64_t Tpad = next_pow2(T);
-    size_t b = align_up((size_t)Tpad * 8, 256);
+    size_t b = align_up((size_t)Tpad * 8, 256) * (T > GS_MAX ? 2 : 1);   // keys (+ the merge rounds' second buffer)
     b += align_up((size_t)T * 4, 256) * 2;         // perm, unique_ids
     b += align_up((size_t)(T + 1) * 4, 256);       // seg_offsets
     b += 256;                                      // n_unique
@@ -312,7 +490,8 @@ size_t embedding_ws_bytes(int64_t T, int64_t H) {
 // step keeps from its norm pass to its update pass.
 size_t embedding_grouping_bytes(int64_t T) {
     if (T <= 0) return 0;
-    return align_up((size_t)next_pow2(T) * 8, 256) + align_up((size_t)T * 4, 256) * 2 + align_up((size_t)(T + 1) * 4, 256) + 256;
+    return align_up((size_t)next_pow2(T) * 8, 256) * (T > GS_MAX ? 2 : 1) + align_up((size_t)T * 4, 256) * 2 +
+           align_up((size_t)(T + 1) * 4, 256) + 256;
 }
 
 EmbeddingWs carve_embedding_ws(void* ws, int64_t T, int64_t H) {
@@ -321,6 +500,11 @@ EmbeddingWs carve_embedding_ws(void* ws, int64_t T, int64_t H) {
     const int64_t Tpad = next_pow2(T);
     w.keys = reinterpret_cast<uint64_t*>(p);
     p += align_up((size_t)Tpad * 8, 256);
+    w.keys2 = nullptr;
+    if (T > GS_MAX) {
+        w.keys2 = reinterpret_cast<uint64_t*>(p);
+        p += align_up((size_t)Tpad * 8, 256);
+    }
     w.perm = reinterpret_cast<int32_t*>(p);
     p += align_up((size_t)T * 4, 256);
     w.unique_ids = reinterpret_cast<int32_t*>(p);
@@ -340,6 +524,26 @@ hipError_t launch_embedding_grouping(const int32_t* ids, int64_t T, int64_t V, c
     if (group_small_plan(T, V, &N, &shift, &id_bits)) {
         hipLaunchKernelGGL(emb_group_small, dim3(1), dim3((unsigned)(N / GS_KPT)), 0, st, ids, (int)T, N, shift, id_bits,
                            w.perm, w.unique_ids, w.seg_offsets, w.n_unique);
+        return hipGetLastError();
+    }
+    if (w.keys2 && group_chunks_plan(T, V, &id_bits)) {
+        const int64_t chunks = (T + GS_MAX - 1) / GS_MAX;
+        int rounds = 0;
+        for (int64_t run = GS_MAX; run < T; run <<= 1) ++rounds;
+        uint64_t* cur = (rounds & 1) ? w.keys2 : w.keys;      // after `rounds` exchanges the result is in w.keys
+        uint64_t* other = (rounds & 1) ? w.keys : w.keys2;
+        hipLaunchKernelGGL(emb_sort_chunks, dim3((unsigned)chunks), dim3(1024), 0, st, ids, T, id_bits, cur);
+        const unsigned tiles = (unsigned)((T + MG_TILE - 1) / MG_TILE);
+        for (int64_t run = GS_MAX; run < T; run <<= 1) {
+            hipLaunchKernelGGL(emb_merge_round, dim3(tiles), dim3(MG_NT), 0, st, cur, other, T, run);
+            uint64_t* t = cur;
+            cur = other;
+            other = t;
+        }
+        int32_t* counts = reinterpret_cast<int32_t*>(w.keys2);     // free again: one count per 2048 keys
+        hipLaunchKernelGGL(emb_count_heads, dim3(tiles), dim3(MG_NT), 0, st, w.keys, T, counts);
+        hipLaunchKernelGGL(emb_segments_tiled, dim3(tiles), dim3(MG_NT), 0, st, w.keys, T, counts, w.perm, w.unique_ids,
+                           w.seg_offsets, w.n_unique);
         return hipGetLastError();
     }
     if (T == 0) {   // empty batch: zero segments
@@ -432,8 +636,11 @@ __global__ __launch_bounds__(ROW_NT) void emb_chunk_kernel(const int32_t* __rest
     if (MODE == 1 && flag_in != nullptr && flag_in[0] != 0) return;
     if (MODE == 1 && s_dev != nullptr) s = s_dev[0];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int chunk = blockIdx.x * 4 + wave;
-    const int64_t col = (int64_t)blockIdx.y * EMB_COLS + lane * 8;
+    // consecutive workgroups take the column slabs of the same four chunks: the pieces of a dY row are asked for at about
+    // the same time, which the DRAM pages like better than slab after slab over the whole batch
+    const int slabs = (int)((H + EMB_COLS - 1) / EMB_COLS);
+    const int chunk = (int)(blockIdx.x / slabs) * 4 + wave;
+    const int64_t col = (int64_t)(blockIdx.x % slabs) * EMB_COLS + lane * 8;
     const bool active = col < H;
     const int nchunks = (T + EMB_CHUNK - 1) / EMB_CHUNK;
     float sq = 0.f;
@@ -513,7 +720,7 @@ __global__ __launch_bounds__(ROW_NT) void emb_chunk_kernel(const int32_t* __rest
     if (MODE == 0) {      // one share per workgroup: the four waves added in order
         __shared__ float red[4];
         const float total = block_sum_256(sq, red);
-        if (threadIdx.x == 0) partials[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = (double)total;
+        if (threadIdx.x == 0) partials[blockIdx.x] = (double)total;
     }
     if (MODE != 1 && flag_out != nullptr && __any(bad) && lane == 0) atomicOr(flag_out, 1);
 }
@@ -622,7 +829,14 @@ __global__ __launch_bounds__(ROW_NT) void emb_finish_sqnorm(const double* __rest
                                                             double* __restrict__ acc) {
     __shared__ double red[ROW_NT];
     double v = 0.0;
-    for (int i = threadIdx.x; i < n; i += ROW_NT) v += partials[i];
+    int i = threadIdx.x;
+    for (; i + 7 * ROW_NT < n; i += 8 * ROW_NT) {      // eight loads in flight; the order of the sum is fixed by this code
+        double t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = partials[i + u * ROW_NT];
+        v += ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
+    }
+    for (; i < n; i += ROW_NT) v += partials[i];
     red[threadIdx.x] = v;
     __syncthreads();
     for (int off = ROW_NT / 2; off > 0; off >>= 1) {
@@ -635,10 +849,10 @@ __global__ __launch_bounds__(ROW_NT) void emb_finish_sqnorm(const double* __rest
 hipError_t launch_embedding_rows(const int32_t* ids, const uint16_t* dY, uint16_t* W, int64_t T, int64_t H,
                                  const EmbeddingWs& w, int mode, float s, double* acc, int32_t* flag_out,
                                  const int32_t* flag_in, hipStream_t st, float lr, float clipv, const float* s_dev) {
-    const dim3 gridA((unsigned)emb_chunk_blocks(T), (unsigned)emb_slabs(H));
+    const dim3 gridA((unsigned)(emb_chunk_blocks(T) * emb_slabs(H)));
     const int64_t tripsB = (T + 63) / 64;
     const dim3 gridB((unsigned)(tripsB < EMB_FIX_GX ? tripsB : EMB_FIX_GX), (unsigned)emb_slabs(H));
-    double* partB = w.partials + (int64_t)gridA.x * gridA.y;
+    double* partB = w.partials + (int64_t)gridA.x;
 #define LOMO_EMB_LAUNCH(M)                                                                                              \
     hipLaunchKernelGGL(emb_chunk_kernel<M>, gridA, dim3(ROW_NT), 0, st, ids, dY, W, (int)T, H, w.perm, s, w.chunk_rows, \
                        w.partials, flag_out, flag_in, lr, clipv, s_dev);                                                \
@@ -647,7 +861,7 @@ hipError_t launch_embedding_rows(const int32_t* ids, const uint16_t* dY, uint16_
     if (mode == 0) {
         LOMO_EMB_LAUNCH(0)
         hipLaunchKernelGGL(emb_finish_sqnorm, dim3(1), dim3(ROW_NT), 0, st, w.partials,
-                           (int)(gridA.x * gridA.y + gridB.x * gridB.y), acc);
+                           (int)(gridA.x + gridB.x * gridB.y), acc);
     } else if (mode == 1) {
         LOMO_EMB_LAUNCH(1)
     } else {

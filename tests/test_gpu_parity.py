@@ -186,7 +186,11 @@ def _emb_case(T, V, H, mode, seed=0):
 
 EMB_CASES = [(4096, 32000, 512, "zipf"), (0, 50, 64, "uniform"), (1, 50, 64, "uniform"), (2, 50, 64, "same"),
              (777, 100, 72, "uniform"), (300, 1000, 2056, "distinct"), (513, 40, 4096, "same"),
-             (20000, 5000, 64, "zipf"), (8192, 32000, 128, "zipf"), (8193, 300, 8, "uniform")]
+             (20000, 5000, 64, "zipf"), (8192, 32000, 128, "zipf"), (8193, 300, 8, "uniform"),
+             # above 8192 positions: sorted chunks + merge rounds (one, two and three rounds; a last chunk of one
+             # position; heavy ties), and ids too wide for 32-bit keys (the bitonic route, below and above 8192)
+             (65536, 32000, 64, "zipf"), (30000, 200000, 8, "uniform"), (24577, 3, 8, "uniform"),
+             (16384, 1000, 8, "same"), (5000, 1500000, 8, "uniform"), (9000, 1500000, 8, "uniform")]
 
 
 @pytest.mark.parametrize("T,V,H,mode", EMB_CASES)
