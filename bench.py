@@ -206,6 +206,23 @@ def run_resident(L, torch, np, S, dev, wl, steps, warmup, args):
            "flops_per_pass": flops_pass, "gemms_per_linear": gemms, "coefficient": "device" if device_coef else "host"}
     if norm_compare:
         rec["norm_pass_alone"] = norm_compare
+    if getattr(args, "with_clip_value", False) and not args.per_tensor_calls:
+        # the single-pass alternative of section 3.3.1 on the same resident tensors: dgrad + fused clamp-and-update,
+        # two contractions per linear tensor instead of three, no norm pass (not part of `value`)
+        reps = max(2, min(5, steps))
+        for _ in range(2):
+            stepper.clip_value_pass(tensors, lr, 1.0 / wl.loss_scale, 1.0)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(reps):
+            stepper.clip_value_pass(tensors, lr, 1.0 / wl.loss_scale, 1.0)
+        torch.cuda.synchronize()
+        cms = (time.perf_counter() - t1) / reps * 1e3
+        cg = 1 if args.no_dgrad else 2
+        rec["clip_by_value_single_pass"] = {"ms_per_step": cms, "gemms_per_linear": cg, "steps": reps,
+                                            "tflops": cg * flops_pass / (cms * 1e-3) / 1e12,
+                                            "params_per_s": wl.n_params / (cms * 1e-3),
+                                            "overflow": bool(stepper.flags[len(tensors)].item())}
     if device_coef and len(tensors) <= 8:
         # short steps are launch bound: the same step recorded once as a HIP graph and replayed
         from paper_2306_09782_amd.step import CapturedStep
@@ -465,8 +482,10 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    args.with_clip_value = args.only == "all"      # the main workload also runs the single-pass step (not in `value`)
     wl, main_rec = run_workload(L, torch, np, S, dev, args.workload, args.steps, args.warmup, args,
                                 streamed=True if args.streamed else None)
+    args.with_clip_value = False
 
     k1 = main_rec["kernels"]["wgrad_update"]
     roofline = None
@@ -499,7 +518,7 @@ def main():
         "grad_norm": main_rec["grad_norm"], "clip_coef": main_rec["clip_coef"], "overflow": main_rec["overflow"],
         "roofline": roofline,
     }
-    for k in ("norm_pass_alone", "graph_replay", "input_generation_ms_per_step", "tflops_without_input_generation", "device_memory_bytes"):
+    for k in ("norm_pass_alone", "graph_replay", "clip_by_value_single_pass", "input_generation_ms_per_step", "tflops_without_input_generation", "device_memory_bytes"):
         if k in main_rec:
             out[k] = main_rec[k]
 

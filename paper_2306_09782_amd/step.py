@@ -96,6 +96,16 @@ class LomoStep:
             else:
                 B.lomo_vector_update(t["X"], t["dY"], t["W"], lr, inv_loss_scale, clip, self.ws, step_flag, stream)
 
+    def clip_value_pass(self, tensors: List[Dict], lr: float, inv_loss_scale: float, clip_value: float, stream=None):
+        """The single-pass step (section 3.3.1's clipping by value): every gradient element is unscaled, clamped to
+        [-clip_value, clip_value] and applied in the same walk; flags[i] rises where tensor i met a non-finite
+        element (that element's weight is left alone), flags[n] is their OR."""
+        assert self.grouped, "the single-pass step uses the whole-pass call"
+        assert len(tensors) < self.flags.numel()
+        with B.on_stream(stream):
+            self.flags.zero_()
+        B.lomo_step_update_pass_clip_value(self._list(tensors), lr, inv_loss_scale, clip_value, self.flags, self.ws, stream)
+
     def read_back(self, n: int, stream=None) -> Dict:
         """The one host read-back of a step: scaled squared norm, per-tensor flags, step flag."""
         with B.on_stream(stream):      # the blocking copy is queued on, and waits for, the step's stream
