@@ -356,6 +356,14 @@ def test_step_clip_by_value_all_kinds(L):
         want = O.sgd_update_clip_value(t["W"], O.tensor_grad(t), float(np.float32(lr)), float(np.float32(clipv)), Sc)
         assert_weights_close(host(g_["W"]), want, t["kind"])
     assert host(gpu[2]["W"])[9] == 1.0
+    # the same pass through the stepper (its own flags and workspace), from the same start
+    from paper_2306_09782_amd.step import LomoStep
+    gpu2 = [{k: (dev(v) if isinstance(v, np.ndarray) else v) for k, v in t.items()} for t in cpu]
+    stepper = LomoStep(DEV, max_T=T, max_H=H, max_tensors=len(gpu2))
+    stepper.clip_value_pass(gpu2, lr, 1.0 / Sc, clipv)
+    assert stepper.flags[:len(gpu2) + 1].cpu().tolist() == [0, 0, 1, 0, 1]
+    for a, b in zip(gpu, gpu2):
+        np.testing.assert_array_equal(host(a["W"]).view(np.uint16), host(b["W"]).view(np.uint16))
 
 
 def test_reduce_flags(L):
