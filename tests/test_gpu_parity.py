@@ -73,6 +73,13 @@ LINEAR_SHAPES = [
     (300, 776, 392),
     (70, 3600, 3320),      # 15 x 13 tiles of 256 x 256, ragged tails
     (64, 4096, 4096),      # 256 full 256 x 256 tiles
+    # edges of the persistent 256 x 256 x 32 kernels: the shortest contraction they take (one round of their four
+    # stages) and an odd number of rounds, the smallest tile count they take (192), for the weight gradient ...
+    (128, 4096, 4096),
+    (384, 3072, 4096),
+    # ... and for dgrad (tokens are the tile rows there, N is contracted)
+    (3328, 3840, 128),
+    (3328, 3840, 384),
 ]
 
 
