@@ -490,7 +490,9 @@ def main():
     k1 = main_rec["kernels"]["wgrad_update"]
     roofline = None
     if k1:
-        traffic, traffic_src = profiled_traffic(wl.name)
+        # the committed counter summary describes the whole named workload, launched as this run launches it
+        whole = args.workload == wl.name and not args.per_tensor_calls and not args.no_dgrad
+        traffic, traffic_src = profiled_traffic(wl.name) if whole else (None, None)
         algorithmic_bytes = sum(2 * s.T * (s.N + s.K) + 4 * s.N * s.K for s in wl.tensors if s.kind == "linear")
         roofline = {"kernel": "fused wgrad + SGD update (lomo_contract_dma_kernel<true, EPI_UPDATE>)", "bound": "mfma",
                     "achieved": k1["tflops"], "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s",
