@@ -341,14 +341,50 @@ bool gram_eligible(const GemmArgs& a) {
 
 // Estimated cost in units of one 256 x 256 x 32 slice on one CU.  A 256 x 128 x 32 slice of this kernel
 // does half the arithmetic but is bound by LDS bandwidth (a wave tile of 128 x 64 reads 1.5 times the
-// operand bytes per flop of the direct kernel's 128 x 128): measured 0.73 of a full slice, 0.8 with the
-// uneven last round of mixed tile lengths.
+// operand bytes per flop of the direct kernel's 128 x 128): measured 0.73 of a full slice.
+constexpr double kGramSlice = 0.73;
 double gram_cost(const GemmArgs& a) {
     const double tm = (double)(a.C / gram::BM);
-    return 0.8 * tm * (tm + 1.0) * (double)(a.M + a.Nn) / 32.0;
+    return kGramSlice * tm * (tm + 1.0) * (double)(a.M + a.Nn) / 32.0;
 }
 double direct_cost(const GemmArgs& a) {
     return (double)((a.M + 255) / 256) * (double)((a.Nn + 255) / 256) * (double)a.C / 32.0;
+}
+
+// The order launch_gram_group runs its tensors in: longest tiles first, so that the static walk ends on the short ones.
+static void gram_launch_order(std::vector<GemmArgs>& v) {
+    std::stable_sort(v.begin(), v.end(), [](const GemmArgs& x, const GemmArgs& y) { return x.M + x.Nn > y.M + y.Nn; });
+}
+
+// When the Gram launches of these tensors finish, in the same units: workgroup p of a launch walks tiles p, p + G, ...
+// (the kernel's static assignment), every tile of a tensor costs the same, and a launch ends with its busiest workgroup.
+// A few hundred long tiles on 256 CUs end far later than (total work) / (number of CUs) says.
+static double gram_finish_time(std::vector<GemmArgs> v) {
+    gram_launch_order(v);
+    const int cus = gram_cu_count();
+    double total = 0.0;
+    std::vector<double> load;
+    for (size_t first = 0; first < v.size(); first += gram::MAX_GROUP) {
+        const size_t cnt = v.size() - first < (size_t)gram::MAX_GROUP ? v.size() - first : (size_t)gram::MAX_GROUP;
+        int64_t tiles = 0;
+        for (size_t i = 0; i < cnt; ++i) {
+            const int64_t tm = v[first + i].C / gram::BM;
+            tiles += tm * (tm + 1);
+        }
+        const int64_t G = tiles < cus ? tiles : cus;
+        load.assign((size_t)G, 0.0);
+        int64_t w = 0;
+        for (size_t i = 0; i < cnt; ++i) {
+            const GemmArgs& a = v[first + i];
+            const int64_t tm = a.C / gram::BM, n = tm * (tm + 1);
+            const double tile = kGramSlice * (double)(a.M + a.Nn) / 32.0;
+            for (int64_t k = 0; k < n; ++k, ++w) load[(size_t)(w % G)] += tile;
+        }
+        double longest = 0.0;
+        for (double l : load) longest = l > longest ? l : longest;
+        total += longest;
+    }
+    return total;
 }
 
 void choose_norm_route(int mode, const std::vector<GemmArgs>& all, std::vector<GemmArgs>& gram, std::vector<GemmArgs>& direct) {
@@ -357,18 +393,11 @@ void choose_norm_route(int mode, const std::vector<GemmArgs>& all, std::vector<G
         (g ? gram : direct).push_back(a);
     }
     if (mode != LOMO_NORM_AUTO || gram.empty()) return;
-    // A few long tiles cannot fill the chip: compare finishing times, not total work.
-    const double cus = (double)gram_cu_count();
-    double work_g = 0.0, longest = 0.0, work_d = 0.0;
-    for (const GemmArgs& a : gram) {
-        const double tm = (double)(a.C / gram::BM);
-        const double tile = gram_cost(a) / (tm * (tm + 1.0));
-        work_g += gram_cost(a);
-        longest = tile > longest ? tile : longest;
-        work_d += direct_cost(a);
-    }
-    const double t_gram = work_g / cus > longest ? work_g / cus : longest;
-    if (t_gram >= work_d / cus) {
+    // Compare finishing times, not total work: the direct kernels' tiles are short and many (their share of the chip is
+    // their work), the Gram tiles are long and few.
+    double work_d = 0.0;
+    for (const GemmArgs& a : gram) work_d += direct_cost(a);
+    if (gram_finish_time(gram) >= work_d / (double)gram_cu_count()) {
         direct.insert(direct.end(), gram.begin(), gram.end());
         gram.clear();
     }
@@ -382,8 +411,7 @@ hipError_t launch_gram_group(const GemmArgs* list, int n, hipStream_t st) {
     if (cfg0 != hipSuccess) return cfg0;
     // Longest tiles first: the static round-robin then ends on the short ones.
     std::vector<GemmArgs> order(list, list + n);
-    std::stable_sort(order.begin(), order.end(),
-                     [](const GemmArgs& x, const GemmArgs& y) { return x.M + x.Nn > y.M + y.Nn; });
+    gram_launch_order(order);
     list = order.data();
     for (int first = 0; first < n; first += MAX_GROUP) {
         const int cnt = (n - first < MAX_GROUP) ? (n - first) : MAX_GROUP;
