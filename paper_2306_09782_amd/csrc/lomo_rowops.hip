@@ -20,7 +20,10 @@ static inline int64_t next_pow2(int64_t v) {
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ------------------------------------------------------------------------------------------
-// Embedding grouping: bitonic sort of unique 64-bit keys (id << 32 | position).  Unique keys make
+// Embedding grouping.  Three routes, one result (positions sorted by id, ties in position order; unique ids
+// ascending; segment offsets): one workgroup for batches of at most 8192 positions, sorted chunks + merge rounds
+// for larger ones (both below), and, for ids too wide for their 32-bit keys, the route of this section: a
+// bitonic sort of unique 64-bit keys (id << 32 | position) and a one-workgroup segment scan.  Unique keys make
 // any correct sort stable by construction: ties between equal ids are broken by position.
 // ------------------------------------------------------------------------------------------
 
