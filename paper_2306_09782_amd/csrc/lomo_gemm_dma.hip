@@ -54,6 +54,24 @@ struct GroupArgs {
     GroupTensor t[MAX_GROUP];
 };
 
+// Soft alignment of the workgroups of one XCD between rounds of the update kernels (timing only, no effect on results).
+// The 32 tiles that an XCD works on in a round share operand panels through its L2 as long as they walk the
+// contraction roughly in step; the update epilogue takes a different time on every CU (it waits for HBM), and without
+// anything that pulls them together again the workgroups drift apart over the rounds until a panel has left the L2
+// before its last reader asks for it (measured on the 7B stack: 22 GiB fetched per launch instead of 15.6).  Every
+// workgroup that has finished the main loop of a round adds one to the counter of (next round, XCD) and, before it
+// enters the next main loop, waits a bounded time until the others of its XCD have done so.  The counters are cleared
+// by a small kernel in front of every launch.  Launches that overlap on one GPU share them: a workgroup may then
+// wait less, or up to the bound once (after which it stops waiting), never for ever.
+constexpr int SYNC_ROUNDS = 512;        // rounds beyond this run free
+constexpr int SYNC_POLLS = 24;          // x 2048 clocks: the longest wait, about 30 us
+__device__ int32_t g_round_arrive[SYNC_ROUNDS][8];
+
+__global__ void clear_round_counters(int rounds) {
+    const int i = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (i < rounds * 8) (&g_round_arrive[0][0])[i] = 0;
+}
+
 __device__ __forceinline__ int swz_s(int r) { return ((r & 1) * 10) + ((r & 2) * 2); }
 __device__ __forceinline__ int swz_c(int n) { return ((n >> 1) & 3) ^ ((n >> 3) & 1); }
 
@@ -217,6 +235,18 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga
         const int q = G >> 3, r = G & 7;
         pos = x * q + (x < r ? x : r) + local;
     }
+
+    // round alignment (update kernels): this XCD's run of positions and how many of them have a tile in round k
+    constexpr bool ALIGN_ROUNDS = (EPI == EPI_UPDATE || EPI == EPI_CLIPV) && A_STRIDED && B_STRIDED;
+    const int xcd = (int)(blockIdx.x & 7);
+    const int xcd_first = xcd * (G >> 3) + (xcd < (G & 7) ? xcd : (G & 7));
+    const int xcd_count = (G >> 3) + (xcd < (G & 7) ? 1 : 0);
+    auto xcd_tiles_in_round = [&](int k) {
+        const int v = ga.total_tiles - k * G - xcd_first;
+        return v < 0 ? 0 : (v > xcd_count ? xcd_count : v);
+    };
+    bool align_rounds = ALIGN_ROUNDS;      // cleared after a wait that ran into its bound
+    int round = 0;
 
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
     const uint32_t lds_wave = lds0 + (uint32_t)wave * 4096u;   // this wave's first KiB slot in a tile
@@ -396,7 +426,19 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga
     zero_acc();
 
     while (true) {
-        // every load of this tile's first slices has landed and is visible to all waves
+        if constexpr (ALIGN_ROUNDS) {
+            if (round >= 1 && round < SYNC_ROUNDS && tid == 0 && align_rounds) {
+                const int need = xcd_tiles_in_round(round);
+                int polls = 0;
+                while (__hip_atomic_load(&g_round_arrive[round][xcd], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < need &&
+                       polls < SYNC_POLLS) {
+                    __builtin_amdgcn_s_sleep(32);
+                    ++polls;
+                }
+                if (polls == SYNC_POLLS) align_rounds = false;     // something else holds CUs: stop waiting
+            }
+        }
+        // every load of this tile's first slices has landed and is visible to all waves (and thread 0 is back)
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
         half8 fa0[4], fb0[4], fa1[4], fb1[4];
 #pragma unroll
@@ -437,6 +479,10 @@ __global__ __launch_bounds__(NT) void lomo_contract_dma_kernel(dma::GroupArgs ga
         // request the first blocks of W (update), then the first slices of the next tile, then finish this one
         w += G;
         const bool more = w < ga.total_tiles;
+        ++round;
+        if constexpr (ALIGN_ROUNDS) {
+            if (more && round < SYNC_ROUNDS && tid == 0) atomicAdd(&g_round_arrive[round][xcd], 1);
+        }
         if constexpr (EPI == EPI_UPDATE || EPI == EPI_STORE) {
             const RowEpilogue re(g, smem, wave, em0, en0);
             if constexpr (EPI == EPI_UPDATE) {
@@ -512,6 +558,11 @@ static hipError_t launch_dma_group_impl(const GemmArgs* list, int n, hipStream_t
         }
         ga.total_tiles = tiles;
         const int grid = tiles < cu_count() ? tiles : cu_count();
+        if ((EPI == EPI_UPDATE || EPI == EPI_CLIPV) && A_STRIDED && B_STRIDED) {     // the kernels that align their rounds
+            int rounds = (tiles + grid - 1) / grid;
+            if (rounds > SYNC_ROUNDS) rounds = SYNC_ROUNDS;
+            hipLaunchKernelGGL(clear_round_counters, dim3((unsigned)((rounds * 8 + 255) / 256)), dim3(256), 0, st, rounds);
+        }
         hipError_t e = launch_timed(list[first].family, kern, dim3((unsigned)grid), dim3(NT), (size_t)LDS_BYTES, st, ga);
         if (e != hipSuccess) return e;
     }
