@@ -19,8 +19,10 @@
  *     dY carries the loss scale; inv_loss_scale = 1 / loss_scale removes it.
  *   - the caller owns every buffer; the library allocates no device memory and keeps no state that
  *     changes a result between calls (what it does keep: the event pool of lomo_timing_*, one-time
- *     kernel attributes, and the fixed scratch array of lomo_vector_update_static, described with
- *     that call).  Every choice that changes how a result is computed is an argument.  Calls
+ *     kernel attributes, the fixed scratch array of lomo_vector_update_static, described with that
+ *     call, and a 16 KB array of counters through which the workgroups of the fused update kernel
+ *     keep in step, cleared before every such launch: it affects timing only).  Every choice that
+ *     changes how a result is computed is an argument.  Calls
  *     launch on `stream` (a hipStream_t, NULL = default stream) and never synchronise.  `acc` and
  *     `overflow_flag` are zeroed by the caller before pass 1.
  *   - pointers must be 16-byte aligned; K, N and H must be multiples of 8; T >= 0 is free.
