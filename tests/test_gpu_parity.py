@@ -124,6 +124,40 @@ def test_linear_sqnorm_update_dgrad(L, T, K, N):
     assert_weights_close(host(Wd2), O.sgd_update(W, G, float(np.float32(1e-2)), float(np.float32(coef)), Sc), "clipped")
 
 
+def _random_linear_shapes():
+    """Seeded shapes around the boundaries between the three contraction kernels: ragged ones for the guarded kernel,
+    multiples of 128 for the whole-tile kernel, and a few with 256-multiples and token counts next to a multiple of 64."""
+    rng = np.random.default_rng(20240611)
+    shapes = []
+    for _ in range(10):
+        shapes.append((int(rng.integers(1, 400)), 8 * int(rng.integers(1, 130)), 8 * int(rng.integers(1, 130))))
+    for _ in range(6):
+        shapes.append((64 * int(rng.integers(1, 6)), 128 * int(rng.integers(1, 9)), 128 * int(rng.integers(1, 9))))
+    for _ in range(4):
+        shapes.append((64 * int(rng.integers(2, 5)) + int(rng.integers(-1, 2)), 256 * int(rng.integers(1, 5)), 256 * int(rng.integers(1, 5))))
+    return shapes
+
+
+@pytest.mark.parametrize("T,K,N", _random_linear_shapes())
+def test_linear_random_shapes(L, T, K, N):
+    """Norm, visible update and dX on seeded random shapes, element by element against the oracle."""
+    Sc = 256.0
+    X = S.normal_f16_np(S.tensor_key(71, T, K, N), (T, K), S.normal_mult(1.0))
+    dY = S.normal_f16_np(S.tensor_key(72, T, K, N), (T, N), S.normal_mult(0.01, Sc))
+    W = S.normal_f16_np(S.tensor_key(73, T, K, N), (N, K), S.normal_mult(0.02))
+    G = O.linear_grad(X, dY)
+    acc = torch.zeros(1, dtype=torch.float64, device=DEV)
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    Xd, dYd, Wd = dev(X), dev(dY), dev(W)
+    L.lomo_wgrad_sqnorm(Xd, dYd, acc, flag)
+    assert abs(float(acc.item()) / O.sqnorm(G) - 1) < 2e-5 and int(flag.item()) == 0
+    lr = float(np.float32(30 * 2.0 ** -16 / (math.sqrt(T) * 0.01)))
+    dX = torch.empty(T, K, dtype=torch.float16, device=DEV)
+    L.lomo_linear_backward_update(Xd, dYd, Wd, dX, lr, 1.0 / Sc, 1.0, flag)
+    assert_weights_close(host(Wd), O.sgd_update(W, G, lr, 1.0, Sc), f"W {T}x{K}x{N}")
+    assert_dx_close(host(dX), dY, W, f"dX {T}x{K}x{N}")
+
+
 def test_dgrad_reads_weights_before_the_update(L):
     T, K, N = 96, 512, 256
     X, dY, W = gen(4, (T, K), 1.0), gen(5, (T, N), 0.5), gen(6, (N, K), 0.02)
