@@ -90,6 +90,11 @@ def test_shape_errors_are_reported_before_any_launch(lib):
     assert lib.lomo_step_workspace_bytes(bad, 0) == 0
     assert lib.lomo_embedding_workspace_bytes(0, 4096) == 0
     assert lib.lomo_embedding_workspace_bytes(4096, 4096) >= 4096 * 8 + 3 * 4096 * 4
+    # above 8192 positions the grouping merges sorted chunks between two key buffers
+    assert lib.lomo_embedding_workspace_bytes(20000, 64) >= 2 * 32768 * 8 + 3 * 20000 * 4
+    emb = (binding.LomoTensor * 1)()
+    emb[0].kind, emb[0].T, emb[0].K, emb[0].N = 1, 20000, 64, 32000
+    assert lib.lomo_step_workspace_bytes(emb, 1) == lib.lomo_embedding_workspace_bytes(20000, 64)
     assert lib.lomo_vector_workspace_bytes(4096, 4096) >= 4096 * 4
 
 
